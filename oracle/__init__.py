@@ -1,0 +1,217 @@
+"""ctypes binding of the CPU oracle (oracle/s24_oracle.c).
+
+TEST INFRASTRUCTURE, NOT PRODUCT CODE: only tests/, __graft_entry__.smoke() and
+bench.py's cpu_baseline leg may import this package.  It never imports the HIP
+package and the HIP package never imports it.
+
+bf16 tensors travel as numpy uint16 arrays (raw bit patterns); fp32 tensors as
+float32 arrays.  Floating-point results come back as float64 arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+F32, BF16 = 0, 1
+ACT_RELU, ACT_GELU_ERF = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "s24_oracle.c")
+_LIB = os.path.join(_HERE, "liborc.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
+                               _SRC, "-o", _LIB, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        for name in ("orc_pattern_table", "orc_transposable_mask", "orc_compress", "orc_spmm_fwd",
+                     "orc_spmm_bwd_dx", "orc_dense_dw", "orc_dense_gemm", "orc_masked_decay",
+                     "orc_swiglu_fwd", "orc_swiglu_bwd", "orc_act_fwd", "orc_act_bwd", "orc_num_threads"):
+            getattr(_lib, name).restype = C.c_int
+        _lib.orc_round_bf16.restype = None
+    return _lib
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"expected float32 or uint16(bf16 bits), got {a.dtype}")
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dtype=None):
+    a = np.ascontiguousarray(a) if dtype is None else np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _rows(rows):
+    if rows is None:
+        return None, 0
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    return rows, rows.size
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+def num_threads() -> int:
+    return _load().orc_num_threads()
+
+
+def pattern_table() -> np.ndarray:
+    out = np.zeros(128, dtype=np.uint16)
+    n = _load().orc_pattern_table(_p(out), C.c_int(128))
+    return out[:n].copy()
+
+
+def transposable_mask(W: np.ndarray, want_index: bool = False, exact_wide: bool = False):
+    """Block masks uint16 [r/4, q/4] (and pattern ids uint8) of the best transposable mask."""
+    W = _c(W)
+    r, q = W.shape
+    mask = np.zeros((r // 4, q // 4), dtype=np.uint16)
+    index = np.zeros((r // 4, q // 4), dtype=np.uint8) if want_index else None
+    rc = _load().orc_transposable_mask(_p(W), _dt(W), C.c_int64(r), C.c_int64(q), C.c_int64(q),
+                                       _p(mask), _p(index), C.c_int(1 if exact_wide else 0))
+    _check(rc, "transposable_mask")
+    return (mask, index) if want_index else mask
+
+
+def compress(W: np.ndarray, mask: np.ndarray):
+    """Returns vals[r,q/2], meta[r,q/16], valsT[q,r/2], metaT[q,r/16]."""
+    W = _c(W)
+    mask = _c(mask, np.uint16)
+    r, q = W.shape
+    vals = np.zeros((r, q // 2), dtype=W.dtype)
+    meta = np.zeros((r, q // 16), dtype=np.uint16)
+    valsT = np.zeros((q, r // 2), dtype=W.dtype)
+    metaT = np.zeros((q, r // 16), dtype=np.uint16)
+    rc = _load().orc_compress(_p(W), _dt(W), C.c_int64(r), C.c_int64(q), C.c_int64(q), _p(mask),
+                              _p(vals), _p(meta), _p(valsT), _p(metaT))
+    _check(rc, "compress")
+    return vals, meta, valsT, metaT
+
+
+def spmm_fwd(X, vals, meta, rows=None):
+    """Y[rows, r] = X . (M*W)^T from the compressed form, fp64."""
+    X, vals, meta = _c(X), _c(vals), _c(meta, np.uint16)
+    p, q = X.shape
+    r = vals.shape[0]
+    rows, n = _rows(rows)
+    Y = np.zeros((n if rows is not None else p, r), dtype=np.float64)
+    rc = _load().orc_spmm_fwd(_p(X), _p(vals), _p(meta), _dt(X), C.c_int64(p), C.c_int64(q), C.c_int64(r),
+                              _p(rows), C.c_int64(n), _p(Y))
+    _check(rc, "spmm_fwd")
+    return Y
+
+
+def spmm_bwd_dx(dY, valsT, metaT, beta=0.0, dX0=None, rows=None):
+    """dX[rows, q] = beta*dX0 + dY . (M*W) from the compressed transpose, fp64."""
+    dY, valsT, metaT = _c(dY), _c(valsT), _c(metaT, np.uint16)
+    p, r = dY.shape
+    q = valsT.shape[0]
+    rows, n = _rows(rows)
+    if dX0 is not None:
+        dX0 = _c(dX0, np.float64)
+    dX = np.zeros((n if rows is not None else p, q), dtype=np.float64)
+    rc = _load().orc_spmm_bwd_dx(_p(dY), _p(valsT), _p(metaT), _dt(dY), C.c_int64(p), C.c_int64(q), C.c_int64(r),
+                                 C.c_double(beta), _p(dX0), _p(rows), C.c_int64(n), _p(dX))
+    _check(rc, "spmm_bwd_dx")
+    return dX
+
+
+def dense_dw(dY, X, beta=0.0, dW0=None, rows=None):
+    """dW[rows, q] = beta*dW0 + dY^T . X, fp64 (rows selects out-features)."""
+    dY, X = _c(dY), _c(X)
+    p, r = dY.shape
+    q = X.shape[1]
+    rows, n = _rows(rows)
+    if dW0 is not None:
+        dW0 = _c(dW0, np.float64)
+    dW = np.zeros((n if rows is not None else r, q), dtype=np.float64)
+    rc = _load().orc_dense_dw(_p(dY), _p(X), _dt(X), C.c_int64(p), C.c_int64(q), C.c_int64(r),
+                              C.c_double(beta), _p(dW0), _p(rows), C.c_int64(n), _p(dW))
+    _check(rc, "dense_dw")
+    return dW
+
+
+def dense_gemm(X, W, rows=None):
+    """Y[rows, r] = X . W^T, fp64."""
+    X, W = _c(X), _c(W)
+    p, q = X.shape
+    r = W.shape[0]
+    rows, n = _rows(rows)
+    Y = np.zeros((n if rows is not None else p, r), dtype=np.float64)
+    rc = _load().orc_dense_gemm(_p(X), _p(W), _dt(X), C.c_int64(p), C.c_int64(q), C.c_int64(r),
+                                _p(rows), C.c_int64(n), _p(Y))
+    _check(rc, "dense_gemm")
+    return Y
+
+
+def masked_decay(dW, W, mask, lam):
+    dW = _c(dW, np.float32)
+    W, mask = _c(W), _c(mask, np.uint16)
+    r, q = W.shape
+    G = np.zeros((r, q), dtype=np.float64)
+    rc = _load().orc_masked_decay(_p(dW), _p(W), _dt(W), _p(mask), C.c_float(lam), C.c_int64(r), C.c_int64(q), _p(G))
+    _check(rc, "masked_decay")
+    return G
+
+
+def swiglu_fwd(G, U):
+    G, U = _c(G), _c(U)
+    p, f = G.shape
+    H = np.zeros((p, f), dtype=np.float64)
+    _check(_load().orc_swiglu_fwd(_p(G), _p(U), _dt(G), C.c_int64(p), C.c_int64(f), C.c_int64(f), _p(H)), "swiglu_fwd")
+    return H
+
+
+def swiglu_bwd(dH, G, U):
+    dH, G, U = _c(dH), _c(G), _c(U)
+    p, f = G.shape
+    dG = np.zeros((p, f), dtype=np.float64)
+    dU = np.zeros((p, f), dtype=np.float64)
+    _check(_load().orc_swiglu_bwd(_p(dH), _p(G), _p(U), _dt(G), C.c_int64(p), C.c_int64(f), C.c_int64(f),
+                                  _p(dG), _p(dU)), "swiglu_bwd")
+    return dG, dU
+
+
+def act_fwd(Z, act):
+    Z = _c(Z)
+    H = np.zeros(Z.shape, dtype=np.float64)
+    _check(_load().orc_act_fwd(_p(Z), _dt(Z), C.c_int64(Z.size), C.c_int(act), _p(H)), "act_fwd")
+    return H
+
+
+def act_bwd(dH, Z, act):
+    dH, Z = _c(dH), _c(Z)
+    dZ = np.zeros(Z.shape, dtype=np.float64)
+    _check(_load().orc_act_bwd(_p(dH), _p(Z), _dt(Z), C.c_int64(Z.size), C.c_int(act), _p(dZ)), "act_bwd")
+    return dZ
+
+
+def round_bf16(x) -> np.ndarray:
+    """fp64 -> fp32 -> bf16 bits (round-to-nearest-even at each step)."""
+    x = _c(x, np.float64)
+    out = np.zeros(x.shape, dtype=np.uint16)
+    _load().orc_round_bf16(_p(x), C.c_int64(x.size), _p(out))
+    return out

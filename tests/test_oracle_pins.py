@@ -1,0 +1,369 @@
+"""Pins of the CPU oracle against facts that do not come from the oracle:
+the paper's pattern count, exhaustive enumeration and exact rational
+arithmetic written here in Python, numpy/torch library routines, closed forms
+and finite differences.  CPU only."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import s24_inputs as si
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def skey(enc):
+    return "".join("1" if (enc >> t) & 1 else "0" for t in range(16))
+
+
+def expand_mask(mask):
+    """uint16 block masks [r/4,q/4] -> 0/1 array [r,q] (bit 4i+j = m_ij)."""
+    br, bq = mask.shape
+    out = np.zeros((br * 4, bq * 4), dtype=np.uint8)
+    for i in range(4):
+        for j in range(4):
+            out[i::4, j::4] = (mask >> (4 * i + j)) & 1
+    return out
+
+
+def f64(a):
+    return si.to_f32(a).astype(np.float64)
+
+
+# ---------------------------------------------------------------- patterns
+def test_pattern_count_is_90_as_in_paper():
+    # Sec. 5.1 step 1: "mask diversity n_t = 90"
+    assert len(oracle.pattern_table()) == 90
+
+
+def test_pattern_table_equals_independent_enumeration(legal_blocks):
+    tab = [int(v) for v in oracle.pattern_table()]
+    assert tab == legal_blocks
+    assert [skey(v) for v in tab] == sorted(skey(v) for v in tab)
+
+
+def test_pattern_table_invariants():
+    tab = [int(v) for v in oracle.pattern_table()]
+    assert len(set(tab)) == 90
+    for t in range(16):                      # every cell is set in exactly half of the patterns
+        assert sum((v >> t) & 1 for v in tab) == 45
+    assert sum(tab) == 45 * 65535
+
+    def transpose(v):
+        return sum((((v >> (4 * i + j)) & 1) << (4 * j + i)) for i in range(4) for j in range(4))
+
+    assert {transpose(v) for v in tab} == set(tab)          # closed under transpose
+    assert sum(transpose(v) == v for v in tab) == 18
+    assert {(~v) & 0xFFFF for v in tab} == set(tab)         # and under complement
+    firsts = [v & 0xF for v in tab]
+    assert all(firsts.count(x) == 15 for x in set(firsts)) and len(set(firsts)) == 6
+    # first and last in string order
+    assert tab[0] == 0x33CC and tab[89] == 0xCC33
+
+
+def test_pattern_golden_file_matches():
+    rows = [l.split() for l in open(os.path.join(HERE, "golden", "pattern_table.txt")) if not l.startswith("#")]
+    tab = oracle.pattern_table()
+    assert [int(b, 16) for _, b in rows] == [int(v) for v in tab]
+
+
+# ---------------------------------------------------------------- mask search
+def brute_force_block(vals16, legal_blocks):
+    """Exact optimum of one block with rational arithmetic, first in string order."""
+    mags = [abs(Fraction(float(v))) for v in vals16]
+    best, best_s = None, None
+    for enc in legal_blocks:   # already in string order
+        s = sum(mags[t] for t in range(16) if (enc >> t) & 1)
+        if best_s is None or s > best_s:
+            best, best_s = enc, s
+    return best
+
+
+def check_against_brute_force(W, legal_blocks, **kw):
+    mask, index = oracle.transposable_mask(W, want_index=True, **kw)
+    Wf = si.to_f32(W)
+    r, q = Wf.shape
+    for bi in range(r // 4):
+        for bj in range(q // 4):
+            blk = Wf[4 * bi:4 * bi + 4, 4 * bj:4 * bj + 4].reshape(-1)
+            want = brute_force_block(blk, legal_blocks)
+            assert int(mask[bi, bj]) == want, (bi, bj, blk)
+            assert legal_blocks[int(index[bi, bj])] == want
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mask_matches_exact_brute_force_random(dtype, legal_blocks):
+    W = si.random_matrix(11, (32, 48), 0.02, dtype)
+    check_against_brute_force(W, legal_blocks)
+    check_against_brute_force(W, legal_blocks, exact_wide=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal"])
+def test_mask_matches_exact_brute_force_ties(dtype, kind, legal_blocks):
+    W = si.tie_matrix(5, 16, 32, dtype, kind)
+    check_against_brute_force(W, legal_blocks)
+    check_against_brute_force(W, legal_blocks, exact_wide=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mask_fast_and_wide_paths_agree(dtype):
+    for kind in ["few", "equal", "zeros", "tiny", "range", "subnormal"]:
+        W = si.tie_matrix(9, 64, 128, dtype, kind)
+        a = oracle.transposable_mask(W)
+        b = oracle.transposable_mask(W, exact_wide=True)
+        assert np.array_equal(a, b), kind
+    W = si.random_matrix(3, (128, 256), 0.02, dtype)
+    assert np.array_equal(oracle.transposable_mask(W), oracle.transposable_mask(W, exact_wide=True))
+
+
+def test_mask_every_block_is_legal():
+    W = si.random_matrix(4, (256, 512), 0.02, "bf16")
+    m = expand_mask(oracle.transposable_mask(W))
+    assert (m.reshape(256, 128, 4).sum(-1) == 2).all()                # 2 per row group
+    assert (m.reshape(64, 4, 512).sum(1) == 2).all()                   # 2 per column group
+    assert m.sum() == m.size // 2
+
+
+def test_mask_all_equal_block_picks_first_pattern():
+    W = np.full((4, 4), 0.375, dtype=np.float32)
+    assert int(oracle.transposable_mask(W)[0, 0]) == 0x33CC
+    W[1, 2] = -0.375
+    assert int(oracle.transposable_mask(W)[0, 0]) == 0x33CC
+
+
+def test_mask_planted_pattern_is_recovered(legal_blocks):
+    rng = np.random.default_rng(0)
+    W = np.zeros((4, 4 * 90), dtype=np.float32)
+    for k, enc in enumerate(legal_blocks):
+        for t in range(16):
+            big = (enc >> t) & 1
+            W[t // 4, 4 * k + t % 4] = (1.0 if big else 0.01) * (1 + 0.1 * rng.random()) * rng.choice([-1, 1])
+    mask, index = oracle.transposable_mask(W, want_index=True)
+    assert [int(v) for v in mask[0]] == legal_blocks
+    assert [int(v) for v in index[0]] == list(range(90))
+
+
+def test_mask_invariant_to_sign_and_power_of_two_scale():
+    W = si.to_f32(si.random_matrix(6, (64, 64), 0.02, "bf16"))
+    base = oracle.transposable_mask(W)
+    rng = np.random.default_rng(1)
+    flips = rng.choice([-1.0, 1.0], size=W.shape).astype(np.float32)
+    assert np.array_equal(oracle.transposable_mask(W * flips), base)
+    assert np.array_equal(oracle.transposable_mask(W * np.float32(2.0 ** -9)), base)
+    assert np.array_equal(oracle.transposable_mask(W * np.float32(2.0 ** 20)), base)
+
+
+def test_mask_transpose_retains_same_magnitude():
+    W = si.to_f32(si.random_matrix(8, (64, 96), 0.02, "bf16"))
+    m = expand_mask(oracle.transposable_mask(W))
+    mt = expand_mask(oracle.transposable_mask(np.ascontiguousarray(W.T)))
+    a = np.abs(W).astype(np.float64)
+    kept = (a * m).reshape(16, 4, 24, 4).sum(axis=(1, 3))
+    kept_t = (a.T * mt).reshape(24, 4, 16, 4).sum(axis=(1, 3))
+    assert np.array_equal(kept, kept_t.T)       # sums of bf16 magnitudes are exact in fp64
+
+
+def test_mask_retained_l1_bounded_by_one_sided_optima():
+    W = si.to_f32(si.random_matrix(10, (64, 64), 0.02, "bf16"))
+    a = np.abs(W).astype(np.float64)
+    m = expand_mask(oracle.transposable_mask(W))
+    kept = (a * m).reshape(16, 4, 16, 4).sum(axis=(1, 3))
+    row_opt = np.sort(a.reshape(64, 16, 4), axis=-1)[..., 2:].sum(-1).reshape(16, 4, 16).sum(1)
+    col_opt = np.sort(a.reshape(16, 4, 64), axis=1)[:, 2:, :].sum(1).reshape(16, 16, 4).sum(-1)
+    assert (kept <= row_opt).all() and (kept <= col_opt).all()
+    assert (kept < row_opt).any()      # the transposable constraint does bind somewhere
+
+
+def test_mask_bad_shape_is_rejected():
+    with pytest.raises(ValueError):
+        oracle.transposable_mask(np.zeros((6, 8), dtype=np.float32))
+
+
+# ---------------------------------------------------------------- compress
+def decode(vals, meta, width):
+    """Python decoder of the compressed form (written here, not in the oracle)."""
+    rows = vals.shape[0]
+    out = np.zeros((rows, width), dtype=vals.dtype)
+    for o in range(rows):
+        for g in range(width // 4):
+            nib = (int(meta[o, g // 4]) >> (4 * (g % 4))) & 0xF
+            i0, i1 = nib & 3, nib >> 2
+            assert i0 < i1
+            out[o, 4 * g + i0] = vals[o, 2 * g]
+            out[o, 4 * g + i1] = vals[o, 2 * g + 1]
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_compress_decodes_to_masked_weight_bitwise(dtype):
+    W = si.random_matrix(12, (32, 64), 0.02, dtype)
+    W[3, 5] = 0          # a kept or pruned exact zero must not disturb the indices
+    W[0:4, 0:4] = 0
+    mask = oracle.transposable_mask(W)
+    m = expand_mask(mask).astype(bool)
+    vals, meta, valsT, metaT = oracle.compress(W, mask)
+    masked = np.where(m, W, np.zeros_like(W))
+    assert np.array_equal(decode(vals, meta, 64), masked)
+    assert np.array_equal(decode(valsT, metaT, 32), masked.T)
+    legal = {0b0100, 0b1000, 0b1100, 0b1001, 0b1101, 0b1110}
+    for mm in (meta, metaT):
+        nibs = {(int(w) >> s) & 0xF for w in mm.reshape(-1) for s in (0, 4, 8, 12)}
+        assert nibs <= legal
+
+
+def test_compress_rejects_illegal_mask():
+    W = si.random_matrix(1, (16, 16), 0.02, "f32")
+    mask = oracle.transposable_mask(W)
+    mask[0, 0] = 0x000F
+    with pytest.raises(ValueError):
+        oracle.compress(W, mask)
+
+
+# ---------------------------------------------------------------- GEMMs
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sparse_gemms_equal_dense_gemm_on_masked_weight(dtype):
+    p, q, r = 24, 64, 48
+    W = si.random_matrix(20, (r, q), 0.02, dtype)
+    X = si.random_matrix(21, (p, q), 1.0, dtype)
+    dY = si.random_matrix(22, (p, r), 1.0, dtype)
+    mask = oracle.transposable_mask(W)
+    vals, meta, valsT, metaT = oracle.compress(W, mask)
+    Wm = f64(W) * expand_mask(mask)
+    Y = oracle.spmm_fwd(X, vals, meta)
+    np.testing.assert_allclose(Y, f64(X) @ Wm.T, rtol=1e-12, atol=1e-13)
+    dX = oracle.spmm_bwd_dx(dY, valsT, metaT)
+    np.testing.assert_allclose(dX, f64(dY) @ Wm, rtol=1e-12, atol=1e-13)
+    dX0 = np.random.default_rng(0).standard_normal((p, q))
+    dXb = oracle.spmm_bwd_dx(dY, valsT, metaT, beta=1.0, dX0=dX0)
+    np.testing.assert_allclose(dXb, dX0 + f64(dY) @ Wm, rtol=1e-12, atol=1e-13)
+    rows = np.array([5, 0, 23], dtype=np.int64)
+    assert np.array_equal(oracle.spmm_fwd(X, vals, meta, rows=rows), Y[rows])
+    assert np.array_equal(oracle.spmm_bwd_dx(dY, valsT, metaT, rows=rows), dX[rows])
+    # torch as a second library
+    Yt = torch.from_numpy(f64(X)) @ torch.from_numpy(Wm).T
+    np.testing.assert_allclose(Y, Yt.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_sparse_gemm_one_hot_rows_reproduce_masked_weight():
+    q, r = 32, 16
+    W = si.random_matrix(23, (r, q), 0.02, "bf16")
+    mask = oracle.transposable_mask(W)
+    vals, meta, valsT, metaT = oracle.compress(W, mask)
+    Wm = f64(W) * expand_mask(mask)
+    eye_q = si.f32_to_bf16_bits(torch.eye(q))
+    eye_r = si.f32_to_bf16_bits(torch.eye(r))
+    assert np.array_equal(oracle.spmm_fwd(eye_q, vals, meta), Wm.T)      # Y = I (MW)^T
+    assert np.array_equal(oracle.spmm_bwd_dx(eye_r, valsT, metaT), Wm)   # dX = I (MW)
+    # not symmetric, so a transposed operand would show
+    assert not np.array_equal(Wm[:, :16], Wm[:, :16].T)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dense_gemms_match_library(dtype):
+    p, q, r = 40, 24, 16
+    X = si.random_matrix(30, (p, q), 1.0, dtype)
+    dY = si.random_matrix(31, (p, r), 1.0, dtype)
+    W = si.random_matrix(32, (r, q), 0.02, dtype)
+    dW = oracle.dense_dw(dY, X)
+    np.testing.assert_allclose(dW, f64(dY).T @ f64(X), rtol=1e-12, atol=1e-13)
+    dW0 = np.random.default_rng(2).standard_normal((r, q))
+    np.testing.assert_allclose(oracle.dense_dw(dY, X, beta=1.0, dW0=dW0), dW0 + f64(dY).T @ f64(X), rtol=1e-12)
+    rows = np.array([3, 15], dtype=np.int64)
+    assert np.array_equal(oracle.dense_dw(dY, X, rows=rows), dW[rows])
+    np.testing.assert_allclose(oracle.dense_gemm(X, W), f64(X) @ f64(W).T, rtol=1e-12, atol=1e-13)
+    # rank one: p = 1 is exactly the outer product
+    assert np.array_equal(oracle.dense_dw(dY[:1], X[:1]), np.outer(f64(dY)[0], f64(X)[0]))
+
+
+# ---------------------------------------------------------------- masked decay (Eq. 10)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_masked_decay_touches_only_pruned_cells(dtype):
+    r, q, lam = 32, 48, np.float32(2e-4)
+    W = si.random_matrix(40, (r, q), 0.02, dtype)
+    dW = si.random_matrix(41, (r, q), 1e-3, "f32")
+    mask = oracle.transposable_mask(W)
+    m = expand_mask(mask).astype(bool)
+    G = oracle.masked_decay(dW, W, mask, lam)
+    assert np.array_equal(G[m], dW.astype(np.float64)[m])                      # kept: untouched
+    want = dW.astype(np.float64) + np.float64(lam) * f64(W)
+    np.testing.assert_allclose(G[~m], want[~m], rtol=1e-15)                    # pruned: + lambda w
+    assert (~m).sum() == m.size // 2
+    assert np.array_equal(oracle.masked_decay(dW, W, mask, 0.0), dW.astype(np.float64))
+    # sign: the term pulls pruned weights towards zero under gradient descent
+    big = np.abs(f64(W)) > 1e-3
+    sel = ~m & big
+    assert (np.sign(G - dW)[sel] == np.sign(f64(W))[sel]).all()
+
+
+# ---------------------------------------------------------------- activations
+def test_swiglu_matches_library_and_special_values():
+    g = si.random_matrix(50, (8, 32), 2.0, "bf16")
+    u = si.random_matrix(51, (8, 32), 1.0, "bf16")
+    H = oracle.swiglu_fwd(g, u)
+    tg, tu = torch.from_numpy(f64(g)), torch.from_numpy(f64(u))
+    np.testing.assert_allclose(H, (torch.nn.functional.silu(tg) * tu).numpy(), rtol=1e-13, atol=1e-300)
+    z = si.f32_to_bf16_bits(torch.tensor([[0.0, 88.0, -88.0, 300.0, -300.0, -0.0, 1.0, -1.0]]))
+    one = si.f32_to_bf16_bits(torch.ones(1, 8))
+    h = oracle.swiglu_fwd(z, one)[0]
+    assert h[0] == 0 and h[5] == 0 and np.isfinite(h).all()
+    assert h[1] == 88.0 and h[3] == 300.0 and abs(h[2]) < 1e-30 and abs(h[4]) < 1e-100
+    np.testing.assert_allclose(h[6], 1 / (1 + np.exp(-1.0)), rtol=1e-15)
+    # gate is the FIRST operand: swapping operands changes the result
+    assert not np.allclose(oracle.swiglu_fwd(u, g), H)
+
+
+def test_swiglu_bwd_matches_autograd_and_finite_differences():
+    g = si.random_matrix(52, (4, 16), 2.0, "bf16")
+    u = si.random_matrix(53, (4, 16), 1.0, "bf16")
+    d = si.random_matrix(54, (4, 16), 1.0, "bf16")
+    dG, dU = oracle.swiglu_bwd(d, g, u)
+    tg = torch.from_numpy(f64(g)).requires_grad_()
+    tu = torch.from_numpy(f64(u)).requires_grad_()
+    (torch.nn.functional.silu(tg) * tu).backward(torch.from_numpy(f64(d)))
+    np.testing.assert_allclose(dG, tg.grad.numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(dU, tu.grad.numpy(), rtol=1e-12, atol=1e-15)
+    # central differences on the closed form, in fp64
+    G, U, D = f64(g), f64(u), f64(d)
+    silu = lambda x: x / (1 + np.exp(-x))
+    eps = 1e-6
+    np.testing.assert_allclose(dG, D * U * (silu(G + eps) - silu(G - eps)) / (2 * eps), rtol=1e-6, atol=1e-8)
+    H = oracle.swiglu_fwd(g, u)
+    nz = U != 0
+    np.testing.assert_allclose(dU[nz] / D[nz], (H / np.where(nz, U, 1))[nz], rtol=1e-12)
+    # silu'(0) = 1/2
+    z = np.zeros((1, 16), dtype=np.uint16)
+    one = si.f32_to_bf16_bits(torch.ones(1, 16))
+    dg0, du0 = oracle.swiglu_bwd(one, z, one)
+    assert (dg0 == 0.5).all() and (du0 == 0).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_relu_and_gelu_match_library(dtype):
+    z = si.random_matrix(60, (6, 40), 1.5, dtype)
+    d = si.random_matrix(61, (6, 40), 1.0, dtype)
+    z.reshape(-1)[:3] = 0
+    tz = torch.from_numpy(f64(z))
+    np.testing.assert_array_equal(oracle.act_fwd(z, oracle.ACT_RELU), torch.relu(tz).numpy())
+    np.testing.assert_allclose(oracle.act_fwd(z, oracle.ACT_GELU_ERF),
+                               torch.nn.functional.gelu(tz, approximate="none").numpy(), rtol=1e-13, atol=1e-300)
+    dz = oracle.act_bwd(d, z, oracle.ACT_RELU)
+    np.testing.assert_array_equal(dz, f64(d) * (f64(z) > 0))          # relu'(0) = 0
+    tz2 = tz.clone().requires_grad_()
+    torch.nn.functional.gelu(tz2, approximate="none").backward(torch.from_numpy(f64(d)))
+    np.testing.assert_allclose(oracle.act_bwd(d, z, oracle.ACT_GELU_ERF), tz2.grad.numpy(), rtol=1e-12, atol=1e-15)
+    # GELU(0) = 0, GELU'(0) = 1/2
+    zero = np.zeros((1, 4), dtype=z.dtype)
+    one = si.f32_to_bf16_bits(torch.ones(1, 4)) if dtype == "bf16" else np.ones((1, 4), dtype=np.float32)
+    assert (oracle.act_fwd(zero, oracle.ACT_GELU_ERF) == 0).all()
+    assert (oracle.act_bwd(one, zero, oracle.ACT_GELU_ERF) == 0.5).all()
+
+
+def test_round_bf16_matches_torch():
+    x = np.random.default_rng(7).standard_normal(4096) * np.exp(np.random.default_rng(8).uniform(-30, 30, 4096))
+    x[:4] = [0.0, -0.0, 1.00390625, 1.01171875]   # exact ties: round to even
+    want = torch.from_numpy(x).float().to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.round_bf16(x), want)
