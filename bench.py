@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the 2:4-sparse FFN training step on one MI355X.
+
+One step = the whole hot path once on one batch of synthetic input already
+resident in HBM: per weight the transposable mask search fused with
+prune/compress, the sparse forward GEMMs, the activation, the sparse
+input-gradient GEMMs, the dense weight-gradient GEMMs and the masked decay.
+
+    python bench.py [--workload c4] [--steps K] [--warmup W]
+
+Prints ONE JSON line.  `value` is the dense-equivalent GEMM TFLOP/s of the whole
+step (all 6 or 9 GEMMs' 2*p*d*d_ff FLOPs divided by the wall time of the step,
+mask/compress/activation/decay included).  `roofline` describes the kernel that
+takes the largest share of the step; `kernels` lists every kernel with its own
+roofline fraction; `cpu_baseline` is the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_DENSE_BF16 = 2500.0      # TFLOP/s, dense bf16 MFMA
+PEAK_SPARSE_BF16 = 5000.0     # TFLOP/s, 2:4 structured-sparse bf16 (dense-equivalent FLOPs)
+PEAK_HBM = 8000.0             # GB/s
+
+
+def kernel_model(wl):
+    """Algorithmic work of one launch of each kernel: (kind, amount, peak, unit)."""
+    p, d, f = wl.p, wl.d_model, wl.d_ff
+    es = 2 if wl.dtype == "bf16" else 4
+    blocks = d * f / 16
+    gemm = 2.0 * p * d * f
+    m = {
+        "spmm_fwd": ("mfma", gemm, PEAK_SPARSE_BF16, "TFLOP/s"),
+        "spmm_bwd_dx": ("mfma", gemm, PEAK_SPARSE_BF16, "TFLOP/s"),
+        "dense_dw": ("mfma", gemm, PEAK_DENSE_BF16, "TFLOP/s"),
+        # per 4x4 block: read 16 weights; write mask 2, vals 16*es/2, meta 2, valsT 16*es/2, metaT 2
+        "mask_compress": ("hbm", blocks * (16 * es + 2 + 8 * es + 2 + 8 * es + 2), PEAK_HBM, "GB/s"),
+        # per element: read dW 4 + W es + mask 1/8, write 4
+        "masked_decay": ("hbm", d * f * (8 + es + 0.125), PEAK_HBM, "GB/s"),
+        "swiglu_fwd": ("hbm", p * f * 3 * es, PEAK_HBM, "GB/s"),
+        "swiglu_bwd": ("hbm", p * f * 5 * es, PEAK_HBM, "GB/s"),
+        "act_fwd": ("hbm", p * f * 2 * es, PEAK_HBM, "GB/s"),
+        "act_bwd": ("hbm", p * f * 3 * es, PEAK_HBM, "GB/s"),
+    }
+    return m
+
+
+def cpu_baseline(wl, tensors_host, budget_tokens=16):
+    """The oracle, as it stands, on a bounded sample: every weight-side stage
+    (mask, compress, decay) at full size, every token-side stage (GEMMs,
+    activation) on the first `budget_tokens` tokens, extrapolated linearly in
+    the token count.  Returns dense-equivalent TFLOP/s of the whole step."""
+    import numpy as np
+    import oracle
+    import s24_inputs as si
+    t = tensors_host
+    n = min(budget_tokens, wl.p)
+    X, dY = np.ascontiguousarray(t["X"][:n]), np.ascontiguousarray(t["dY"][:n])
+    t0 = time.perf_counter()
+    comp = {}
+    for name in wl.weight_names:
+        m = oracle.transposable_mask(t[name])
+        comp[name] = (m,) + oracle.compress(t[name], m)
+    for name in wl.weight_names:
+        r, q = t[name].shape
+        oracle.masked_decay(np.zeros((r, q), np.float32), t[name], comp[name][0], wl.lam)
+    t_weights = time.perf_counter() - t0
+    rnd = oracle.round_bf16 if wl.dtype == "bf16" else (lambda a: a.astype(np.float32))
+    t0 = time.perf_counter()
+    if wl.gated:
+        G = rnd(oracle.spmm_fwd(X, comp["Wg"][1], comp["Wg"][2]))
+        U = rnd(oracle.spmm_fwd(X, comp["Wu"][1], comp["Wu"][2]))
+        H = rnd(oracle.swiglu_fwd(G, U))
+        oracle.spmm_fwd(H, comp["Wd"][1], comp["Wd"][2])
+        dH = rnd(oracle.spmm_bwd_dx(dY, comp["Wd"][3], comp["Wd"][4]))
+        dG, dU = (rnd(a) for a in oracle.swiglu_bwd(dH, G, U))
+        oracle.spmm_bwd_dx(dG, comp["Wg"][3], comp["Wg"][4])
+        oracle.spmm_bwd_dx(dU, comp["Wu"][3], comp["Wu"][4])
+        oracle.dense_dw(dY, H)
+        oracle.dense_dw(dG, X)
+        oracle.dense_dw(dU, X)
+    else:
+        act = oracle.ACT_RELU if wl.act == "relu" else oracle.ACT_GELU_ERF
+        Z = rnd(oracle.spmm_fwd(X, comp["W1"][1], comp["W1"][2]))
+        H = rnd(oracle.act_fwd(Z, act))
+        oracle.spmm_fwd(H, comp["W2"][1], comp["W2"][2])
+        dH = rnd(oracle.spmm_bwd_dx(dY, comp["W2"][3], comp["W2"][4]))
+        dZ = rnd(oracle.act_bwd(dH, Z, act))
+        oracle.spmm_bwd_dx(dZ, comp["W1"][3], comp["W1"][4])
+        oracle.dense_dw(dY, H)
+        oracle.dense_dw(dZ, X)
+    t_tokens = time.perf_counter() - t0
+    est = t_weights + t_tokens * (wl.p / n)
+    return {
+        "value": wl.gemm_flops / est / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": (f"mask+compress+decay of all {len(wl.weight_names)} weights at full size ({t_weights:.1f} s); GEMMs and "
+                   f"activation on the first {n} of {wl.p} tokens ({t_tokens:.1f} s), extrapolated linearly in tokens "
+                   f"to {est:.0f} s per step"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1. "
+                 "DESIGN.md describes how the step would shard over data-parallel ranks.")
+
+    import torch
+    import s24_inputs as si
+    import paper_2404_01847_amd as s24
+    from paper_2404_01847_amd.ffn import SparseFFN
+
+    s24.lib()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    wl = si.WORKLOADS[args.workload]
+    host = si.make(wl)
+
+    def to_dev(a):
+        import numpy as np
+        t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+        return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
+
+    dev = {k: to_dev(v) for k, v in host.items()}
+    ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam)
+    X, dY = dev["X"], dev["dY"]
+
+    for _ in range(args.warmup):
+        ffn.step(X, dY)
+    torch.cuda.synchronize()
+    ffn.timings = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ffn.step(X, dY)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = wl.gemm_flops / (ms_per_step * 1e-3) / 1e12
+
+    model = kernel_model(wl)
+    kernels = {}
+    for name, pairs in ffn.timings.items():
+        ms = [a.elapsed_time(b) for a, b in pairs]
+        avg = sum(ms) / len(ms)
+        kind, amount, peak, unit = model[name]
+        achieved = amount / (avg * 1e-3) / (1e12 if kind == "mfma" else 1e9)
+        kernels[name] = {"launches_per_step": len(ms) // args.steps, "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
+                         "share_of_step": round(sum(ms) / args.steps / ms_per_step, 4), "bound": kind,
+                         "achieved": round(achieved, 1), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
+    dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])
+    kd = kernels[dom]
+    roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"], "unit": kd["unit"],
+                "frac": kd["frac"], "traffic": None}
+
+    out = {
+        "metric": "2:4 FFN fwd+bwd TFLOP/s (dense-equivalent GEMM FLOPs over the whole step)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: FFN d_model={wl.d_model} d_ff={wl.d_ff} tokens={wl.p} act={wl.act} "
+                               f"{wl.dtype}, {len(wl.weight_names)} weights, mask+compress every step",
+                   "gemm_flops_per_step": wl.gemm_flops},
+        "pct_of_sparse_mfma_peak_whole_step": round(100 * value / PEAK_SPARSE_BF16, 2),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, host)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

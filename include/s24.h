@@ -1,0 +1,144 @@
+/*
+ * s24 -- the 2:4-sparse FFN training step of arXiv 2404.01847 on AMD MI355X (gfx950).
+ *
+ * C ABI.  Notation follows the paper (Sec. 3.1): X is p x q (tokens x
+ * in-features, batch and sequence axes flattened), W is r x q (out-features x
+ * in-features), Z/Y is p x r.  Every matrix is row-major and dense in memory
+ * unless a leading dimension is given.
+ *
+ * Pointers: every data pointer is a DEVICE pointer owned by the caller, except
+ * where a comment says "host".  The library never allocates, frees or
+ * synchronises; each call only enqueues kernels on `stream` (a hipStream_t
+ * passed as void*, NULL = the default stream) and returns.
+ *
+ * Errors: every entry point returns an s24_status.  Arguments are validated on
+ * the host before anything is launched, so a failing call has no effect on
+ * device memory.  Nothing throws or aborts.  Inputs are assumed finite.
+ *
+ * Data formats
+ *   block mask   uint16 per aligned 4x4 block, mask[(r/4)][(q/4)], bit (4i+j) =
+ *                m_ij (i = row, j = column inside the block).
+ *   pattern id   the 90 legal blocks (two ones in every row and column) are
+ *                numbered in lexicographic order of the 16-character row-major
+ *                string m00 m01 ... m33 with '0' < '1'.
+ *   compressed   for a matrix A (R x K) that keeps exactly two of every four
+ *                consecutive elements along K:  vals[R][K/2] holds the kept
+ *                elements in order (bit copies), and meta[R][K/16] holds one
+ *                uint16 per 16 columns: group g (columns 4g..4g+3) contributes
+ *                the nibble  i0 | i1 << 2  (i0 < i1 the kept column offsets) at
+ *                bits 4*(g mod 4) of word g/4.
+ *   dtypes       S24_BF16 buffers hold raw bfloat16; S24_F32 buffers hold float.
+ */
+#ifndef S24_H
+#define S24_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    S24_OK = 0,
+    S24_ERR_NULL = -1,        /* a required pointer is NULL */
+    S24_ERR_SHAPE = -2,       /* a size is negative or not a multiple of what the call needs */
+    S24_ERR_DTYPE = -3,       /* unknown dtype / activation enum */
+    S24_ERR_ALIGN = -4,       /* a pointer or leading dimension breaks the 16-byte alignment rule */
+    S24_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch */
+    S24_ERR_UNSUPPORTED = -6  /* valid request that this build does not implement */
+} s24_status;
+
+typedef enum { S24_F32 = 0, S24_BF16 = 1 } s24_dtype;
+typedef enum { S24_ACT_RELU = 0, S24_ACT_GELU_ERF = 1 } s24_act;
+
+#define S24_NUM_PATTERNS 90
+
+/* Text for a status code (host, static storage). */
+const char *s24_strerror(int status);
+
+/* The 90 legal block masks in pattern-id order (Sec. 5.1, step 1: the mask
+ * blocks found by exhaustive inspection, n_t = 90).  `out` is a HOST array. */
+int s24_pattern_table(uint16_t out[S24_NUM_PATTERNS]);
+
+/* Transposable mask search (Sec. 5.1 problem formulation; Alg. 1).
+ * For every aligned 4x4 block of W picks, among the 90 legal patterns, the one
+ * that keeps the largest sum of |w|; scores are compared exactly and ties go
+ * to the smallest pattern id.
+ *   W      [r][ldw] device, dtype dt, ldw >= q elements
+ *   mask   [r/4][q/4] device, out
+ *   index  [r/4][q/4] device, out, pattern ids; may be NULL
+ * r, q multiples of 4 (S24_ERR_SHAPE otherwise); W and ldw*elemsize 8-byte
+ * aligned for bf16, 16-byte for f32 (S24_ERR_ALIGN). */
+int s24_transposable_mask(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
+                          uint16_t *mask, uint8_t *index, void *stream);
+
+/* Prune and compress (Sec. 5 item 1 "enforcing the mask"; the sparse_W and
+ * sparse_W_T operands of the App. B workflow).  Emits the compressed form of
+ * M.*W along q (vals, meta) and of (M.*W)^T along r (valsT, metaT).
+ *   mask      [r/4][q/4] device, in; NULL = search the mask in the same pass
+ *   vals      [r][q/2]  meta  [r][q/16]
+ *   valsT     [q][r/2]  metaT [q][r/16]
+ *   mask_out  [r/4][q/4] device, out, may be NULL (only used when mask == NULL)
+ * r, q multiples of 16.  A given mask must be legal (two kept per row and
+ * column of each block); an illegal mask gives unspecified values but no fault. */
+int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
+                 const uint16_t *mask, void *vals, uint16_t *meta, void *valsT, uint16_t *metaT,
+                 uint16_t *mask_out, void *stream);
+
+/* Forward sparse GEMM (Eq. 2):  Y[p][r] = X[p][q] . (M.*W)^T, contraction over
+ * q against the compressed weight (vals [r][q/2], meta [r][q/16]).
+ * bf16 in / fp32 accumulate / bf16 out (f32 throughout for S24_F32).
+ * p >= 1; q multiple of 64; r multiple of 16. */
+int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y,
+                 int64_t p, int64_t q, int64_t r, s24_dtype dt, void *stream);
+
+/* Backward sparse GEMM for the input gradient (Eq. 3):
+ * dX[p][q] = beta*dX + dY[p][r] . (M.*W), contraction over r against the
+ * compressed transpose (valsT [q][r/2], metaT [q][r/16]); legal because the
+ * mask is transposable (Eq. 5).  beta is 0 or 1 (1 sums the gate and up
+ * branches of a gated FFN).  r multiple of 64; q multiple of 16. */
+int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, void *dX,
+                    int64_t p, int64_t q, int64_t r, float beta, s24_dtype dt, void *stream);
+
+/* Dense weight gradient (Eq. 1, third GEMM; straight-through estimator):
+ * dW[r][q] = beta*dW + dY[p][r]^T . X[p][q], fp32 output, beta 0 or 1
+ * (1 accumulates over micro-batches).  q, r multiples of 16. */
+int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q, int64_t r,
+                 float beta, s24_dtype dt, void *stream);
+
+/* Dense comparison GEMM (Eq. 1, first GEMM): Y[p][r] = X[p][q] . W[r][q]^T,
+ * same tiling family as the sparse kernels.  q multiple of 32; r of 16. */
+int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r,
+                   s24_dtype dt, void *stream);
+
+/* Masked decay on gradients (Eq. 10), in place:
+ * G[r][q] (fp32) += lambda * W on the cells the mask prunes; kept cells are
+ * left bit-identical.  W has dtype wdt; mask is [r/4][q/4].  q multiple of 16. */
+int s24_masked_decay_grad(float *G, const void *W, s24_dtype wdt, const uint16_t *mask,
+                          float lambda, int64_t r, int64_t q, void *stream);
+
+/* Gated activation (Sec. 5.2, with SiLU in place of GELU and no biases):
+ * H[p][f] = silu(G) .* U, the gate G being the first operand (Z_1).  G and U
+ * are p x f with row stride ld_gu elements (so they may be the two halves of
+ * one [p][2f] buffer); H is dense.  f, ld_gu multiples of 8. */
+int s24_swiglu_fwd(const void *G, const void *U, void *H, int64_t p, int64_t f, int64_t ld_gu,
+                   s24_dtype dt, void *stream);
+
+/* Backward of the gated activation: dG = dH .* U .* silu'(G), dU = dH .* silu(G),
+ * silu'(x) = s(x)(1 + x(1 - s(x))).  dH is dense p x f; dG, dU are written
+ * with row stride ld_gu like G and U. */
+int s24_swiglu_bwd(const void *dH, const void *G, const void *U, void *dG, void *dU,
+                   int64_t p, int64_t f, int64_t ld_gu, s24_dtype dt, void *stream);
+
+/* Ungated activations of the smaller workloads: H = act(Z), n elements.
+ * GELU is the erf form.  n multiple of 8. */
+int s24_act_fwd(const void *Z, void *H, int64_t n, s24_act act, s24_dtype dt, void *stream);
+
+/* dZ = dH .* act'(Z); relu'(0) = 0; gelu'(z) = Phi(z) + z phi(z). */
+int s24_act_bwd(const void *dH, const void *Z, void *dZ, int64_t n, s24_act act, s24_dtype dt,
+                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S24_H */

@@ -1,0 +1,13 @@
+"""s24: the 2:4-sparse FFN training step of arXiv 2404.01847 for AMD MI355X.
+
+The product is the C-ABI library libs24.so (include/s24.h); this package is a
+thin ctypes binding with the same names.  Importing it loads nothing: the
+library is opened on first use and a missing library is an error, never a
+fallback.
+"""
+from .binding import (  # noqa: F401
+    S24Error, lib, lib_path, strerror, pattern_table,
+    transposable_mask, compress, spmm_fwd, spmm_bwd_dx, dense_dw, dense_gemm,
+    masked_decay_grad, swiglu_fwd, swiglu_bwd, act_fwd, act_bwd,
+    F32, BF16, ACT_RELU, ACT_GELU_ERF,
+)

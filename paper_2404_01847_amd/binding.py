@@ -1,0 +1,168 @@
+"""ctypes binding of libs24.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (bf16 data as
+torch.bfloat16, masks/metadata as int16/uint16 views, pattern ids as uint8),
+passes their data pointers and the current HIP stream to the C entry point of
+the same name, and raises S24Error on a non-zero status.  Nothing is computed
+here and nothing falls back to PyTorch.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+F32, BF16 = 0, 1
+ACT_RELU, ACT_GELU_ERF = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libs24.so")
+_lib = None
+
+_i64, _vp, _int, _f32 = C.c_int64, C.c_void_p, C.c_int, C.c_float
+_SIGNATURES = {
+    "s24_strerror": (C.c_char_p, [_int]),
+    "s24_pattern_table": (_int, [_vp]),
+    "s24_transposable_mask": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp]),
+    "s24_compress": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "s24_spmm_fwd": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "s24_spmm_bwd_dx": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
+    "s24_dense_dw": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
+    "s24_dense_gemm": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "s24_masked_decay_grad": (_int, [_vp, _vp, _int, _vp, _f32, _i64, _i64, _vp]),
+    "s24_swiglu_fwd": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "s24_swiglu_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "s24_act_fwd": (_int, [_vp, _vp, _i64, _int, _int, _vp]),
+    "s24_act_bwd": (_int, [_vp, _vp, _vp, _i64, _int, _int, _vp]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+class S24Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library.  Raises if libs24.so has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2404_01847_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        handle = C.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().s24_strerror(status).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise S24Error(status, where)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"s24 supports float32 and bfloat16 tensors, got {t.dtype}")
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def pattern_table():
+    out = (C.c_uint16 * 90)()
+    _check(lib().s24_pattern_table(C.cast(out, C.c_void_p)), "s24_pattern_table")
+    return list(out)
+
+
+def transposable_mask(W, mask, index=None):
+    r, q = W.shape
+    _check(lib().s24_transposable_mask(_ptr(W), _dt(W), r, q, W.stride(0), _ptr(mask), _ptr(index), _stream()),
+           "s24_transposable_mask")
+    return mask
+
+
+def compress(W, mask, vals, meta, valsT, metaT, mask_out=None):
+    r, q = W.shape
+    _check(lib().s24_compress(_ptr(W), _dt(W), r, q, W.stride(0), _ptr(mask), _ptr(vals), _ptr(meta), _ptr(valsT),
+                              _ptr(metaT), _ptr(mask_out), _stream()), "s24_compress")
+
+
+def spmm_fwd(X, vals, meta, Y):
+    p, q = X.shape
+    r = vals.shape[0]
+    _check(lib().s24_spmm_fwd(_ptr(X), _ptr(vals), _ptr(meta), _ptr(Y), p, q, r, _dt(X), _stream()), "s24_spmm_fwd")
+    return Y
+
+
+def spmm_bwd_dx(dY, valsT, metaT, dX, beta=0.0):
+    p, r = dY.shape
+    q = valsT.shape[0]
+    _check(lib().s24_spmm_bwd_dx(_ptr(dY), _ptr(valsT), _ptr(metaT), _ptr(dX), p, q, r, beta, _dt(dY), _stream()),
+           "s24_spmm_bwd_dx")
+    return dX
+
+
+def dense_dw(dY, X, dW, beta=0.0):
+    p, r = dY.shape
+    q = X.shape[1]
+    _check(lib().s24_dense_dw(_ptr(dY), _ptr(X), _ptr(dW), p, q, r, beta, _dt(X), _stream()), "s24_dense_dw")
+    return dW
+
+
+def dense_gemm(X, W, Y):
+    p, q = X.shape
+    r = W.shape[0]
+    _check(lib().s24_dense_gemm(_ptr(X), _ptr(W), _ptr(Y), p, q, r, _dt(X), _stream()), "s24_dense_gemm")
+    return Y
+
+
+def masked_decay_grad(G, W, mask, lam):
+    r, q = W.shape
+    _check(lib().s24_masked_decay_grad(_ptr(G), _ptr(W), _dt(W), _ptr(mask), lam, r, q, _stream()),
+           "s24_masked_decay_grad")
+    return G
+
+
+def swiglu_fwd(G, U, H):
+    p, f = G.shape
+    _check(lib().s24_swiglu_fwd(_ptr(G), _ptr(U), _ptr(H), p, f, G.stride(0), _dt(G), _stream()), "s24_swiglu_fwd")
+    return H
+
+
+def swiglu_bwd(dH, G, U, dG, dU):
+    p, f = G.shape
+    _check(lib().s24_swiglu_bwd(_ptr(dH), _ptr(G), _ptr(U), _ptr(dG), _ptr(dU), p, f, G.stride(0), _dt(G), _stream()),
+           "s24_swiglu_bwd")
+    return dG, dU
+
+
+def act_fwd(Z, H, act):
+    _check(lib().s24_act_fwd(_ptr(Z), _ptr(H), Z.numel(), act, _dt(Z), _stream()), "s24_act_fwd")
+    return H
+
+
+def act_bwd(dH, Z, dZ, act):
+    _check(lib().s24_act_bwd(_ptr(dH), _ptr(Z), _ptr(dZ), Z.numel(), act, _dt(Z), _stream()), "s24_act_bwd")
+    return dZ

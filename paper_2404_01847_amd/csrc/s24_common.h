@@ -1,0 +1,34 @@
+// Shared host/device helpers of the s24 library (argument checks, launch
+// plumbing, bf16 conversions).  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "s24.h"
+
+#define S24_REQUIRE(cond, code) \
+    do {                        \
+        if (!(cond)) return (code); \
+    } while (0)
+
+static inline bool s24_aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+static inline bool s24_valid_dtype(int dt) { return dt == S24_F32 || dt == S24_BF16; }
+static inline size_t s24_elem_size(int dt) { return dt == S24_F32 ? 4 : 2; }
+
+// Call after a kernel launch: turns a refused launch into S24_ERR_LAUNCH.
+static inline int s24_launch_status() { return hipGetLastError() == hipSuccess ? S24_OK : S24_ERR_LAUNCH; }
+
+__device__ __forceinline__ float s24_bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// fp32 -> bf16, round to nearest even (inputs are finite).
+__device__ __forceinline__ uint32_t s24_f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ uint32_t s24_pack_bf16x2(float lo, float hi)
+{
+    return s24_f32_to_bf16(lo) | (s24_f32_to_bf16(hi) << 16);
+}

@@ -1,0 +1,466 @@
+// GEMMs of the 2:4-sparse FFN step on gfx950 matrix cores.
+//
+//   sparse NT  out[n][m] = sum_k B[n][k] * A[m][k], A 2:4-compressed along k
+//              (Eq. 2 with A = W, Eq. 3 with A = W^T): v_smfmac_f32_32x32x32_bf16
+//   dense  NT  Y = X W^T (Eq. 1, first GEMM): v_mfma_f32_32x32x16_bf16
+//   dense  TN  dW = dY^T X (Eq. 1, third GEMM): same MFMA after an in-register
+//              8x8 transpose of both operands on their way into LDS
+//
+// Register layout of the sparse instruction (one 32x32 tile, 32 of k):
+// lane l holds for A row l%32 the eight kept values of k in [16*(l/32),
+// 16*(l/32)+16) in order, with their 2-bit positions in bits [2j+1:2j] of the
+// index register half chosen by ABID; for B column l%32, element j holds
+// k = 16*(j/8) + 8*(l/32) + j%8; accumulator i holds row 8*(i/4)+4*(l/32)+i%4
+// of column l%32.  The canonical metadata word (one uint16 per 16 of k) is
+// exactly one lane's index half, so compressed weights feed the instruction
+// straight from global memory and only the dense operand goes through LDS.
+#include "s24_common.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BM = 128, BN = 128, BK = 64;  // workgroup tile; BK in elements of k
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x16 as_bf16x16(uint4 lo, uint4 hi)
+{
+    struct { uint4 a, b; } t{lo, hi};
+    return __builtin_bit_cast(bf16x16, t);
+}
+
+// LDS tile of a k-contiguous operand: rows of 64 bf16 (128 bytes = 8 chunks of
+// 16 bytes); chunk c of row r sits at chunk position c ^ ((r ^ r>>3) & 7), which
+// keeps 16-byte accesses to one chunk column free of bank conflicts both over
+// consecutive rows (MFMA operand reads) and over rows 8 apart (transposed stores).
+__device__ __forceinline__ int lds_off(int row, int chunk)
+{
+    return row * 128 + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 4);
+}
+__device__ __forceinline__ uint4 lds_read(const unsigned char *buf, int row, int chunk)
+{
+    return *reinterpret_cast<const uint4 *>(buf + lds_off(row, chunk));
+}
+
+// Copy a [rows x 64] bf16 tile (row stride ld elements) from global memory into
+// registers: 1024 chunks of 16 bytes, four per thread.  Rows >= nrows read as zero.
+struct TileRegs { uint4 v[4]; };
+__device__ __forceinline__ void tile_load(TileRegs &t, const uint16_t *g, int64_t ld, int row0, int nrows, int k0, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + kThreads * i, row = id >> 3, c = id & 7;
+        if (row0 + row < nrows) t.v[i] = *reinterpret_cast<const uint4 *>(g + (int64_t)(row0 + row) * ld + k0 + 8 * c);
+        else t.v[i] = make_uint4(0, 0, 0, 0);
+    }
+}
+__device__ __forceinline__ void tile_store(const TileRegs &t, unsigned char *buf, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + kThreads * i, row = id >> 3, c = id & 7;
+        *reinterpret_cast<uint4 *>(buf + lds_off(row, c)) = t.v[i];
+    }
+}
+
+// ------------------------------------------------------------------ sparse NT
+struct SparseA { uint4 v[2][2]; uint32_t idx[2]; };  // per m-fragment: 32 bytes of values, one index dword
+
+__device__ __forceinline__ void sparse_a_load(SparseA &a, const uint16_t *Av, const uint16_t *Am, int K, int M, int mrow0,
+                                              int k0, int lane)
+{
+    const int ga = lane >> 5;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+        const int row = min(mrow0 + 32 * mi + (lane & 31), M - 1);
+        const uint4 *pv = reinterpret_cast<const uint4 *>(Av + (int64_t)row * (K / 2) + k0 / 2 + 16 * ga);
+        a.v[mi][0] = pv[0];
+        a.v[mi][1] = pv[1];
+        a.idx[mi] = reinterpret_cast<const uint32_t *>(Am + (int64_t)row * (K / 16) + k0 / 16)[ga];
+    }
+}
+
+template <bool ACCUM>
+__global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__restrict__ B, const uint16_t *__restrict__ Av,
+                                                           const uint16_t *__restrict__ Am, uint16_t *__restrict__ Out,
+                                                           int N, int K, int M)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][BN * 128];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int nk = K / BK;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+
+    SparseA a_cur, a_nxt;
+    TileRegs breg;
+    sparse_a_load(a_cur, Av, Am, K, M, m0 + 64 * wm, 0, lane);
+    tile_load(breg, B, K, n0, N, 0, tid);
+    tile_store(breg, s_b[0], tid);
+    __syncthreads();
+
+    for (int kc = 0; kc < nk; ++kc) {
+        const bool more = kc + 1 < nk;
+        if (more) {
+            tile_load(breg, B, K, n0, N, (kc + 1) * BK, tid);
+            sparse_a_load(a_nxt, Av, Am, K, M, m0 + 64 * wm, (kc + 1) * BK, lane);
+        }
+        const unsigned char *buf = s_b[kc & 1];
+        const int gb = lane >> 5;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int row = 64 * wn + 32 * ni + (lane & 31);
+            const bf16x16 b0 = as_bf16x16(lds_read(buf, row, gb), lds_read(buf, row, 4 + gb));
+            const bf16x16 b1 = as_bf16x16(lds_read(buf, row, 2 + gb), lds_read(buf, row, 6 + gb));
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(as_bf16x8(a_cur.v[mi][0]), b0, acc[mi][ni],
+                                                                        (int)a_cur.idx[mi], 0, 0);
+                acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(as_bf16x8(a_cur.v[mi][1]), b1, acc[mi][ni],
+                                                                        (int)a_cur.idx[mi], 0, 1);
+            }
+        }
+        if (more) tile_store(breg, s_b[(kc + 1) & 1], tid);
+        __syncthreads();
+        if (more) a_cur = a_nxt;
+    }
+
+    // epilogue: accumulator i of lane l is out[n][m] with n = l%32, m = 8*(i/4) + 4*(l/32) + i%4
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+        if (n >= N) continue;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int m = m0 + 64 * wm + 32 * mi + 8 * g + 4 * (lane >> 5);
+                if (m >= M) continue;  // M is a multiple of 16, so groups of four are all in or all out
+                uint2 *dst = reinterpret_cast<uint2 *>(Out + (int64_t)n * M + m);
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][4 * g + e];
+                if (ACCUM) {
+                    const uint2 old = *dst;
+                    v[0] += s24_bf16_to_f32(old.x & 0xFFFFu);
+                    v[1] += s24_bf16_to_f32(old.x >> 16);
+                    v[2] += s24_bf16_to_f32(old.y & 0xFFFFu);
+                    v[3] += s24_bf16_to_f32(old.y >> 16);
+                }
+                *dst = make_uint2(s24_pack_bf16x2(v[0], v[1]), s24_pack_bf16x2(v[2], v[3]));
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ dense MFMA core
+// Both operands in LDS as k-contiguous swizzled tiles.  MFMA step i of a lane
+// with k-group g = lane/32 uses chunk 4*g + i of its row, i.e. k in
+// [32*g + 8*i, 32*g + 8*i + 8) of the 64-wide chunk, for A and B alike.
+__device__ __forceinline__ void dense_chunk(f32x16 (&acc)[2][2], const unsigned char *sa, const unsigned char *sb, int wm,
+                                            int wn, int lane)
+{
+    const int g = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        bf16x8 a[2], b[2];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) a[mi] = as_bf16x8(lds_read(sa, 64 * wm + 32 * mi + (lane & 31), 4 * g + i));
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) b[ni] = as_bf16x8(lds_read(sb, 64 * wn + 32 * ni + (lane & 31), 4 * g + i));
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+    }
+}
+
+// Y[n][m] = sum_k X[n][k] W[m][k]  (n tokens, m out-features)
+__global__ __launch_bounds__(kThreads) void dense_nt_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W,
+                                                            uint16_t *__restrict__ Y, int N, int K, int M)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char s_a[2][BM * 128];
+    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][BN * 128];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int nk = K / BK;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+    TileRegs ra, rb;
+    tile_load(ra, W, K, m0, M, 0, tid);
+    tile_load(rb, X, K, n0, N, 0, tid);
+    tile_store(ra, s_a[0], tid);
+    tile_store(rb, s_b[0], tid);
+    __syncthreads();
+    for (int kc = 0; kc < nk; ++kc) {
+        const bool more = kc + 1 < nk;
+        if (more) {
+            tile_load(ra, W, K, m0, M, (kc + 1) * BK, tid);
+            tile_load(rb, X, K, n0, N, (kc + 1) * BK, tid);
+        }
+        dense_chunk(acc, s_a[kc & 1], s_b[kc & 1], wm, wn, lane);
+        if (more) {
+            tile_store(ra, s_a[(kc + 1) & 1], tid);
+            tile_store(rb, s_b[(kc + 1) & 1], tid);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+        if (n >= N) continue;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int m = m0 + 64 * wm + 32 * mi + 8 * g + 4 * (lane >> 5);
+                if (m >= M) continue;
+                *reinterpret_cast<uint2 *>(Y + (int64_t)n * M + m) =
+                    make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1]),
+                               s24_pack_bf16x2(acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]));
+            }
+    }
+}
+
+// ------------------------------------------------------------------ dense TN (dW)
+// dW[m][n] = sum_t dY[t][m] X[t][n].  Both operands are contiguous along the
+// output axis, not along t, so each thread loads an 8(t) x 8 sub-block (eight
+// 16-byte rows), transposes it in registers and writes eight 16-byte rows of
+// 8 consecutive t into the swizzled LDS tile.  Threads 0..127 stage the dY tile
+// (64 t x 128 m), threads 128..255 the X tile (64 t x 128 n).
+struct Sub8 { uint4 r[8]; };
+
+__device__ __forceinline__ void sub8_load(Sub8 &s, const uint16_t *g, int64_t ld, int t0, int T, int col, int ncols)
+{
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (t0 + k < T && col < ncols) s.r[k] = *reinterpret_cast<const uint4 *>(g + (int64_t)(t0 + k) * ld + col);
+        else s.r[k] = make_uint4(0, 0, 0, 0);
+    }
+}
+
+// in: r[k] = eight bf16 (columns c..c+7) of row t0+k.  out: o[c] = eight bf16 (t0..t0+7) of column c.
+__device__ __forceinline__ void sub8_transpose_store(const Sub8 &s, unsigned char *buf, int col_local, int tchunk)
+{
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(&s.r[0]);  // w[4*k + d] = columns (2d, 2d+1) of row k
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        uint32_t o[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const uint32_t lo = w[4 * (2 * kk) + c / 2], hi = w[4 * (2 * kk + 1) + c / 2];
+            o[kk] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+        *reinterpret_cast<uint4 *>(buf + lds_off(col_local + c, tchunk)) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+template <bool ACCUM>
+__global__ __launch_bounds__(kThreads) void dense_tn_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ X,
+                                                            float *__restrict__ dW, int T, int M, int N)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char s_a[2][BM * 128];
+    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][BN * 128];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int nk = (T + BK - 1) / BK;
+    // staging role of this thread
+    const bool is_a = tid < 128;
+    const int sid = tid & 127;
+    const int scol = (sid & 15) * 8, stc = sid >> 4;  // 16 column groups x 8 t-chunks
+    const uint16_t *src = is_a ? dY : X;
+    const int64_t ld = is_a ? M : N;
+    const int gcol = (is_a ? m0 : n0) + scol, ncols = is_a ? M : N;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+    Sub8 sub;
+    sub8_load(sub, src, ld, 8 * stc, T, gcol, ncols);
+    sub8_transpose_store(sub, is_a ? s_a[0] : s_b[0], scol, stc);
+    __syncthreads();
+    for (int kc = 0; kc < nk; ++kc) {
+        const bool more = kc + 1 < nk;
+        if (more) sub8_load(sub, src, ld, (kc + 1) * BK + 8 * stc, T, gcol, ncols);
+        dense_chunk(acc, s_a[kc & 1], s_b[kc & 1], wm, wn, lane);
+        if (more) sub8_transpose_store(sub, is_a ? s_a[(kc + 1) & 1] : s_b[(kc + 1) & 1], scol, stc);
+        __syncthreads();
+    }
+    // accumulator i of lane l: column n = l%32, rows m = 8*(i/4) + 4*(l/32) + i%4
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+        if (n >= N) continue;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = m0 + 64 * wm + 32 * mi + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                if (m >= M) continue;
+                float *dst = dW + (int64_t)m * N + n;
+                *dst = ACCUM ? (*dst + acc[mi][ni][i]) : acc[mi][ni][i];
+            }
+    }
+}
+
+// ------------------------------------------------------------------ fp32 fallbacks (small correctness workload)
+// One thread per output element, plain fp32 FMA; no matrix-core claim.
+template <bool ACCUM>
+__global__ __launch_bounds__(kThreads) void spmm_nt_f32_kernel(const float *__restrict__ B, const float *__restrict__ Av,
+                                                               const uint16_t *__restrict__ Am, float *__restrict__ Out,
+                                                               int64_t N, int64_t K, int64_t M)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= N * M) return;
+    const int64_t n = idx / M, m = idx - n * M;
+    float acc = 0.0f;
+    for (int64_t g = 0; g < K / 4; ++g) {
+        const unsigned nib = (Am[m * (K / 16) + g / 4] >> (4 * (g & 3))) & 0xFu;
+        acc = fmaf(Av[m * (K / 2) + 2 * g], B[n * K + 4 * g + (nib & 3u)], acc);
+        acc = fmaf(Av[m * (K / 2) + 2 * g + 1], B[n * K + 4 * g + (nib >> 2)], acc);
+    }
+    Out[idx] = ACCUM ? Out[idx] + acc : acc;
+}
+
+__global__ __launch_bounds__(kThreads) void dense_nt_f32_kernel(const float *__restrict__ X, const float *__restrict__ W,
+                                                                float *__restrict__ Y, int64_t N, int64_t K, int64_t M)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= N * M) return;
+    const int64_t n = idx / M, m = idx - n * M;
+    float acc = 0.0f;
+    for (int64_t k = 0; k < K; ++k) acc = fmaf(X[n * K + k], W[m * K + k], acc);
+    Y[idx] = acc;
+}
+
+template <bool ACCUM>
+__global__ __launch_bounds__(kThreads) void dense_tn_f32_kernel(const float *__restrict__ dY, const float *__restrict__ X,
+                                                                float *__restrict__ dW, int64_t T, int64_t M, int64_t N)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= M * N) return;
+    const int64_t m = idx / N, n = idx - m * N;
+    float acc = 0.0f;
+    for (int64_t t = 0; t < T; ++t) acc = fmaf(dY[t * M + m], X[t * N + n], acc);
+    dW[idx] = ACCUM ? dW[idx] + acc : acc;
+}
+
+inline unsigned ceil_div(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
+
+// dtype and sizes first; pointers are only required when the output is not empty.
+int check_gemm(const void *a, const void *b, const void *c, int64_t p, int64_t q, int64_t r, int dt, int64_t out_elems)
+{
+    S24_REQUIRE(s24_valid_dtype(dt), S24_ERR_DTYPE);
+    S24_REQUIRE(p >= 0 && q >= 0 && r >= 0, S24_ERR_SHAPE);
+    S24_REQUIRE(p < (1ll << 31) && q < (1ll << 31) && r < (1ll << 31), S24_ERR_SHAPE);
+    if (out_elems == 0) return S24_OK;
+    S24_REQUIRE(a && b && c, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(a, 16) && s24_aligned(b, 16) && s24_aligned(c, 16), S24_ERR_ALIGN);
+    return S24_OK;
+}
+
+int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, int64_t N, int64_t K, int64_t M, float beta,
+                int dt, hipStream_t st)
+{
+    if (N == 0 || M == 0) return S24_OK;
+    const bool accum = beta != 0.0f;
+    if (dt == S24_BF16) {
+        const dim3 grid(ceil_div(M, BM), ceil_div(N, BN)), block(kThreads);
+        S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
+        auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av);
+        auto *o = static_cast<uint16_t *>(Out);
+        if (accum) hipLaunchKernelGGL(spmm_nt_kernel<true>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M);
+        else hipLaunchKernelGGL(spmm_nt_kernel<false>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M);
+    } else {
+        const dim3 grid(ceil_div(N * M, kThreads)), block(kThreads);
+        auto *b = static_cast<const float *>(B), *av = static_cast<const float *>(Av);
+        auto *o = static_cast<float *>(Out);
+        if (accum) hipLaunchKernelGGL(spmm_nt_f32_kernel<true>, grid, block, 0, st, b, av, Am, o, N, K, M);
+        else hipLaunchKernelGGL(spmm_nt_f32_kernel<false>, grid, block, 0, st, b, av, Am, o, N, K, M);
+    }
+    return s24_launch_status();
+}
+
+}  // namespace
+
+extern "C" int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y, int64_t p, int64_t q, int64_t r,
+                            s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(q % 64 == 0 && r % 16 == 0 && q > 0, S24_ERR_SHAPE);
+    const int rc = check_gemm(X, vals, Y, p, q, r, dt, p * r);
+    if (rc != S24_OK || p * r == 0) return rc;
+    S24_REQUIRE(meta != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(meta, 4), S24_ERR_ALIGN);
+    return launch_spmm(X, vals, meta, Y, p, q, r, 0.0f, dt, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, void *dX, int64_t p, int64_t q,
+                               int64_t r, float beta, s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(r % 64 == 0 && q % 16 == 0 && r > 0, S24_ERR_SHAPE);
+    S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
+    const int rc = check_gemm(dY, valsT, dX, p, q, r, dt, p * q);
+    if (rc != S24_OK || p * q == 0) return rc;
+    S24_REQUIRE(metaT != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(metaT, 4), S24_ERR_ALIGN);
+    return launch_spmm(dY, valsT, metaT, dX, p, r, q, beta, dt, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r, s24_dtype dt,
+                              void *stream)
+{
+    S24_REQUIRE(q % 64 == 0 && r % 16 == 0 && q > 0, S24_ERR_SHAPE);
+    const int rc = check_gemm(X, W, Y, p, q, r, dt, p * r);
+    if (rc != S24_OK || p * r == 0) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == S24_BF16) {
+        const dim3 grid(ceil_div(r, BM), ceil_div(p, BN)), block(kThreads);
+        S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
+        hipLaunchKernelGGL(dense_nt_kernel, grid, block, 0, st, static_cast<const uint16_t *>(X),
+                           static_cast<const uint16_t *>(W), static_cast<uint16_t *>(Y), (int)p, (int)q, (int)r);
+    } else {
+        hipLaunchKernelGGL(dense_nt_f32_kernel, dim3(ceil_div(p * r, kThreads)), dim3(kThreads), 0, st,
+                           static_cast<const float *>(X), static_cast<const float *>(W), static_cast<float *>(Y), p, q, r);
+    }
+    return s24_launch_status();
+}
+
+extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q, int64_t r, float beta,
+                            s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(q % 16 == 0 && r % 16 == 0, S24_ERR_SHAPE);
+    S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
+    const int rc = check_gemm(dY, X, dW, p, q, r, dt, q * r);
+    if (rc != S24_OK || q * r == 0) return rc;
+    const bool accum = beta != 0.0f;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == S24_BF16) {
+        const dim3 grid(ceil_div(r, BM), ceil_div(q, BN)), block(kThreads);
+        S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
+        auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
+        if (accum) hipLaunchKernelGGL(dense_tn_kernel<true>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q);
+        else hipLaunchKernelGGL(dense_tn_kernel<false>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q);
+    } else {
+        const dim3 grid(ceil_div(r * q, kThreads)), block(kThreads);
+        auto *a = static_cast<const float *>(dY), *b = static_cast<const float *>(X);
+        if (accum) hipLaunchKernelGGL(dense_tn_f32_kernel<true>, grid, block, 0, st, a, b, dW, p, r, q);
+        else hipLaunchKernelGGL(dense_tn_f32_kernel<false>, grid, block, 0, st, a, b, dW, p, r, q);
+    }
+    return s24_launch_status();
+}

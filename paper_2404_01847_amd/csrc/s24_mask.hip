@@ -1,0 +1,459 @@
+// Transposable 2:4 mask search and prune/compress (Sec. 5.1 and Sec. 5 item 1).
+//
+// One lane owns one aligned 4x4 block.  A workgroup of 256 lanes walks a tile
+// of 32 x 32 blocks (128 x 128 weights), four blocks per lane, so that both
+// the row-wise compressed operand and, through an LDS transpose, the
+// column-wise one are written in runs of 128 bytes or more.
+//
+// Scoring.  A legal block is a choice of one of six column pairs per row
+// whose columns each get picked twice.  Rows 0-1 and rows 2-3 are scored
+// separately ("top" and "bottom" halves) and matched through the column-count
+// vector of the top half, which leaves 19 classes:
+//   6  where both top rows use the same pair (bottom rows both use its
+//      complement),
+//   1  where the top rows use complementary pairs (so do the bottom rows),
+//   12 where the top rows share exactly one column x and miss one column w.
+// That is 24 + 72 + 19 additions and 53 maxima per block instead of 90 x 7
+// additions, and yields the same maximum because every legal block falls in
+// exactly one class.
+//
+// Exactness and tie-break.  Scores are held in fp64.  Let 2^(E+1) bound the
+// largest magnitude of the block and eps = 2^(E-47).  If every nonzero
+// magnitude is a multiple of 2048*eps, all partial sums are integers times
+// eps below 2^52*eps, hence exact.  Each cell (i,j) is first increased by
+// beta_j * 6^(3-i) * eps with beta = (0,2,3,4): the total added to a pattern
+// is below 2048*eps, cannot reorder different true scores, and orders equal
+// scores exactly like the pattern ids (smaller id = larger bonus).  The bonus
+// is read back from the low 11 bits of (best + 2^52*eps) and indexes a table
+// that returns the block mask and id.  Blocks whose magnitudes span more
+// binades than that window take a slow path that scores all 90 patterns in
+// 320-bit fixed point.
+#include "s24_common.h"
+
+namespace {
+
+// Column pairs in row-string order ("0011" < "0101" < ... < "1100"): pair k
+// keeps columns kC1[k] < kC2[k]; the complementary pair is 5 - k.
+__host__ __device__ constexpr int pair_c1(int k) { return k == 0 ? 2 : (k <= 2 ? 1 : 0); }
+__host__ __device__ constexpr int pair_c2(int k) { return (k == 0 || k == 1 || k == 3) ? 3 : ((k == 2 || k == 4) ? 2 : 1); }
+__host__ __device__ constexpr unsigned pair_bits(int k) { return (1u << pair_c1(k)) | (1u << pair_c2(k)); }
+__host__ __device__ constexpr int pair_of(int a, int b)
+{
+    const int lo = a < b ? a : b, hi = a < b ? b : a;
+    for (int k = 0; k < 6; ++k)
+        if (pair_c1(k) == lo && pair_c2(k) == hi) return k;
+    return -1;
+}
+
+constexpr int kRowMult[4] = {216, 36, 6, 1};
+constexpr int kColBonus[4] = {0, 2, 3, 4};
+constexpr int kBonusBase = 2 * (216 + 36 + 6 + 1);  // every row contributes at least 2
+
+struct MaskLut {
+    uint16_t mask[1296];
+    uint8_t id[1296];
+};
+
+// Index: sum_i 6^(3-i) * (5 - k_i) for row pair indices k_i.  Walking
+// (k0,k1,k2,k3) in ascending order visits the legal blocks in id order.
+constexpr MaskLut make_lut()
+{
+    MaskLut t{};
+    int n = 0;
+    for (int a = 0; a < 6; ++a)
+        for (int b = 0; b < 6; ++b)
+            for (int c = 0; c < 6; ++c)
+                for (int d = 0; d < 6; ++d) {
+                    const unsigned rows[4] = {pair_bits(a), pair_bits(b), pair_bits(c), pair_bits(d)};
+                    bool ok = true;
+                    for (int j = 0; j < 4; ++j) {
+                        int s = 0;
+                        for (int i = 0; i < 4; ++i) s += (rows[i] >> j) & 1u;
+                        if (s != 2) ok = false;
+                    }
+                    if (!ok) continue;
+                    const int x = 216 * (5 - a) + 36 * (5 - b) + 6 * (5 - c) + (5 - d);
+                    t.mask[x] = (uint16_t)(rows[0] | rows[1] << 4 | rows[2] << 8 | rows[3] << 12);
+                    t.id[x] = (uint8_t)n;
+                    ++n;
+                }
+    return t;
+}
+
+__device__ const MaskLut g_lut = make_lut();
+
+struct PatList {
+    uint16_t mask[S24_NUM_PATTERNS];
+};
+constexpr PatList make_patlist()
+{
+    PatList p{};
+    const MaskLut t = make_lut();
+    for (int x = 0; x < 1296; ++x)
+        if (t.mask[x] != 0) p.mask[t.id[x]] = t.mask[x];
+    return p;
+}
+__device__ const PatList g_patterns = make_patlist();
+
+// ---------------------------------------------------------------------------
+// Slow path: exact scores of all 90 patterns in fixed point.  A magnitude given
+// as an fp32 bit pattern is sig * 2^(shift-149) with sig < 2^24; a score is kept
+// as ten limbs of 32 payload bits (units of 2^-149), enough for eight fp32
+// magnitudes of any exponent.  First maximum in id order wins.
+// ---------------------------------------------------------------------------
+struct Mag16 { uint32_t v[16]; };
+
+__device__ __noinline__ unsigned slow_best_pattern(Mag16 mag)
+{
+    // Deliberately loop-based with locally indexed arrays: this path is rare, and
+    // keeping it small keeps the register budget of the common path.
+    uint32_t sig[16], limb[16], off[16];
+#pragma unroll 1
+    for (int t = 0; t < 16; ++t) {
+        const uint32_t e = mag.v[t] >> 23;
+        sig[t] = (mag.v[t] & 0x7FFFFFu) | (e ? 0x800000u : 0u);
+        const uint32_t shift = (e ? e : 1u) - 1u;
+        limb[t] = shift >> 5;
+        off[t] = shift & 31u;
+    }
+    uint32_t best[10];
+#pragma unroll 1
+    for (int L = 0; L < 10; ++L) best[L] = 0;
+    unsigned best_id = 0;
+#pragma unroll 1
+    for (unsigned k = 0; k < S24_NUM_PATTERNS; ++k) {
+        const unsigned pm = g_patterns.mask[k];
+        uint64_t acc[10];
+#pragma unroll 1
+        for (int L = 0; L < 10; ++L) acc[L] = 0;
+#pragma unroll 1
+        for (int t = 0; t < 16; ++t) {
+            if (!((pm >> t) & 1u)) continue;
+            const uint64_t v = (uint64_t)sig[t] << off[t];
+            acc[limb[t]] += (uint32_t)v;
+            acc[limb[t] + 1] += (uint32_t)(v >> 32);   // limb <= 7, so limb + 1 <= 8
+        }
+        uint32_t s[10];
+        uint64_t carry = 0;
+#pragma unroll 1
+        for (int L = 0; L < 10; ++L) {
+            const uint64_t x = acc[L] + carry;
+            s[L] = (uint32_t)x;
+            carry = x >> 32;
+        }
+        // lexicographic compare from the top limb: greater = strictly larger score
+        bool greater = false, decided = false;
+#pragma unroll 1
+        for (int L = 9; L >= 0; --L) {
+            if (!decided && s[L] != best[L]) {
+                greater = s[L] > best[L];
+                decided = true;
+            }
+        }
+        if (greater) {
+#pragma unroll 1
+            for (int L = 0; L < 10; ++L) best[L] = s[L];
+            best_id = k;
+        }
+    }
+    return (unsigned)g_patterns.mask[best_id] | (best_id << 16);
+}
+
+// ---------------------------------------------------------------------------
+// Fast path.  mag[4*i+j] = |w_ij| as fp32 bit patterns.  Returns mask | id<<16.
+// WINDOW = binades below the block maximum within which every element is a
+// multiple of 2048*eps (29 for bf16 data, 13 for fp32 data).
+// ---------------------------------------------------------------------------
+template <int WINDOW>
+__device__ __forceinline__ unsigned best_pattern(const uint32_t (&mag)[16], const uint16_t *lut_mask, const uint8_t *lut_id)
+{
+    uint32_t mx = 0, mn = 0xFFFFFFFFu;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        mx = max(mx, mag[t]);
+        mn = min(mn, mag[t] - 1u);  // zero wraps to the top and never wins
+    }
+    const uint32_t emax = max(mx >> 23, 1u);
+    const uint32_t emin = (mn == 0xFFFFFFFFu) ? 255u : max(mn >> 23, 1u);
+    if (emin + WINDOW < emax) {
+        Mag16 m16;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) m16.v[t] = mag[t];
+        return slow_best_pattern(m16);
+    }
+
+    const double eps = __hiloint2double((int)((emax + 849u) << 20), 0);       // 2^(E-47), E = emax-127
+    const double big = __hiloint2double((int)((emax + 849u + 52u) << 20), 0);  // 2^52 * eps
+    double a[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double v = (double)__uint_as_float(mag[4 * i + j]);
+            a[i][j] = (j == 0) ? v : __builtin_fma((double)(kColBonus[j] * kRowMult[i]), eps, v);
+        }
+    double rs[4][6];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int k = 0; k < 6; ++k) rs[i][k] = a[i][pair_c1(k)] + a[i][pair_c2(k)];
+
+    // both top rows on the same pair
+    double best = (rs[0][0] + rs[1][0]) + (rs[2][5] + rs[3][5]);
+#pragma unroll
+    for (int k = 1; k < 6; ++k) best = __builtin_fmax(best, (rs[0][k] + rs[1][k]) + (rs[2][5 - k] + rs[3][5 - k]));
+    // top rows complementary
+    {
+        double t = rs[0][0] + rs[1][5], b = rs[2][0] + rs[3][5];
+#pragma unroll
+        for (int k = 1; k < 6; ++k) {
+            t = __builtin_fmax(t, rs[0][k] + rs[1][5 - k]);
+            b = __builtin_fmax(b, rs[2][k] + rs[3][5 - k]);
+        }
+        best = __builtin_fmax(best, t + b);
+    }
+    // top rows share column x and leave column w empty
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w == x) continue;
+            int y = -1, z = -1;
+            for (int c = 0; c < 4; ++c)
+                if (c != x && c != w) (y < 0 ? y : z) = c;
+            const int xy = pair_of(x, y), xz = pair_of(x, z), yw = pair_of(y, w), zw = pair_of(z, w);
+            const double t = __builtin_fmax(rs[0][xy] + rs[1][xz], rs[0][xz] + rs[1][xy]);
+            const double b = __builtin_fmax(rs[2][yw] + rs[3][zw], rs[2][zw] + rs[3][yw]);
+            best = __builtin_fmax(best, t + b);
+        }
+    const unsigned bonus = (unsigned)__double2loint(best + big) & 0x7FFu;
+    const unsigned x = min(bonus - (unsigned)kBonusBase, 1295u);
+    return (unsigned)lut_mask[x] | ((unsigned)lut_id[x] << 16);
+}
+
+// ---------------------------------------------------------------------------
+// Per-dtype access to one block row (four consecutive weights).
+// ---------------------------------------------------------------------------
+template <typename T> struct RowOps;
+
+template <> struct RowOps<uint16_t> {  // bf16
+    using Row = uint2;     // four bf16
+    using Pair = uint32_t; // two bf16
+    static constexpr int kWindow = 29;
+    static __device__ __forceinline__ Row load(const uint16_t *p) { return *reinterpret_cast<const uint2 *>(p); }
+    static __device__ __forceinline__ uint32_t bits(const Row &r, int j)
+    {
+        const uint64_t v = ((uint64_t)r.y << 32) | r.x;
+        return (uint32_t)(v >> (16 * j)) & 0xFFFFu;
+    }
+    static __device__ __forceinline__ uint32_t mag(const Row &r, int j)  // compile-time j
+    {
+        const uint32_t d = (j < 2) ? r.x : r.y;
+        return (j & 1) ? (d & 0x7FFF0000u) : ((d << 16) & 0x7FFF0000u);
+    }
+    static __device__ __forceinline__ Pair pair(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
+};
+
+template <> struct RowOps<float> {
+    using Row = uint4;
+    using Pair = uint2;
+    static constexpr int kWindow = 13;
+    static __device__ __forceinline__ Row load(const float *p) { return *reinterpret_cast<const uint4 *>(p); }
+    static __device__ __forceinline__ uint32_t bits(const Row &r, int j)
+    {
+        return j == 0 ? r.x : (j == 1 ? r.y : (j == 2 ? r.z : r.w));
+    }
+    static __device__ __forceinline__ uint32_t mag(const Row &r, int j) { return bits(r, j) & 0x7FFFFFFFu; }
+    static __device__ __forceinline__ Pair pair(uint32_t lo, uint32_t hi) { return make_uint2(lo, hi); }
+};
+
+constexpr int kTile = 32;        // blocks per tile edge
+constexpr int kPitch = kTile + 1;
+
+template <typename T, bool SEARCH, bool COMPRESS>
+__global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict__ W, int64_t ldw, int br, int bq,
+                                                            const uint16_t *__restrict__ mask_in,
+                                                            uint16_t *__restrict__ mask_out, uint8_t *__restrict__ index_out,
+                                                            T *__restrict__ vals, uint16_t *__restrict__ meta,
+                                                            T *__restrict__ valsT, uint16_t *__restrict__ metaT)
+{
+    using Ops = RowOps<T>;
+    using Row = typename Ops::Row;
+    using Pair = typename Ops::Pair;
+    __shared__ uint16_t s_lut_mask[SEARCH ? 1296 : 1];
+    __shared__ uint8_t s_lut_id[SEARCH ? 1296 : 1];
+    __shared__ Pair s_valsT[COMPRESS ? 4 * kTile * kPitch : 1];
+    __shared__ uint8_t s_nibT[COMPRESS ? 4 * kTile * kPitch : 1];
+
+    const int tid = threadIdx.x;
+    if constexpr (SEARCH) {
+        for (int x = tid; x < 1296; x += 256) {
+            s_lut_mask[x] = g_lut.mask[x];
+            s_lut_id[x] = g_lut.id[x];
+        }
+        __syncthreads();
+    }
+    const int bj0 = blockIdx.x * kTile, bi0 = blockIdx.y * kTile;
+    const int lbj = tid & 31;
+    const int bj = bj0 + lbj;
+    const int64_t q2 = bq;  // kept pairs per row of vals: one per block column
+    const int64_t r2 = br;  // kept pairs per row of valsT: one per block row
+
+#pragma unroll 1
+    for (int s = 0; s < 4; ++s) {
+        const int lbi = (tid >> 5) + 8 * s;
+        const int bi = bi0 + lbi;
+        const bool valid = (bi < br) && (bj < bq);
+        Row rows[4];
+        if (SEARCH || COMPRESS) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (valid) rows[i] = Ops::load(W + (int64_t)(4 * bi + i) * ldw + 4 * bj);
+                else rows[i] = Row{};
+            }
+        }
+        unsigned m = 0, id = 0;
+        if constexpr (SEARCH) {
+            uint32_t mag[16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) mag[4 * i + j] = Ops::mag(rows[i], j);
+            const unsigned res = best_pattern<Ops::kWindow>(mag, s_lut_mask, s_lut_id);
+            m = res & 0xFFFFu;
+            id = res >> 16;
+            if (valid) {
+                if (mask_out) mask_out[(int64_t)bi * bq + bj] = (uint16_t)m;
+                if (index_out) index_out[(int64_t)bi * bq + bj] = (uint8_t)id;
+            }
+        } else {
+            m = valid ? mask_in[(int64_t)bi * bq + bj] : 0x33CCu;
+        }
+        if constexpr (COMPRESS) {
+            // along q: two kept weights and one nibble per block row
+            uint32_t nib_lo = 0, nib_hi = 0;  // nibbles of rows (0,1) and (2,3), 16 bits apart
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned m4 = (m >> (4 * i)) & 0xFu;
+                const int i0 = (__ffs((int)m4) - 1) & 3;
+                const int i1 = (31 - __clz((int)(m4 | 1u))) & 3;
+                const Pair pr = Ops::pair(Ops::bits(rows[i], i0), Ops::bits(rows[i], i1));
+                if (valid) reinterpret_cast<Pair *>(vals)[(int64_t)(4 * bi + i) * q2 + bj] = pr;
+                const uint32_t nib = (uint32_t)(i0 | (i1 << 2));
+                if (i < 2) nib_lo |= nib << (16 * i);
+                else nib_hi |= nib << (16 * (i - 2));
+            }
+            // four neighbouring lanes (same block row) form one metadata word per row
+            nib_lo |= (uint32_t)__shfl_down((int)nib_lo, 1) << 4;
+            nib_hi |= (uint32_t)__shfl_down((int)nib_hi, 1) << 4;
+            nib_lo |= (uint32_t)__shfl_down((int)nib_lo, 2) << 8;
+            nib_hi |= (uint32_t)__shfl_down((int)nib_hi, 2) << 8;
+            if (valid && (lbj & 3) == 0) {
+                const int64_t w = bj >> 2, mw = bq >> 2;
+                meta[(int64_t)(4 * bi + 0) * mw + w] = (uint16_t)(nib_lo & 0xFFFFu);
+                meta[(int64_t)(4 * bi + 1) * mw + w] = (uint16_t)(nib_lo >> 16);
+                meta[(int64_t)(4 * bi + 2) * mw + w] = (uint16_t)(nib_hi & 0xFFFFu);
+                meta[(int64_t)(4 * bi + 3) * mw + w] = (uint16_t)(nib_hi >> 16);
+            }
+            // along r: kept rows of each column go through LDS to be written transposed
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned c = m >> j;
+                const unsigned cm = (c & 1u) | ((c >> 3) & 2u) | ((c >> 6) & 4u) | ((c >> 9) & 8u);
+                const int i0 = (__ffs((int)cm) - 1) & 3;
+                const int i1 = (31 - __clz((int)(cm | 1u))) & 3;
+                uint32_t e[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) e[i] = Ops::bits(rows[i], j);
+                const uint32_t v0 = i0 == 0 ? e[0] : (i0 == 1 ? e[1] : (i0 == 2 ? e[2] : e[3]));
+                const uint32_t v1 = i1 == 0 ? e[0] : (i1 == 1 ? e[1] : (i1 == 2 ? e[2] : e[3]));
+                const int a = (j * kTile + lbj) * kPitch + lbi;
+                s_valsT[a] = Ops::pair(v0, v1);
+                s_nibT[a] = (uint8_t)(i0 | (i1 << 2));
+            }
+        }
+    }
+    if constexpr (COMPRESS) {
+        __syncthreads();
+        // valsT: 128 columns of W, each a run of 32 pairs
+        for (int idx = tid; idx < 4 * kTile * kTile; idx += 256) {
+            const int lbi = idx & 31, col = idx >> 5;  // col = 4*lbj + j
+            const int j = col & 3, lb = col >> 2;
+            if (bj0 + lb < bq && bi0 + lbi < br)
+                reinterpret_cast<Pair *>(valsT)[(int64_t)(4 * (bj0 + lb) + j) * r2 + bi0 + lbi] =
+                    s_valsT[(j * kTile + lb) * kPitch + lbi];
+        }
+        // metaT: 128 columns x 8 words
+        for (int idx = tid; idx < 4 * kTile * 8; idx += 256) {
+            const int w = idx & 7, col = idx >> 3;
+            const int j = col & 3, lb = col >> 2;
+            if (bj0 + lb < bq && bi0 + 4 * w < br) {
+                const uint8_t *n = &s_nibT[(j * kTile + lb) * kPitch + 4 * w];
+                const unsigned word = n[0] | (n[1] << 4) | (n[2] << 8) | (n[3] << 12);
+                metaT[(int64_t)(4 * (bj0 + lb) + j) * (br >> 2) + (bi0 >> 2) + w] = (uint16_t)word;
+            }
+        }
+    }
+}
+
+template <typename T>
+int launch(const void *W, int64_t r, int64_t q, int64_t ldw, const uint16_t *mask_in, uint16_t *mask_out,
+           uint8_t *index_out, void *vals, uint16_t *meta, void *valsT, uint16_t *metaT, bool compress, hipStream_t st)
+{
+    const int br = (int)(r / 4), bq = (int)(q / 4);
+    if (br == 0 || bq == 0) return S24_OK;
+    const dim3 grid((bq + kTile - 1) / kTile, (br + kTile - 1) / kTile), block(256);
+    const T *w = static_cast<const T *>(W);
+    if (!compress)
+        hipLaunchKernelGGL((mask_compress_kernel<T, true, false>), grid, block, 0, st, w, ldw, br, bq, nullptr, mask_out,
+                           index_out, nullptr, nullptr, nullptr, nullptr);
+    else if (mask_in)
+        hipLaunchKernelGGL((mask_compress_kernel<T, false, true>), grid, block, 0, st, w, ldw, br, bq, mask_in, nullptr,
+                           nullptr, static_cast<T *>(vals), meta, static_cast<T *>(valsT), metaT);
+    else
+        hipLaunchKernelGGL((mask_compress_kernel<T, true, true>), grid, block, 0, st, w, ldw, br, bq, nullptr, mask_out,
+                           nullptr, static_cast<T *>(vals), meta, static_cast<T *>(valsT), metaT);
+    return s24_launch_status();
+}
+
+// Shape and dtype are checked first; an empty matrix (r or q zero) is accepted
+// whatever the pointers are, since nothing will be read or written.
+int check_weight(const void *W, int dt, int64_t r, int64_t q, int64_t ldw, int64_t gran)
+{
+    S24_REQUIRE(s24_valid_dtype(dt), S24_ERR_DTYPE);
+    S24_REQUIRE(r >= 0 && q >= 0 && r % gran == 0 && q % gran == 0 && ldw >= q, S24_ERR_SHAPE);
+    S24_REQUIRE(r / 4 < (1ll << 30) && q / 4 < (1ll << 30), S24_ERR_SHAPE);
+    if (r == 0 || q == 0) return S24_OK;
+    S24_REQUIRE(W != nullptr, S24_ERR_NULL);
+    const size_t row_bytes = dt == S24_F32 ? 16 : 8;  // one block row is loaded as a single vector
+    S24_REQUIRE(s24_aligned(W, row_bytes) && (ldw * s24_elem_size(dt)) % row_bytes == 0, S24_ERR_ALIGN);
+    return S24_OK;
+}
+
+}  // namespace
+
+extern "C" int s24_transposable_mask(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw, uint16_t *mask,
+                                     uint8_t *index, void *stream)
+{
+    const int rc = check_weight(W, dt, r, q, ldw, 4);
+    if (rc != S24_OK || r == 0 || q == 0) return rc;
+    S24_REQUIRE(mask != nullptr, S24_ERR_NULL);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == S24_BF16)
+        return launch<uint16_t>(W, r, q, ldw, nullptr, mask, index, nullptr, nullptr, nullptr, nullptr, false, st);
+    return launch<float>(W, r, q, ldw, nullptr, mask, index, nullptr, nullptr, nullptr, nullptr, false, st);
+}
+
+extern "C" int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw, const uint16_t *mask,
+                            void *vals, uint16_t *meta, void *valsT, uint16_t *metaT, uint16_t *mask_out, void *stream)
+{
+    const int rc = check_weight(W, dt, r, q, ldw, 16);
+    if (rc != S24_OK || r == 0 || q == 0) return rc;
+    S24_REQUIRE(vals && meta && valsT && metaT, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(vals, 8) && s24_aligned(valsT, 8) && s24_aligned(meta, 2) && s24_aligned(metaT, 2),
+                S24_ERR_ALIGN);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == S24_BF16)
+        return launch<uint16_t>(W, r, q, ldw, mask, mask_out, nullptr, vals, meta, valsT, metaT, true, st);
+    return launch<float>(W, r, q, ldw, mask, mask_out, nullptr, vals, meta, valsT, metaT, true, st);
+}

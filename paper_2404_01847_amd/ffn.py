@@ -1,0 +1,113 @@
+"""Host-side sequencing of one 2:4-sparse FFN training step (App. B workflow).
+
+Only call ordering and buffer ownership live here; every arithmetic step is a
+libs24 kernel.  One step = for every weight: transposable mask search fused
+with prune/compress (Sec. 5.1), the sparse forward GEMMs (Eq. 2), the
+activation (Sec. 5.2), the sparse input-gradient GEMMs (Eq. 3), the dense
+weight-gradient GEMMs (Eq. 1) and the masked decay on gradients (Eq. 10).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as s24
+
+_ACT = {"relu": s24.ACT_RELU, "gelu": s24.ACT_GELU_ERF}
+
+
+class SparseWeight:
+    """A weight W [r, q] with its block mask and both compressed orientations."""
+
+    def __init__(self, W: torch.Tensor):
+        r, q = W.shape
+        dev, dt = W.device, W.dtype
+        self.W = W
+        self.mask = torch.empty((r // 4, q // 4), dtype=torch.int16, device=dev)
+        self.vals = torch.empty((r, q // 2), dtype=dt, device=dev)
+        self.meta = torch.empty((r, q // 16), dtype=torch.int16, device=dev)
+        self.valsT = torch.empty((q, r // 2), dtype=dt, device=dev)
+        self.metaT = torch.empty((q, r // 16), dtype=torch.int16, device=dev)
+        self.grad = torch.empty((r, q), dtype=torch.float32, device=dev)
+
+    def refresh(self, call=None):
+        """Search the mask and rebuild both compressed operands in one pass over W."""
+        call = call or (lambda name, fn, *a, **k: fn(*a, **k))
+        call("mask_compress", s24.compress, self.W, None, self.vals, self.meta, self.valsT, self.metaT,
+             mask_out=self.mask)
+
+
+class SparseFFN:
+    """Buffers and call sequence of one FFN layer.  act: 'relu' | 'gelu' | 'swiglu'."""
+
+    def __init__(self, weights: dict, p: int, act: str, lam: float):
+        self.act, self.lam, self.p = act, lam, p
+        self.timings = None   # when a dict: kernel name -> list of (start, end) torch.cuda.Event pairs
+        self.gated = act == "swiglu"
+        names = ("Wg", "Wu", "Wd") if self.gated else ("W1", "W2")
+        self.w = {n: SparseWeight(weights[n]) for n in names}
+        up = self.w["Wg" if self.gated else "W1"].W
+        f, d = up.shape
+        dev, dt = up.device, up.dtype
+        new = lambda *shape: torch.empty(shape, dtype=dt, device=dev)
+        self.H, self.dH, self.Y, self.dX = new(p, f), new(p, f), new(p, d), new(p, d)
+        if self.gated:
+            self.G, self.U, self.dG, self.dU = new(p, f), new(p, f), new(p, f), new(p, f)
+        else:
+            self.Z, self.dZ = new(p, f), new(p, f)
+
+    def _k(self, name, fn, *args, **kw):
+        """Run one library call; with `timings` set, bracket it with events on the current stream."""
+        if self.timings is None:
+            return fn(*args, **kw)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = fn(*args, **kw)
+        e1.record()
+        self.timings.setdefault(name, []).append((e0, e1))
+        return out
+
+    def prune(self):
+        for w in self.w.values():
+            w.refresh(self._k)
+
+    def forward(self, X):
+        w = self.w
+        if self.gated:
+            self._k('spmm_fwd', s24.spmm_fwd, X, w["Wg"].vals, w["Wg"].meta, self.G)
+            self._k('spmm_fwd', s24.spmm_fwd, X, w["Wu"].vals, w["Wu"].meta, self.U)
+            self._k('swiglu_fwd', s24.swiglu_fwd, self.G, self.U, self.H)
+            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["Wd"].vals, w["Wd"].meta, self.Y)
+        else:
+            self._k('spmm_fwd', s24.spmm_fwd, X, w["W1"].vals, w["W1"].meta, self.Z)
+            self._k('act_fwd', s24.act_fwd, self.Z, self.H, _ACT[self.act])
+            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["W2"].vals, w["W2"].meta, self.Y)
+        return self.Y
+
+    def backward(self, X, dY):
+        w = self.w
+        if self.gated:
+            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["Wd"].valsT, w["Wd"].metaT, self.dH)
+            self._k('dense_dw', s24.dense_dw, dY, self.H, w["Wd"].grad)
+            self._k('swiglu_bwd', s24.swiglu_bwd, self.dH, self.G, self.U, self.dG, self.dU)
+            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dG, w["Wg"].valsT, w["Wg"].metaT, self.dX)
+            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dU, w["Wu"].valsT, w["Wu"].metaT, self.dX, beta=1.0)
+            self._k('dense_dw', s24.dense_dw, self.dG, X, w["Wg"].grad)
+            self._k('dense_dw', s24.dense_dw, self.dU, X, w["Wu"].grad)
+        else:
+            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["W2"].valsT, w["W2"].metaT, self.dH)
+            self._k('dense_dw', s24.dense_dw, dY, self.H, w["W2"].grad)
+            self._k('act_bwd', s24.act_bwd, self.dH, self.Z, self.dZ, _ACT[self.act])
+            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dZ, w["W1"].valsT, w["W1"].metaT, self.dX)
+            self._k('dense_dw', s24.dense_dw, self.dZ, X, w["W1"].grad)
+        return self.dX
+
+    def decay(self):
+        for w in self.w.values():
+            self._k('masked_decay', s24.masked_decay_grad, w.grad, w.W, w.mask, self.lam)
+
+    def step(self, X, dY):
+        """Mask + compress, forward, backward, masked decay: the whole hot path once."""
+        self.prune()
+        self.forward(X)
+        self.backward(X, dY)
+        self.decay()

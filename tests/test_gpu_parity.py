@@ -1,0 +1,282 @@
+"""GPU parity: every libs24 entry point against the CPU oracle, element by
+element, on seeded inputs that span several tiles and ragged tails.  Masks,
+pattern ids, compressed values and metadata must match bit for bit; GEMM and
+activation outputs within the tolerance of tests/util.py."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import s24_inputs as si
+from util import BF16_TOL, F32_TOL, assert_close, dev, dev_bf16, host_bits, host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def s24():
+    import paper_2404_01847_amd as lib
+    lib.lib()   # fail loudly here if libs24.so is missing
+    assert torch.cuda.is_available()
+    return lib
+
+
+def tdtype(dtype):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def tol(dtype):
+    return BF16_TOL if dtype == "bf16" else F32_TOL
+
+
+def gpu_mask(s24, W, want_index=True):
+    Wd = dev_bf16(W)
+    r, q = W.shape
+    mask = torch.zeros((r // 4, q // 4), dtype=torch.int16, device="cuda")
+    index = torch.zeros((r // 4, q // 4), dtype=torch.uint8, device="cuda") if want_index else None
+    s24.transposable_mask(Wd, mask, index)
+    torch.cuda.synchronize()
+    return host_bits(mask), (host_bits(index) if want_index else None)
+
+
+def gpu_compress(s24, W, mask=None):
+    Wd = dev_bf16(W)
+    r, q = W.shape
+    dt = Wd.dtype
+    vals = torch.zeros((r, q // 2), dtype=dt, device="cuda")
+    meta = torch.zeros((r, q // 16), dtype=torch.int16, device="cuda")
+    valsT = torch.zeros((q, r // 2), dtype=dt, device="cuda")
+    metaT = torch.zeros((q, r // 16), dtype=torch.int16, device="cuda")
+    mask_out = torch.zeros((r // 4, q // 4), dtype=torch.int16, device="cuda")
+    s24.compress(Wd, None if mask is None else dev(mask), vals, meta, valsT, metaT, mask_out=mask_out)
+    torch.cuda.synchronize()
+    return vals, meta, valsT, metaT, mask_out
+
+
+# ------------------------------------------------------------------ pattern table
+def test_pattern_table_matches_oracle(s24):
+    assert s24.pattern_table() == [int(v) for v in oracle.pattern_table()]
+
+
+# ------------------------------------------------------------------ mask search
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(4, 4), (128, 128), (260, 388), (516, 132), (64, 1024)])
+def test_mask_random_bit_exact(s24, dtype, shape):
+    W = si.random_matrix(100 + shape[0], shape, 0.02, dtype)
+    want_m, want_i = oracle.transposable_mask(W, want_index=True)
+    got_m, got_i = gpu_mask(s24, W)
+    assert np.array_equal(got_m, want_m)
+    assert np.array_equal(got_i, want_i)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal"])
+def test_mask_ties_and_wide_ranges_bit_exact(s24, dtype, kind):
+    W = si.tie_matrix(77, 192, 320, dtype, kind)
+    want_m, want_i = oracle.transposable_mask(W, want_index=True)
+    got_m, got_i = gpu_mask(s24, W)
+    assert np.array_equal(got_m, want_m), kind
+    assert np.array_equal(got_i, want_i), kind
+
+
+def test_mask_strided_weight_and_empty(s24):
+    W = si.random_matrix(5, (64, 256), 0.02, "bf16")
+    Wd = dev_bf16(W)
+    view = Wd[:, 64:192]                       # ldw = 256 > q = 128
+    mask = torch.zeros((16, 32), dtype=torch.int16, device="cuda")
+    s24.transposable_mask(view, mask, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(mask), oracle.transposable_mask(np.ascontiguousarray(W[:, 64:192])))
+    empty = torch.zeros((0, 128), dtype=torch.bfloat16, device="cuda")
+    s24.transposable_mask(empty, torch.zeros((0, 32), dtype=torch.int16, device="cuda"), None)
+
+
+# ------------------------------------------------------------------ compress
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(16, 16), (128, 128), (272, 400), (528, 144)])
+@pytest.mark.parametrize("fused", [False, True])
+def test_compress_bit_exact(s24, dtype, shape, fused):
+    W = si.random_matrix(200 + shape[1], shape, 0.02, dtype)
+    W[0:4, 0:8] = 0
+    mask = oracle.transposable_mask(W)
+    want = oracle.compress(W, mask)
+    vals, meta, valsT, metaT, mask_out = gpu_compress(s24, W, None if fused else mask)
+    if fused:
+        assert np.array_equal(host_bits(mask_out), mask)
+    for got, ref, name in zip((vals, meta, valsT, metaT), want, ("vals", "meta", "valsT", "metaT")):
+        g = host_bits(got)
+        assert np.array_equal(g.view(ref.dtype) if g.dtype != ref.dtype else g, ref), name
+
+
+def test_compress_tie_matrix_fused(s24):
+    W = si.tie_matrix(3, 128, 256, "bf16", "few")
+    mask = oracle.transposable_mask(W)
+    want = oracle.compress(W, mask)
+    got = gpu_compress(s24, W, None)
+    assert np.array_equal(host_bits(got[4]), mask)
+    for g, ref in zip(got[:4], want):
+        assert np.array_equal(host_bits(g), ref)
+
+
+# ------------------------------------------------------------------ sparse GEMMs
+def compressed(W):
+    mask = oracle.transposable_mask(W)
+    return (mask,) + oracle.compress(W, mask)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pqr", [(1, 64, 16), (128, 128, 128), (300, 256, 208), (77, 192, 400), (513, 64, 144)])
+def test_spmm_fwd(s24, dtype, pqr):
+    p, q, r = pqr
+    W = si.random_matrix(300 + r, (r, q), 0.02, dtype)
+    X = si.random_matrix(301 + p, (p, q), 1.0, dtype)
+    mask, vals, meta, valsT, metaT = compressed(W)
+    Y = torch.full((p, r), 7.0, dtype=tdtype(dtype), device="cuda")
+    s24.spmm_fwd(dev_bf16(X), dev_bf16(vals), dev(meta), Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y), oracle.spmm_fwd(X, vals, meta), tol(dtype), f"spmm_fwd {pqr}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pqr", [(1, 16, 64), (128, 128, 128), (300, 208, 256), (77, 400, 192)])
+@pytest.mark.parametrize("beta", [0.0, 1.0])
+def test_spmm_bwd_dx(s24, dtype, pqr, beta):
+    p, q, r = pqr
+    W = si.random_matrix(310 + r, (r, q), 0.02, dtype)
+    dY = si.random_matrix(311 + p, (p, r), 1e-2, dtype)
+    dX0 = si.random_matrix(312, (p, q), 1e-3, dtype)
+    mask, vals, meta, valsT, metaT = compressed(W)
+    dX = dev_bf16(dX0).clone()
+    s24.spmm_bwd_dx(dev_bf16(dY), dev_bf16(valsT), dev(metaT), dX, beta=beta)
+    torch.cuda.synchronize()
+    ref = oracle.spmm_bwd_dx(dY, valsT, metaT, beta=beta, dX0=si.to_f32(dX0).astype(np.float64))
+    assert_close(host_f64(dX), ref, tol(dtype), f"spmm_bwd_dx {pqr} beta={beta}")
+
+
+def test_spmm_one_hot_reproduces_masked_weight_exactly(s24):
+    q, r = 128, 144
+    W = si.random_matrix(320, (r, q), 0.02, "bf16")
+    mask, vals, meta, valsT, metaT = compressed(W)
+    eye = dev_bf16(si.f32_to_bf16_bits(torch.eye(q)))
+    Y = torch.zeros((q, r), dtype=torch.bfloat16, device="cuda")
+    s24.spmm_fwd(eye, dev_bf16(vals), dev(meta), Y)
+    torch.cuda.synchronize()
+    ref = oracle.spmm_fwd(si.f32_to_bf16_bits(torch.eye(q)), vals, meta)
+    assert np.array_equal(host_f64(Y), ref)       # products with 1 and sums with 0 are exact
+
+
+# ------------------------------------------------------------------ dense GEMMs
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pqr", [(1, 16, 16), (64, 128, 128), (300, 208, 272), (1000, 144, 400)])
+@pytest.mark.parametrize("beta", [0.0, 1.0])
+def test_dense_dw(s24, dtype, pqr, beta):
+    p, q, r = pqr
+    dY = si.random_matrix(400 + p, (p, r), 1e-2, dtype)
+    X = si.random_matrix(401 + q, (p, q), 1.0, dtype)
+    dW0 = si.random_matrix(402, (r, q), 1e-2, "f32")
+    dW = dev(dW0).clone()
+    s24.dense_dw(dev_bf16(dY), dev_bf16(X), dW, beta=beta)
+    torch.cuda.synchronize()
+    ref = oracle.dense_dw(dY, X, beta=beta, dW0=dW0.astype(np.float64))
+    # fp32 output: only accumulation-order noise, whatever the input dtype
+    assert_close(host_f64(dW), ref, F32_TOL, f"dense_dw {pqr} beta={beta}")
+
+
+def test_dense_dw_rank_one_is_exact(s24):
+    dY = si.random_matrix(410, (1, 144), 1.0, "bf16")
+    X = si.random_matrix(411, (1, 208), 1.0, "bf16")
+    dW = torch.zeros((144, 208), dtype=torch.float32, device="cuda")
+    s24.dense_dw(dev_bf16(dY), dev_bf16(X), dW)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_f64(dW), oracle.dense_dw(dY, X))    # bf16 x bf16 fits fp32 exactly
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pqr", [(1, 64, 16), (128, 128, 128), (300, 256, 208)])
+def test_dense_gemm(s24, dtype, pqr):
+    p, q, r = pqr
+    X = si.random_matrix(420 + p, (p, q), 1.0, dtype)
+    W = si.random_matrix(421 + r, (r, q), 0.02, dtype)
+    Y = torch.zeros((p, r), dtype=tdtype(dtype), device="cuda")
+    s24.dense_gemm(dev_bf16(X), dev_bf16(W), Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y), oracle.dense_gemm(X, W), tol(dtype), f"dense_gemm {pqr}")
+
+
+# ------------------------------------------------------------------ masked decay
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(16, 16), (260, 400), (128, 1024)])
+def test_masked_decay(s24, dtype, shape):
+    lam = 2e-4
+    W = si.random_matrix(500 + shape[0], shape, 0.02, dtype)
+    dW = si.random_matrix(501, shape, 1e-3, "f32")
+    mask = oracle.transposable_mask(W)
+    G = dev(dW).clone()
+    s24.masked_decay_grad(G, dev_bf16(W), dev(mask), lam)
+    torch.cuda.synchronize()
+    got = host_bits(G)
+    ref = oracle.masked_decay(dW, W, mask, lam)
+    keep = np.zeros(shape, dtype=bool)
+    for i in range(4):
+        for j in range(4):
+            keep[i::4, j::4] = ((mask >> (4 * i + j)) & 1).astype(bool)
+    assert np.array_equal(got[keep], dW[keep])                       # kept cells bit-identical
+    np.testing.assert_allclose(got.astype(np.float64), ref, rtol=3e-7, atol=0)
+
+
+# ------------------------------------------------------------------ activations
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("pf", [(1, 8), (37, 264), (256, 1000)])
+def test_swiglu_fwd_bwd(s24, dtype, pf):
+    p, f = pf
+    g = si.random_matrix(600 + p, (p, f), 2.0, dtype)
+    u = si.random_matrix(601 + f, (p, f), 1.0, dtype)
+    d = si.random_matrix(602, (p, f), 1e-2, dtype)
+    G, U, D = dev_bf16(g), dev_bf16(u), dev_bf16(d)
+    H = torch.zeros_like(G)
+    dG, dU = torch.zeros_like(G), torch.zeros_like(G)
+    s24.swiglu_fwd(G, U, H)
+    s24.swiglu_bwd(D, G, U, dG, dU)
+    torch.cuda.synchronize()
+    assert_close(host_f64(H), oracle.swiglu_fwd(g, u), tol(dtype), "swiglu_fwd")
+    rg, ru = oracle.swiglu_bwd(d, g, u)
+    assert_close(host_f64(dG), rg, tol(dtype), "swiglu_bwd dG")
+    assert_close(host_f64(dU), ru, tol(dtype), "swiglu_bwd dU")
+
+
+def test_swiglu_halves_of_one_buffer_and_extremes(s24):
+    p, f = 19, 136
+    gu = si.random_matrix(610, (p, 2 * f), 1.5, "bf16")
+    gu[0, :8] = si.f32_to_bf16_bits(torch.tensor([0.0, -0.0, 88.0, -88.0, 3e38, -3e38, 1e-30, -1e-30]))
+    d = si.random_matrix(611, (p, f), 1.0, "bf16")
+    GU = dev_bf16(gu)
+    G, U = GU[:, :f], GU[:, f:]
+    H = torch.zeros((p, f), dtype=torch.bfloat16, device="cuda")
+    dGU = torch.zeros_like(GU)
+    s24.swiglu_fwd(G, U, H)
+    s24.swiglu_bwd(dev_bf16(d), G, U, dGU[:, :f], dGU[:, f:])
+    torch.cuda.synchronize()
+    g, u = np.ascontiguousarray(gu[:, :f]), np.ascontiguousarray(gu[:, f:])
+    h = host_f64(H)
+    assert np.isfinite(h).all()
+    assert_close(h, oracle.swiglu_fwd(g, u), BF16_TOL, "swiglu_fwd halves")
+    rg, ru = oracle.swiglu_bwd(d, g, u)
+    out = host_f64(dGU)
+    assert_close(out[:, :f], rg, BF16_TOL, "swiglu_bwd dG halves")
+    assert_close(out[:, f:], ru, BF16_TOL, "swiglu_bwd dU halves")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("act", ["relu", "gelu"])
+def test_act_fwd_bwd(s24, dtype, act):
+    code = {"relu": (s24.ACT_RELU, oracle.ACT_RELU), "gelu": (s24.ACT_GELU_ERF, oracle.ACT_GELU_ERF)}[act]
+    z = si.random_matrix(620, (33, 264), 1.5, dtype)
+    z.reshape(-1)[:5] = 0
+    d = si.random_matrix(621, (33, 264), 1e-2, dtype)
+    Z, D = dev_bf16(z), dev_bf16(d)
+    H, dZ = torch.zeros_like(Z), torch.zeros_like(Z)
+    s24.act_fwd(Z, H, code[0])
+    s24.act_bwd(D, Z, dZ, code[0])
+    torch.cuda.synchronize()
+    assert_close(host_f64(H), oracle.act_fwd(z, code[1]), tol(dtype), f"{act} fwd")
+    assert_close(host_f64(dZ), oracle.act_bwd(d, z, code[1]), tol(dtype), f"{act} bwd")

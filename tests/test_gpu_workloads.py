@@ -1,0 +1,218 @@
+"""GPU parity on the five benchmark workloads.
+
+c1 (fp32, ReLU) runs the whole FFN step and is compared stage by stage with an
+oracle chain.  c2..c5 are checked at full size, in the launch configuration the
+benchmark times: masks, compressed values and metadata bit-exactly over every
+weight; GEMM outputs on randomly sampled output rows (the oracle computes each
+sampled row in full); elementwise kernels on sampled row bands."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import s24_inputs as si
+from util import BF16_TOL, F32_TOL, assert_close, dev, dev_bf16, host_bits, host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def s24():
+    import paper_2404_01847_amd as lib
+    lib.lib()
+    assert torch.cuda.is_available()
+    return lib
+
+
+def keep_of(mask):
+    r4, q4 = mask.shape
+    keep = np.zeros((4 * r4, 4 * q4), dtype=bool)
+    for i in range(4):
+        for j in range(4):
+            keep[i::4, j::4] = ((mask >> (4 * i + j)) & 1).astype(bool)
+    return keep
+
+
+# ------------------------------------------------------------------ whole step, oracle chain
+def oracle_chain(wl, t, rnd):
+    """Reference FFN step.  `rnd` rounds a stage output to the storage dtype the
+    GPU pipeline uses between kernels, so both sides round at the same points."""
+    out = {}
+    comp = {}
+    for n in wl.weight_names:
+        m = oracle.transposable_mask(t[n])
+        comp[n] = (m,) + oracle.compress(t[n], m)
+        out["mask_" + n] = m
+    X, dY = t["X"], t["dY"]
+    if wl.gated:
+        G = rnd(oracle.spmm_fwd(X, comp["Wg"][1], comp["Wg"][2]))
+        U = rnd(oracle.spmm_fwd(X, comp["Wu"][1], comp["Wu"][2]))
+        H = rnd(oracle.swiglu_fwd(G, U))
+        Y = oracle.spmm_fwd(H, comp["Wd"][1], comp["Wd"][2])
+        dH = rnd(oracle.spmm_bwd_dx(dY, comp["Wd"][3], comp["Wd"][4]))
+        dG64, dU64 = oracle.swiglu_bwd(dH, G, U)
+        dG, dU = rnd(dG64), rnd(dU64)
+        dX1 = oracle.spmm_bwd_dx(dG, comp["Wg"][3], comp["Wg"][4])
+        dX = oracle.spmm_bwd_dx(dU, comp["Wu"][3], comp["Wu"][4], beta=1.0, dX0=si.to_f32(rnd(dX1)).astype(np.float64))
+        grads = {"Wd": oracle.dense_dw(dY, H), "Wg": oracle.dense_dw(dG, X), "Wu": oracle.dense_dw(dU, X)}
+        out.update(G=G, U=U, H=H, dH=dH, dG=dG, dU=dU)
+    else:
+        act = oracle.ACT_RELU if wl.act == "relu" else oracle.ACT_GELU_ERF
+        Z = rnd(oracle.spmm_fwd(X, comp["W1"][1], comp["W1"][2]))
+        H = rnd(oracle.act_fwd(Z, act))
+        Y = oracle.spmm_fwd(H, comp["W2"][1], comp["W2"][2])
+        dH = rnd(oracle.spmm_bwd_dx(dY, comp["W2"][3], comp["W2"][4]))
+        dZ = rnd(oracle.act_bwd(dH, Z, act))
+        dX = oracle.spmm_bwd_dx(dZ, comp["W1"][3], comp["W1"][4])
+        grads = {"W2": oracle.dense_dw(dY, H), "W1": oracle.dense_dw(dZ, X)}
+        out.update(Z=Z, H=H, dH=dH, dZ=dZ)
+    out.update(Y=Y, dX=dX)
+    for n in wl.weight_names:
+        out["grad_" + n] = oracle.masked_decay(grads[n].astype(np.float32), t[n], comp[n][0], wl.lam)
+    return out
+
+
+def run_chain(s24, wl, t, tol_act, tol_grad):
+    from paper_2404_01847_amd.ffn import SparseFFN
+    bf16 = wl.dtype == "bf16"
+    rnd = (lambda a: oracle.round_bf16(a)) if bf16 else (lambda a: a.astype(np.float32))
+    ref = oracle_chain(wl, t, rnd)
+    ffn = SparseFFN({n: dev_bf16(t[n]) for n in wl.weight_names}, t["X"].shape[0], wl.act, wl.lam)
+    X, dY = dev_bf16(t["X"]), dev_bf16(t["dY"])
+    ffn.step(X, dY)
+    torch.cuda.synchronize()
+    for n in wl.weight_names:
+        assert np.array_equal(host_bits(ffn.w[n].mask), ref["mask_" + n]), n
+    names = ("G", "U", "H", "Y", "dH", "dG", "dU", "dX") if wl.gated else ("Z", "H", "Y", "dH", "dZ", "dX")
+    for k in names:
+        want = ref[k]
+        want = si.to_f32(want).astype(np.float64) if want.dtype != np.float64 else want
+        assert_close(host_f64(getattr(ffn, k)), want, tol_act, f"{wl.name} {k}")
+    for n in wl.weight_names:
+        assert_close(host_f64(ffn.w[n].grad), ref["grad_" + n], tol_grad, f"{wl.name} grad {n}")
+
+
+def test_c1_whole_step_fp32(s24):
+    wl = si.WORKLOADS["c1"]
+    run_chain(s24, wl, si.make(wl), F32_TOL, F32_TOL)
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_reduced_bf16_whole_step(s24, act):
+    # a small layer of the same structure as c2/c3 (ungated) and c4/c5 (gated); ragged token count
+    wl = si.Workload("mini_" + act, 200, 128, 448, act, "bf16", 17)
+    # the chain compounds bf16 roundings: a 1-ulp flip upstream moves a downstream value by up to its own
+    # rounding step, so the element bound is doubled here; the normwise bound stays
+    run_chain(s24, wl, si.make(wl), (2e-2, 5e-3), (2e-2, 5e-3))
+
+
+# ------------------------------------------------------------------ full-size workloads
+def sample_rows(n, k, seed):
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([[0, n - 1], rng.integers(0, n, size=k)]))
+    return rows.astype(np.int64)
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_workload_full_size(s24, name):
+    wl = si.WORKLOADS[name]
+    t = si.make(wl)
+    p, d, f = wl.p, wl.d_model, wl.d_ff
+    X, dY = t["X"], t["dY"]
+    Xd, dYd = dev_bf16(X), dev_bf16(dY)
+    up = wl.weight_names[0]
+    down = wl.weight_names[-1]
+    comp = {}
+    # --- mask + compress over every weight, bit-exact
+    for n in wl.weight_names:
+        W = t[n]
+        r, q = W.shape
+        Wd = dev_bf16(W)
+        vals = torch.zeros((r, q // 2), dtype=torch.bfloat16, device="cuda")
+        meta = torch.zeros((r, q // 16), dtype=torch.int16, device="cuda")
+        valsT = torch.zeros((q, r // 2), dtype=torch.bfloat16, device="cuda")
+        metaT = torch.zeros((q, r // 16), dtype=torch.int16, device="cuda")
+        mask = torch.zeros((r // 4, q // 4), dtype=torch.int16, device="cuda")
+        mask2 = torch.zeros_like(mask)
+        s24.compress(Wd, None, vals, meta, valsT, metaT, mask_out=mask)
+        s24.transposable_mask(Wd, mask2, None)
+        torch.cuda.synchronize()
+        want_mask = oracle.transposable_mask(W)
+        assert np.array_equal(host_bits(mask), want_mask), f"{name} {n} fused mask"
+        assert np.array_equal(host_bits(mask2), want_mask), f"{name} {n} mask"
+        want = oracle.compress(W, want_mask)
+        for got, ref, what in zip((vals, meta, valsT, metaT), want, ("vals", "meta", "valsT", "metaT")):
+            assert np.array_equal(host_bits(got), ref), f"{name} {n} {what}"
+        # masked decay on a sampled band of rows (the kernel runs over the whole matrix)
+        G = torch.zeros((r, q), dtype=torch.float32, device="cuda")
+        s24.masked_decay_grad(G, Wd, mask, wl.lam)
+        torch.cuda.synchronize()
+        r0 = (r // 3) // 4 * 4
+        band = slice(r0, r0 + 64)
+        ref = oracle.masked_decay(np.zeros((64, q), np.float32), np.ascontiguousarray(W[band]),
+                                  np.ascontiguousarray(want_mask[r0 // 4:r0 // 4 + 16]), wl.lam)
+        got = host_bits(G[band])
+        np.testing.assert_allclose(got.astype(np.float64), ref, rtol=3e-7, atol=0)
+        assert (got[keep_of(want_mask[r0 // 4:r0 // 4 + 16])] == 0).all()
+        comp[n] = (want, (vals, meta, valsT, metaT))
+        del Wd, G
+    # --- forward sparse GEMM, up projection: sampled token rows
+    rows = sample_rows(p, 24, 1)
+    (ovals, ometa, ovalsT, ometaT), (vals, meta, valsT, metaT) = comp[up]
+    Z = torch.zeros((p, f), dtype=torch.bfloat16, device="cuda")
+    s24.spmm_fwd(Xd, vals, meta, Z)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Z[torch.from_numpy(rows).cuda()]), oracle.spmm_fwd(X, ovals, ometa, rows=rows), BF16_TOL,
+                 f"{name} spmm_fwd")
+    # --- backward sparse GEMM through the up projection: dX = dZ . W, synthetic dZ
+    dZ = si.random_matrix(900 + wl.seed, (p, f), 1e-2, "bf16")
+    dZd = dev_bf16(dZ)
+    dX = torch.zeros((p, d), dtype=torch.bfloat16, device="cuda")
+    s24.spmm_bwd_dx(dZd, valsT, metaT, dX)
+    torch.cuda.synchronize()
+    assert_close(host_f64(dX[torch.from_numpy(rows).cuda()]), oracle.spmm_bwd_dx(dZ, ovalsT, ometaT, rows=rows),
+                 BF16_TOL, f"{name} spmm_bwd_dx")
+    # --- dense weight gradient dW = dZ^T X and dense comparison GEMM: sampled output rows
+    orow = sample_rows(f, 6, 2)
+    dW = torch.zeros((f, d), dtype=torch.float32, device="cuda")
+    s24.dense_dw(dZd, Xd, dW)
+    torch.cuda.synchronize()
+    assert_close(host_f64(dW[torch.from_numpy(orow).cuda()]), oracle.dense_dw(dZ, X, rows=orow), F32_TOL,
+                 f"{name} dense_dw")
+    del dW
+    s24.dense_gemm(Xd, dev_bf16(t[up]), Z)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Z[torch.from_numpy(rows).cuda()]), oracle.dense_gemm(X, t[up], rows=rows), BF16_TOL,
+                 f"{name} dense_gemm")
+    # --- down projection forward (contraction over d_ff) on synthetic H
+    Hh = si.random_matrix(901 + wl.seed, (p, f), 0.5, "bf16")
+    (ovals, ometa, _, _), (vals, meta, _, _) = comp[down]
+    Y = torch.zeros((p, d), dtype=torch.bfloat16, device="cuda")
+    Hd = dev_bf16(Hh)
+    s24.spmm_fwd(Hd, vals, meta, Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y[torch.from_numpy(rows).cuda()]), oracle.spmm_fwd(Hh, ovals, ometa, rows=rows), BF16_TOL,
+                 f"{name} spmm_fwd down")
+    # --- activation on the full buffers, compared on sampled rows
+    band = sample_rows(p, 48, 3)
+    bidx = torch.from_numpy(band).cuda()
+    if wl.gated:
+        Uh = si.random_matrix(902 + wl.seed, (p, f), 1.0, "bf16")
+        Ud = dev_bf16(Uh)
+        out, dG, dU = torch.zeros_like(Hd), torch.zeros_like(Hd), torch.zeros_like(Hd)
+        s24.swiglu_fwd(Hd, Ud, out)
+        s24.swiglu_bwd(dZd, Hd, Ud, dG, dU)
+        torch.cuda.synchronize()
+        g, u, dd = Hh[band], Uh[band], dZ[band]
+        assert_close(host_f64(out[bidx]), oracle.swiglu_fwd(g, u), BF16_TOL, f"{name} swiglu_fwd")
+        rg, ru = oracle.swiglu_bwd(dd, g, u)
+        assert_close(host_f64(dG[bidx]), rg, BF16_TOL, f"{name} swiglu_bwd dG")
+        assert_close(host_f64(dU[bidx]), ru, BF16_TOL, f"{name} swiglu_bwd dU")
+    else:
+        out, dz = torch.zeros_like(Hd), torch.zeros_like(Hd)
+        s24.act_fwd(Hd, out, s24.ACT_GELU_ERF)
+        s24.act_bwd(dZd, Hd, dz, s24.ACT_GELU_ERF)
+        torch.cuda.synchronize()
+        assert_close(host_f64(out[bidx]), oracle.act_fwd(Hh[band], oracle.ACT_GELU_ERF), BF16_TOL, f"{name} gelu fwd")
+        assert_close(host_f64(dz[bidx]), oracle.act_bwd(dZ[band], Hh[band], oracle.ACT_GELU_ERF), BF16_TOL,
+                     f"{name} gelu bwd")

@@ -1,0 +1,113 @@
+"""CPU-side checks of the HIP library: it loads without a GPU, exports every
+symbol include/s24.h declares, and rejects bad arguments on the host before
+anything is launched.  No kernel runs here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2404_01847_amd as s24
+    if not os.path.exists(s24.lib_path()):
+        from paper_2404_01847_amd.build import build
+        build(verbose=False)
+    return s24.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "s24.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(s24_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2404_01847_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_pattern_table_is_the_lexicographic_enumeration(lib, legal_blocks):
+    import paper_2404_01847_amd as s24
+    assert s24.pattern_table() == legal_blocks
+
+
+def test_strerror_covers_all_codes(lib):
+    import paper_2404_01847_amd as s24
+    texts = {s24.strerror(c) for c in range(0, -7, -1)}
+    assert len(texts) == 7 and "ok" in texts
+    assert "unknown" in s24.strerror(-99)
+
+
+OK, NULL, SHAPE, DTYPE, ALIGN, UNSUP = 0, -1, -2, -3, -4, -6
+P = 0x1000  # a fake, well-aligned device address: validation never dereferences it
+
+
+def test_mask_argument_errors(lib):
+    f = lib.s24_transposable_mask
+    assert f(None, 1, 8, 8, 8, P, None, None) == NULL
+    assert f(P, 1, 8, 8, 8, None, None, None) == NULL
+    assert f(P, 7, 8, 8, 8, P, None, None) == DTYPE
+    assert f(P, 1, 6, 8, 8, P, None, None) == SHAPE
+    assert f(P, 1, 8, 10, 12, P, None, None) == SHAPE
+    assert f(P, 1, -4, 8, 8, P, None, None) == SHAPE
+    assert f(P, 1, 8, 8, 4, P, None, None) == SHAPE          # ldw < q
+    assert f(P + 2, 1, 8, 8, 8, P, None, None) == ALIGN
+    assert f(P, 1, 8, 8, 10, P, None, None) == ALIGN          # row stride not a multiple of 8 bytes
+    assert f(P + 8, 0, 8, 8, 8, P, None, None) == ALIGN       # fp32 rows need 16 bytes
+    assert f(P, 1, 0, 8, 8, P, None, None) == OK              # empty: nothing to do
+
+
+def test_compress_argument_errors(lib):
+    f = lib.s24_compress
+    assert f(P, 1, 16, 16, 16, None, None, P, P, P, None, None) == NULL
+    assert f(P, 1, 16, 24, 24, None, P, P, P, P, None, None) == SHAPE    # q not a multiple of 16
+    assert f(P, 1, 16, 16, 16, None, P + 4, P, P, P, None, None) == ALIGN
+    assert f(P, 1, 0, 16, 16, None, P, P, P, P, None, None) == OK
+
+
+def test_gemm_argument_errors(lib):
+    assert lib.s24_spmm_fwd(P, P, P, P, 4, 96, 16, 1, None) == SHAPE          # q % 64
+    assert lib.s24_spmm_fwd(P, P, P, P, 4, 64, 24, 1, None) == SHAPE          # r % 16
+    assert lib.s24_spmm_fwd(P, P, None, P, 4, 64, 16, 1, None) == NULL
+    assert lib.s24_spmm_fwd(P, P, P, P + 2, 4, 64, 16, 1, None) == ALIGN
+    assert lib.s24_spmm_fwd(P, P, P, P, 4, 64, 16, 3, None) == DTYPE
+    assert lib.s24_spmm_fwd(P, P, P, P, 0, 64, 16, 1, None) == OK
+    assert lib.s24_spmm_bwd_dx(P, P, P, P, 4, 16, 96, 0.0, 1, None) == SHAPE  # r % 64
+    assert lib.s24_spmm_bwd_dx(P, P, P, P, 4, 16, 64, 0.5, 1, None) == UNSUP  # beta must be 0 or 1
+    assert lib.s24_dense_dw(P, P, P, 4, 24, 16, 0.0, 1, None) == SHAPE
+    assert lib.s24_dense_dw(P, P, P, 4, 16, 16, 2.0, 1, None) == UNSUP
+    assert lib.s24_dense_dw(P, None, P, 4, 16, 16, 0.0, 1, None) == NULL
+    assert lib.s24_dense_gemm(P, P, P, 4, 32, 16, 1, None) == SHAPE
+    assert lib.s24_dense_gemm(P, P, P, 0, 64, 16, 1, None) == OK
+
+
+def test_elementwise_argument_errors(lib):
+    assert lib.s24_masked_decay_grad(P, P, 1, None, 1e-4, 16, 16, None) == NULL
+    assert lib.s24_masked_decay_grad(P, P, 1, P, 1e-4, 16, 24, None) == SHAPE
+    assert lib.s24_masked_decay_grad(P + 4, P, 1, P, 1e-4, 16, 16, None) == ALIGN
+    assert lib.s24_masked_decay_grad(P, P, 5, P, 1e-4, 16, 16, None) == DTYPE
+    assert lib.s24_swiglu_fwd(P, P, P, 4, 12, 16, 1, None) == SHAPE
+    assert lib.s24_swiglu_fwd(P, P, P, 4, 16, 8, 1, None) == SHAPE            # ld < f
+    assert lib.s24_swiglu_fwd(P, None, P, 4, 16, 16, 1, None) == NULL
+    assert lib.s24_swiglu_bwd(P, P, P, P, None, 4, 16, 16, 1, None) == NULL
+    assert lib.s24_swiglu_bwd(P, P, P, P, P + 8, 4, 16, 16, 1, None) == ALIGN
+    assert lib.s24_act_fwd(P, P, 12, 0, 1, None) == SHAPE
+    assert lib.s24_act_fwd(P, P, 16, 9, 1, None) == DTYPE
+    assert lib.s24_act_bwd(P, P, None, 16, 0, 1, None) == NULL
+    assert lib.s24_act_fwd(P, P, 0, 0, 1, None) == OK
+
+
+def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
+    from paper_2404_01847_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libs24.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.lib()

@@ -1,0 +1,57 @@
+"""Helpers shared by the GPU parity tests: host<->device conversion of the
+seeded inputs and the error measures of the parity bar."""
+import numpy as np
+import torch
+
+import s24_inputs as si
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    """numpy (float32, or uint16 = bf16 bits / mask words, or uint8) -> CUDA tensor."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def dev_bf16(a: np.ndarray) -> torch.Tensor:
+    """bf16 bit array (uint16) -> CUDA bfloat16 tensor; float32 arrays pass through."""
+    t = dev(a)
+    return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
+
+
+def host_bits(t: torch.Tensor) -> np.ndarray:
+    """CUDA tensor -> numpy; bfloat16 and int16 come back as uint16 bit arrays."""
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        t = t.view(torch.int16)
+    a = t.numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a
+
+
+def host_f64(t: torch.Tensor) -> np.ndarray:
+    return si.to_f32(host_bits(t)).astype(np.float64)
+
+
+def errors(got: np.ndarray, ref: np.ndarray):
+    """(max scaled element error, normwise error).  The element error divides by
+    max(|ref|, 1e-2 * rms(ref)) so that cancellations do not blow it up."""
+    got, ref = got.astype(np.float64), ref.astype(np.float64)
+    rms = np.sqrt(np.mean(ref * ref)) if ref.size else 0.0
+    den = np.maximum(np.abs(ref), 1e-2 * rms)
+    den[den == 0] = 1.0
+    d = np.abs(got - ref)
+    nrm = np.linalg.norm(ref.reshape(-1))
+    return float((d / den).max()) if ref.size else 0.0, float(np.linalg.norm(d.reshape(-1)) / (nrm if nrm else 1.0))
+
+
+# bf16 in / fp32 accumulate: max relative error 1e-2, normwise 5e-3
+BF16_TOL = (1e-2, 5e-3)
+# fp32 data path (small correctness workload): accumulation-order noise only
+F32_TOL = (1e-3, 2e-5)
+
+
+def assert_close(got, ref, tol, what=""):
+    e_max, e_nrm = errors(got, ref)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    assert e_max <= tol[0] and e_nrm <= tol[1], f"{what}: max rel {e_max:.3e} (<= {tol[0]}), normwise {e_nrm:.3e} (<= {tol[1]})"
+    return e_max, e_nrm
