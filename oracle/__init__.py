@@ -37,7 +37,7 @@ def _load():
     if _lib is None:
         build()
         _lib = C.CDLL(_LIB)
-        for name in ("orc_pattern_table", "orc_transposable_mask", "orc_compress", "orc_spmm_fwd",
+        for name in ("orc_pack_chunk_major", "orc_pattern_table", "orc_transposable_mask", "orc_compress", "orc_spmm_fwd",
                      "orc_spmm_bwd_dx", "orc_dense_dw", "orc_dense_gemm", "orc_masked_decay",
                      "orc_swiglu_fwd", "orc_swiglu_bwd", "orc_act_fwd", "orc_act_bwd", "orc_num_threads"):
             getattr(_lib, name).restype = C.c_int
@@ -109,6 +109,18 @@ def compress(W: np.ndarray, mask: np.ndarray):
                               _p(vals), _p(meta), _p(valsT), _p(metaT))
     _check(rc, "compress")
     return vals, meta, valsT, metaT
+
+
+def pack(vals, meta):
+    """Row-major compressed operand -> chunk-major storage: vals_p[K/64, R, 32], meta_p[K/64, R, 4]."""
+    vals, meta = _c(vals), _c(meta, np.uint16)
+    R, half = vals.shape
+    K = 2 * half
+    vals_p = np.zeros((K // 64, R, 32), dtype=vals.dtype)
+    meta_p = np.zeros((K // 64, R, 4), dtype=np.uint16)
+    rc = _load().orc_pack_chunk_major(_p(vals), _p(meta), _dt(vals), C.c_int64(R), C.c_int64(K), _p(vals_p), _p(meta_p))
+    _check(rc, "pack_chunk_major")
+    return vals_p, meta_p
 
 
 def spmm_fwd(X, vals, meta, rows=None):

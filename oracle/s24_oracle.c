@@ -19,7 +19,9 @@
  *   - pattern scores are compared as exact real numbers;
  *   - a block mask is stored as uint16 with bit (4i+j) = m_ij;
  *   - compressed format: kept values in column order, one 4-bit metadata
- *     nibble i0 | i1<<2 per group of four, nibbles packed little-endian.
+ *     nibble i0 | i1<<2 per group of four, nibbles packed little-endian;
+ *     orc_pack_chunk_major() permutes it into the chunk-major storage order
+ *     the GPU library exchanges (64 of the contraction axis per chunk).
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py against
  * facts that do not come from this file (exhaustive enumeration in Python,
@@ -252,6 +254,31 @@ int orc_compress(const void *W, int dt, int64_t r, int64_t q, int64_t ldw, const
             metaT[i * (r / 16) + g / 4] |= (uint16_t)(nib << (4 * (g % 4)));
         }
     return bad ? -3 : 0;
+}
+
+/* Re-layout of a compressed operand for the matrix-core kernels (a permutation,
+ * no arithmetic).  The paper leaves the compressed format to its spMM library;
+ * the reading taken here groups the contraction axis in chunks of 64: chunk c
+ * of row o holds 32 kept values and 4 metadata words, and all rows of one chunk
+ * are stored together:
+ *     vals_p[c][o][0..31] = vals[o][32c .. 32c+31]
+ *     meta_p[c][o][0..3]  = meta[o][4c .. 4c+3]
+ * R rows, K = contraction length (multiple of 64). */
+int orc_pack_chunk_major(const void *vals, const uint16_t *meta, int dt, int64_t R, int64_t K,
+                         void *vals_p, uint16_t *meta_p)
+{
+    if (R < 0 || K < 0 || K % 64) return -1;
+    size_t es = dt == ORC_F32 ? 4 : 2;
+    int64_t nc = K / 64;
+    for (int64_t c = 0; c < nc; ++c)
+        for (int64_t o = 0; o < R; ++o) {
+            for (int j = 0; j < 32; ++j)
+                memcpy((char *)vals_p + (size_t)((c * R + o) * 32 + j) * es,
+                       (const char *)vals + (size_t)(o * (K / 2) + 32 * c + j) * es, es);
+            for (int j = 0; j < 4; ++j)
+                meta_p[(c * R + o) * 4 + j] = meta[o * (K / 16) + 4 * c + j];
+        }
+    return 0;
 }
 
 static int meta_idx(const uint16_t *meta, int64_t words_per_row, int64_t row, int64_t g, int s)

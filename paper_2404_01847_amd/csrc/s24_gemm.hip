@@ -161,6 +161,181 @@ __global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__res
     }
 }
 
+// ------------------------------------------------------------------ sparse NT, large tile
+// Workgroup tile 256 (m) x 256 (n) x 64 (k), eight waves as 2 (m) x 4 (n), each
+// wave 128 x 64 = 4 x 2 accumulator tiles.  Both operands are copied from
+// global memory straight into LDS (no register staging) through a ring of
+// three 48 KB stages, two chunks ahead of the math; only the index words go
+// through registers.  LDS layouts: dense operand rows of 128 bytes with the
+// 16-byte chunk c of row r at slot c ^ ((r ^ r>>3) & 7); compressed operand
+// rows of 64 bytes with chunk c at slot c ^ ((r>>2) & 3).  Both keep any 16
+// consecutive lanes of an operand read on distinct 16-byte slots modulo 256
+// bytes, which is what a full-rate 128-bit LDS read needs on this chip.
+namespace big {
+constexpr int BM = 256, BN = 256, STAGES = 3, THREADS = 512;
+constexpr int B_STAGE = BN * 128, A_STAGE = BM * 64, STAGE = B_STAGE + A_STAGE;
+typedef __attribute__((address_space(3))) void *lds_ptr;
+typedef const __attribute__((address_space(1))) void *glb_ptr;
+
+__device__ __forceinline__ int b_slot(int row, int c) { return row * 128 + ((c ^ ((row ^ (row >> 3)) & 7)) << 4); }
+__device__ __forceinline__ int a_slot(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
+
+// s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt unconstrained
+__host__ __device__ constexpr int wait_vm_lgkm0(int n) { return (n & 15) | (7 << 4) | ((n >> 4) << 14); }
+
+template <bool ACCUM>
+__global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
+                                                              const uint16_t *__restrict__ Av,
+                                                              const uint16_t *__restrict__ Am,
+                                                              uint16_t *__restrict__ Out, int N, int K, int M,
+                                                              int tiles_m, int tiles_n)
+{
+    // One array per ring stage: the compiler then knows which stage a direct-to-LDS
+    // copy writes and does not make reads of the other stages wait for it.
+    __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s1[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s2[STAGE];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
+    const int wm = wave & 1, wn = wave >> 1;
+    // Workgroups are dealt round-robin to the eight XCDs; give each XCD one contiguous
+    // slab of the tile grid and walk it in groups of eight n-tiles so that the
+    // workgroups resident on one XCD share operand rows in its L2.
+    const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8;
+    const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (t >= total) return;
+    constexpr int GROUP = 8;
+    const int group_sz = GROUP * tiles_m, grp = t / group_sz, in_grp = t - grp * group_sz;
+    const int gw = min(GROUP, tiles_n - grp * GROUP);
+    const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int nk = K / 64;
+
+    // per-lane source pointers of the direct-to-LDS copies (elements), advanced by one chunk per stage
+    const uint16_t *gb[4];
+    const uint16_t *ga_[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 32 * wave + 8 * i + (lane >> 3);
+        const int c = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
+        gb[i] = B + (int64_t)min(n0 + row, N - 1) * K + 8 * c;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = 32 * wave + 16 * i + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        ga_[i] = Av + (int64_t)min(m0 + row, M - 1) * (K / 2) + 8 * c;
+    }
+    // index words: lane (row l%32, half l/32) of m-fragment mi needs dword l/32 of its row's four words per chunk
+    const uint32_t *gm[4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        const int row = min(m0 + 128 * wm + 32 * mi + (lane & 31), M - 1);
+        gm[mi] = reinterpret_cast<const uint32_t *>(Am + (int64_t)row * (K / 16)) + (lane >> 5);
+    }
+    // Every call issues exactly six copies and four index loads per lane, so the wait
+    // counts below are constants; past the last chunk it re-reads the last one into
+    // a stage nobody will read again.  The index words of chunk kc live in idx[kc % 3].
+    uint32_t idx[3][4];
+    auto issue = [&](unsigned char *st, uint32_t (&ix)[4], int kc) {
+        kc = min(kc, nk - 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((glb_ptr)(gb[i] + (int64_t)kc * 64), (lds_ptr)(st + (32 * wave + 8 * i) * 128), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            __builtin_amdgcn_global_load_lds((glb_ptr)(ga_[i] + (int64_t)kc * 32), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) ix[mi] = gm[mi][2 * kc];
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+
+    // keep the program order of these groups: the constant wait counts rely on it
+    issue(s0, idx[0], 0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s1, idx[1], 1);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // One chunk: wait for its stage, refill the stage that was read last time, do the math.
+    auto chunk = [&](const unsigned char *cur, const uint32_t (&ix)[4], unsigned char *refill, uint32_t (&ix_refill)[4], int kc) {
+        // all but the ten most recent vector-memory operations (chunk kc+1: six copies, four index
+        // loads) are complete, so this lane's part of chunk kc is in LDS; its own LDS reads are done
+        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(10));
+        __builtin_amdgcn_s_barrier();   // everybody's part landed; everybody finished reading `refill`
+        issue(refill, ix_refill, kc + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char *sb = cur, *sa = cur + B_STAGE;
+        const int g = lane >> 5;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            bf16x16 b[2];
+            bf16x8 a[4];
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const int row = 64 * wn + 32 * ni + (lane & 31);
+                b[ni] = as_bf16x16(*reinterpret_cast<const uint4 *>(sb + b_slot(row, 2 * h + g)),
+                                   *reinterpret_cast<const uint4 *>(sb + b_slot(row, 4 + 2 * h + g)));
+            }
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) {
+                const int row = 128 * wm + 32 * mi + (lane & 31);
+                a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(row, 2 * g + h)));
+            }
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    if (h == 0)
+                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 0);
+                    else
+                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 1);
+                }
+        }
+    };
+    int kc = 0;
+    for (; kc + 3 <= nk; kc += 3) {
+        chunk(s0, idx[0], s2, idx[2], kc);
+        chunk(s1, idx[1], s0, idx[0], kc + 1);
+        chunk(s2, idx[2], s1, idx[1], kc + 2);
+    }
+    if (kc < nk) chunk(s0, idx[0], s2, idx[2], kc);
+    if (kc + 1 < nk) chunk(s1, idx[1], s0, idx[0], kc + 1);
+    // drain the copies still in flight before the workgroup's LDS is released
+    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));
+
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+        if (n >= N) continue;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int m = m0 + 128 * wm + 32 * mi + 8 * g4 + 4 * (lane >> 5);
+                if (m >= M) continue;
+                uint2 *dst = reinterpret_cast<uint2 *>(Out + (int64_t)n * M + m);
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][4 * g4 + e];
+                if (ACCUM) {
+                    const uint2 old = *dst;
+                    v[0] += s24_bf16_to_f32(old.x & 0xFFFFu);
+                    v[1] += s24_bf16_to_f32(old.x >> 16);
+                    v[2] += s24_bf16_to_f32(old.y & 0xFFFFu);
+                    v[3] += s24_bf16_to_f32(old.y >> 16);
+                }
+                *dst = make_uint2(s24_pack_bf16x2(v[0], v[1]), s24_pack_bf16x2(v[2], v[3]));
+            }
+        }
+    }
+}
+}  // namespace big
+
 // ------------------------------------------------------------------ dense MFMA core
 // Both operands in LDS as k-contiguous swizzled tiles.  MFMA step i of a lane
 // with k-group g = lane/32 uses chunk 4*g + i of its row, i.e. k in
@@ -380,7 +555,20 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
 {
     if (N == 0 || M == 0) return S24_OK;
     const bool accum = beta != 0.0f;
-    if (dt == S24_BF16) {
+    if (dt == S24_BF16 && (int64_t)ceil_div(M, big::BM) * ceil_div(N, big::BN) >= 192) {
+        // enough 256x256 tiles to fill the chip: large-tile kernel
+        const int tiles_m = (int)ceil_div(M, big::BM), tiles_n = (int)ceil_div(N, big::BN);
+        const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+        const dim3 grid(per_xcd * 8), block(big::THREADS);
+        auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av);
+        auto *o = static_cast<uint16_t *>(Out);
+        if (accum)
+            hipLaunchKernelGGL(big::spmm_nt_big_kernel<true>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
+                               tiles_m, tiles_n);
+        else
+            hipLaunchKernelGGL(big::spmm_nt_big_kernel<false>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
+                               tiles_m, tiles_n);
+    } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(M, BM), ceil_div(N, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
         auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av);

@@ -153,6 +153,30 @@ def test_spmm_bwd_dx(s24, dtype, pqr, beta):
     assert_close(host_f64(dX), ref, tol(dtype), f"spmm_bwd_dx {pqr} beta={beta}")
 
 
+@pytest.mark.parametrize("k", [64, 128, 192, 256, 320, 448])
+def test_spmm_large_tile_path(s24, k):
+    """Shapes with at least 192 tiles of 256 x 256 take the large-tile kernel: ragged token and
+    feature tails, every residue of the chunk count modulo the three-stage ring."""
+    p, r = 6100, 2000
+    W = si.random_matrix(330 + k, (r, k), 0.02, "bf16")
+    X = si.random_matrix(331 + k, (p, k), 1.0, "bf16")
+    mask, vals, meta, valsT, metaT = compressed(W)
+    rows = np.unique(np.concatenate([[0, 255, 256, p - 1], np.random.default_rng(k).integers(0, p, 40)])).astype(np.int64)
+    ridx = torch.from_numpy(rows).cuda()
+    Y = torch.full((p, r), 3.0, dtype=torch.bfloat16, device="cuda")
+    s24.spmm_fwd(dev_bf16(X), dev_bf16(vals), dev(meta), Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y[ridx]), oracle.spmm_fwd(X, vals, meta, rows=rows), BF16_TOL, f"large spmm_fwd k={k}")
+    # the same operands as an input-gradient GEMM: dX[p][r'] with r' = 2000 features, contraction k
+    # (valsT of a [k x 2000] weight is a [2000 x k/2] operand, which is what `vals` already is)
+    dX0 = si.random_matrix(332, (p, r), 1e-2, "bf16")
+    dX = dev_bf16(dX0).clone()
+    s24.spmm_bwd_dx(dev_bf16(X), dev_bf16(vals), dev(meta), dX, beta=1.0)
+    torch.cuda.synchronize()
+    ref = oracle.spmm_bwd_dx(X, vals, meta, beta=1.0, dX0=si.to_f32(dX0[rows]).astype(np.float64), rows=rows)
+    assert_close(host_f64(dX[ridx]), ref, BF16_TOL, f"large spmm_bwd_dx k={k}")
+
+
 def test_spmm_one_hot_reproduces_masked_weight_exactly(s24):
     q, r = 128, 144
     W = si.random_matrix(320, (r, q), 0.02, "bf16")

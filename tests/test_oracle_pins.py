@@ -215,6 +215,18 @@ def test_compress_decodes_to_masked_weight_bitwise(dtype):
         assert nibs <= legal
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pack_is_the_documented_permutation(dtype):
+    W = si.random_matrix(13, (80, 192), 0.02, dtype)
+    mask = oracle.transposable_mask(W)
+    vals, meta, valsT, metaT = oracle.compress(W, mask)
+    vp, mp = oracle.pack(vals, meta)
+    assert np.array_equal(vp, vals.reshape(80, 3, 32).transpose(1, 0, 2))
+    assert np.array_equal(mp, meta.reshape(80, 3, 4).transpose(1, 0, 2))
+    with pytest.raises(ValueError):
+        oracle.pack(valsT, metaT)          # contraction length 80 is not a multiple of 64
+
+
 def test_compress_rejects_illegal_mask():
     W = si.random_matrix(1, (16, 16), 0.02, "f32")
     mask = oracle.transposable_mask(W)
