@@ -21,12 +21,17 @@
  *   pattern id   the 90 legal blocks (two ones in every row and column) are
  *                numbered in lexicographic order of the 16-character row-major
  *                string m00 m01 ... m33 with '0' < '1'.
- *   compressed   for a matrix A (R x K) that keeps exactly two of every four
- *                consecutive elements along K:  vals[R][K/2] holds the kept
- *                elements in order (bit copies), and meta[R][K/16] holds one
- *                uint16 per 16 columns: group g (columns 4g..4g+3) contributes
- *                the nibble  i0 | i1 << 2  (i0 < i1 the kept column offsets) at
- *                bits 4*(g mod 4) of word g/4.
+ *   compressed   for a matrix A (R x K, K a multiple of 64) that keeps exactly two
+ *                of every four consecutive elements along K.  Per row the kept
+ *                elements in order (bit copies) form K/2 values, and every 16
+ *                columns give one uint16 of metadata: group g (columns
+ *                4g..4g+3) contributes the nibble  i0 | i1 << 2  (i0 < i1 the
+ *                kept column offsets) at bits 4*(g mod 4) of word g/4.
+ *                Storage is chunk-major, 64 columns per chunk, all rows of a
+ *                chunk together:  vals[K/64][R][32]  (value j of chunk c of row
+ *                o is the row's kept value 32c+j)  and  meta[K/64][R][4]  (word
+ *                4c+j of the row).  One chunk of one row is exactly what one
+ *                lane pair feeds to two sparse matrix-core instructions.
  *   dtypes       S24_BF16 buffers hold raw bfloat16; S24_F32 buffers hold float.
  */
 #ifndef S24_H
@@ -76,17 +81,17 @@ int s24_transposable_mask(const void *W, s24_dtype dt, int64_t r, int64_t q, int
  * sparse_W_T operands of the App. B workflow).  Emits the compressed form of
  * M.*W along q (vals, meta) and of (M.*W)^T along r (valsT, metaT).
  *   mask      [r/4][q/4] device, in; NULL = search the mask in the same pass
- *   vals      [r][q/2]  meta  [r][q/16]
- *   valsT     [q][r/2]  metaT [q][r/16]
+ *   vals      [q/64][r][32]  meta  [q/64][r][4]    (rows of W, chunks along q)
+ *   valsT     [r/64][q][32]  metaT [r/64][q][4]    (rows of W^T, chunks along r)
  *   mask_out  [r/4][q/4] device, out, may be NULL (only used when mask == NULL)
- * r, q multiples of 16.  A given mask must be legal (two kept per row and
+ * r, q multiples of 64.  A given mask must be legal (two kept per row and
  * column of each block); an illegal mask gives unspecified values but no fault. */
 int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
                  const uint16_t *mask, void *vals, uint16_t *meta, void *valsT, uint16_t *metaT,
                  uint16_t *mask_out, void *stream);
 
 /* Forward sparse GEMM (Eq. 2):  Y[p][r] = X[p][q] . (M.*W)^T, contraction over
- * q against the compressed weight (vals [r][q/2], meta [r][q/16]).
+ * q against the compressed weight (vals [q/64][r][32], meta [q/64][r][4]).
  * bf16 in / fp32 accumulate / bf16 out (f32 throughout for S24_F32).
  * p >= 1; q multiple of 64; r multiple of 16. */
 int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y,
@@ -94,7 +99,7 @@ int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y,
 
 /* Backward sparse GEMM for the input gradient (Eq. 3):
  * dX[p][q] = beta*dX + dY[p][r] . (M.*W), contraction over r against the
- * compressed transpose (valsT [q][r/2], metaT [q][r/16]); legal because the
+ * compressed transpose (valsT [r/64][q][32], metaT [r/64][q][4]); legal because the
  * mask is transposable (Eq. 5).  beta is 0 or 1 (1 sums the gate and up
  * branches of a gated FFN).  r multiple of 64; q multiple of 16. */
 int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, void *dX,

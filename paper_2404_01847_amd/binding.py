@@ -111,14 +111,14 @@ def compress(W, mask, vals, meta, valsT, metaT, mask_out=None):
 
 def spmm_fwd(X, vals, meta, Y):
     p, q = X.shape
-    r = vals.shape[0]
+    r = vals.shape[1]          # vals is chunk-major: [q/64, r, 32]
     _check(lib().s24_spmm_fwd(_ptr(X), _ptr(vals), _ptr(meta), _ptr(Y), p, q, r, _dt(X), _stream()), "s24_spmm_fwd")
     return Y
 
 
 def spmm_bwd_dx(dY, valsT, metaT, dX, beta=0.0):
     p, r = dY.shape
-    q = valsT.shape[0]
+    q = valsT.shape[1]         # valsT is chunk-major: [r/64, q, 32]
     _check(lib().s24_spmm_bwd_dx(_ptr(dY), _ptr(valsT), _ptr(metaT), _ptr(dX), p, q, r, beta, _dt(dY), _stream()),
            "s24_spmm_bwd_dx")
     return dX

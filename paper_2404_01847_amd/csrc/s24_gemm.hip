@@ -11,9 +11,10 @@
 // 16*(l/32)+16) in order, with their 2-bit positions in bits [2j+1:2j] of the
 // index register half chosen by ABID; for B column l%32, element j holds
 // k = 16*(j/8) + 8*(l/32) + j%8; accumulator i holds row 8*(i/4)+4*(l/32)+i%4
-// of column l%32.  The canonical metadata word (one uint16 per 16 of k) is
-// exactly one lane's index half, so compressed weights feed the instruction
-// straight from global memory and only the dense operand goes through LDS.
+// of column l%32.  One metadata word (a uint16 per 16 of k) is exactly one
+// lane's index half, and the chunk-major storage of the compressed operand
+// (vals[K/64][M][32], meta[K/64][M][4]) makes the 64-byte value run and the
+// four index words of one row and chunk contiguous, rows back to back.
 #include "s24_common.h"
 
 namespace {
@@ -76,10 +77,11 @@ __device__ __forceinline__ void sparse_a_load(SparseA &a, const uint16_t *Av, co
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi) {
         const int row = min(mrow0 + 32 * mi + (lane & 31), M - 1);
-        const uint4 *pv = reinterpret_cast<const uint4 *>(Av + (int64_t)row * (K / 2) + k0 / 2 + 16 * ga);
+        const int64_t cr = (int64_t)(k0 / 64) * M + row;  // (chunk, row) in chunk-major storage
+        const uint4 *pv = reinterpret_cast<const uint4 *>(Av + cr * 32 + 16 * ga);
         a.v[mi][0] = pv[0];
         a.v[mi][1] = pv[1];
-        a.idx[mi] = reinterpret_cast<const uint32_t *>(Am + (int64_t)row * (K / 16) + k0 / 16)[ga];
+        a.idx[mi] = reinterpret_cast<const uint32_t *>(Am + cr * 4)[ga];
     }
 }
 
@@ -165,15 +167,14 @@ __global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__res
 // Workgroup tile 256 (m) x 256 (n) x 64 (k), eight waves as 2 (m) x 4 (n), each
 // wave 128 x 64 = 4 x 2 accumulator tiles.  Both operands are copied from
 // global memory straight into LDS (no register staging) through a ring of
-// three 48 KB stages, two chunks ahead of the math; only the index words go
-// through registers.  LDS layouts: dense operand rows of 128 bytes with the
+// three 50 KB stages, two chunks ahead of the math.  LDS layouts: dense operand rows of 128 bytes with the
 // 16-byte chunk c of row r at slot c ^ ((r ^ r>>3) & 7); compressed operand
 // rows of 64 bytes with chunk c at slot c ^ ((r>>2) & 3).  Both keep any 16
 // consecutive lanes of an operand read on distinct 16-byte slots modulo 256
 // bytes, which is what a full-rate 128-bit LDS read needs on this chip.
 namespace big {
-constexpr int BM = 256, BN = 256, STAGES = 3, THREADS = 512;
-constexpr int B_STAGE = BN * 128, A_STAGE = BM * 64, STAGE = B_STAGE + A_STAGE;
+constexpr int BM = 256, BN = 256, THREADS = 512;
+constexpr int B_STAGE = BN * 128, A_STAGE = BM * 64, M_STAGE = BM * 8, STAGE = B_STAGE + A_STAGE + M_STAGE;
 typedef __attribute__((address_space(3))) void *lds_ptr;
 typedef const __attribute__((address_space(1))) void *glb_ptr;
 
@@ -224,29 +225,22 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     for (int i = 0; i < 2; ++i) {
         const int row = 32 * wave + 16 * i + (lane >> 2);
         const int c = (lane & 3) ^ ((row >> 2) & 3);
-        ga_[i] = Av + (int64_t)min(m0 + row, M - 1) * (K / 2) + 8 * c;
+        ga_[i] = Av + (int64_t)min(m0 + row, M - 1) * 32 + 8 * c;
     }
-    // index words: lane (row l%32, half l/32) of m-fragment mi needs dword l/32 of its row's four words per chunk
-    const uint32_t *gm[4];
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        const int row = min(m0 + 128 * wm + 32 * mi + (lane & 31), M - 1);
-        gm[mi] = reinterpret_cast<const uint32_t *>(Am + (int64_t)row * (K / 16)) + (lane >> 5);
-    }
-    // Every call issues exactly six copies and four index loads per lane, so the wait
-    // counts below are constants; past the last chunk it re-reads the last one into
-    // a stage nobody will read again.  The index words of chunk kc live in idx[kc % 3].
-    uint32_t idx[3][4];
-    auto issue = [&](unsigned char *st, uint32_t (&ix)[4], int kc) {
+    // index words: one 4-byte direct-to-LDS copy per lane and chunk (row 32*wave + lane/2, dword lane%2)
+    const uint16_t *gmeta = Am + (int64_t)min(m0 + 32 * wave + (lane >> 1), M - 1) * 4 + 2 * (lane & 1);
+    // Every call issues exactly seven copies per lane (four of the dense operand, two of the
+    // values, one of the index words), so the wait counts below are constants; past the last
+    // chunk it re-reads the last one into a stage nobody will read again.
+    auto issue = [&](unsigned char *st, int kc) {
         kc = min(kc, nk - 1);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             __builtin_amdgcn_global_load_lds((glb_ptr)(gb[i] + (int64_t)kc * 64), (lds_ptr)(st + (32 * wave + 8 * i) * 128), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(ga_[i] + (int64_t)kc * 32), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) ix[mi] = gm[mi][2 * kc];
+            __builtin_amdgcn_global_load_lds((glb_ptr)(ga_[i] + (int64_t)kc * M * 32), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_ptr)(gmeta + (int64_t)kc * M * 4), (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), 4, 0, 0);
     };
 
     f32x16 acc[4][2];
@@ -256,21 +250,25 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
 
     // keep the program order of these groups: the constant wait counts rely on it
-    issue(s0, idx[0], 0);
+    issue(s0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    issue(s1, idx[1], 1);
+    issue(s1, 1);
     __builtin_amdgcn_sched_barrier(0);
 
     // One chunk: wait for its stage, refill the stage that was read last time, do the math.
-    auto chunk = [&](const unsigned char *cur, const uint32_t (&ix)[4], unsigned char *refill, uint32_t (&ix_refill)[4], int kc) {
-        // all but the ten most recent vector-memory operations (chunk kc+1: six copies, four index
-        // loads) are complete, so this lane's part of chunk kc is in LDS; its own LDS reads are done
-        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(10));
+    auto chunk = [&](const unsigned char *cur, unsigned char *refill, int kc) {
+        // all but the seven most recent vector-memory operations (the copies of chunk kc+1) are
+        // complete, so this lane's part of chunk kc is in LDS; its own LDS reads are done too
+        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(7));
         __builtin_amdgcn_s_barrier();   // everybody's part landed; everybody finished reading `refill`
-        issue(refill, ix_refill, kc + 2);
+        issue(refill, kc + 2);
         __builtin_amdgcn_sched_barrier(0);
-        const unsigned char *sb = cur, *sa = cur + B_STAGE;
+        const unsigned char *sb = cur, *sa = cur + B_STAGE, *sm = cur + B_STAGE + A_STAGE;
         const int g = lane >> 5;
+        uint32_t ix[4];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+            ix[mi] = *reinterpret_cast<const uint32_t *>(sm + (128 * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             bf16x16 b[2];
@@ -299,12 +297,12 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     };
     int kc = 0;
     for (; kc + 3 <= nk; kc += 3) {
-        chunk(s0, idx[0], s2, idx[2], kc);
-        chunk(s1, idx[1], s0, idx[0], kc + 1);
-        chunk(s2, idx[2], s1, idx[1], kc + 2);
+        chunk(s0, s2, kc);
+        chunk(s1, s0, kc + 1);
+        chunk(s2, s1, kc + 2);
     }
-    if (kc < nk) chunk(s0, idx[0], s2, idx[2], kc);
-    if (kc + 1 < nk) chunk(s1, idx[1], s0, idx[0], kc + 1);
+    if (kc < nk) chunk(s0, s2, kc);
+    if (kc + 1 < nk) chunk(s1, s0, kc + 1);
     // drain the copies still in flight before the workgroup's LDS is released
     __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));
 
@@ -506,9 +504,10 @@ __global__ __launch_bounds__(kThreads) void spmm_nt_f32_kernel(const float *__re
     const int64_t n = idx / M, m = idx - n * M;
     float acc = 0.0f;
     for (int64_t g = 0; g < K / 4; ++g) {
-        const unsigned nib = (Am[m * (K / 16) + g / 4] >> (4 * (g & 3))) & 0xFu;
-        acc = fmaf(Av[m * (K / 2) + 2 * g], B[n * K + 4 * g + (nib & 3u)], acc);
-        acc = fmaf(Av[m * (K / 2) + 2 * g + 1], B[n * K + 4 * g + (nib >> 2)], acc);
+        const int64_t cr = (g / 16) * M + m;  // chunk-major storage: (chunk, row)
+        const unsigned nib = (Am[cr * 4 + (g & 15) / 4] >> (4 * (g & 3))) & 0xFu;
+        acc = fmaf(Av[cr * 32 + 2 * (g & 15)], B[n * K + 4 * g + (nib & 3u)], acc);
+        acc = fmaf(Av[cr * 32 + 2 * (g & 15) + 1], B[n * K + 4 * g + (nib >> 2)], acc);
     }
     Out[idx] = ACCUM ? Out[idx] + acc : acc;
 }

@@ -1,9 +1,10 @@
 // Transposable 2:4 mask search and prune/compress (Sec. 5.1 and Sec. 5 item 1).
 //
 // One lane owns one aligned 4x4 block.  A workgroup of 256 lanes walks a tile
-// of 32 x 32 blocks (128 x 128 weights), four blocks per lane, so that both
-// the row-wise compressed operand and, through an LDS transpose, the
-// column-wise one are written in runs of 128 bytes or more.
+// of 32 x 32 blocks (128 x 128 weights), four blocks per lane.  The compressed
+// operands are stored chunk-major (64 of the contraction axis per chunk, all
+// rows of a chunk together), so a tile covers two chunks of each orientation
+// and the column-wise operand, after an LDS transpose, leaves in 8 KB runs.
 //
 // Scoring.  A legal block is a choice of one of six column pairs per row
 // whose columns each get picked twice.  Rows 0-1 and rows 2-3 are scored
@@ -296,8 +297,7 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     const int bj0 = blockIdx.x * kTile, bi0 = blockIdx.y * kTile;
     const int lbj = tid & 31;
     const int bj = bj0 + lbj;
-    const int64_t q2 = bq;  // kept pairs per row of vals: one per block column
-    const int64_t r2 = br;  // kept pairs per row of valsT: one per block row
+    const int64_t R = 4 * (int64_t)br, Q = 4 * (int64_t)bq;  // rows of vals / of valsT
 
 #pragma unroll 1
     for (int s = 0; s < 4; ++s) {
@@ -338,7 +338,8 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
                 const int i0 = (__ffs((int)m4) - 1) & 3;
                 const int i1 = (31 - __clz((int)(m4 | 1u))) & 3;
                 const Pair pr = Ops::pair(Ops::bits(rows[i], i0), Ops::bits(rows[i], i1));
-                if (valid) reinterpret_cast<Pair *>(vals)[(int64_t)(4 * bi + i) * q2 + bj] = pr;
+                // chunk bj/16 of row 4bi+i, pair bj%16 of its 16 pairs
+                if (valid) reinterpret_cast<Pair *>(vals)[((int64_t)(bj >> 4) * R + 4 * bi + i) * 16 + (bj & 15)] = pr;
                 const uint32_t nib = (uint32_t)(i0 | (i1 << 2));
                 if (i < 2) nib_lo |= nib << (16 * i);
                 else nib_hi |= nib << (16 * (i - 2));
@@ -349,11 +350,12 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
             nib_lo |= (uint32_t)__shfl_down((int)nib_lo, 2) << 8;
             nib_hi |= (uint32_t)__shfl_down((int)nib_hi, 2) << 8;
             if (valid && (lbj & 3) == 0) {
-                const int64_t w = bj >> 2, mw = bq >> 2;
-                meta[(int64_t)(4 * bi + 0) * mw + w] = (uint16_t)(nib_lo & 0xFFFFu);
-                meta[(int64_t)(4 * bi + 1) * mw + w] = (uint16_t)(nib_lo >> 16);
-                meta[(int64_t)(4 * bi + 2) * mw + w] = (uint16_t)(nib_hi & 0xFFFFu);
-                meta[(int64_t)(4 * bi + 3) * mw + w] = (uint16_t)(nib_hi >> 16);
+                const int w = bj >> 2;  // metadata word of the row: chunk w/4, word w%4
+                uint16_t *mrow = meta + ((int64_t)(w >> 2) * R + 4 * bi) * 4 + (w & 3);
+                mrow[0] = (uint16_t)(nib_lo & 0xFFFFu);
+                mrow[4] = (uint16_t)(nib_lo >> 16);
+                mrow[8] = (uint16_t)(nib_hi & 0xFFFFu);
+                mrow[12] = (uint16_t)(nib_hi >> 16);
             }
             // along r: kept rows of each column go through LDS to be written transposed
 #pragma unroll
@@ -375,22 +377,25 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     }
     if constexpr (COMPRESS) {
         __syncthreads();
-        // valsT: 128 columns of W, each a run of 32 pairs
+        // valsT: two chunks (16 pairs each) of 128 columns of W; walk pairs fastest, then columns,
+        // so that consecutive lanes write consecutive addresses inside a chunk
         for (int idx = tid; idx < 4 * kTile * kTile; idx += 256) {
-            const int lbi = idx & 31, col = idx >> 5;  // col = 4*lbj + j
+            const int lbi = (idx & 15) | ((idx >> 11) << 4), col = (idx >> 4) & 127;  // col = 4*lbj + j
             const int j = col & 3, lb = col >> 2;
-            if (bj0 + lb < bq && bi0 + lbi < br)
-                reinterpret_cast<Pair *>(valsT)[(int64_t)(4 * (bj0 + lb) + j) * r2 + bi0 + lbi] =
+            const int bi = bi0 + lbi;
+            if (bj0 + lb < bq && bi < br)
+                reinterpret_cast<Pair *>(valsT)[((int64_t)(bi >> 4) * Q + 4 * (bj0 + lb) + j) * 16 + (bi & 15)] =
                     s_valsT[(j * kTile + lb) * kPitch + lbi];
         }
-        // metaT: 128 columns x 8 words
+        // metaT: 128 columns x 8 words = two chunks of four words
         for (int idx = tid; idx < 4 * kTile * 8; idx += 256) {
-            const int w = idx & 7, col = idx >> 3;
+            const int w = (idx & 3) | ((idx >> 9) << 2), col = (idx >> 2) & 127;
             const int j = col & 3, lb = col >> 2;
             if (bj0 + lb < bq && bi0 + 4 * w < br) {
                 const uint8_t *n = &s_nibT[(j * kTile + lb) * kPitch + 4 * w];
                 const unsigned word = n[0] | (n[1] << 4) | (n[2] << 8) | (n[3] << 12);
-                metaT[(int64_t)(4 * (bj0 + lb) + j) * (br >> 2) + (bi0 >> 2) + w] = (uint16_t)word;
+                const int ww = (bi0 >> 2) + w;
+                metaT[((int64_t)(ww >> 2) * Q + 4 * (bj0 + lb) + j) * 4 + (ww & 3)] = (uint16_t)word;
             }
         }
     }
@@ -447,7 +452,7 @@ extern "C" int s24_transposable_mask(const void *W, s24_dtype dt, int64_t r, int
 extern "C" int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw, const uint16_t *mask,
                             void *vals, uint16_t *meta, void *valsT, uint16_t *metaT, uint16_t *mask_out, void *stream)
 {
-    const int rc = check_weight(W, dt, r, q, ldw, 16);
+    const int rc = check_weight(W, dt, r, q, ldw, 64);
     if (rc != S24_OK || r == 0 || q == 0) return rc;
     S24_REQUIRE(vals && meta && valsT && metaT, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(vals, 8) && s24_aligned(valsT, 8) && s24_aligned(meta, 2) && s24_aligned(metaT, 2),

@@ -23,10 +23,11 @@ class SparseWeight:
         dev, dt = W.device, W.dtype
         self.W = W
         self.mask = torch.empty((r // 4, q // 4), dtype=torch.int16, device=dev)
-        self.vals = torch.empty((r, q // 2), dtype=dt, device=dev)
-        self.meta = torch.empty((r, q // 16), dtype=torch.int16, device=dev)
-        self.valsT = torch.empty((q, r // 2), dtype=dt, device=dev)
-        self.metaT = torch.empty((q, r // 16), dtype=torch.int16, device=dev)
+        # chunk-major compressed operands: 64 of the contraction axis per chunk
+        self.vals = torch.empty((q // 64, r, 32), dtype=dt, device=dev)
+        self.meta = torch.empty((q // 64, r, 4), dtype=torch.int16, device=dev)
+        self.valsT = torch.empty((r // 64, q, 32), dtype=dt, device=dev)
+        self.metaT = torch.empty((r // 64, q, 4), dtype=torch.int16, device=dev)
         self.grad = torch.empty((r, q), dtype=torch.float32, device=dev)
 
     def refresh(self, call=None):

@@ -39,14 +39,20 @@ def gpu_mask(s24, W, want_index=True):
     return host_bits(mask), (host_bits(index) if want_index else None)
 
 
+def packed(vals, meta):
+    """Oracle's row-major compressed operand -> the library's chunk-major storage, on the GPU."""
+    vp, mp = oracle.pack(vals, meta)
+    return dev_bf16(vp), dev(mp)
+
+
 def gpu_compress(s24, W, mask=None):
     Wd = dev_bf16(W)
     r, q = W.shape
     dt = Wd.dtype
-    vals = torch.zeros((r, q // 2), dtype=dt, device="cuda")
-    meta = torch.zeros((r, q // 16), dtype=torch.int16, device="cuda")
-    valsT = torch.zeros((q, r // 2), dtype=dt, device="cuda")
-    metaT = torch.zeros((q, r // 16), dtype=torch.int16, device="cuda")
+    vals = torch.zeros((q // 64, r, 32), dtype=dt, device="cuda")
+    meta = torch.zeros((q // 64, r, 4), dtype=torch.int16, device="cuda")
+    valsT = torch.zeros((r // 64, q, 32), dtype=dt, device="cuda")
+    metaT = torch.zeros((r // 64, q, 4), dtype=torch.int16, device="cuda")
     mask_out = torch.zeros((r // 4, q // 4), dtype=torch.int16, device="cuda")
     s24.compress(Wd, None if mask is None else dev(mask), vals, meta, valsT, metaT, mask_out=mask_out)
     torch.cuda.synchronize()
@@ -93,13 +99,14 @@ def test_mask_strided_weight_and_empty(s24):
 
 # ------------------------------------------------------------------ compress
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("shape", [(16, 16), (128, 128), (272, 400), (528, 144)])
+@pytest.mark.parametrize("shape", [(64, 64), (128, 128), (320, 448), (576, 192)])
 @pytest.mark.parametrize("fused", [False, True])
 def test_compress_bit_exact(s24, dtype, shape, fused):
     W = si.random_matrix(200 + shape[1], shape, 0.02, dtype)
     W[0:4, 0:8] = 0
     mask = oracle.transposable_mask(W)
-    want = oracle.compress(W, mask)
+    c = oracle.compress(W, mask)
+    want = oracle.pack(c[0], c[1]) + oracle.pack(c[2], c[3])
     vals, meta, valsT, metaT, mask_out = gpu_compress(s24, W, None if fused else mask)
     if fused:
         assert np.array_equal(host_bits(mask_out), mask)
@@ -111,7 +118,8 @@ def test_compress_bit_exact(s24, dtype, shape, fused):
 def test_compress_tie_matrix_fused(s24):
     W = si.tie_matrix(3, 128, 256, "bf16", "few")
     mask = oracle.transposable_mask(W)
-    want = oracle.compress(W, mask)
+    c = oracle.compress(W, mask)
+    want = oracle.pack(c[0], c[1]) + oracle.pack(c[2], c[3])
     got = gpu_compress(s24, W, None)
     assert np.array_equal(host_bits(got[4]), mask)
     for g, ref in zip(got[:4], want):
@@ -132,7 +140,7 @@ def test_spmm_fwd(s24, dtype, pqr):
     X = si.random_matrix(301 + p, (p, q), 1.0, dtype)
     mask, vals, meta, valsT, metaT = compressed(W)
     Y = torch.full((p, r), 7.0, dtype=tdtype(dtype), device="cuda")
-    s24.spmm_fwd(dev_bf16(X), dev_bf16(vals), dev(meta), Y)
+    s24.spmm_fwd(dev_bf16(X), *packed(vals, meta), Y)
     torch.cuda.synchronize()
     assert_close(host_f64(Y), oracle.spmm_fwd(X, vals, meta), tol(dtype), f"spmm_fwd {pqr}")
 
@@ -147,7 +155,7 @@ def test_spmm_bwd_dx(s24, dtype, pqr, beta):
     dX0 = si.random_matrix(312, (p, q), 1e-3, dtype)
     mask, vals, meta, valsT, metaT = compressed(W)
     dX = dev_bf16(dX0).clone()
-    s24.spmm_bwd_dx(dev_bf16(dY), dev_bf16(valsT), dev(metaT), dX, beta=beta)
+    s24.spmm_bwd_dx(dev_bf16(dY), *packed(valsT, metaT), dX, beta=beta)
     torch.cuda.synchronize()
     ref = oracle.spmm_bwd_dx(dY, valsT, metaT, beta=beta, dX0=si.to_f32(dX0).astype(np.float64))
     assert_close(host_f64(dX), ref, tol(dtype), f"spmm_bwd_dx {pqr} beta={beta}")
@@ -164,14 +172,14 @@ def test_spmm_large_tile_path(s24, k):
     rows = np.unique(np.concatenate([[0, 255, 256, p - 1], np.random.default_rng(k).integers(0, p, 40)])).astype(np.int64)
     ridx = torch.from_numpy(rows).cuda()
     Y = torch.full((p, r), 3.0, dtype=torch.bfloat16, device="cuda")
-    s24.spmm_fwd(dev_bf16(X), dev_bf16(vals), dev(meta), Y)
+    s24.spmm_fwd(dev_bf16(X), *packed(vals, meta), Y)
     torch.cuda.synchronize()
     assert_close(host_f64(Y[ridx]), oracle.spmm_fwd(X, vals, meta, rows=rows), BF16_TOL, f"large spmm_fwd k={k}")
     # the same operands as an input-gradient GEMM: dX[p][r'] with r' = 2000 features, contraction k
     # (valsT of a [k x 2000] weight is a [2000 x k/2] operand, which is what `vals` already is)
     dX0 = si.random_matrix(332, (p, r), 1e-2, "bf16")
     dX = dev_bf16(dX0).clone()
-    s24.spmm_bwd_dx(dev_bf16(X), dev_bf16(vals), dev(meta), dX, beta=1.0)
+    s24.spmm_bwd_dx(dev_bf16(X), *packed(vals, meta), dX, beta=1.0)
     torch.cuda.synchronize()
     ref = oracle.spmm_bwd_dx(X, vals, meta, beta=1.0, dX0=si.to_f32(dX0[rows]).astype(np.float64), rows=rows)
     assert_close(host_f64(dX[ridx]), ref, BF16_TOL, f"large spmm_bwd_dx k={k}")
@@ -183,7 +191,7 @@ def test_spmm_one_hot_reproduces_masked_weight_exactly(s24):
     mask, vals, meta, valsT, metaT = compressed(W)
     eye = dev_bf16(si.f32_to_bf16_bits(torch.eye(q)))
     Y = torch.zeros((q, r), dtype=torch.bfloat16, device="cuda")
-    s24.spmm_fwd(eye, dev_bf16(vals), dev(meta), Y)
+    s24.spmm_fwd(eye, *packed(vals, meta), Y)
     torch.cuda.synchronize()
     ref = oracle.spmm_fwd(si.f32_to_bf16_bits(torch.eye(q)), vals, meta)
     assert np.array_equal(host_f64(Y), ref)       # products with 1 and sums with 0 are exact

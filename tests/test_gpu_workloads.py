@@ -128,10 +128,10 @@ def test_workload_full_size(s24, name):
         W = t[n]
         r, q = W.shape
         Wd = dev_bf16(W)
-        vals = torch.zeros((r, q // 2), dtype=torch.bfloat16, device="cuda")
-        meta = torch.zeros((r, q // 16), dtype=torch.int16, device="cuda")
-        valsT = torch.zeros((q, r // 2), dtype=torch.bfloat16, device="cuda")
-        metaT = torch.zeros((q, r // 16), dtype=torch.int16, device="cuda")
+        vals = torch.zeros((q // 64, r, 32), dtype=torch.bfloat16, device="cuda")
+        meta = torch.zeros((q // 64, r, 4), dtype=torch.int16, device="cuda")
+        valsT = torch.zeros((r // 64, q, 32), dtype=torch.bfloat16, device="cuda")
+        metaT = torch.zeros((r // 64, q, 4), dtype=torch.int16, device="cuda")
         mask = torch.zeros((r // 4, q // 4), dtype=torch.int16, device="cuda")
         mask2 = torch.zeros_like(mask)
         s24.compress(Wd, None, vals, meta, valsT, metaT, mask_out=mask)
@@ -141,8 +141,10 @@ def test_workload_full_size(s24, name):
         assert np.array_equal(host_bits(mask), want_mask), f"{name} {n} fused mask"
         assert np.array_equal(host_bits(mask2), want_mask), f"{name} {n} mask"
         want = oracle.compress(W, want_mask)
-        for got, ref, what in zip((vals, meta, valsT, metaT), want, ("vals", "meta", "valsT", "metaT")):
+        want_packed = oracle.pack(want[0], want[1]) + oracle.pack(want[2], want[3])
+        for got, ref, what in zip((vals, meta, valsT, metaT), want_packed, ("vals", "meta", "valsT", "metaT")):
             assert np.array_equal(host_bits(got), ref), f"{name} {n} {what}"
+        del want_packed
         # masked decay on a sampled band of rows (the kernel runs over the whole matrix)
         G = torch.zeros((r, q), dtype=torch.float32, device="cuda")
         s24.masked_decay_grad(G, Wd, mask, wl.lam)

@@ -67,10 +67,11 @@ def test_mask_argument_errors(lib):
 
 def test_compress_argument_errors(lib):
     f = lib.s24_compress
-    assert f(P, 1, 16, 16, 16, None, None, P, P, P, None, None) == NULL
-    assert f(P, 1, 16, 24, 24, None, P, P, P, P, None, None) == SHAPE    # q not a multiple of 16
-    assert f(P, 1, 16, 16, 16, None, P + 4, P, P, P, None, None) == ALIGN
-    assert f(P, 1, 0, 16, 16, None, P, P, P, P, None, None) == OK
+    assert f(P, 1, 64, 64, 64, None, None, P, P, P, None, None) == NULL
+    assert f(P, 1, 64, 96, 96, None, P, P, P, P, None, None) == SHAPE    # q not a multiple of 64
+    assert f(P, 1, 16, 64, 64, None, P, P, P, P, None, None) == SHAPE    # r not a multiple of 64
+    assert f(P, 1, 64, 64, 64, None, P + 4, P, P, P, None, None) == ALIGN
+    assert f(P, 1, 0, 64, 64, None, P, P, P, P, None, None) == OK
 
 
 def test_gemm_argument_errors(lib):
