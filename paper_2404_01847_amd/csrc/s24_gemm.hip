@@ -416,12 +416,15 @@ __global__ __launch_bounds__(kThreads) void dense_nt_kernel(const uint16_t *__re
 // (64 t x 128 m), threads 128..255 the X tile (64 t x 128 n).
 struct Sub8 { uint4 r[8]; };
 
+// Rows at or past T read as zero (their products must vanish); columns past ncols are
+// clamped to the last valid group, their results are never stored.  T >= 1.
 __device__ __forceinline__ void sub8_load(Sub8 &s, const uint16_t *g, int64_t ld, int t0, int T, int col, int ncols)
 {
+    const int c = min(col, ncols - 8);
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        if (t0 + k < T && col < ncols) s.r[k] = *reinterpret_cast<const uint4 *>(g + (int64_t)(t0 + k) * ld + col);
-        else s.r[k] = make_uint4(0, 0, 0, 0);
+        const uint4 v = *reinterpret_cast<const uint4 *>(g + (int64_t)min(t0 + k, T - 1) * ld + c);
+        s.r[k] = (t0 + k < T) ? v : make_uint4(0, 0, 0, 0);
     }
 }
 
@@ -492,6 +495,99 @@ __global__ __launch_bounds__(kThreads) void dense_tn_kernel(const uint16_t *__re
     }
 }
 
+// ------------------------------------------------------------------ dense TN (dW), large tile
+// Workgroup tile 256 (m) x 256 (n) x 64 (t), eight waves as 2 x 4, each wave
+// 128 x 64.  Staging as in the small kernel (8x8 register transposes), one
+// sub-block per thread: threads 0..255 the dY tile, 256..511 the X tile.  Two
+// LDS stages of 64 KB; the global loads of chunk kc+1 are issued before the
+// math of chunk kc and written to the other stage after it.
+namespace bigtn {
+constexpr int BM = 256, BN = 256, THREADS = 512, OPERAND = 256 * 128;
+
+template <bool ACCUM>
+__global__ __launch_bounds__(THREADS) void dense_tn_big_kernel(const uint16_t *__restrict__ dY,
+                                                               const uint16_t *__restrict__ X, float *__restrict__ dW,
+                                                               int T, int M, int N, int tiles_m, int tiles_n)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char s_a[2][OPERAND];
+    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][OPERAND];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8;
+    const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (t >= total) return;
+    constexpr int GROUP = 8;
+    const int group_sz = GROUP * tiles_m, grp = t / group_sz, in_grp = t - grp * group_sz;
+    const int gw = min(GROUP, tiles_n - grp * GROUP);
+    const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int nk = (T + 63) / 64;
+
+    const bool is_a = tid < 256;
+    const int sid = tid & 255;
+    const int scol = (sid & 31) * 8, stc = sid >> 5;  // 32 column groups x 8 t-chunks
+    const uint16_t *src = is_a ? dY : X;
+    const int64_t ld = is_a ? M : N;
+    const int gcol = (is_a ? m0 : n0) + scol, ncols = is_a ? M : N;
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+
+    // The staged sub-block of chunk kc+1 sits in registers while chunk kc is multiplied; it is
+    // transposed and written to the other LDS stage between the two halves of the chunk's math,
+    // so that those writes run under the matrix pipe, and the loads of chunk kc+2 follow at once.
+    Sub8 sub;
+    sub8_load(sub, src, ld, 8 * stc, T, gcol, ncols);
+    sub8_transpose_store(sub, is_a ? s_a[0] : s_b[0], scol, stc);
+    if (nk > 1) sub8_load(sub, src, ld, 64 + 8 * stc, T, gcol, ncols);
+    __syncthreads();
+    const int g = lane >> 5;
+    auto ksteps = [&](const unsigned char *sa, const unsigned char *sb, int i0) {
+#pragma unroll
+        for (int i = i0; i < i0 + 2; ++i) {
+            bf16x8 a[4], b[2];
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi) a[mi] = as_bf16x8(lds_read(sa, 128 * wm + 32 * mi + (lane & 31), 4 * g + i));
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) b[ni] = as_bf16x8(lds_read(sb, 64 * wn + 32 * ni + (lane & 31), 4 * g + i));
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+        }
+    };
+    for (int kc = 0; kc < nk; ++kc) {
+        const unsigned char *sa = s_a[kc & 1], *sb = s_b[kc & 1];
+        ksteps(sa, sb, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kc + 1 < nk) sub8_transpose_store(sub, is_a ? s_a[(kc + 1) & 1] : s_b[(kc + 1) & 1], scol, stc);
+        if (kc + 2 < nk) sub8_load(sub, src, ld, (kc + 2) * 64 + 8 * stc, T, gcol, ncols);
+        __builtin_amdgcn_sched_barrier(0);
+        ksteps(sa, sb, 2);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+        if (n >= N) continue;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = m0 + 128 * wm + 32 * mi + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                if (m >= M) continue;
+                float *dst = dW + (int64_t)m * N + n;
+                *dst = ACCUM ? (*dst + acc[mi][ni][i]) : acc[mi][ni][i];
+            }
+    }
+}
+}  // namespace bigtn
+
 // ------------------------------------------------------------------ fp32 fallbacks (small correctness workload)
 // One thread per output element, plain fp32 FMA; no matrix-core claim.
 template <bool ACCUM>
@@ -533,6 +629,12 @@ __global__ __launch_bounds__(kThreads) void dense_tn_f32_kernel(const float *__r
     float acc = 0.0f;
     for (int64_t t = 0; t < T; ++t) acc = fmaf(dY[t * M + m], X[t * N + n], acc);
     dW[idx] = ACCUM ? dW[idx] + acc : acc;
+}
+
+__global__ __launch_bounds__(kThreads) void fill_zero_kernel(float *__restrict__ p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
 }
 
 inline unsigned ceil_div(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
@@ -635,9 +737,27 @@ extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p,
     S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
     const int rc = check_gemm(dY, X, dW, p, q, r, dt, q * r);
     if (rc != S24_OK || q * r == 0) return rc;
+    if (p == 0) {  // empty contraction: dW = beta * dW (the GEMM kernels need at least one token)
+        if (beta == 0.0f) {
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(ceil_div(q * r, kThreads)), dim3(kThreads), 0,
+                               static_cast<hipStream_t>(stream), dW, q * r);
+            return s24_launch_status();
+        }
+        return S24_OK;
+    }
     const bool accum = beta != 0.0f;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt == S24_BF16) {
+    if (dt == S24_BF16 && (int64_t)ceil_div(r, bigtn::BM) * ceil_div(q, bigtn::BN) >= 192) {
+        const int tiles_m = (int)ceil_div(r, bigtn::BM), tiles_n = (int)ceil_div(q, bigtn::BN);
+        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(bigtn::THREADS);
+        auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
+        if (accum)
+            hipLaunchKernelGGL(bigtn::dense_tn_big_kernel<true>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
+                               tiles_m, tiles_n);
+        else
+            hipLaunchKernelGGL(bigtn::dense_tn_big_kernel<false>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
+                               tiles_m, tiles_n);
+    } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(r, BM), ceil_div(q, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
         auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);

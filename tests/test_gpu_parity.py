@@ -214,6 +214,33 @@ def test_dense_dw(s24, dtype, pqr, beta):
     assert_close(host_f64(dW), ref, F32_TOL, f"dense_dw {pqr} beta={beta}")
 
 
+@pytest.mark.parametrize("p", [1, 64, 130, 200])
+@pytest.mark.parametrize("beta", [0.0, 1.0])
+def test_dense_dw_large_tile_path(s24, p, beta):
+    """At least 192 tiles of 256 x 256 take the large-tile kernel: ragged feature tails and token counts."""
+    q, r = 6096, 2000
+    dY = si.random_matrix(430 + p, (p, r), 1e-2, "bf16")
+    X = si.random_matrix(431 + p, (p, q), 1.0, "bf16")
+    dW0 = si.random_matrix(432, (r, q), 1e-2, "f32")
+    dW = dev(dW0).clone()
+    s24.dense_dw(dev_bf16(dY), dev_bf16(X), dW, beta=beta)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 255, 256, r - 1], np.random.default_rng(p).integers(0, r, 24)])).astype(np.int64)
+    ref = oracle.dense_dw(dY, X, beta=beta, dW0=dW0[rows].astype(np.float64), rows=rows)
+    assert_close(host_f64(dW[torch.from_numpy(rows).cuda()]), ref, F32_TOL, f"large dense_dw p={p} beta={beta}")
+
+
+def test_dense_dw_no_tokens(s24):
+    dW = torch.full((64, 128), 5.0, dtype=torch.float32, device="cuda")
+    # with no tokens the operand pointers are never read: any aligned non-null value will do
+    assert s24.lib().s24_dense_dw(0x1000, 0x1000, dW.data_ptr(), 0, 128, 64, 1.0, s24.BF16, None) == 0
+    torch.cuda.synchronize()
+    assert (dW == 5.0).all()                       # beta = 1 keeps the gradient
+    assert s24.lib().s24_dense_dw(0x1000, 0x1000, dW.data_ptr(), 0, 128, 64, 0.0, s24.BF16, None) == 0
+    torch.cuda.synchronize()
+    assert (dW == 0.0).all()                       # beta = 0 clears it
+
+
 def test_dense_dw_rank_one_is_exact(s24):
     dY = si.random_matrix(410, (1, 144), 1.0, "bf16")
     X = si.random_matrix(411, (1, 208), 1.0, "bf16")
