@@ -110,6 +110,49 @@ def cpu_baseline(wl, tensors_host, budget_tokens=16):
     }
 
 
+def _time_ms(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def side_measurements(torch, s24, wl, ffn, X):
+    """Outside the timed step: (1) the mask search alone, over all weights of the layer in turn
+    (34 algorithmic bytes per 4x4 bf16 block: 32 read, 2 written); (2) the dense-MFMA GEMM of the
+    library next to the sparse GEMM, on the up-projection shape."""
+    out = {}
+    es = 2 if wl.dtype == "bf16" else 4
+    ws = list(ffn.w.values())
+    masks = [torch.empty_like(w.mask) for w in ws]
+
+    def sweep():
+        for w, m in zip(ws, masks):
+            s24.transposable_mask(w.W, m, None)
+
+    ms = _time_ms(torch, sweep, 10)
+    nbytes = sum(w.W.numel() / 16 * (16 * es + 2) for w in ws)
+    out["mask_search_only"] = {"ms_per_sweep": round(ms, 4), "matrices": len(ws), "GB/s": round(nbytes / ms / 1e6, 1),
+                               "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM, 4)}
+    if wl.dtype == "bf16":
+        up = ws[0]
+        Yd = torch.empty((wl.p, up.W.shape[0]), dtype=X.dtype, device=X.device)
+        flops = 2.0 * wl.p * wl.d_model * wl.d_ff
+        t_dense = _time_ms(torch, lambda: s24.dense_gemm(X, up.W, Yd), 5)
+        t_sparse = _time_ms(torch, lambda: s24.spmm_fwd(X, up.vals, up.meta, Yd), 5)
+        out["dense_vs_sparse_up_projection"] = {
+            "shape_p_q_r": [wl.p, wl.d_model, wl.d_ff],
+            "dense_mfma_ms": round(t_dense, 4), "dense_mfma_TFLOP/s": round(flops / t_dense / 1e9, 1),
+            "sparse_smfmac_ms": round(t_sparse, 4), "sparse_dense_equiv_TFLOP/s": round(flops / t_sparse / 1e9, 1),
+            "speedup": round(t_dense / t_sparse, 3)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +160,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the measurements outside the timed step")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a 1 GiB device-to-device copy five times (reference for HBM byte counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1. "
@@ -131,6 +177,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}))
+        return
     wl = si.WORKLOADS[args.workload]
     host = si.make(wl)
 
@@ -154,6 +208,8 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = wl.gemm_flops / (ms_per_step * 1e-3) / 1e12
+
+    extras = None if args.no_extras else side_measurements(torch, s24, wl, ffn, X)
 
     model = kernel_model(wl)
     kernels = {}
@@ -181,6 +237,7 @@ def main():
         "pct_of_sparse_mfma_peak_whole_step": round(100 * value / PEAK_SPARSE_BF16, 2),
         "roofline": roofline,
         "kernels": kernels,
+        "extras": extras,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, host)

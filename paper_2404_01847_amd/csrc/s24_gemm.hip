@@ -495,6 +495,108 @@ __global__ __launch_bounds__(kThreads) void dense_tn_kernel(const uint16_t *__re
     }
 }
 
+// ------------------------------------------------------------------ dense NT, large tile
+// The dense comparison GEMM in the same tiling family as the sparse kernel:
+// 256 x 256 x 64 workgroup tiles, eight waves of 128 x 64, both operands copied
+// straight into LDS.  A dense operand tile is twice the compressed one, so the
+// ring has two 64 KB stages: the copies of chunk kc+1 fly during the math of kc.
+namespace bignt {
+constexpr int BM = 256, BN = 256, THREADS = 512, OPERAND = 256 * 128;
+using big::b_slot;
+using big::glb_ptr;
+using big::lds_ptr;
+using big::wait_vm_lgkm0;
+
+__global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *__restrict__ X,
+                                                               const uint16_t *__restrict__ W, uint16_t *__restrict__ Y,
+                                                               int N, int K, int M, int tiles_m, int tiles_n)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char s0[2 * OPERAND];
+    __shared__ __attribute__((aligned(16))) unsigned char s1[2 * OPERAND];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8;
+    const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (t >= total) return;
+    constexpr int GROUP = 8;
+    const int group_sz = GROUP * tiles_m, grp = t / group_sz, in_grp = t - grp * group_sz;
+    const int gw = min(GROUP, tiles_n - grp * GROUP);
+    const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int nk = K / 64;
+
+    const uint16_t *gx[4], *gw_[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 32 * wave + 8 * i + (lane >> 3);
+        const int c = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
+        gx[i] = X + (int64_t)min(n0 + row, N - 1) * K + 8 * c;
+        gw_[i] = W + (int64_t)min(m0 + row, M - 1) * K + 8 * c;
+    }
+    auto issue = [&](unsigned char *st, int kc) {   // eight copies per lane: X rows then W rows
+        kc = min(kc, nk - 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((glb_ptr)(gx[i] + (int64_t)kc * 64), (lds_ptr)(st + (32 * wave + 8 * i) * 128), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((glb_ptr)(gw_[i] + (int64_t)kc * 64), (lds_ptr)(st + OPERAND + (32 * wave + 8 * i) * 128), 16, 0, 0);
+    };
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+    issue(s0, 0);
+    auto chunk = [&](const unsigned char *cur, unsigned char *other, int kc) {
+        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // this lane's copies of chunk kc are in LDS
+        __builtin_amdgcn_s_barrier();                   // everyone's are, and `other` is no longer read
+        issue(other, kc + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        const unsigned char *sb = cur, *sa = cur + OPERAND;
+        const int g = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            bf16x8 a[4], b[2];
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+                a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + b_slot(128 * wm + 32 * mi + (lane & 31), 4 * g + i)));
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                b[ni] = as_bf16x8(*reinterpret_cast<const uint4 *>(sb + b_slot(64 * wn + 32 * ni + (lane & 31), 4 * g + i)));
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+        }
+    };
+    int kc = 0;
+    for (; kc + 2 <= nk; kc += 2) {
+        chunk(s0, s1, kc);
+        chunk(s1, s0, kc + 1);
+    }
+    if (kc < nk) chunk(s0, s1, kc);
+    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // drain the last (redundant) copies before LDS is released
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+        if (n >= N) continue;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int m = m0 + 128 * wm + 32 * mi + 8 * g4 + 4 * (lane >> 5);
+                if (m >= M) continue;
+                *reinterpret_cast<uint2 *>(Y + (int64_t)n * M + m) =
+                    make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g4], acc[mi][ni][4 * g4 + 1]),
+                               s24_pack_bf16x2(acc[mi][ni][4 * g4 + 2], acc[mi][ni][4 * g4 + 3]));
+            }
+    }
+}
+}  // namespace bignt
+
 // ------------------------------------------------------------------ dense TN (dW), large tile
 // Workgroup tile 256 (m) x 256 (n) x 64 (t), eight waves as 2 x 4, each wave
 // 128 x 64.  Staging as in the small kernel (8x8 register transposes), one
@@ -718,7 +820,12 @@ extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, 
     const int rc = check_gemm(X, W, Y, p, q, r, dt, p * r);
     if (rc != S24_OK || p * r == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt == S24_BF16) {
+    if (dt == S24_BF16 && (int64_t)ceil_div(r, bignt::BM) * ceil_div(p, bignt::BN) >= 192) {
+        const int tiles_m = (int)ceil_div(r, bignt::BM), tiles_n = (int)ceil_div(p, bignt::BN);
+        hipLaunchKernelGGL(bignt::dense_nt_big_kernel, dim3(((tiles_m * tiles_n + 7) / 8) * 8), dim3(bignt::THREADS), 0, st,
+                           static_cast<const uint16_t *>(X), static_cast<const uint16_t *>(W), static_cast<uint16_t *>(Y),
+                           (int)p, (int)q, (int)r, tiles_m, tiles_n);
+    } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(r, BM), ceil_div(p, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
         hipLaunchKernelGGL(dense_nt_kernel, grid, block, 0, st, static_cast<const uint16_t *>(X),

@@ -262,6 +262,19 @@ def test_dense_gemm(s24, dtype, pqr):
     assert_close(host_f64(Y), oracle.dense_gemm(X, W), tol(dtype), f"dense_gemm {pqr}")
 
 
+@pytest.mark.parametrize("k", [64, 128, 192, 320])
+def test_dense_gemm_large_tile_path(s24, k):
+    p, r = 6100, 2000
+    X = si.random_matrix(440 + k, (p, k), 1.0, "bf16")
+    W = si.random_matrix(441 + k, (r, k), 0.02, "bf16")
+    Y = torch.full((p, r), 3.0, dtype=torch.bfloat16, device="cuda")
+    s24.dense_gemm(dev_bf16(X), dev_bf16(W), Y)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 255, 256, p - 1], np.random.default_rng(k).integers(0, p, 40)])).astype(np.int64)
+    assert_close(host_f64(Y[torch.from_numpy(rows).cuda()]), oracle.dense_gemm(X, W, rows=rows), BF16_TOL,
+                 f"large dense_gemm k={k}")
+
+
 # ------------------------------------------------------------------ masked decay
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(16, 16), (260, 400), (128, 1024)])
