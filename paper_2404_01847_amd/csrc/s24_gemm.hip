@@ -184,6 +184,56 @@ __device__ __forceinline__ int a_slot(int row, int c) { return row * 64 + ((c ^ 
 // s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt unconstrained
 __host__ __device__ constexpr int wait_vm_lgkm0(int n) { return (n & 15) | (7 << 4) | ((n >> 4) << 14); }
 
+// Workgroup barrier that leaves up to VM vector-memory operations (direct-to-LDS copies of later
+// chunks) in flight.  The raw wait and barrier instructions carry no memory semantics for the
+// compiler, so they are fenced on both sides against reordering of LDS accesses, in the
+// optimiser (empty asm with a memory clobber) and in the instruction scheduler.
+template <int VM>
+__device__ __forceinline__ void wait_and_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(VM));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+}
+
+// Output of one wave's 64 (n) x 128 (m) accumulator tile as bf16.  The wave parks the tile in LDS as
+// 64 rows of 256 bytes and streams it out 16 bytes per lane, 16 lanes covering one 256-byte row
+// segment of the output.  Inside a row the 8-byte unit u is stored at u ^ (row & 31), so the
+// accumulator writes of 32 consecutive rows (same u) fall on distinct banks; a 16-byte read gets
+// units 2c and 2c+1 from one aligned slot, in swapped order on odd rows.
+// `estage` is EWAVE bytes of LDS private to the wave and no longer used for anything else.
+constexpr int EWAVE = 64 * 256;
+__device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned char *estage, uint16_t *__restrict__ Out,
+                                             int N, int M, int n_base, int m_base, int lane)
+{
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int nl = 32 * ni + (lane & 31), u = 8 * mi + 2 * g4 + (lane >> 5);
+                *reinterpret_cast<uint2 *>(estage + nl * 256 + ((u ^ (nl & 31)) << 3)) =
+                    make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g4], acc[mi][ni][4 * g4 + 1]),
+                               s24_pack_bf16x2(acc[mi][ni][4 * g4 + 2], acc[mi][ni][4 * g4 + 3]));
+            }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
+    asm volatile("" ::: "memory");
+#pragma unroll 4
+    for (int j = 0; j < 16; ++j) {
+        const int nl = 4 * j + (lane >> 4), c = lane & 15;
+        const int n = n_base + nl, m = m_base + 8 * c;
+        if (n >= N || m >= M) continue;   // M is a multiple of 16 (and of 8): a chunk is all in or all out
+        const int x = nl & 31;
+        const uint4 v = *reinterpret_cast<const uint4 *>(estage + nl * 256 + ((((2 * c) ^ x) & ~1) << 3));
+        *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + m) = (x & 1) ? make_uint4(v.z, v.w, v.x, v.y) : v;
+    }
+}
+
 template <bool ACCUM>
 __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ Av,
@@ -205,7 +255,7 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8;
     const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if (t >= total) return;
-    constexpr int GROUP = 8;
+    constexpr int GROUP = 4;   // 4 token tiles x 8 feature tiles resident per XCD: least unique bytes per round
     const int group_sz = GROUP * tiles_m, grp = t / group_sz, in_grp = t - grp * group_sz;
     const int gw = min(GROUP, tiles_n - grp * GROUP);
     const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
@@ -259,8 +309,7 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     auto chunk = [&](const unsigned char *cur, unsigned char *refill, int kc) {
         // all but the seven most recent vector-memory operations (the copies of chunk kc+1) are
         // complete, so this lane's part of chunk kc is in LDS; its own LDS reads are done too
-        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(7));
-        __builtin_amdgcn_s_barrier();   // everybody's part landed; everybody finished reading `refill`
+        wait_and_barrier<7>();   // everybody's part landed; everybody finished reading `refill`
         issue(refill, kc + 2);
         __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sb = cur, *sa = cur + B_STAGE, *sm = cur + B_STAGE + A_STAGE;
@@ -303,34 +352,33 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     }
     if (kc < nk) chunk(s0, s2, kc);
     if (kc + 1 < nk) chunk(s1, s0, kc + 1);
-    // drain the copies still in flight before the workgroup's LDS is released
-    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));
-
+    // drain the copies still in flight, then reuse the ring as a staging area for the output tile
+    wait_and_barrier<0>();
+    if constexpr (ACCUM) {
+        // beta = 1: add the old output in fp32 straight from the accumulators (a single rounding)
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
-        if (n >= N) continue;
+        for (int ni = 0; ni < 2; ++ni) {
+            const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+            if (n >= N) continue;
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
+            for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int m = m0 + 128 * wm + 32 * mi + 8 * g4 + 4 * (lane >> 5);
-                if (m >= M) continue;
-                uint2 *dst = reinterpret_cast<uint2 *>(Out + (int64_t)n * M + m);
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][4 * g4 + e];
-                if (ACCUM) {
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int m = m0 + 128 * wm + 32 * mi + 8 * g4 + 4 * (lane >> 5);
+                    if (m >= M) continue;
+                    uint2 *dst = reinterpret_cast<uint2 *>(Out + (int64_t)n * M + m);
                     const uint2 old = *dst;
-                    v[0] += s24_bf16_to_f32(old.x & 0xFFFFu);
-                    v[1] += s24_bf16_to_f32(old.x >> 16);
-                    v[2] += s24_bf16_to_f32(old.y & 0xFFFFu);
-                    v[3] += s24_bf16_to_f32(old.y >> 16);
+                    *dst = make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g4] + s24_bf16_to_f32(old.x & 0xFFFFu),
+                                                      acc[mi][ni][4 * g4 + 1] + s24_bf16_to_f32(old.x >> 16)),
+                                      s24_pack_bf16x2(acc[mi][ni][4 * g4 + 2] + s24_bf16_to_f32(old.y & 0xFFFFu),
+                                                      acc[mi][ni][4 * g4 + 3] + s24_bf16_to_f32(old.y >> 16)));
                 }
-                *dst = make_uint2(s24_pack_bf16x2(v[0], v[1]), s24_pack_bf16x2(v[2], v[3]));
-            }
         }
+        return;
     }
+    static_assert(3 * EWAVE <= STAGE, "three wave tiles must fit one ring stage");
+    staged_store(acc, (wave < 3 ? s0 : (wave < 6 ? s1 : s2)) + (wave % 3) * EWAVE, Out, N, M, n0 + 64 * wn,
+                 m0 + 128 * wm, lane);
 }
 }  // namespace big
 
@@ -550,8 +598,7 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
         for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
     issue(s0, 0);
     auto chunk = [&](const unsigned char *cur, unsigned char *other, int kc) {
-        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // this lane's copies of chunk kc are in LDS
-        __builtin_amdgcn_s_barrier();                   // everyone's are, and `other` is no longer read
+        big::wait_and_barrier<0>();   // everyone's copies of chunk kc are in LDS, and `other` is no longer read
         issue(other, kc + 1);
         __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sb = cur, *sa = cur + OPERAND;
@@ -578,22 +625,8 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
         chunk(s1, s0, kc + 1);
     }
     if (kc < nk) chunk(s0, s1, kc);
-    __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // drain the last (redundant) copies before LDS is released
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
-        if (n >= N) continue;
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int m = m0 + 128 * wm + 32 * mi + 8 * g4 + 4 * (lane >> 5);
-                if (m >= M) continue;
-                *reinterpret_cast<uint2 *>(Y + (int64_t)n * M + m) =
-                    make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g4], acc[mi][ni][4 * g4 + 1]),
-                               s24_pack_bf16x2(acc[mi][ni][4 * g4 + 2], acc[mi][ni][4 * g4 + 3]));
-            }
-    }
+    big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
+    big::staged_store(acc, (wave < 4 ? s0 : s1) + (wave & 3) * big::EWAVE, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
 }
 }  // namespace bignt
 
