@@ -11,12 +11,15 @@
 // separately ("top" and "bottom" halves) and matched through the column-count
 // vector of the top half, which leaves 19 classes:
 //   6  where both top rows use the same pair (bottom rows both use its
-//      complement),
-//   1  where the top rows use complementary pairs (so do the bottom rows),
-//   12 where the top rows share exactly one column x and miss one column w.
-// That is 24 + 72 + 19 additions and 53 maxima per block instead of 90 x 7
+//      complement): four column sums of the halves;
+//   1  where the top rows use complementary pairs (so do the bottom rows):
+//      one whole row plus the two largest per-column gains of the other row;
+//   12 where the top rows share exactly one column x and miss one column w:
+//      column sum x (top) + column sum w (bottom) + the better crossing of the
+//      two remaining columns in each half, which only depends on that pair.
+// That is about 100 additions and 45 maxima per block instead of 90 x 7
 // additions, and yields the same maximum because every legal block falls in
-// exactly one class.
+// exactly one class and each class maximum is taken over exactly its blocks.
 //
 // Exactness and tie-break.  Scores are held in fp64.  Let 2^(E+1) bound the
 // largest magnitude of the block and eps = 2^(E-47).  If every nonzero
@@ -95,6 +98,68 @@ constexpr PatList make_patlist()
     return p;
 }
 __device__ const PatList g_patterns = make_patlist();
+
+// What the compressor needs for a bf16 block, precomputed per pattern id (48 bytes each).
+// A selector is a v_perm_b32 byte selector that picks two of the four 16-bit values held in a
+// register pair {hi : lo} (positions 2,3 : positions 0,1) and packs them into one dword.
+struct CompressEntry {
+    uint32_t rowsel[4];   // row i: its two kept columns out of {cols 2,3 : cols 0,1}
+    uint32_t colsel[4];   // column j: its two kept rows out of {rows 2,3 : rows 0,1}
+    uint32_t rowmeta_lo;  // metadata nibbles of rows 0 and 1 at bits 0 and 16
+    uint32_t rowmeta_hi;  // rows 2 and 3
+    uint32_t colmeta;     // nibbles of columns 0..3 at bits 0, 4, 8, 12
+    uint32_t pad;
+};
+struct CompressLut {
+    CompressEntry e[S24_NUM_PATTERNS];
+};
+constexpr uint32_t perm_selector(int p0, int p1)
+{
+    return (uint32_t)(2 * p0) | ((uint32_t)(2 * p0 + 1) << 8) | ((uint32_t)(2 * p1) << 16) | ((uint32_t)(2 * p1 + 1) << 24);
+}
+constexpr CompressLut make_compress_lut()
+{
+    CompressLut t{};
+    const PatList pl = make_patlist();
+    for (int id = 0; id < S24_NUM_PATTERNS; ++id) {
+        const unsigned m = pl.mask[id];
+        uint32_t rowmeta[4] = {0, 0, 0, 0};
+        for (int i = 0; i < 4; ++i) {
+            int kept[2] = {0, 0}, n = 0;
+            for (int j = 0; j < 4; ++j)
+                if ((m >> (4 * i + j)) & 1u) kept[n++] = j;
+            t.e[id].rowsel[i] = perm_selector(kept[0], kept[1]);
+            rowmeta[i] = (uint32_t)(kept[0] | (kept[1] << 2));
+        }
+        t.e[id].rowmeta_lo = rowmeta[0] | (rowmeta[1] << 16);
+        t.e[id].rowmeta_hi = rowmeta[2] | (rowmeta[3] << 16);
+        for (int j = 0; j < 4; ++j) {
+            int kept[2] = {0, 0}, n = 0;
+            for (int i = 0; i < 4; ++i)
+                if ((m >> (4 * i + j)) & 1u) kept[n++] = i;
+            t.e[id].colsel[j] = perm_selector(kept[0], kept[1]);
+            t.e[id].colmeta |= (uint32_t)(kept[0] | (kept[1] << 2)) << (4 * j);
+        }
+    }
+    return t;
+}
+__device__ const CompressLut g_clut = make_compress_lut();
+
+// Pattern id of a given block mask through the bonus-indexed table: row nibble -> pair index k
+// (0 for anything illegal), then the same mixed-radix index the search produces.
+__device__ __forceinline__ unsigned lut_index_of_mask(unsigned m)
+{
+    unsigned x = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const unsigned m4 = (m >> (4 * i)) & 0xFu;
+        // k for m4 = 3,5,6 in the low word (4 bits each), for m4 = 9,10,12 in the high word
+        const unsigned tbl = (m4 & 8u) ? 0x00000130u : 0x02405000u;
+        const unsigned k = (tbl >> (4 * (m4 & 7u))) & 7u;
+        x = x * 6u + (5u - k);
+    }
+    return x;
+}
 
 // ---------------------------------------------------------------------------
 // Slow path: exact scores of all 90 patterns in fixed point.  A magnitude given
@@ -193,27 +258,42 @@ __device__ __forceinline__ unsigned best_pattern(const uint32_t (&mag)[16], cons
             const double v = (double)__uint_as_float(mag[4 * i + j]);
             a[i][j] = (j == 0) ? v : __builtin_fma((double)(kColBonus[j] * kRowMult[i]), eps, v);
         }
-    double rs[4][6];
+    // column sums of the top (rows 0,1) and bottom (rows 2,3) halves
+    double dt[4], db[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int k = 0; k < 6; ++k) rs[i][k] = a[i][pair_c1(k)] + a[i][pair_c2(k)];
-
-    // both top rows on the same pair
-    double best = (rs[0][0] + rs[1][0]) + (rs[2][5] + rs[3][5]);
-#pragma unroll
-    for (int k = 1; k < 6; ++k) best = __builtin_fmax(best, (rs[0][k] + rs[1][k]) + (rs[2][5 - k] + rs[3][5 - k]));
-    // top rows complementary
-    {
-        double t = rs[0][0] + rs[1][5], b = rs[2][0] + rs[3][5];
-#pragma unroll
-        for (int k = 1; k < 6; ++k) {
-            t = __builtin_fmax(t, rs[0][k] + rs[1][5 - k]);
-            b = __builtin_fmax(b, rs[2][k] + rs[3][5 - k]);
-        }
-        best = __builtin_fmax(best, t + b);
+    for (int j = 0; j < 4; ++j) {
+        dt[j] = a[0][j] + a[1][j];
+        db[j] = a[2][j] + a[3][j];
     }
-    // top rows share column x and leave column w empty
+    // (i) both top rows keep the pair {c1,c2}, both bottom rows its complement
+    double best = 0.0;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        const double tot = (dt[pair_c1(k)] + dt[pair_c2(k)]) + (db[pair_c1(5 - k)] + db[pair_c2(5 - k)]);
+        best = (k == 0) ? tot : __builtin_fmax(best, tot);
+    }
+    // (ii) complementary pairs in each half: all of row 1 plus the two largest gains of swapping a
+    // column to row 0 (and the same for rows 3 and 2)
+    {
+        auto half = [](const double (&r0)[4], const double (&r1)[4]) {
+            const double d0 = r0[0] - r1[0], d1 = r0[1] - r1[1], d2 = r0[2] - r1[2], d3 = r0[3] - r1[3];
+            const double m1 = __builtin_fmax(d0, d1), n1 = __builtin_fmin(d0, d1);
+            const double m2 = __builtin_fmax(d2, d3), n2 = __builtin_fmin(d2, d3);
+            const double hi = __builtin_fmax(m1, m2), lo = __builtin_fmin(m1, m2);
+            const double second = __builtin_fmax(lo, __builtin_fmax(n1, n2));
+            return ((r1[0] + r1[1]) + (r1[2] + r1[3])) + (hi + second);
+        };
+        best = __builtin_fmax(best, half(a[0], a[1]) + half(a[2], a[3]));
+    }
+    // (iii) top rows share column x and keep one each of {y,z}; bottom rows share w and keep the
+    // other of {y,z}: dt[x] + db[w] + best crossing of {y,z} in the top + in the bottom
+    double cross[6];   // indexed by the pair {y,z}
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        const int y = pair_c1(k), z = pair_c2(k);
+        cross[k] = __builtin_fmax(a[0][y] + a[1][z], a[0][z] + a[1][y]) +
+                   __builtin_fmax(a[2][y] + a[3][z], a[2][z] + a[3][y]);
+    }
 #pragma unroll
     for (int x = 0; x < 4; ++x)
 #pragma unroll
@@ -222,10 +302,7 @@ __device__ __forceinline__ unsigned best_pattern(const uint32_t (&mag)[16], cons
             int y = -1, z = -1;
             for (int c = 0; c < 4; ++c)
                 if (c != x && c != w) (y < 0 ? y : z) = c;
-            const int xy = pair_of(x, y), xz = pair_of(x, z), yw = pair_of(y, w), zw = pair_of(z, w);
-            const double t = __builtin_fmax(rs[0][xy] + rs[1][xz], rs[0][xz] + rs[1][xy]);
-            const double b = __builtin_fmax(rs[2][yw] + rs[3][zw], rs[2][zw] + rs[3][yw]);
-            best = __builtin_fmax(best, t + b);
+            best = __builtin_fmax(best, (dt[x] + db[w]) + cross[pair_of(y, z)]);
         }
     const unsigned bonus = (unsigned)__double2loint(best + big) & 0x7FFu;
     const unsigned x = min(bonus - (unsigned)kBonusBase, 1295u);
@@ -281,16 +358,23 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     using Ops = RowOps<T>;
     using Row = typename Ops::Row;
     using Pair = typename Ops::Pair;
+    constexpr bool FAST = COMPRESS && sizeof(T) == 2;   // bf16: table-driven compressor
+    constexpr bool PREFETCH_ROWS = true;   // measured faster in every variant, even the register-heavy fused one
     __shared__ uint16_t s_lut_mask[SEARCH ? 1296 : 1];
-    __shared__ uint8_t s_lut_id[SEARCH ? 1296 : 1];
+    __shared__ uint8_t s_lut_id[(SEARCH || FAST) ? 1296 : 1];
+    __shared__ uint4 s_clut[FAST ? 3 * S24_NUM_PATTERNS : 1];
     __shared__ Pair s_valsT[COMPRESS ? 4 * kTile * kPitch : 1];
     __shared__ uint8_t s_nibT[COMPRESS ? 4 * kTile * kPitch : 1];
 
     const int tid = threadIdx.x;
-    if constexpr (SEARCH) {
+    if constexpr (SEARCH || FAST) {
         for (int x = tid; x < 1296; x += 256) {
-            s_lut_mask[x] = g_lut.mask[x];
+            if constexpr (SEARCH) s_lut_mask[x] = g_lut.mask[x];
             s_lut_id[x] = g_lut.id[x];
+        }
+        if constexpr (FAST) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(&g_clut);
+            for (int x = tid; x < 3 * S24_NUM_PATTERNS; x += 256) s_clut[x] = src[x];
         }
         __syncthreads();
     }
@@ -299,19 +383,31 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     const int bj = bj0 + lbj;
     const int64_t R = 4 * (int64_t)br, Q = 4 * (int64_t)bq;  // rows of vals / of valsT
 
+    // first weight row of this lane's first block; each step of the loop moves 8 block rows down.
+    // The rows of the next block are requested before the current one is scored.
+    const T *wrow = W + (int64_t)(4 * (bi0 + (tid >> 5))) * ldw + 4 * bj;
+    auto fetch = [&](Row (&dst)[4], const T *p, bool ok) {
+        if (ok) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dst[i] = Ops::load(p + i * ldw);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dst[i] = Row{};
+        }
+    };
+    Row nxt[4];
+    fetch(nxt, wrow, (bi0 + (tid >> 5) < br) && (bj < bq));
 #pragma unroll 1
     for (int s = 0; s < 4; ++s) {
         const int lbi = (tid >> 5) + 8 * s;
         const int bi = bi0 + lbi;
         const bool valid = (bi < br) && (bj < bq);
         Row rows[4];
-        if (SEARCH || COMPRESS) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (valid) rows[i] = Ops::load(W + (int64_t)(4 * bi + i) * ldw + 4 * bj);
-                else rows[i] = Row{};
-            }
-        }
+        for (int i = 0; i < 4; ++i) rows[i] = nxt[i];
+        if (!PREFETCH_ROWS && s > 0) fetch(rows, wrow, valid);
+        wrow += 32 * ldw;
+        if (PREFETCH_ROWS && s < 3) fetch(nxt, wrow, (bi + 8 < br) && (bj < bq));
         unsigned m = 0, id = 0;
         if constexpr (SEARCH) {
             uint32_t mag[16];
@@ -329,7 +425,42 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
         } else {
             m = valid ? mask_in[(int64_t)bi * bq + bj] : 0x33CCu;
         }
-        if constexpr (COMPRESS) {
+        if constexpr (FAST) {
+            if constexpr (!SEARCH) id = s_lut_id[min(lut_index_of_mask(m), 1295u)];
+            const uint4 rsel = s_clut[3 * id], csel = s_clut[3 * id + 1], mt = s_clut[3 * id + 2];
+            const uint32_t rs[4] = {rsel.x, rsel.y, rsel.z, rsel.w}, cs[4] = {csel.x, csel.y, csel.z, csel.w};
+            // along q: one dword (two kept bf16) per block row
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t pr = __builtin_amdgcn_perm(rows[i].y, rows[i].x, rs[i]);
+                if (valid) reinterpret_cast<uint32_t *>(vals)[((int64_t)(bj >> 4) * R + 4 * bi + i) * 16 + (bj & 15)] = pr;
+            }
+            uint32_t nib_lo = mt.x, nib_hi = mt.y;
+            nib_lo |= (uint32_t)__shfl_down((int)nib_lo, 1) << 4;
+            nib_hi |= (uint32_t)__shfl_down((int)nib_hi, 1) << 4;
+            nib_lo |= (uint32_t)__shfl_down((int)nib_lo, 2) << 8;
+            nib_hi |= (uint32_t)__shfl_down((int)nib_hi, 2) << 8;
+            if (valid && (lbj & 3) == 0) {
+                const int w = bj >> 2;  // metadata word of the row: chunk w/4, word w%4
+                uint16_t *mrow = meta + ((int64_t)(w >> 2) * R + 4 * bi) * 4 + (w & 3);
+                mrow[0] = (uint16_t)(nib_lo & 0xFFFFu);
+                mrow[4] = (uint16_t)(nib_lo >> 16);
+                mrow[8] = (uint16_t)(nib_hi & 0xFFFFu);
+                mrow[12] = (uint16_t)(nib_hi >> 16);
+            }
+            // along r: gather each column from the four rows, pick its two kept rows, park in LDS
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t half = (j & 1) ? 0x07060302u : 0x05040100u;
+                const uint32_t r0 = (j < 2) ? rows[0].x : rows[0].y, r1 = (j < 2) ? rows[1].x : rows[1].y;
+                const uint32_t r2 = (j < 2) ? rows[2].x : rows[2].y, r3 = (j < 2) ? rows[3].x : rows[3].y;
+                const uint32_t col_lo = __builtin_amdgcn_perm(r1, r0, half);  // rows 0,1 of column j
+                const uint32_t col_hi = __builtin_amdgcn_perm(r3, r2, half);  // rows 2,3
+                const int a = (j * kTile + lbj) * kPitch + lbi;
+                s_valsT[a] = __builtin_amdgcn_perm(col_hi, col_lo, cs[j]);
+                s_nibT[a] = (uint8_t)((mt.z >> (4 * j)) & 0xFu);
+            }
+        } else if constexpr (COMPRESS) {
             // along q: two kept weights and one nibble per block row
             uint32_t nib_lo = 0, nib_hi = 0;  // nibbles of rows (0,1) and (2,3), 16 bits apart
 #pragma unroll
@@ -377,25 +508,41 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     }
     if constexpr (COMPRESS) {
         __syncthreads();
-        // valsT: two chunks (16 pairs each) of 128 columns of W; walk pairs fastest, then columns,
-        // so that consecutive lanes write consecutive addresses inside a chunk
-        for (int idx = tid; idx < 4 * kTile * kTile; idx += 256) {
-            const int lbi = (idx & 15) | ((idx >> 11) << 4), col = (idx >> 4) & 127;  // col = 4*lbj + j
+        // valsT: two chunks (16 pairs each) of 128 columns of W.  One item = four consecutive pairs of
+        // one column; consecutive lanes take consecutive items of a column, then the next column, so a
+        // chunk of the tile leaves as one contiguous run.
+        Pair *outT = reinterpret_cast<Pair *>(valsT);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int idx = tid + 256 * it;                    // 1024 items
+            const int quad = idx & 3, col = (idx >> 2) & 127, half = idx >> 9;   // col = 4*lbj + j
             const int j = col & 3, lb = col >> 2;
-            const int bi = bi0 + lbi;
-            if (bj0 + lb < bq && bi < br)
-                reinterpret_cast<Pair *>(valsT)[((int64_t)(bi >> 4) * Q + 4 * (bj0 + lb) + j) * 16 + (bi & 15)] =
-                    s_valsT[(j * kTile + lb) * kPitch + lbi];
+            const int lbi = 16 * half + 4 * quad, bi = bi0 + lbi;
+            if (bj0 + lb < bq && bi < br) {   // br is a multiple of 16: a quad is all in or all out
+                const Pair *src = &s_valsT[(j * kTile + lb) * kPitch + lbi];
+                Pair *dst = outT + ((int64_t)(bi >> 4) * Q + 4 * (bj0 + lb) + j) * 16 + (bi & 15);
+                if constexpr (sizeof(Pair) == 4) {
+                    *reinterpret_cast<uint4 *>(dst) = make_uint4(src[0], src[1], src[2], src[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dst[e] = src[e];
+                }
+            }
         }
-        // metaT: 128 columns x 8 words = two chunks of four words
-        for (int idx = tid; idx < 4 * kTile * 8; idx += 256) {
-            const int w = (idx & 3) | ((idx >> 9) << 2), col = (idx >> 2) & 127;
+        // metaT: per column two chunks of four words; one thread packs the 16 nibbles of one (column, chunk)
+        {
+            const int col = tid & 127, half = tid >> 7;
             const int j = col & 3, lb = col >> 2;
-            if (bj0 + lb < bq && bi0 + 4 * w < br) {
-                const uint8_t *n = &s_nibT[(j * kTile + lb) * kPitch + 4 * w];
-                const unsigned word = n[0] | (n[1] << 4) | (n[2] << 8) | (n[3] << 12);
-                const int ww = (bi0 >> 2) + w;
-                metaT[((int64_t)(ww >> 2) * Q + 4 * (bj0 + lb) + j) * 4 + (ww & 3)] = (uint16_t)word;
+            if (bj0 + lb < bq && bi0 + 16 * half < br) {
+                const uint8_t *n = &s_nibT[(j * kTile + lb) * kPitch + 16 * half];
+                uint32_t w01 = 0, w23 = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    w01 |= (uint32_t)n[e] << (4 * e);
+                    w23 |= (uint32_t)n[8 + e] << (4 * e);
+                }
+                const int kc = (bi0 >> 4) + half;   // chunk index along r
+                *reinterpret_cast<uint2 *>(metaT + ((int64_t)kc * Q + 4 * (bj0 + lb) + j) * 4) = make_uint2(w01, w23);
             }
         }
     }
