@@ -630,22 +630,41 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
 }
 }  // namespace bignt
 
-// ------------------------------------------------------------------ dense TN (dW), large tile
-// Workgroup tile 256 (m) x 256 (n) x 64 (t), eight waves as 2 x 4, each wave
-// 128 x 64.  Staging as in the small kernel (8x8 register transposes), one
-// sub-block per thread: threads 0..255 the dY tile, 256..511 the X tile.  Two
-// LDS stages of 64 KB; the global loads of chunk kc+1 are issued before the
-// math of chunk kc and written to the other stage after it.
-namespace bigtn {
-constexpr int BM = 256, BN = 256, THREADS = 512, OPERAND = 256 * 128;
+// ------------------------------------------------------------------ dense TN (dW), direct-to-LDS + transposing reads
+// Workgroup tile 256 (m) x 256 (n) x 64 (t), eight waves of 128 x 64.  The token-major operand tiles
+// ([64 t][256 columns], 512-byte rows) are copied global->LDS as they are, and the k-contiguous MFMA fragments are produced by the LDS
+// transposing read: in a group of 16 lanes, lane i points at row i/4, columns 4*(i%4)..+3 of a
+// 4 (t) x 16 (columns) patch and receives, for column i, the four consecutive t (measured on the
+// device with an index-filled tile).  Two such reads give one lane its eight k values.
+// LDS swizzle: 16-byte chunk c of row t sits at slot c ^ (4*(t&3)), which keeps the eight 32-byte
+// row segments touched by 32 lanes in one cycle on distinct banks.  Two 64 KB stages.
+namespace dmatn {
+constexpr int BM = 256, BN = 256, THREADS = 512, OPERAND = 64 * 512;
+using big::glb_ptr;
+using big::lds_ptr;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16 *lds_v4i16;
+
+__device__ __forceinline__ int tr_off(int row, int col)
+{
+    return row * 512 + ((((col >> 3) ^ ((row & 3) << 2))) << 4) + ((col & 7) << 1);
+}
+__device__ __forceinline__ bf16x8 tr_frag(const unsigned char *tile, int row, int col)
+{
+    // rows row..row+3 and row+4..row+7 of this lane group's patch
+    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(tile + tr_off(row, col)));
+    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(tile + tr_off(row + 4, col)));
+    struct { v4i16 a, b; } t{lo, hi};
+    return __builtin_bit_cast(bf16x8, t);
+}
 
 template <bool ACCUM>
-__global__ __launch_bounds__(THREADS) void dense_tn_big_kernel(const uint16_t *__restrict__ dY,
+__global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *__restrict__ dY,
                                                                const uint16_t *__restrict__ X, float *__restrict__ dW,
                                                                int T, int M, int N, int tiles_m, int tiles_n)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char s_a[2][OPERAND];
-    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][OPERAND];
+    __shared__ __attribute__((aligned(16))) unsigned char s0[2 * OPERAND];
+    __shared__ __attribute__((aligned(16))) unsigned char s1[2 * OPERAND];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
@@ -659,36 +678,60 @@ __global__ __launch_bounds__(THREADS) void dense_tn_big_kernel(const uint16_t *_
     const int m0 = tm * BM, n0 = tn * BN;
     const int nk = (T + 63) / 64;
 
-    const bool is_a = tid < 256;
-    const int sid = tid & 255;
-    const int scol = (sid & 31) * 8, stc = sid >> 5;  // 32 column groups x 8 t-chunks
-    const uint16_t *src = is_a ? dY : X;
-    const int64_t ld = is_a ? M : N;
-    const int gcol = (is_a ? m0 : n0) + scol, ncols = is_a ? M : N;
-
+    // copies: this wave owns rows 8*wave .. 8*wave+7 of both tiles; instruction i covers rows 2i, 2i+1
+    // (32 lanes per 512-byte row).  Columns past the matrix edge are clamped to its last 16-byte chunk.
+    const int crow = lane >> 5, cslot = lane & 31;
+    int col_a[4], col_b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 8 * wave + 2 * i + crow;
+        const int c = cslot ^ ((row & 3) << 2);
+        col_a[i] = m0 + 8 * min(c, (min(M - m0, BM) >> 3) - 1);
+        col_b[i] = n0 + 8 * min(c, (min(N - n0, BN) >> 3) - 1);
+    }
+    auto issue = [&](unsigned char *st, int kc) {   // eight copies per lane; token rows past T re-read row T-1
+        kc = min(kc, nk - 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int trow = min(kc * 64 + 8 * wave + 2 * i + crow, T - 1);
+            __builtin_amdgcn_global_load_lds((glb_ptr)(dY + (int64_t)trow * M + col_a[i]), (lds_ptr)(st + (8 * wave + 2 * i) * 512), 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int trow = min(kc * 64 + 8 * wave + 2 * i + crow, T - 1);
+            __builtin_amdgcn_global_load_lds((glb_ptr)(X + (int64_t)trow * N + col_b[i]), (lds_ptr)(st + OPERAND + (8 * wave + 2 * i) * 512), 16, 0, 0);
+        }
+    };
     f32x16 acc[4][2];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
 
-    // The staged sub-block of chunk kc+1 sits in registers while chunk kc is multiplied; it is
-    // transposed and written to the other LDS stage between the two halves of the chunk's math,
-    // so that those writes run under the matrix pipe, and the loads of chunk kc+2 follow at once.
-    Sub8 sub;
-    sub8_load(sub, src, ld, 8 * stc, T, gcol, ncols);
-    sub8_transpose_store(sub, is_a ? s_a[0] : s_b[0], scol, stc);
-    if (nk > 1) sub8_load(sub, src, ld, 64 + 8 * stc, T, gcol, ncols);
-    __syncthreads();
-    const int g = lane >> 5;
-    auto ksteps = [&](const unsigned char *sa, const unsigned char *sb, int i0) {
+    // fragment addressing of this lane: group G = lane/16 -> k half G/2, column half G%2
+    const int gi = lane & 15, G = lane >> 4;
+    const int frow = 8 * (G >> 1) + (gi >> 2), fcol = 16 * (G & 1) + 4 * (gi & 3);
+
+    issue(s0, 0);
+    auto chunk = [&](unsigned char *cur, unsigned char *other, int kc) {
+        big::wait_and_barrier<0>();   // everyone's copies of chunk kc are in LDS, and `other` is no longer read
+        issue(other, kc + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        const int rem = T - kc * 64;
+        if (rem < 64) {
+            // last, partial chunk: token rows past T must not contribute; clear them in the dY tile
+            for (int idx = tid; idx < (64 - rem) * 32; idx += THREADS)
+                *reinterpret_cast<uint4 *>(cur + (rem + (idx >> 5)) * 512 + ((idx & 31) << 4)) = make_uint4(0, 0, 0, 0);
+            __syncthreads();
+        }
+        const unsigned char *sa = cur, *sb = cur + OPERAND;
 #pragma unroll
-        for (int i = i0; i < i0 + 2; ++i) {
+        for (int ks = 0; ks < 4; ++ks) {
             bf16x8 a[4], b[2];
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi) a[mi] = as_bf16x8(lds_read(sa, 128 * wm + 32 * mi + (lane & 31), 4 * g + i));
+            for (int mi = 0; mi < 4; ++mi) a[mi] = tr_frag(sa, 16 * ks + frow, 128 * wm + 32 * mi + fcol);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) b[ni] = as_bf16x8(lds_read(sb, 64 * wn + 32 * ni + (lane & 31), 4 * g + i));
+            for (int ni = 0; ni < 2; ++ni) b[ni] = tr_frag(sb, 16 * ks + frow, 64 * wn + 32 * ni + fcol);
 #pragma unroll
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
@@ -696,16 +739,13 @@ __global__ __launch_bounds__(THREADS) void dense_tn_big_kernel(const uint16_t *_
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
         }
     };
-    for (int kc = 0; kc < nk; ++kc) {
-        const unsigned char *sa = s_a[kc & 1], *sb = s_b[kc & 1];
-        ksteps(sa, sb, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (kc + 1 < nk) sub8_transpose_store(sub, is_a ? s_a[(kc + 1) & 1] : s_b[(kc + 1) & 1], scol, stc);
-        if (kc + 2 < nk) sub8_load(sub, src, ld, (kc + 2) * 64 + 8 * stc, T, gcol, ncols);
-        __builtin_amdgcn_sched_barrier(0);
-        ksteps(sa, sb, 2);
-        __syncthreads();
+    int kc = 0;
+    for (; kc + 2 <= nk; kc += 2) {
+        chunk(s0, s1, kc);
+        chunk(s1, s0, kc + 1);
     }
+    if (kc < nk) chunk(s0, s1, kc);
+    __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // drain the last (redundant) copies before LDS is released
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
         const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
@@ -721,7 +761,7 @@ __global__ __launch_bounds__(THREADS) void dense_tn_big_kernel(const uint16_t *_
             }
     }
 }
-}  // namespace bigtn
+}  // namespace dmatn
 
 // ------------------------------------------------------------------ fp32 fallbacks (small correctness workload)
 // One thread per output element, plain fp32 FMA; no matrix-core claim.
@@ -887,15 +927,15 @@ extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p,
     }
     const bool accum = beta != 0.0f;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt == S24_BF16 && (int64_t)ceil_div(r, bigtn::BM) * ceil_div(q, bigtn::BN) >= 192) {
-        const int tiles_m = (int)ceil_div(r, bigtn::BM), tiles_n = (int)ceil_div(q, bigtn::BN);
-        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(bigtn::THREADS);
+    if (dt == S24_BF16 && (int64_t)ceil_div(r, dmatn::BM) * ceil_div(q, dmatn::BN) >= 192) {
+        const int tiles_m = (int)ceil_div(r, dmatn::BM), tiles_n = (int)ceil_div(q, dmatn::BN);
+        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(dmatn::THREADS);
         auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
         if (accum)
-            hipLaunchKernelGGL(bigtn::dense_tn_big_kernel<true>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
+            hipLaunchKernelGGL(dmatn::dense_tn_dma_kernel<true>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
                                tiles_m, tiles_n);
         else
-            hipLaunchKernelGGL(bigtn::dense_tn_big_kernel<false>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
+            hipLaunchKernelGGL(dmatn::dense_tn_dma_kernel<false>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
                                tiles_m, tiles_n);
     } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(r, BM), ceil_div(q, BN)), block(kThreads);
