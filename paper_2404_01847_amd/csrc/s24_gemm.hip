@@ -311,7 +311,6 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         // complete, so this lane's part of chunk kc is in LDS; its own LDS reads are done too
         wait_and_barrier<7>();   // everybody's part landed; everybody finished reading `refill`
         issue(refill, kc + 2);
-        __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sb = cur, *sa = cur + B_STAGE, *sm = cur + B_STAGE + A_STAGE;
         const int g = lane >> 5;
         uint32_t ix[4];
@@ -343,6 +342,18 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
                         acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 1);
                 }
         }
+        // Issue order: the twelve LDS reads of the first half, then its eight matrix instructions with the
+        // second half's eight reads and the seven copies of chunk kc+2 dealt out between them (a wave that
+        // issues all its copies at once sits in the memory pipeline's queue while the matrix unit idles).
+        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i < 7) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
     };
     int kc = 0;
     for (; kc + 3 <= nk; kc += 3) {
@@ -630,16 +641,27 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
 }
 }  // namespace bignt
 
-// ------------------------------------------------------------------ dense TN (dW), direct-to-LDS + transposing reads
-// Workgroup tile 256 (m) x 256 (n) x 64 (t), eight waves of 128 x 64.  The token-major operand tiles
-// ([64 t][256 columns], 512-byte rows) are copied global->LDS as they are, and the k-contiguous MFMA fragments are produced by the LDS
-// transposing read: in a group of 16 lanes, lane i points at row i/4, columns 4*(i%4)..+3 of a
-// 4 (t) x 16 (columns) patch and receives, for column i, the four consecutive t (measured on the
-// device with an index-filled tile).  Two such reads give one lane its eight k values.
-// LDS swizzle: 16-byte chunk c of row t sits at slot c ^ (4*(t&3)), which keeps the eight 32-byte
-// row segments touched by 32 lanes in one cycle on distinct banks.  Two 64 KB stages.
+// ------------------------------------------------------------------ dense TN (dW), large tile
+// dW[m][n] = sum_t dY[t][m] X[t][n] with 256 x 256 workgroup tiles.  Both operands are token-major, so a
+// tile chunk (32 tokens x 256 columns) is copied into LDS as it lies in memory, rows of 512 bytes, and the
+// matrix-core fragments (8 consecutive t per lane) are gathered with the transposing LDS read.
+// ds_read_b64_tr_b16: in a group of 16 lanes, lane i points at row i/4, columns 4*(i%4)..+3 of a
+// 4 (t) x 16 (columns) patch and receives, for column i, the four consecutive t (measured on the device
+// with an index-filled tile); two such reads give one lane its eight k values.
+// LDS swizzle: 16-byte chunk c of row t sits at slot c ^ (4*(t&3)), which keeps the eight 32-byte row
+// segments touched by 32 lanes in one cycle on distinct banks.
+// Four waves, one per SIMD, each a 128 x 128 tile of 4 x 4 accumulator blocks (256 accumulator registers):
+// against eight waves of 128 x 64 this reads a third less LDS per matrix instruction, which matters
+// because the chip sheds clock under the combined matrix + LDS + copy load.  The token axis moves through
+// a ring of four 32 KB stages.  A chunk is waited for one iteration before it is used, so the first
+// fragments of chunk kc+1 are fetched during the last matrix instructions of chunk kc and the barrier
+// finds the matrix unit busy; the copies of chunk kc+3 are dealt out between the matrix instructions
+// rather than issued in one burst.
 namespace dmatn {
-constexpr int BM = 256, BN = 256, THREADS = 512, OPERAND = 64 * 512;
+constexpr int BM = 256, BN = 256, BT = 32, THREADS = 256, WT = 4;   // WT: 32 x 32 blocks per wave and axis
+constexpr int ROWB = BM * 2, OPERAND = BT * ROWB, STAGE = 2 * OPERAND, CPR = ROWB / 16;
+constexpr int NIO = OPERAND / 1024 / 4, NI = 2 * NIO;   // copies per wave, chunk and operand / in total
+static_assert(BM == BN, "one row pitch for both operands");
 using big::glb_ptr;
 using big::lds_ptr;
 typedef short v4i16 __attribute__((ext_vector_type(4)));
@@ -647,13 +669,13 @@ typedef __attribute__((address_space(3))) v4i16 *lds_v4i16;
 
 __device__ __forceinline__ int tr_off(int row, int col)
 {
-    return row * 512 + ((((col >> 3) ^ ((row & 3) << 2))) << 4) + ((col & 7) << 1);
+    return row * ROWB + ((((col >> 3) ^ ((row & 3) << 2))) << 4) + ((col & 7) << 1);
 }
-__device__ __forceinline__ bf16x8 tr_frag(const unsigned char *tile, int row, int col)
+__device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
 {
-    // rows row..row+3 and row+4..row+7 of this lane group's patch
-    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(tile + tr_off(row, col)));
-    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(tile + tr_off(row + 4, col)));
+    // token rows t..t+3 and t+4..t+7 of this lane group's patch
+    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(p));
+    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16)(p + 4 * ROWB));
     struct { v4i16 a, b; } t{lo, hi};
     return __builtin_bit_cast(bf16x8, t);
 }
@@ -663,8 +685,10 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
                                                                const uint16_t *__restrict__ X, float *__restrict__ dW,
                                                                int T, int M, int N, int tiles_m, int tiles_n)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char s0[2 * OPERAND];
-    __shared__ __attribute__((aligned(16))) unsigned char s1[2 * OPERAND];
+    __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s1[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s2[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s3[STAGE];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
@@ -676,85 +700,134 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
     const int gw = min(GROUP, tiles_n - grp * GROUP);
     const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
     const int m0 = tm * BM, n0 = tn * BN;
-    const int nk = (T + 63) / 64;
+    const int nk = (T + BT - 1) / BT;
 
-    // copies: this wave owns rows 8*wave .. 8*wave+7 of both tiles; instruction i covers rows 2i, 2i+1
-    // (32 lanes per 512-byte row).  Columns past the matrix edge are clamped to its last 16-byte chunk.
-    const int crow = lane >> 5, cslot = lane & 31;
-    int col_a[4], col_b[4];
+    // Copies: instruction g of an operand fills the 16-byte slots 64g .. 64g+63 of its stage region, slot ->
+    // (row = slot / CPR, chunk = slot % CPR); the source chunk is chunk ^ (4 * (row & 3)).  Columns past the
+    // matrix edge are clamped to its last 16-byte chunk.  Offsets are elements from the chunk's first row.
+    int voffA[NIO], voffB[NIO];
+    const int lastA = (min(M - m0, BM) >> 3) - 1, lastB = (min(N - n0, BN) >> 3) - 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = 8 * wave + 2 * i + crow;
-        const int c = cslot ^ ((row & 3) << 2);
-        col_a[i] = m0 + 8 * min(c, (min(M - m0, BM) >> 3) - 1);
-        col_b[i] = n0 + 8 * min(c, (min(N - n0, BN) >> 3) - 1);
+    for (int j = 0; j < NIO; ++j) {
+        const int slot = (wave * NIO + j) * 64 + lane, row = slot / CPR, c = (slot % CPR) ^ ((row & 3) << 2);
+        voffA[j] = row * M + m0 + 8 * min(c, lastA);
+        voffB[j] = row * N + n0 + 8 * min(c, lastB);
     }
-    auto issue = [&](unsigned char *st, int kc) {   // eight copies per lane; token rows past T re-read row T-1
+    // which: 1 = the dY tile, 2 = the X tile.  Token rows past T (last chunk only) re-read row T-1.
+    auto issue = [&](unsigned char *st, int kc, int which) {
         kc = min(kc, nk - 1);
+        const char *ya = reinterpret_cast<const char *>(dY + (int64_t)kc * BT * M);
+        const char *xb = reinterpret_cast<const char *>(X + (int64_t)kc * BT * N);
+        const int lastrow = T - 1 - kc * BT;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int trow = min(kc * 64 + 8 * wave + 2 * i + crow, T - 1);
-            __builtin_amdgcn_global_load_lds((glb_ptr)(dY + (int64_t)trow * M + col_a[i]), (lds_ptr)(st + (8 * wave + 2 * i) * 512), 16, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int trow = min(kc * 64 + 8 * wave + 2 * i + crow, T - 1);
-            __builtin_amdgcn_global_load_lds((glb_ptr)(X + (int64_t)trow * N + col_b[i]), (lds_ptr)(st + OPERAND + (8 * wave + 2 * i) * 512), 16, 0, 0);
+        for (int j = 0; j < NIO; ++j) {
+            const int over = max(((wave * NIO + j) * 64 + lane) / CPR - lastrow, 0);
+            if (which == 1)
+                __builtin_amdgcn_global_load_lds((glb_ptr)(ya + (uint32_t)(voffA[j] - over * M) * 2u),
+                                                 (lds_ptr)(st + (wave * NIO + j) * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((glb_ptr)(xb + (uint32_t)(voffB[j] - over * N) * 2u),
+                                                 (lds_ptr)(st + OPERAND + (wave * NIO + j) * 1024), 16, 0, 0);
         }
     };
-    f32x16 acc[4][2];
+    f32x16 acc[WT][WT];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < WT; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+        for (int ni = 0; ni < WT; ++ni) acc[mi][ni] = f32x16{};
 
     // fragment addressing of this lane: group G = lane/16 -> k half G/2, column half G%2
     const int gi = lane & 15, G = lane >> 4;
     const int frow = 8 * (G >> 1) + (gi >> 2), fcol = 16 * (G & 1) + 4 * (gi & 3);
-
-    issue(s0, 0);
-    auto chunk = [&](unsigned char *cur, unsigned char *other, int kc) {
-        big::wait_and_barrier<0>();   // everyone's copies of chunk kc are in LDS, and `other` is no longer read
-        issue(other, kc + 1);
+    int offA[WT], offB[WT];
+#pragma unroll
+    for (int i = 0; i < WT; ++i) {
+        offA[i] = tr_off(frow, 32 * WT * wm + 32 * i + fcol);
+        offB[i] = OPERAND + tr_off(frow, 32 * WT * wn + 32 * i + fcol);
+    }
+    auto load_frags = [&](const unsigned char *st, int ks, bf16x8 (&a)[WT], bf16x8 (&b)[WT]) {
+#pragma unroll
+        for (int ni = 0; ni < WT; ++ni) b[ni] = tr_frag(st + offB[ni] + 16 * ks * ROWB);
+#pragma unroll
+        for (int mi = 0; mi < WT; ++mi) a[mi] = tr_frag(st + offA[mi] + 16 * ks * ROWB);
+    };
+    auto mma = [&](const bf16x8 (&a)[WT], const bf16x8 (&b)[WT]) {
+#pragma unroll
+        for (int mi = 0; mi < WT; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < WT; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+    };
+    // Issue order of one 16-token step: a matrix instruction, an LDS read of the next step's fragments,
+    // and after every other matrix instruction one copy.
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < WT * WT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if ((i & 1) && (i >> 1) < NIO) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
-        const int rem = T - kc * 64;
-        if (rem < 64) {
-            // last, partial chunk: token rows past T must not contribute; clear them in the dY tile
-            for (int idx = tid; idx < (64 - rem) * 32; idx += THREADS)
-                *reinterpret_cast<uint4 *>(cur + (rem + (idx >> 5)) * 512 + ((idx & 31) << 4)) = make_uint4(0, 0, 0, 0);
-            __syncthreads();
-        }
-        const unsigned char *sa = cur, *sb = cur + OPERAND;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 a[4], b[2];
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) a[mi] = tr_frag(sa, 16 * ks + frow, 128 * wm + 32 * mi + fcol);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) b[ni] = tr_frag(sb, 16 * ks + frow, 64 * wn + 32 * ni + fcol);
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
-        }
+    };
+    static_assert(4 * WT == WT * WT && 2 * NIO <= WT * WT, "one LDS read per matrix instruction");
+    // token rows past T must not contribute: clear them in the dY tile of the (last, partial) chunk kc
+    auto clear_tail = [&](unsigned char *st, int kc) {
+        const int rem = T - kc * BT;
+        for (int idx = tid; idx < (BT - rem) * CPR; idx += THREADS)
+            *reinterpret_cast<uint4 *>(st + (rem + idx / CPR) * ROWB + ((idx % CPR) << 4)) = make_uint4(0, 0, 0, 0);
+        __syncthreads();
+    };
+    const bool partial = (T % BT) != 0;
+
+    // prologue: chunks 0..2 in flight, chunk 0 landed, its first fragments in registers
+    issue(s0, 0, 1);
+    issue(s0, 0, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s1, 1, 1);
+    issue(s1, 1, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s2, 2, 1);
+    issue(s2, 2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    big::wait_and_barrier<2 * NI>();
+    if (partial && nk == 1) clear_tail(s0, 0);
+    bf16x8 a0[WT], b0[WT], a1[WT], b1[WT];
+    load_frags(s0, 0, a0, b0);
+
+    // Iteration kc: all but the NI most recent copies (chunk kc+2) are complete, so chunk kc+1 is in LDS for
+    // every wave after the barrier, and nobody reads the stage of chunk kc-1 any more: it takes chunk kc+3.
+    auto chunk = [&](const unsigned char *cur, unsigned char *nxt, unsigned char *refill, int kc) {
+        big::wait_and_barrier<NI>();
+        if (partial && kc + 2 == nk) clear_tail(nxt, kc + 1);
+        issue(refill, kc + 3, 1);
+        load_frags(cur, 1, a1, b1);
+        mma(a0, b0);
+        interleave();
+        issue(refill, kc + 3, 2);
+        load_frags(nxt, 0, a0, b0);   // past the last chunk this reads a stage nobody uses; the result is dropped
+        mma(a1, b1);
+        interleave();
     };
     int kc = 0;
-    for (; kc + 2 <= nk; kc += 2) {
-        chunk(s0, s1, kc);
-        chunk(s1, s0, kc + 1);
+    for (; kc + 4 <= nk; kc += 4) {
+        chunk(s0, s1, s3, kc);
+        chunk(s1, s2, s0, kc + 1);
+        chunk(s2, s3, s1, kc + 2);
+        chunk(s3, s0, s2, kc + 3);
     }
-    if (kc < nk) chunk(s0, s1, kc);
+    if (kc < nk) chunk(s0, s1, s3, kc);
+    if (kc + 1 < nk) chunk(s1, s2, s0, kc + 1);
+    if (kc + 2 < nk) chunk(s2, s3, s1, kc + 2);
     __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // drain the last (redundant) copies before LDS is released
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
+    for (int ni = 0; ni < WT; ++ni) {
+        const int n = n0 + 32 * WT * wn + 32 * ni + (lane & 31);
         if (n >= N) continue;
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+        for (int mi = 0; mi < WT; ++mi)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int m = m0 + 128 * wm + 32 * mi + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                const int m = m0 + 32 * WT * wm + 32 * mi + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
                 if (m >= M) continue;
                 float *dst = dW + (int64_t)m * N + n;
                 *dst = ACCUM ? (*dst + acc[mi][ni][i]) : acc[mi][ni][i];
