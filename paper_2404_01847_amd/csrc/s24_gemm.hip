@@ -611,7 +611,6 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
     auto chunk = [&](const unsigned char *cur, unsigned char *other, int kc) {
         big::wait_and_barrier<0>();   // everyone's copies of chunk kc are in LDS, and `other` is no longer read
         issue(other, kc + 1);
-        __builtin_amdgcn_sched_barrier(0);
         const unsigned char *sb = cur, *sa = cur + OPERAND;
         const int g = lane >> 5;
 #pragma unroll
@@ -629,6 +628,16 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
                 for (int ni = 0; ni < 2; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
         }
+        // Issue order: the six LDS reads of the first 16-wide step, then one matrix instruction at a time with
+        // the other steps' eighteen reads after the first eighteen and one copy of chunk kc+1 after every fourth.
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (j < 18) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if ((j & 3) == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
     int kc = 0;
     for (; kc + 2 <= nk; kc += 2) {
