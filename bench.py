@@ -122,10 +122,45 @@ def _time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-def side_measurements(torch, s24, wl, ffn, X):
-    """Outside the timed step: (1) the mask search alone, over all weights of the layer in turn
-    (34 algorithmic bytes per 4x4 bf16 block: 32 read, 2 written); (2) the dense-MFMA GEMM of the
-    library next to the sparse GEMM, on the up-projection shape."""
+def _clock_mhz(torch, s24, fn, reps=6):
+    """Core clock the chip holds under `fn` (a large-tile GEMM launch): the library's clock probe makes
+    workgroup 0 of the last launch report core cycles and 100 MHz reference ticks over its lifetime."""
+    buf = torch.zeros(2, dtype=torch.int64, device="cuda")
+    s24.set_clock_probe(buf)
+    try:
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+    finally:
+        s24.set_clock_probe(None)
+        torch.cuda.synchronize()
+    cycles, ticks = (int(v) for v in buf.tolist())
+    return round(100.0 * cycles / ticks, 0) if ticks > 0 else None
+
+
+def _capture(torch, fn):
+    """fn (kernel launches on the current stream only, no allocation) recorded into a HIP graph."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fn()
+    return graph
+
+
+def side_measurements(torch, s24, wl, ffn, X, dY):
+    """Outside the timed step:
+    (1) the mask search alone, over all weights of the layer in turn (34 algorithmic bytes per 4x4 bf16
+        block: 32 read, 2 written); for c3 also over 72 distinct matrices of the layer's shape (36 layers x 2,
+        944 MB, more than the 256 MB Infinity Cache holds) so that the rate is an HBM rate;
+    (2) the dense-MFMA GEMM of the library next to the sparse GEMM at the layer's GEMM shapes (all three
+        for c5, the up-projection otherwise);
+    (3) the core clock under each large-tile GEMM kernel, and the clock-scaled matrix-core peak;
+    (4) the step replayed from a HIP graph."""
+    import s24_inputs as si
     out = {}
     es = 2 if wl.dtype == "bf16" else 4
     ws = list(ffn.w.values())
@@ -139,25 +174,84 @@ def side_measurements(torch, s24, wl, ffn, X):
     nbytes = sum(w.W.numel() / 16 * (16 * es + 2) for w in ws)
     out["mask_search_only"] = {"ms_per_sweep": round(ms, 4), "matrices": len(ws), "GB/s": round(nbytes / ms / 1e6, 1),
                                "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM, 4)}
+    if wl.name == "c3":
+        import numpy as np
+        # the 72 matrices, stacked by shape the way a model can hold its layers' weights: [36*d_ff][d] and [36*d][d_ff]
+        stacks = []
+        for which in range(2):
+            a = np.concatenate([si.sweep_weight(layer, which, wl) for layer in range(36)], axis=0)
+            t = torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+            stacks.append((t, torch.empty((t.shape[0] // 4, t.shape[1] // 4), dtype=torch.int16, device="cuda")))
+        rows = [wl.d_ff, wl.d_model]
+
+        def sweep_per_matrix():
+            for (t, m), r in zip(stacks, rows):
+                for layer in range(36):
+                    s24.transposable_mask(t[layer * r:(layer + 1) * r], m[layer * r // 4:(layer + 1) * r // 4], None)
+
+        def sweep_stacked():
+            for t, m in stacks:
+                s24.transposable_mask(t, m, None)
+
+        ms72 = _time_ms(torch, sweep_per_matrix, 5)
+        ms2 = _time_ms(torch, sweep_stacked, 5)
+        nb72 = sum(t.numel() / 16 * 34 for t, _ in stacks)
+        out["mask_search_only_72_matrices"] = {
+            "matrices": 72, "MB": round(sum(t.numel() * 2 for t, _ in stacks) / 1e6, 1),
+            "one_launch_per_matrix": {"ms_per_sweep": round(ms72, 4), "GB/s": round(nb72 / ms72 / 1e6, 1),
+                                      "frac_of_hbm_peak": round(nb72 / ms72 / 1e6 / PEAK_HBM, 4)},
+            "one_launch_per_shape": {"ms_per_sweep": round(ms2, 4), "GB/s": round(nb72 / ms2 / 1e6, 1),
+                                     "frac_of_hbm_peak": round(nb72 / ms2 / 1e6 / PEAK_HBM, 4)},
+            "note": "13 MB matrices are 400 workgroups each, 1.6 per compute unit: a launch per matrix is bound by "
+                    "launch-to-launch latency, not by HBM; the same bytes in two launches show the kernel's rate"}
+        del stacks
+    # (4) the whole step replayed from one HIP graph: what the step costs once launch overhead is gone
+    graph = ffn.capture(X, dY)
+    ms_g = _time_ms(torch, graph.replay, 20)
+    out["step_as_hip_graph"] = {"ms_per_step": round(ms_g, 4), "TFLOP/s": round(wl.gemm_flops / ms_g / 1e9, 1)}
+    del graph
     if wl.dtype == "bf16":
+        names = list(ffn.w) if wl.name == "c5" else list(ffn.w)[:1]
+        cmp_ = []
+        for name in names:
+            w = ffn.w[name]
+            r, q = w.W.shape
+            A = X if q == X.shape[1] else torch.empty((wl.p, q), dtype=X.dtype, device=X.device).normal_()
+            Yd = torch.empty((wl.p, r), dtype=X.dtype, device=X.device)
+            flops = 2.0 * wl.p * q * r
+            t_dense = _time_ms(torch, lambda: s24.dense_gemm(A, w.W, Yd), 5)
+            t_sparse = _time_ms(torch, lambda: s24.spmm_fwd(A, w.vals, w.meta, Yd), 5)
+            cmp_.append({"weight": name, "shape_p_q_r": [wl.p, q, r],
+                         "dense_mfma_ms": round(t_dense, 4), "dense_mfma_TFLOP/s": round(flops / t_dense / 1e9, 1),
+                         "sparse_smfmac_ms": round(t_sparse, 4),
+                         "sparse_dense_equiv_TFLOP/s": round(flops / t_sparse / 1e9, 1),
+                         "speedup": round(t_dense / t_sparse, 3)})
+        out["dense_vs_sparse"] = cmp_
         up = ws[0]
-        Yd = torch.empty((wl.p, up.W.shape[0]), dtype=X.dtype, device=X.device)
-        flops = 2.0 * wl.p * wl.d_model * wl.d_ff
-        t_dense = _time_ms(torch, lambda: s24.dense_gemm(X, up.W, Yd), 5)
-        t_sparse = _time_ms(torch, lambda: s24.spmm_fwd(X, up.vals, up.meta, Yd), 5)
-        out["dense_vs_sparse_up_projection"] = {
-            "shape_p_q_r": [wl.p, wl.d_model, wl.d_ff],
-            "dense_mfma_ms": round(t_dense, 4), "dense_mfma_TFLOP/s": round(flops / t_dense / 1e9, 1),
-            "sparse_smfmac_ms": round(t_sparse, 4), "sparse_dense_equiv_TFLOP/s": round(flops / t_sparse / 1e9, 1),
-            "speedup": round(t_dense / t_sparse, 3)}
+        r, q = up.W.shape
+        Yd = torch.empty((wl.p, r), dtype=X.dtype, device=X.device)
+        dYr = torch.empty((wl.p, r), dtype=X.dtype, device=X.device).normal_()
+        clocks = {
+            "spmm_fwd": _clock_mhz(torch, s24, lambda: s24.spmm_fwd(X, up.vals, up.meta, Yd)),
+            "dense_dw": _clock_mhz(torch, s24, lambda: s24.dense_dw(dYr, X, up.grad, 0.0)),
+            "dense_gemm": _clock_mhz(torch, s24, lambda: s24.dense_gemm(X, up.W, Yd)),
+        }
+        # per clock: 256 CUs x 4 matrix cores x 1024 dense bf16 FLOP (2048 dense-equivalent for 2:4 sparse)
+        out["core_clock_under_load"] = {
+            "MHz": clocks, "nominal_MHz": 2400,
+            "clock_scaled_peak_TFLOP/s": {k: (round(256 * 4 * (2048 if k == "spmm_fwd" else 1024) * v * 1e6 / 1e12, 0)
+                                              if v else None) for k, v in clocks.items()},
+            "note": "the large-tile GEMMs run (only when the tile count fills the chip); the chip lowers its clock "
+                    "under matrix-core + LDS + copy load, so the fraction of the published peak understates how "
+                    "busy the matrix cores are"}
     return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the measurements outside the timed step")
@@ -207,18 +301,21 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    timings, ffn.timings = ffn.timings, None
     value = wl.gemm_flops / (ms_per_step * 1e-3) / 1e12
 
-    extras = None if args.no_extras else side_measurements(torch, s24, wl, ffn, X)
+    extras = None if args.no_extras else side_measurements(torch, s24, wl, ffn, X, dY)
 
     model = kernel_model(wl)
     kernels = {}
-    for name, pairs in ffn.timings.items():
+    for name, pairs in timings.items():
         ms = [a.elapsed_time(b) for a, b in pairs]
         avg = sum(ms) / len(ms)
+        med = sorted(ms)[len(ms) // 2]
         kind, amount, peak, unit = model[name]
         achieved = amount / (avg * 1e-3) / (1e12 if kind == "mfma" else 1e9)
-        kernels[name] = {"launches_per_step": len(ms) // args.steps, "avg_ms": round(avg, 4), "min_ms": round(min(ms), 4),
+        kernels[name] = {"launches_per_step": len(ms) // args.steps, "avg_ms": round(avg, 4), "median_ms": round(med, 4),
+                         "min_ms": round(min(ms), 4),
                          "share_of_step": round(sum(ms) / args.steps / ms_per_step, 4), "bound": kind,
                          "achieved": round(achieved, 1), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
     dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])

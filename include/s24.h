@@ -143,6 +143,15 @@ int s24_act_fwd(const void *Z, void *H, int64_t n, s24_act act, s24_dtype dt, vo
 int s24_act_bwd(const void *dH, const void *Z, void *dZ, int64_t n, s24_act act, s24_dtype dt,
                 void *stream);
 
+/* Instrumentation, not part of the method: registers a DEVICE buffer of two uint64 (8-byte aligned), or
+ * NULL to switch the probe off (the default).  While a buffer is registered, workgroup 0 of every
+ * large-tile bf16 GEMM launched by s24_spmm_fwd / s24_spmm_bwd_dx / s24_dense_dw / s24_dense_gemm
+ * overwrites it with {core-clock cycles, ticks of the fixed 100 MHz reference} between its first and its
+ * last instruction: cycles / ticks * 100 MHz is the core clock the chip held under that kernel.  The
+ * setting is process-wide and not synchronised with launches in flight; the caller keeps the buffer alive
+ * until it has unregistered it and the stream has drained. */
+int s24_set_clock_probe(void *two_counters);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,7 @@ _SIGNATURES = {
     "s24_swiglu_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_act_fwd": (_int, [_vp, _vp, _i64, _int, _int, _vp]),
     "s24_act_bwd": (_int, [_vp, _vp, _vp, _i64, _int, _int, _vp]),
+    "s24_set_clock_probe": (_int, [_vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -166,3 +167,8 @@ def act_fwd(Z, H, act):
 def act_bwd(dH, Z, dZ, act):
     _check(lib().s24_act_bwd(_ptr(dH), _ptr(Z), _ptr(dZ), Z.numel(), act, _dt(Z), _stream()), "s24_act_bwd")
     return dZ
+
+
+def set_clock_probe(buf):
+    """buf: int64 tensor of two elements on the GPU, or None to switch the probe off."""
+    _check(lib().s24_set_clock_probe(_ptr(buf)), "s24_set_clock_probe")

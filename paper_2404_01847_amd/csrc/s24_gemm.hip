@@ -199,6 +199,23 @@ __device__ __forceinline__ void wait_and_barrier()
     asm volatile("" ::: "memory");
 }
 
+// Clock probe (instrumentation, off unless a buffer is registered): workgroup 0 of a large-tile kernel
+// reports how many core-clock cycles and how many ticks of the fixed 100 MHz reference passed between its
+// first and its last instruction.  Their ratio is the core clock the chip sustained under this kernel.
+struct ClockStamp { unsigned long long cycles, ticks; };
+__device__ __forceinline__ ClockStamp clock_now()
+{
+    return {__builtin_readcyclecounter(), __builtin_amdgcn_s_memrealtime()};
+}
+__device__ __forceinline__ void clock_report(unsigned long long *probe, const ClockStamp &t0)
+{
+    if (probe != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+        const ClockStamp t1 = clock_now();
+        probe[0] = t1.cycles - t0.cycles;
+        probe[1] = t1.ticks - t0.ticks;
+    }
+}
+
 // Output of one wave's 64 (n) x 128 (m) accumulator tile as bf16.  The wave parks the tile in LDS as
 // 64 rows of 256 bytes and streams it out 16 bytes per lane, 16 lanes covering one 256-byte row
 // segment of the output.  Inside a row the 8-byte unit u is stored at u ^ (row & 31), so the
@@ -239,8 +256,9 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
                                                               const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
                                                               uint16_t *__restrict__ Out, int N, int K, int M,
-                                                              int tiles_m, int tiles_n)
+                                                              int tiles_m, int tiles_n, unsigned long long *probe)
 {
+    const ClockStamp t_start = clock_now();
     // One array per ring stage: the compiler then knows which stage a direct-to-LDS
     // copy writes and does not make reads of the other stages wait for it.
     __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
@@ -365,6 +383,7 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     if (kc + 1 < nk) chunk(s1, s0, kc + 1);
     // drain the copies still in flight, then reuse the ring as a staging area for the output tile
     wait_and_barrier<0>();
+    clock_report(probe, t_start);
     if constexpr (ACCUM) {
         // beta = 1: add the old output in fp32 straight from the accumulators (a single rounding)
 #pragma unroll
@@ -568,8 +587,9 @@ using big::wait_vm_lgkm0;
 
 __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *__restrict__ X,
                                                                const uint16_t *__restrict__ W, uint16_t *__restrict__ Y,
-                                                               int N, int K, int M, int tiles_m, int tiles_n)
+                                                               int N, int K, int M, int tiles_m, int tiles_n, unsigned long long *probe)
 {
+    const big::ClockStamp t_start = big::clock_now();
     __shared__ __attribute__((aligned(16))) unsigned char s0[2 * OPERAND];
     __shared__ __attribute__((aligned(16))) unsigned char s1[2 * OPERAND];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -646,6 +666,7 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
     }
     if (kc < nk) chunk(s0, s1, kc);
     big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
+    big::clock_report(probe, t_start);
     big::staged_store(acc, (wave < 4 ? s0 : s1) + (wave & 3) * big::EWAVE, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
 }
 }  // namespace bignt
@@ -692,8 +713,10 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
 template <bool ACCUM>
 __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *__restrict__ dY,
                                                                const uint16_t *__restrict__ X, float *__restrict__ dW,
-                                                               int T, int M, int N, int tiles_m, int tiles_n)
+                                                               int T, int M, int N, int tiles_m, int tiles_n,
+                                                               unsigned long long *probe)
 {
+    const big::ClockStamp t_start = big::clock_now();
     __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
     __shared__ __attribute__((aligned(16))) unsigned char s1[STAGE];
     __shared__ __attribute__((aligned(16))) unsigned char s2[STAGE];
@@ -828,6 +851,7 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
     if (kc + 1 < nk) chunk(s1, s2, s0, kc + 1);
     if (kc + 2 < nk) chunk(s2, s3, s1, kc + 2);
     __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // drain the last (redundant) copies before LDS is released
+    big::clock_report(probe, t_start);
 #pragma unroll
     for (int ni = 0; ni < WT; ++ni) {
         const int n = n0 + 32 * WT * wn + 32 * ni + (lane & 31);
@@ -896,6 +920,8 @@ __global__ __launch_bounds__(kThreads) void fill_zero_kernel(float *__restrict__
 
 inline unsigned ceil_div(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b); }
 
+unsigned long long *g_clock_probe = nullptr;   // device buffer of two counters, or none
+
 // dtype and sizes first; pointers are only required when the output is not empty.
 int check_gemm(const void *a, const void *b, const void *c, int64_t p, int64_t q, int64_t r, int dt, int64_t out_elems)
 {
@@ -922,10 +948,10 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
         auto *o = static_cast<uint16_t *>(Out);
         if (accum)
             hipLaunchKernelGGL(big::spmm_nt_big_kernel<true>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
-                               tiles_m, tiles_n);
+                               tiles_m, tiles_n, g_clock_probe);
         else
             hipLaunchKernelGGL(big::spmm_nt_big_kernel<false>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
-                               tiles_m, tiles_n);
+                               tiles_m, tiles_n, g_clock_probe);
     } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(M, BM), ceil_div(N, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
@@ -979,7 +1005,7 @@ extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, 
         const int tiles_m = (int)ceil_div(r, bignt::BM), tiles_n = (int)ceil_div(p, bignt::BN);
         hipLaunchKernelGGL(bignt::dense_nt_big_kernel, dim3(((tiles_m * tiles_n + 7) / 8) * 8), dim3(bignt::THREADS), 0, st,
                            static_cast<const uint16_t *>(X), static_cast<const uint16_t *>(W), static_cast<uint16_t *>(Y),
-                           (int)p, (int)q, (int)r, tiles_m, tiles_n);
+                           (int)p, (int)q, (int)r, tiles_m, tiles_n, g_clock_probe);
     } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(r, BM), ceil_div(p, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
@@ -1015,10 +1041,10 @@ extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p,
         auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
         if (accum)
             hipLaunchKernelGGL(dmatn::dense_tn_dma_kernel<true>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
-                               tiles_m, tiles_n);
+                               tiles_m, tiles_n, g_clock_probe);
         else
             hipLaunchKernelGGL(dmatn::dense_tn_dma_kernel<false>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
-                               tiles_m, tiles_n);
+                               tiles_m, tiles_n, g_clock_probe);
     } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(r, BM), ceil_div(q, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
@@ -1032,4 +1058,11 @@ extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p,
         else hipLaunchKernelGGL(dense_tn_f32_kernel<false>, grid, block, 0, st, a, b, dW, p, r, q);
     }
     return s24_launch_status();
+}
+
+extern "C" int s24_set_clock_probe(void *two_counters)
+{
+    S24_REQUIRE(s24_aligned(two_counters, 8), S24_ERR_ALIGN);
+    g_clock_probe = static_cast<unsigned long long *>(two_counters);
+    return S24_OK;
 }

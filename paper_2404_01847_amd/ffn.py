@@ -112,3 +112,19 @@ class SparseFFN:
         self.forward(X)
         self.backward(X, dY)
         self.decay()
+
+    def capture(self, X, dY):
+        """Record one step into a HIP graph and return it (torch.cuda.CUDAGraph; replay() reruns the step on
+        the same buffers).  Possible because the step allocates nothing, never synchronises and only
+        launches kernels on the current stream.  Worth it where launches, not kernels, bound the step."""
+        if self.timings is not None:
+            raise RuntimeError("switch the per-kernel timing hooks off before capturing")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.step(X, dY)   # once outside the capture: library load and lazy initialisation
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(X, dY)
+        return graph

@@ -218,3 +218,34 @@ def test_workload_full_size(s24, name):
         assert_close(host_f64(out[bidx]), oracle.act_fwd(Hh[band], oracle.ACT_GELU_ERF), BF16_TOL, f"{name} gelu fwd")
         assert_close(host_f64(dz[bidx]), oracle.act_bwd(dZ[band], Hh[band], oracle.ACT_GELU_ERF), BF16_TOL,
                      f"{name} gelu bwd")
+
+
+def test_step_replayed_from_a_hip_graph_matches_eager_launches():
+    """The captured step is replayed several times with eager work and synchronisations in between;
+    every replay must reproduce the eager results bit for bit (the kernels are deterministic)."""
+    import torch
+    from paper_2404_01847_amd.ffn import SparseFFN
+    wl = si.Workload("g", 768, 256, 512, "swiglu", "bf16", 11)
+    host = si.make(wl)
+    d = {k: dev_bf16(v) for k, v in host.items()}
+    ffn = SparseFFN({n: d[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam)
+    X, dY = d["X"], d["dY"]
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (ffn.Y, ffn.dX, ffn.H, *(w.grad for w in ffn.w.values()),
+                                    *(w.mask for w in ffn.w.values()), *(w.valsT for w in ffn.w.values()))]
+
+    ffn.step(X, dY)
+    want = snapshot()
+    graph = ffn.capture(X, dY)
+    for replay in range(3):
+        for t in (ffn.Y, ffn.dX, ffn.H, *(w.grad for w in ffn.w.values())):
+            t.zero_()                      # eager work between replays; also proves the replay rewrites everything
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(want, got):
+            assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                               b.view(torch.int16) if b.dtype == torch.bfloat16 else b), f"replay {replay} differs"
+        ffn.step(X, dY)                    # an eager step between replays
