@@ -255,6 +255,8 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the measurements outside the timed step")
+    ap.add_argument("--no-fuse-decay", action="store_true",
+                    help="masked decay as its own kernel after the weight-gradient GEMM instead of inside its epilogue")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device-to-device copy five times (reference for HBM byte counters) and exit")
     args = ap.parse_args()
@@ -288,7 +290,7 @@ def main():
         return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
 
     dev = {k: to_dev(v) for k, v in host.items()}
-    ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam)
+    ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay)
     X, dY = dev["X"], dev["dY"]
 
     for _ in range(args.warmup):

@@ -111,6 +111,15 @@ int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, vo
 int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q, int64_t r,
                  float beta, s24_dtype dt, void *stream);
 
+/* Weight gradient with the masked decay term added in the same pass (Eq. 1 third GEMM + Eq. 10):
+ * dW[r][q] = beta*dW + dY^T . X + lambda * W on the cells the mask prunes.  W [r][q] (dtype wdt, dense)
+ * and mask [r/4][q/4] as in s24_masked_decay_grad; everything else as in s24_dense_dw.  The result has
+ * the same bits as s24_dense_dw followed by s24_masked_decay_grad.  The decay term does not depend on
+ * the batch: with beta = 1 accumulation over micro-batches it is passed (lambda != 0) once. */
+int s24_dense_dw_decay(const void *dY, const void *X, float *dW, const void *W, s24_dtype wdt,
+                       const uint16_t *mask, float lambda, int64_t p, int64_t q, int64_t r, float beta,
+                       s24_dtype dt, void *stream);
+
 /* Dense comparison GEMM (Eq. 1, first GEMM): Y[p][r] = X[p][q] . W[r][q]^T,
  * same tiling family as the sparse kernels.  q multiple of 32; r of 16. */
 int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r,

@@ -29,6 +29,7 @@ _SIGNATURES = {
     "s24_spmm_fwd": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_spmm_bwd_dx": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_dw": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
+    "s24_dense_dw_decay": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _f32, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_gemm": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_masked_decay_grad": (_int, [_vp, _vp, _int, _vp, _f32, _i64, _i64, _vp]),
     "s24_swiglu_fwd": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
@@ -129,6 +130,14 @@ def dense_dw(dY, X, dW, beta=0.0):
     p, r = dY.shape
     q = X.shape[1]
     _check(lib().s24_dense_dw(_ptr(dY), _ptr(X), _ptr(dW), p, q, r, beta, _dt(X), _stream()), "s24_dense_dw")
+    return dW
+
+
+def dense_dw_decay(dY, X, dW, W, mask, lam, beta=0.0):
+    p, r = dY.shape
+    q = X.shape[1]
+    _check(lib().s24_dense_dw_decay(_ptr(dY), _ptr(X), _ptr(dW), _ptr(W), _dt(W), _ptr(mask), lam, p, q, r, beta,
+                                    _dt(X), _stream()), "s24_dense_dw_decay")
     return dW
 
 

@@ -710,11 +710,16 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
     return __builtin_bit_cast(bf16x8, t);
 }
 
-template <bool ACCUM>
+// DECAY: the masked decay term is added in the epilogue: dW[m][n] += lambda * Wt[m][n] where bit
+// 4*(m%4) + n%4 of mask[m/4][n/4] is clear, with the same single fused multiply-add the stand-alone
+// decay kernel applies to the stored gradient, so both routes give the same bits.
+template <bool ACCUM, bool DECAY>
 __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *__restrict__ dY,
                                                                const uint16_t *__restrict__ X, float *__restrict__ dW,
                                                                int T, int M, int N, int tiles_m, int tiles_n,
-                                                               unsigned long long *probe)
+                                                               unsigned long long *probe,
+                                                               const uint16_t *__restrict__ Wt,
+                                                               const uint16_t *__restrict__ mask, float lambda)
 {
     const big::ClockStamp t_start = big::clock_now();
     __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
@@ -850,21 +855,65 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
     if (kc < nk) chunk(s0, s1, s3, kc);
     if (kc + 1 < nk) chunk(s1, s2, s0, kc + 1);
     if (kc + 2 < nk) chunk(s2, s3, s1, kc + 2);
-    __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // drain the last (redundant) copies before LDS is released
+    big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
     big::clock_report(probe, t_start);
+    // Epilogue through LDS, so that global memory sees 16-byte accesses along rows: each wave parks half of
+    // its tile (128 rows x 64 columns of fp32, 256-byte rows) in its own 32 KB stage, then lane l of pass j
+    // owns row (64j + l) / 16, columns 4 * (l % 16) .. +3: one LDS read, one 16-byte store, and for the
+    // optional terms one 16-byte load of the old gradient, one 8-byte load of W and one mask word.
+    unsigned char *est = wave == 0 ? s0 : (wave == 1 ? s1 : (wave == 2 ? s2 : s3));
 #pragma unroll
-    for (int ni = 0; ni < WT; ++ni) {
-        const int n = n0 + 32 * WT * wn + 32 * ni + (lane & 31);
-        if (n >= N) continue;
+    for (int h2 = 0; h2 < 2; ++h2) {
 #pragma unroll
-        for (int mi = 0; mi < WT; ++mi)
+        for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int m = m0 + 32 * WT * wm + 32 * mi + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
-                if (m >= M) continue;
-                float *dst = dW + (int64_t)m * N + n;
-                *dst = ACCUM ? (*dst + acc[mi][ni][i]) : acc[mi][ni][i];
+            for (int mi = 0; mi < WT; ++mi)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = 32 * mi + 8 * (e / 4) + 4 * (lane >> 5) + (e & 3), col = 32 * nj + (lane & 31);
+                    *reinterpret_cast<float *>(est + row * 256 + col * 4) = acc[mi][2 * h2 + nj][e];
+                }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
+        asm volatile("" ::: "memory");
+        constexpr int BATCH = 8;
+#pragma unroll 1
+        for (int j0 = 0; j0 < 32; j0 += BATCH) {
+            float4 v[BATCH], old[BATCH];
+            uint2 wv[BATCH];
+            uint32_t keep[BATCH];
+            bool live[BATCH];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const int idx = (j0 + b) * 64 + lane, row = idx >> 4, c4 = idx & 15;
+                const int m = m0 + 32 * WT * wm + row, n = n0 + 32 * WT * wn + 64 * h2 + 4 * c4;
+                live[b] = m < M && n < N;   // N is a multiple of 16: the four columns are all in or all out
+                const int mc = min(m, M - 1), nc = min(n, N - 4);
+                v[b] = *reinterpret_cast<const float4 *>(est + row * 256 + c4 * 16);
+                if (ACCUM) old[b] = *reinterpret_cast<const float4 *>(dW + (int64_t)mc * N + nc);
+                if (DECAY) {
+                    wv[b] = *reinterpret_cast<const uint2 *>(Wt + (int64_t)mc * N + nc);
+                    keep[b] = mask[(int64_t)(mc >> 2) * (N >> 2) + (nc >> 2)] >> (4 * (mc & 3));
+                }
             }
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const int idx = (j0 + b) * 64 + lane, row = idx >> 4, c4 = idx & 15;
+                const int m = m0 + 32 * WT * wm + row, n = n0 + 32 * WT * wn + 64 * h2 + 4 * c4;
+                float4 o = v[b];
+                if (ACCUM) { o.x = old[b].x + o.x; o.y = old[b].y + o.y; o.z = old[b].z + o.z; o.w = old[b].w + o.w; }
+                if (DECAY) {
+                    if (!(keep[b] & 1u)) o.x = fmaf(lambda, s24_bf16_to_f32(wv[b].x & 0xFFFFu), o.x);
+                    if (!(keep[b] & 2u)) o.y = fmaf(lambda, s24_bf16_to_f32(wv[b].x >> 16), o.y);
+                    if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_bf16_to_f32(wv[b].y & 0xFFFFu), o.z);
+                    if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_bf16_to_f32(wv[b].y >> 16), o.w);
+                }
+                if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * N + n) = o;
+            }
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // LDS reads done before the other half overwrites
+        asm volatile("" ::: "memory");
     }
 }
 }  // namespace dmatn
@@ -1018,33 +1067,30 @@ extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, 
     return s24_launch_status();
 }
 
-extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q, int64_t r, float beta,
-                            s24_dtype dt, void *stream)
+namespace {
+// Shared by s24_dense_dw and s24_dense_dw_decay.  W == nullptr: no decay term.
+int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q, int64_t r, float beta, int dt,
+                 const void *W, int wdt, const uint16_t *mask, float lambda, hipStream_t st)
 {
-    S24_REQUIRE(q % 16 == 0 && r % 16 == 0, S24_ERR_SHAPE);
-    S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
-    const int rc = check_gemm(dY, X, dW, p, q, r, dt, q * r);
-    if (rc != S24_OK || q * r == 0) return rc;
-    if (p == 0) {  // empty contraction: dW = beta * dW (the GEMM kernels need at least one token)
-        if (beta == 0.0f) {
-            hipLaunchKernelGGL(fill_zero_kernel, dim3(ceil_div(q * r, kThreads)), dim3(kThreads), 0,
-                               static_cast<hipStream_t>(stream), dW, q * r);
-            return s24_launch_status();
-        }
-        return S24_OK;
-    }
     const bool accum = beta != 0.0f;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt == S24_BF16 && (int64_t)ceil_div(r, dmatn::BM) * ceil_div(q, dmatn::BN) >= 192) {
+    bool decay_pending = W != nullptr;
+    if (p == 0) {  // empty contraction: dW = beta * dW (the GEMM kernels need at least one token)
+        if (!accum) hipLaunchKernelGGL(fill_zero_kernel, dim3(ceil_div(q * r, kThreads)), dim3(kThreads), 0, st, dW, q * r);
+    } else if (dt == S24_BF16 && (int64_t)ceil_div(r, dmatn::BM) * ceil_div(q, dmatn::BN) >= 192) {
         const int tiles_m = (int)ceil_div(r, dmatn::BM), tiles_n = (int)ceil_div(q, dmatn::BN);
         const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(dmatn::THREADS);
         auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
-        if (accum)
-            hipLaunchKernelGGL(dmatn::dense_tn_dma_kernel<true>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
-                               tiles_m, tiles_n, g_clock_probe);
-        else
-            hipLaunchKernelGGL(dmatn::dense_tn_dma_kernel<false>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q,
-                               tiles_m, tiles_n, g_clock_probe);
+        const bool fuse = decay_pending && wdt == S24_BF16;
+        auto *w = static_cast<const uint16_t *>(fuse ? W : nullptr);
+#define S24_LAUNCH_DW(ACC, DEC)                                                                                      \
+    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<ACC, DEC>), grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q, \
+                       tiles_m, tiles_n, g_clock_probe, w, mask, lambda)
+        if (accum && fuse) S24_LAUNCH_DW(true, true);
+        else if (accum) S24_LAUNCH_DW(true, false);
+        else if (fuse) S24_LAUNCH_DW(false, true);
+        else S24_LAUNCH_DW(false, false);
+#undef S24_LAUNCH_DW
+        if (fuse) decay_pending = false;
     } else if (dt == S24_BF16) {
         const dim3 grid(ceil_div(r, BM), ceil_div(q, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
@@ -1057,7 +1103,35 @@ extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p,
         if (accum) hipLaunchKernelGGL(dense_tn_f32_kernel<true>, grid, block, 0, st, a, b, dW, p, r, q);
         else hipLaunchKernelGGL(dense_tn_f32_kernel<false>, grid, block, 0, st, a, b, dW, p, r, q);
     }
-    return s24_launch_status();
+    const int rc = s24_launch_status();
+    if (rc != S24_OK || !decay_pending) return rc;
+    // shapes the fused epilogue does not cover: the stand-alone decay kernel on the finished gradient
+    return s24_masked_decay_grad(dW, W, static_cast<s24_dtype>(wdt), mask, lambda, r, q, st);
+}
+}  // namespace
+
+extern "C" int s24_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q, int64_t r, float beta,
+                            s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(q % 16 == 0 && r % 16 == 0, S24_ERR_SHAPE);
+    S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
+    const int rc = check_gemm(dY, X, dW, p, q, r, dt, q * r);
+    if (rc != S24_OK || q * r == 0) return rc;
+    return run_dense_dw(dY, X, dW, p, q, r, beta, dt, nullptr, dt, nullptr, 0.0f, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int s24_dense_dw_decay(const void *dY, const void *X, float *dW, const void *W, s24_dtype wdt,
+                                  const uint16_t *mask, float lambda, int64_t p, int64_t q, int64_t r, float beta,
+                                  s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(q % 16 == 0 && r % 16 == 0, S24_ERR_SHAPE);
+    S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
+    S24_REQUIRE(s24_valid_dtype(wdt), S24_ERR_DTYPE);
+    const int rc = check_gemm(dY, X, dW, p, q, r, dt, q * r);
+    if (rc != S24_OK || q * r == 0) return rc;
+    S24_REQUIRE(W && mask, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(W, 16) && s24_aligned(mask, 4), S24_ERR_ALIGN);
+    return run_dense_dw(dY, X, dW, p, q, r, beta, dt, W, wdt, mask, lambda, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int s24_set_clock_probe(void *two_counters)

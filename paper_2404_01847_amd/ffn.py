@@ -40,8 +40,9 @@ class SparseWeight:
 class SparseFFN:
     """Buffers and call sequence of one FFN layer.  act: 'relu' | 'gelu' | 'swiglu'."""
 
-    def __init__(self, weights: dict, p: int, act: str, lam: float):
+    def __init__(self, weights: dict, p: int, act: str, lam: float, fuse_decay: bool = True):
         self.act, self.lam, self.p = act, lam, p
+        self.fuse_decay = fuse_decay   # masked decay inside the weight-gradient GEMM's epilogue
         self.timings = None   # when a dict: kernel name -> list of (start, end) torch.cuda.Event pairs
         self.gated = act == "swiglu"
         names = ("Wg", "Wu", "Wd") if self.gated else ("W1", "W2")
@@ -84,25 +85,33 @@ class SparseFFN:
             self._k('spmm_fwd', s24.spmm_fwd, self.H, w["W2"].vals, w["W2"].meta, self.Y)
         return self.Y
 
+    def _dw(self, dYw, Xw, weight):
+        if self.fuse_decay:
+            self._k('dense_dw', s24.dense_dw_decay, dYw, Xw, weight.grad, weight.W, weight.mask, self.lam)
+        else:
+            self._k('dense_dw', s24.dense_dw, dYw, Xw, weight.grad)
+
     def backward(self, X, dY):
         w = self.w
         if self.gated:
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["Wd"].valsT, w["Wd"].metaT, self.dH)
-            self._k('dense_dw', s24.dense_dw, dY, self.H, w["Wd"].grad)
+            self._dw(dY, self.H, w["Wd"])
             self._k('swiglu_bwd', s24.swiglu_bwd, self.dH, self.G, self.U, self.dG, self.dU)
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dG, w["Wg"].valsT, w["Wg"].metaT, self.dX)
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dU, w["Wu"].valsT, w["Wu"].metaT, self.dX, beta=1.0)
-            self._k('dense_dw', s24.dense_dw, self.dG, X, w["Wg"].grad)
-            self._k('dense_dw', s24.dense_dw, self.dU, X, w["Wu"].grad)
+            self._dw(self.dG, X, w["Wg"])
+            self._dw(self.dU, X, w["Wu"])
         else:
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["W2"].valsT, w["W2"].metaT, self.dH)
-            self._k('dense_dw', s24.dense_dw, dY, self.H, w["W2"].grad)
+            self._dw(dY, self.H, w["W2"])
             self._k('act_bwd', s24.act_bwd, self.dH, self.Z, self.dZ, _ACT[self.act])
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dZ, w["W1"].valsT, w["W1"].metaT, self.dX)
-            self._k('dense_dw', s24.dense_dw, self.dZ, X, w["W1"].grad)
+            self._dw(self.dZ, X, w["W1"])
         return self.dX
 
     def decay(self):
+        if self.fuse_decay:
+            return   # already applied by backward()
         for w in self.w.values():
             self._k('masked_decay', s24.masked_decay_grad, w.grad, w.W, w.mask, self.lam)
 

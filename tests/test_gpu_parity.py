@@ -296,6 +296,35 @@ def test_masked_decay(s24, dtype, shape):
     np.testing.assert_allclose(got.astype(np.float64), ref, rtol=3e-7, atol=0)
 
 
+# ------------------------------------------------------------------ weight gradient + masked decay in one call
+@pytest.mark.parametrize("case", [
+    # (p, q, r, dtype, beta): small tiles, fp32 route, and enough 256x256 tiles for the fused epilogue
+    (300, 256, 208, "bf16", 0.0), (96, 64, 48, "f32", 1.0),
+    (1000, 3600, 3408, "bf16", 0.0), (777, 3600, 3408, "bf16", 1.0)])
+def test_dense_dw_decay_equals_the_two_calls_and_the_oracle(s24, case):
+    p, q, r, dtype, beta = case
+    lam = 2e-4
+    dY = si.random_matrix(600 + p, (p, r), 1e-2, dtype)
+    X = si.random_matrix(601 + p, (p, q), 1.0, dtype)
+    W = si.random_matrix(602 + p, (r, q), 0.02, dtype)
+    dW0 = si.random_matrix(603 + p, (r, q), 1e-3, "f32")
+    mask = oracle.transposable_mask(W)
+    d_dY, d_X, d_W, d_mask = dev_bf16(dY), dev_bf16(X), dev_bf16(W), dev(mask)
+    fused = dev(dW0).clone()
+    s24.dense_dw_decay(d_dY, d_X, fused, d_W, d_mask, lam, beta=beta)
+    two = dev(dW0).clone()
+    s24.dense_dw(d_dY, d_X, two, beta=beta)
+    s24.masked_decay_grad(two, d_W, d_mask, lam)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.view(torch.int32), two.view(torch.int32))          # same bits by construction
+    rows = np.unique(np.concatenate([[0, 3, 4, r - 1], np.random.default_rng(p).integers(0, r, 20)])).astype(np.int64)
+    g = oracle.dense_dw(dY, X, beta=beta, dW0=dW0[rows].astype(np.float64), rows=rows)
+    # the decay term of the sampled rows, from the oracle's own decay on a zero gradient
+    g = g + oracle.masked_decay(np.zeros((r, q), np.float32), W, mask, lam)[rows]
+    assert_close(host_f64(fused[torch.from_numpy(rows).cuda()]), g, tol("f32") if dtype == "f32" else F32_TOL,
+                 f"dense_dw_decay {case}")
+
+
 # ------------------------------------------------------------------ activations
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("pf", [(1, 8), (37, 264), (256, 1000)])

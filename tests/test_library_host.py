@@ -86,6 +86,11 @@ def test_gemm_argument_errors(lib):
     assert lib.s24_dense_dw(P, P, P, 4, 24, 16, 0.0, 1, None) == SHAPE
     assert lib.s24_dense_dw(P, P, P, 4, 16, 16, 2.0, 1, None) == UNSUP
     assert lib.s24_dense_dw(P, None, P, 4, 16, 16, 0.0, 1, None) == NULL
+    assert lib.s24_dense_dw_decay(P, P, P, P, 1, P, 1e-4, 4, 24, 16, 0.0, 1, None) == SHAPE
+    assert lib.s24_dense_dw_decay(P, P, P, None, 1, P, 1e-4, 4, 16, 16, 0.0, 1, None) == NULL
+    assert lib.s24_dense_dw_decay(P, P, P, P, 7, P, 1e-4, 4, 16, 16, 0.0, 1, None) == DTYPE
+    assert lib.s24_dense_dw_decay(P, P, P, P, 1, P + 2, 1e-4, 4, 16, 16, 0.0, 1, None) == ALIGN
+    assert lib.s24_dense_dw_decay(P, P, P, P, 1, P, 1e-4, 4, 16, 0, 0.0, 1, None) == OK
     assert lib.s24_dense_gemm(P, P, P, 4, 32, 16, 1, None) == SHAPE
     assert lib.s24_dense_gemm(P, P, P, 0, 64, 16, 1, None) == OK
 
