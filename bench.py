@@ -32,19 +32,23 @@ PEAK_HBM = 8000.0             # GB/s
 
 
 def kernel_model(wl):
-    """Algorithmic work of one launch of each kernel: (kind, amount, peak, unit)."""
+    """Algorithmic work of each kernel over one whole step: (kind, amount per step, peak, unit).  Per step and not
+    per launch because the launches of one kernel differ in size when gate and up projection are one weight."""
     p, d, f = wl.p, wl.d_model, wl.d_ff
     es = 2 if wl.dtype == "bf16" else 4
-    blocks = d * f / 16
-    gemm = 2.0 * p * d * f
+    nw = len(wl.weight_names)
+    blocks = nw * d * f / 16
+    gemm = nw * 2.0 * p * d * f
     m = {
         "spmm_fwd": ("mfma", gemm, PEAK_SPARSE_BF16, "TFLOP/s"),
         "spmm_bwd_dx": ("mfma", gemm, PEAK_SPARSE_BF16, "TFLOP/s"),
         "dense_dw": ("mfma", gemm, PEAK_DENSE_BF16, "TFLOP/s"),
         # per 4x4 block: read 16 weights; write mask 2, vals 16*es/2, meta 2, valsT 16*es/2, metaT 2
         "mask_compress": ("hbm", blocks * (16 * es + 2 + 8 * es + 2 + 8 * es + 2), PEAK_HBM, "GB/s"),
+        # with a given mask: read 16 weights + mask 2; write vals, meta, valsT, metaT
+        "compress": ("hbm", blocks * (16 * es + 2 + 8 * es + 2 + 8 * es + 2), PEAK_HBM, "GB/s"),
         # per element: read dW 4 + W es + mask 1/8, write 4
-        "masked_decay": ("hbm", d * f * (8 + es + 0.125), PEAK_HBM, "GB/s"),
+        "masked_decay": ("hbm", nw * d * f * (8 + es + 0.125), PEAK_HBM, "GB/s"),
         "swiglu_fwd": ("hbm", p * f * 3 * es, PEAK_HBM, "GB/s"),
         "swiglu_bwd": ("hbm", p * f * 5 * es, PEAK_HBM, "GB/s"),
         "act_fwd": ("hbm", p * f * 2 * es, PEAK_HBM, "GB/s"),
@@ -151,7 +155,7 @@ def _capture(torch, fn):
     return graph
 
 
-def side_measurements(torch, s24, wl, ffn, X, dY):
+def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     """Outside the timed step:
     (1) the mask search alone, over all weights of the layer in turn (34 algorithmic bytes per 4x4 bf16
         block: 32 read, 2 written); for c3 also over 72 distinct matrices of the layer's shape (36 layers x 2,
@@ -159,11 +163,18 @@ def side_measurements(torch, s24, wl, ffn, X, dY):
     (2) the dense-MFMA GEMM of the library next to the sparse GEMM at the layer's GEMM shapes (all three
         for c5, the up-projection otherwise);
     (3) the core clock under each large-tile GEMM kernel, and the clock-scaled matrix-core peak;
-    (4) the step replayed from a HIP graph."""
+    (4) the step replayed from a HIP graph;
+    (5) the step with the mask searched every 40th step only."""
     import s24_inputs as si
     out = {}
     es = 2 if wl.dtype == "bf16" else 4
-    ws = list(ffn.w.values())
+    from paper_2404_01847_amd.ffn import SparseWeight
+    # the layer's weights one by one (also where the timed step holds gate and up projection as one weight)
+    named = {}
+    for n in wl.weight_names:
+        named[n] = SparseWeight(weights[n])
+        named[n].refresh()
+    ws = list(named.values())
     masks = [torch.empty_like(w.mask) for w in ws]
 
     def sweep():
@@ -210,11 +221,17 @@ def side_measurements(torch, s24, wl, ffn, X, dY):
     ms_g = _time_ms(torch, graph.replay, 20)
     out["step_as_hip_graph"] = {"ms_per_step": round(ms_g, 4), "TFLOP/s": round(wl.gemm_flops / ms_g / 1e9, 1)}
     del graph
+    # (5) the paper's schedule: the mask searched every 40th step, prune + compress with the stored mask on the
+    # others (Sec. 5.1); 40 consecutive steps, one of them with the search
+    ffn.mask_interval, ffn.steps_done = 40, 0
+    ms_40 = _time_ms(torch, lambda: ffn.step(X, dY), 40)
+    ffn.mask_interval, ffn.steps_done = 1, 0
+    out["step_with_mask_every_40_steps"] = {"ms_per_step": round(ms_40, 4), "TFLOP/s": round(wl.gemm_flops / ms_40 / 1e9, 1)}
     if wl.dtype == "bf16":
-        names = list(ffn.w) if wl.name == "c5" else list(ffn.w)[:1]
+        names = list(named) if wl.name == "c5" else list(named)[:1]
         cmp_ = []
         for name in names:
-            w = ffn.w[name]
+            w = named[name]
             r, q = w.W.shape
             A = X if q == X.shape[1] else torch.empty((wl.p, q), dtype=X.dtype, device=X.device).normal_()
             Yd = torch.empty((wl.p, r), dtype=X.dtype, device=X.device)
@@ -255,6 +272,9 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the measurements outside the timed step")
+    ap.add_argument("--separate-gate-up", action="store_true",
+                    help="gate and up projection as two weights (three mask passes and nine GEMMs for a gated FFN) "
+                         "instead of one concatenated [2*d_ff, d_model] weight")
     ap.add_argument("--no-fuse-decay", action="store_true",
                     help="masked decay as its own kernel after the weight-gradient GEMM instead of inside its epilogue")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -290,7 +310,8 @@ def main():
         return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
 
     dev = {k: to_dev(v) for k, v in host.items()}
-    ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay)
+    ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay,
+                    concat_gate_up=not args.separate_gate_up)
     X, dY = dev["X"], dev["dY"]
 
     for _ in range(args.warmup):
@@ -306,19 +327,18 @@ def main():
     timings, ffn.timings = ffn.timings, None
     value = wl.gemm_flops / (ms_per_step * 1e-3) / 1e12
 
-    extras = None if args.no_extras else side_measurements(torch, s24, wl, ffn, X, dY)
+    extras = None if args.no_extras else side_measurements(torch, s24, wl, ffn, X, dY, {n: dev[n] for n in wl.weight_names})
 
     model = kernel_model(wl)
     kernels = {}
     for name, pairs in timings.items():
         ms = [a.elapsed_time(b) for a, b in pairs]
-        avg = sum(ms) / len(ms)
-        med = sorted(ms)[len(ms) // 2]
+        per_step = sum(ms) / args.steps
         kind, amount, peak, unit = model[name]
-        achieved = amount / (avg * 1e-3) / (1e12 if kind == "mfma" else 1e9)
-        kernels[name] = {"launches_per_step": len(ms) // args.steps, "avg_ms": round(avg, 4), "median_ms": round(med, 4),
-                         "min_ms": round(min(ms), 4),
-                         "share_of_step": round(sum(ms) / args.steps / ms_per_step, 4), "bound": kind,
+        achieved = amount / (per_step * 1e-3) / (1e12 if kind == "mfma" else 1e9)
+        kernels[name] = {"launches_per_step": len(ms) // args.steps, "ms_per_step": round(per_step, 4),
+                         "avg_ms": round(sum(ms) / len(ms), 4), "median_ms": round(sorted(ms)[len(ms) // 2], 4),
+                         "min_ms": round(min(ms), 4), "share_of_step": round(per_step / ms_per_step, 4), "bound": kind,
                          "achieved": round(achieved, 1), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
     dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])
     kd = kernels[dom]
@@ -332,6 +352,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: FFN d_model={wl.d_model} d_ff={wl.d_ff} tokens={wl.p} act={wl.act} "
                                f"{wl.dtype}, {len(wl.weight_names)} weights, mask+compress every step",
+                   "gate_up_as_one_weight": ffn.concat, "decay_in_dw_epilogue": ffn.fuse_decay,
                    "gemm_flops_per_step": wl.gemm_flops},
         "pct_of_sparse_mfma_peak_whole_step": round(100 * value / PEAK_SPARSE_BF16, 2),
         "roofline": roofline,

@@ -30,29 +30,48 @@ class SparseWeight:
         self.metaT = torch.empty((r // 64, q, 4), dtype=torch.int16, device=dev)
         self.grad = torch.empty((r, q), dtype=torch.float32, device=dev)
 
-    def refresh(self, call=None):
-        """Search the mask and rebuild both compressed operands in one pass over W."""
+    def refresh(self, call=None, search=True):
+        """Rebuild both compressed operands in one pass over W; with `search` the mask is searched in the
+        same pass, otherwise the stored mask is applied as it is (the steps between two mask updates)."""
         call = call or (lambda name, fn, *a, **k: fn(*a, **k))
-        call("mask_compress", s24.compress, self.W, None, self.vals, self.meta, self.valsT, self.metaT,
-             mask_out=self.mask)
+        if search:
+            call("mask_compress", s24.compress, self.W, None, self.vals, self.meta, self.valsT, self.metaT,
+                 mask_out=self.mask)
+        else:
+            call("compress", s24.compress, self.W, self.mask, self.vals, self.meta, self.valsT, self.metaT)
 
 
 class SparseFFN:
     """Buffers and call sequence of one FFN layer.  act: 'relu' | 'gelu' | 'swiglu'."""
 
-    def __init__(self, weights: dict, p: int, act: str, lam: float, fuse_decay: bool = True):
+    def __init__(self, weights: dict, p: int, act: str, lam: float, fuse_decay: bool = True, mask_interval: int = 1,
+                 concat_gate_up: bool = False):
         self.act, self.lam, self.p = act, lam, p
+        self.mask_interval = mask_interval   # the mask is searched every mask_interval-th step (Sec. 5.1: l = 40)
+        self.steps_done = 0
         self.fuse_decay = fuse_decay   # masked decay inside the weight-gradient GEMM's epilogue
         self.timings = None   # when a dict: kernel name -> list of (start, end) torch.cuda.Event pairs
         self.gated = act == "swiglu"
-        names = ("Wg", "Wu", "Wd") if self.gated else ("W1", "W2")
+        # gate and up projection held as one [2*d_ff, d_model] weight (Sec. 5.2): one mask/compress pass, one
+        # forward GEMM into a [p, 2*d_ff] buffer whose halves are Z_1 and Z_2, one input-gradient GEMM over
+        # the 2*d_ff contraction instead of two accumulated ones, one weight-gradient GEMM
+        self.concat = self.gated and concat_gate_up
+        if self.concat:
+            weights = {"Wgu": torch.cat([weights["Wg"], weights["Wu"]], dim=0).contiguous(), "Wd": weights["Wd"]}
+            names = ("Wgu", "Wd")
+        else:
+            names = ("Wg", "Wu", "Wd") if self.gated else ("W1", "W2")
         self.w = {n: SparseWeight(weights[n]) for n in names}
-        up = self.w["Wg" if self.gated else "W1"].W
-        f, d = up.shape
+        d = weights[names[0]].shape[1]
+        f = weights[names[-1]].shape[1]
+        up = self.w[names[0]].W
         dev, dt = up.device, up.dtype
         new = lambda *shape: torch.empty(shape, dtype=dt, device=dev)
         self.H, self.dH, self.Y, self.dX = new(p, f), new(p, f), new(p, d), new(p, d)
-        if self.gated:
+        if self.concat:
+            self.GU, self.dGU = new(p, 2 * f), new(p, 2 * f)
+            self.G, self.U, self.dG, self.dU = self.GU[:, :f], self.GU[:, f:], self.dGU[:, :f], self.dGU[:, f:]
+        elif self.gated:
             self.G, self.U, self.dG, self.dU = new(p, f), new(p, f), new(p, f), new(p, f)
         else:
             self.Z, self.dZ = new(p, f), new(p, f)
@@ -68,13 +87,17 @@ class SparseFFN:
         self.timings.setdefault(name, []).append((e0, e1))
         return out
 
-    def prune(self):
+    def prune(self, search=True):
         for w in self.w.values():
-            w.refresh(self._k)
+            w.refresh(self._k, search)
 
     def forward(self, X):
         w = self.w
-        if self.gated:
+        if self.concat:
+            self._k('spmm_fwd', s24.spmm_fwd, X, w["Wgu"].vals, w["Wgu"].meta, self.GU)
+            self._k('swiglu_fwd', s24.swiglu_fwd, self.G, self.U, self.H)
+            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["Wd"].vals, w["Wd"].meta, self.Y)
+        elif self.gated:
             self._k('spmm_fwd', s24.spmm_fwd, X, w["Wg"].vals, w["Wg"].meta, self.G)
             self._k('spmm_fwd', s24.spmm_fwd, X, w["Wu"].vals, w["Wu"].meta, self.U)
             self._k('swiglu_fwd', s24.swiglu_fwd, self.G, self.U, self.H)
@@ -93,7 +116,13 @@ class SparseFFN:
 
     def backward(self, X, dY):
         w = self.w
-        if self.gated:
+        if self.concat:
+            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["Wd"].valsT, w["Wd"].metaT, self.dH)
+            self._dw(dY, self.H, w["Wd"])
+            self._k('swiglu_bwd', s24.swiglu_bwd, self.dH, self.G, self.U, self.dG, self.dU)
+            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dGU, w["Wgu"].valsT, w["Wgu"].metaT, self.dX)
+            self._dw(self.dGU, X, w["Wgu"])
+        elif self.gated:
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["Wd"].valsT, w["Wd"].metaT, self.dH)
             self._dw(dY, self.H, w["Wd"])
             self._k('swiglu_bwd', s24.swiglu_bwd, self.dH, self.G, self.U, self.dG, self.dU)
@@ -117,7 +146,8 @@ class SparseFFN:
 
     def step(self, X, dY):
         """Mask + compress, forward, backward, masked decay: the whole hot path once."""
-        self.prune()
+        self.prune(search=self.steps_done % self.mask_interval == 0)
+        self.steps_done += 1
         self.forward(X)
         self.backward(X, dY)
         self.decay()

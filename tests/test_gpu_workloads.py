@@ -249,3 +249,62 @@ def test_step_replayed_from_a_hip_graph_matches_eager_launches():
             assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
                                b.view(torch.int16) if b.dtype == torch.bfloat16 else b), f"replay {replay} differs"
         ffn.step(X, dY)                    # an eager step between replays
+
+
+def test_mask_interval_keeps_the_mask_and_recompresses_the_new_weights():
+    """Between two mask searches the stored mask is applied to the updated weights (prune + compress every
+    step, search every l-th step): checked against the oracle's compress of the new weights under the old mask."""
+    from paper_2404_01847_amd.ffn import SparseFFN
+    wl = si.Workload("i", 256, 128, 256, "gelu", "bf16", 12)
+    host = si.make(wl)
+    d = {k: dev_bf16(v) for k, v in host.items()}
+    ffn = SparseFFN({n: d[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, mask_interval=3)
+    ffn.step(d["X"], d["dY"])
+    torch.cuda.synchronize()
+    mask0 = {n: host_bits(w.mask).copy() for n, w in ffn.w.items()}
+    for n in wl.weight_names:
+        assert np.array_equal(mask0[n], oracle.transposable_mask(host[n]))
+    # new weights (another seed), same buffers
+    new = {n: si.random_matrix(900 + i, host[n].shape, 0.02, "bf16") for i, n in enumerate(wl.weight_names)}
+    for n in wl.weight_names:
+        ffn.w[n].W.copy_(dev_bf16(new[n]))
+    ffn.step(d["X"], d["dY"])          # step 1: no search
+    torch.cuda.synchronize()
+    for n, w in ffn.w.items():
+        assert np.array_equal(host_bits(w.mask), mask0[n])
+        vals, meta, valsT, metaT = oracle.compress(new[n], mask0[n])
+        vp, mp = oracle.pack(vals, meta)
+        vtp, mtp = oracle.pack(valsT, metaT)
+        assert np.array_equal(host_bits(w.vals), vp) and np.array_equal(host_bits(w.meta), mp)
+        assert np.array_equal(host_bits(w.valsT), vtp) and np.array_equal(host_bits(w.metaT), mtp)
+    ffn.step(d["X"], d["dY"])          # step 2: no search
+    ffn.step(d["X"], d["dY"])          # step 3: search again, now on the new weights
+    torch.cuda.synchronize()
+    for n, w in ffn.w.items():
+        assert np.array_equal(host_bits(w.mask), oracle.transposable_mask(new[n]))
+
+
+def test_gate_and_up_as_one_weight_matches_the_separate_weights():
+    """One [2*d_ff, d_model] weight: forward results and weight gradients are bit-identical to the three-weight
+    layout (same per-output arithmetic); dX sums the 2*d_ff contraction in one GEMM, so it agrees to tolerance."""
+    from paper_2404_01847_amd.ffn import SparseFFN
+    wl = si.Workload("c", 640, 256, 448, "swiglu", "bf16", 13)
+    host = si.make(wl)
+    d = {k: dev_bf16(v) for k, v in host.items()}
+    a = SparseFFN({n: d[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam)
+    b = SparseFFN({n: d[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, concat_gate_up=True)
+    a.step(d["X"], d["dY"])
+    b.step(d["X"], d["dY"])
+    torch.cuda.synchronize()
+    f = wl.d_ff
+    bits = lambda t: t.contiguous().view(torch.int16)
+    for x, y in ((a.G, b.G), (a.U, b.U), (a.H, b.H), (a.Y, b.Y), (a.dH, b.dH), (a.dG, b.dG), (a.dU, b.dU)):
+        assert torch.equal(bits(x), bits(y))
+    assert torch.equal(a.w["Wg"].grad, b.w["Wgu"].grad[:f]) and torch.equal(a.w["Wu"].grad, b.w["Wgu"].grad[f:])
+    assert torch.equal(a.w["Wd"].grad, b.w["Wd"].grad)
+    assert torch.equal(a.w["Wg"].mask, b.w["Wgu"].mask[:f // 4]) and torch.equal(a.w["Wu"].mask, b.w["Wgu"].mask[f // 4:])
+    # both routes round to bf16 (the two-GEMM route twice), so they differ by bf16 roundings of partial sums:
+    # normwise agreement, and no element further apart than a few bf16 steps at the scale of the larger sums
+    x, y = host_f64(a.dX), host_f64(b.dX)
+    assert np.linalg.norm(x - y) <= BF16_TOL[1] * np.linalg.norm(x)
+    assert np.abs(x - y).max() <= 2.0 ** -6 * np.abs(x).max()
