@@ -39,7 +39,8 @@ def _load():
         _lib = C.CDLL(_LIB)
         for name in ("orc_pack_chunk_major", "orc_pattern_table", "orc_transposable_mask", "orc_compress", "orc_spmm_fwd",
                      "orc_spmm_bwd_dx", "orc_dense_dw", "orc_dense_gemm", "orc_masked_decay",
-                     "orc_swiglu_fwd", "orc_swiglu_bwd", "orc_act_fwd", "orc_act_bwd", "orc_num_threads"):
+                     "orc_swiglu_fwd", "orc_swiglu_bwd", "orc_act_fwd", "orc_act_bwd", "orc_num_threads",
+                     "orc_mask_flips", "orc_l1_norm_gap"):
             getattr(_lib, name).restype = C.c_int
         _lib.orc_round_bf16.restype = None
     return _lib
@@ -94,6 +95,28 @@ def transposable_mask(W: np.ndarray, want_index: bool = False, exact_wide: bool 
                                        _p(mask), _p(index), C.c_int(1 if exact_wide else 0))
     _check(rc, "transposable_mask")
     return (mask, index) if want_index else mask
+
+
+def mask_flips(mask_new, mask_old, block_flips=None) -> int:
+    """Number of mask cells that differ (the flip rate's numerator); block_flips (uint32, in place) += per block."""
+    a, b = _c(mask_new, np.uint16), _c(mask_old, np.uint16)
+    if a.shape != b.shape:
+        raise ValueError("mask shapes differ")
+    if block_flips is not None and (block_flips.dtype != np.uint32 or not block_flips.flags.c_contiguous
+                                    or block_flips.size != a.size):
+        raise ValueError("block_flips must be a contiguous uint32 array with one entry per block")
+    total = C.c_uint64(0)
+    _check(_load().orc_mask_flips(_p(a), _p(b), C.c_int64(a.size), _p(block_flips), C.byref(total)), "mask_flips")
+    return int(total.value)
+
+
+def l1_norm_gap(W: np.ndarray) -> np.ndarray:
+    """Per 4x4 block: best minus second-best kept L1 norm over the 90 patterns, float64 [r/4, q/4]."""
+    W = _c(W)
+    r, q = W.shape
+    gap = np.zeros((r // 4, q // 4), dtype=np.float64)
+    _check(_load().orc_l1_norm_gap(_p(W), _dt(W), C.c_int64(r), C.c_int64(q), C.c_int64(q), _p(gap)), "l1_norm_gap")
+    return gap
 
 
 def compress(W: np.ndarray, mask: np.ndarray):

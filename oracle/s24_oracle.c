@@ -203,6 +203,78 @@ int orc_transposable_mask(const void *W, int dt, int64_t r, int64_t q, int64_t l
 }
 
 /* ------------------------------------------------------------------ */
+/* Monitors: flip count (Sec. 4.1, definition of the flip rate) and    */
+/* L1-norm gap of a block (Sec. 4.2).                                  */
+/* ------------------------------------------------------------------ */
+
+/* total = || m_new - m_old ||_1 over all mask cells (each changed cell counts one); the flip rate is
+ * total / (16 * nblocks).  block_flips (optional) accumulates every block's own count. */
+int orc_mask_flips(const uint16_t *mask_new, const uint16_t *mask_old, int64_t nblocks, uint32_t *block_flips,
+                   uint64_t *total)
+{
+    if (nblocks < 0) return -1;
+    uint64_t sum = 0;
+    for (int64_t b = 0; b < nblocks; ++b) {
+        unsigned x = (unsigned)(mask_new[b] ^ mask_old[b]), c = 0;
+        for (int t = 0; t < 16; ++t) c += (x >> t) & 1u;
+        if (block_flips) block_flips[b] += c;
+        sum += c;
+    }
+    *total = sum;
+    return 0;
+}
+
+/* a - b for normalised a >= b, rounded once to the 64-bit significand of long double and then to double
+ * (exact whenever the difference has at most 53 significant bits). */
+static double wide_diff(const wide_t *a, const wide_t *b)
+{
+    int64_t d[WIDE_LIMBS];
+    int64_t borrow = 0;
+    for (int i = 0; i < WIDE_LIMBS; ++i) {
+        int64_t t = (int64_t)a->limb[i] - (int64_t)b->limb[i] - borrow;
+        borrow = t < 0;
+        d[i] = t + (borrow << 32);
+    }
+    long double x = 0.0L;
+    for (int i = WIDE_LIMBS - 1; i >= 0; --i) x = x * 4294967296.0L + (long double)d[i];
+    return (double)ldexpl(x, -149);
+}
+
+/* gap[(r/4) x (q/4)]: for every block, the kept L1 norm of the best of the 90 patterns minus that of the
+ * second best pattern (another pattern: zero when two patterns tie for the best), from exact sums. */
+int orc_l1_norm_gap(const void *W, int dt, int64_t r, int64_t q, int64_t ldw, double *gap)
+{
+    if (r < 0 || q < 0 || (r % 4) || (q % 4) || ldw < q) return -1;
+    uint16_t pat[90];
+    if (orc_pattern_table(pat, 90) != 90) return -2;
+    int64_t br = r / 4, bq = q / 4;
+#pragma omp parallel for schedule(static)
+    for (int64_t bi = 0; bi < br; ++bi) {
+        for (int64_t bj = 0; bj < bq; ++bj) {
+            double a[16];
+            for (int i = 0; i < 4; ++i)
+                for (int j = 0; j < 4; ++j)
+                    a[4 * i + j] = fabs(widen(W, dt, (size_t)((4 * bi + i) * ldw + 4 * bj + j)));
+            wide_t first, second;
+            memset(&first, 0, sizeof first);
+            memset(&second, 0, sizeof second);
+            for (int k = 0; k < 90; ++k) {
+                wide_t s;
+                memset(&s, 0, sizeof s);
+                for (int t = 0; t < 16; ++t)
+                    if ((pat[k] >> t) & 1u) wide_add(&s, a[t]);
+                wide_normalise(&s);
+                if (k == 0) { first = s; continue; }
+                if (wide_cmp(&s, &first) > 0) { second = first; first = s; }
+                else if (k == 1 || wide_cmp(&s, &second) > 0) second = s;
+            }
+            gap[bi * bq + bj] = wide_diff(&first, &second);
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Compress ("enforcing the mask", Sec. 5 item 1; sparse_W and         */
 /* sparse_W_T of the workflow in App. B).                              */
 /* ------------------------------------------------------------------ */

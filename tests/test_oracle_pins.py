@@ -379,3 +379,80 @@ def test_round_bf16_matches_torch():
     x[:4] = [0.0, -0.0, 1.00390625, 1.01171875]   # exact ties: round to even
     want = torch.from_numpy(x).float().to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(oracle.round_bf16(x), want)
+
+
+# ---------------------------------------------------------------- monitors: flip count, L1-norm gap
+def test_flip_count_hand_examples():
+    # Sec. 4.1, definition of the flip rate: the L1 distance of the two 0/1 mask vectors
+    a = np.array([[0x33CC, 0xCC33], [0x5A5A, 0x33CC]], dtype=np.uint16)
+    assert oracle.mask_flips(a, a) == 0
+    b = a.copy()
+    b[0, 0] = 0xCC33                      # the complementary pattern: all 16 cells change
+    assert oracle.mask_flips(b, a) == 16
+    b[1, 0] = 0x5A5A ^ 0x0003             # two more cells
+    per_block = np.zeros(4, dtype=np.uint32)
+    assert oracle.mask_flips(b, a, per_block) == 18
+    assert per_block.tolist() == [16, 0, 2, 0]
+    assert oracle.mask_flips(b, a, per_block) == 18          # the per-block counter accumulates
+    assert per_block.tolist() == [32, 0, 4, 0]
+    assert oracle.mask_flips(a, b) == oracle.mask_flips(b, a)
+
+
+def test_flip_count_equals_numpy_on_expanded_masks():
+    w0 = si.random_matrix(31, (64, 96), 0.02, "bf16")
+    w1 = si.random_matrix(32, (64, 96), 0.02, "bf16")
+    m0, m1 = oracle.transposable_mask(w0), oracle.transposable_mask(w1)
+    want = int(np.abs(expand_mask(m0).astype(np.int64) - expand_mask(m1).astype(np.int64)).sum())
+    assert oracle.mask_flips(m1, m0) == want
+    assert 0 < want <= 64 * 96
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_l1_gap_equals_exact_rational_enumeration(legal_blocks, dtype):
+    # Sec. 4.2: g = ||m1 . w||_1 - ||m2 . w||_1 with m1, m2 the masks of largest and second largest kept norm
+    W = si.random_matrix(41, (16, 24), 0.02, dtype)
+    a = np.abs(f64(W))
+    got = oracle.l1_norm_gap(W)
+    for bi in range(4):
+        for bj in range(6):
+            blk = [Fraction(float(a[4 * bi + i, 4 * bj + j])) for i in range(4) for j in range(4)]
+            sums = sorted((sum(blk[t] for t in range(16) if (p >> t) & 1) for p in legal_blocks), reverse=True)
+            assert Fraction(float(got[bi, bj])) == sums[0] - sums[1]      # exact: the difference fits fp64
+
+
+def test_l1_gap_special_cases():
+    ones = np.ones((4, 4), dtype=np.float32)
+    assert oracle.l1_norm_gap(ones)[0, 0] == 0.0                          # every pattern keeps 8
+    w = ones.copy()
+    w[0, 0] = 3.0                                                         # many patterns keep cell (0,0): still tied
+    assert oracle.l1_norm_gap(w)[0, 0] == 0.0
+    # a block whose best pattern is unique: heavy cells on 0x33CC, then one kept cell lowered by 0.25 --
+    # the runner-up swaps one 2x2 sub-pattern, so the gap is the cost of that swap
+    pat = 0x33CC
+    w = np.full(16, 1.0, dtype=np.float32)
+    for t in range(16):
+        if (pat >> t) & 1:
+            w[t] = 8.0
+    g0 = oracle.l1_norm_gap(w.reshape(4, 4))[0, 0]
+    assert g0 == 2 * (8.0 - 1.0)                                          # any other legal pattern drops >= 2 heavy cells
+    # scaling by a power of two scales the gap exactly; the gap is never negative
+    W = si.random_matrix(43, (32, 32), 0.02, "f32")
+    g = oracle.l1_norm_gap(W)
+    assert (g >= 0).all()
+    assert np.array_equal(oracle.l1_norm_gap((W * 4.0).astype(np.float32)), 4.0 * g)
+
+
+def test_l1_gap_is_consistent_with_the_mask_search():
+    # best kept norm = norm kept by the oracle's own mask; with a strictly positive gap that mask is the unique optimum
+    W = si.random_matrix(44, (32, 48), 0.02, "bf16")
+    a = np.abs(f64(W))
+    keep = expand_mask(oracle.transposable_mask(W)).astype(bool)
+    g = oracle.l1_norm_gap(W)
+    tab = [int(v) for v in oracle.pattern_table()]
+    for bi in range(8):
+        for bj in range(12):
+            blk = a[4 * bi:4 * bi + 4, 4 * bj:4 * bj + 4]
+            best = blk[keep[4 * bi:4 * bi + 4, 4 * bj:4 * bj + 4]].sum()
+            others = sorted(sum(blk[t // 4, t % 4] for t in range(16) if (p >> t) & 1) for p in tab)
+            assert abs(others[-1] - best) <= 1e-12 * best
+            assert abs((others[-1] - others[-2]) - g[bi, bj]) <= 1e-12 * best
