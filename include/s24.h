@@ -152,6 +152,22 @@ int s24_act_fwd(const void *Z, void *H, int64_t n, s24_act act, s24_dtype dt, vo
 int s24_act_bwd(const void *dH, const void *Z, void *dZ, int64_t n, s24_act act, s24_dtype dt,
                 void *stream);
 
+/* Flip count (Sec. 4.1, definition of the flip rate): *flips = || m_new - m_old ||_1 over all mask cells,
+ * i.e. the number of cells whose mask bit differs; the flip rate r_t is *flips / (16 * nblocks).
+ *   mask_new, mask_old  [nblocks] device, 16-byte aligned
+ *   block_flips         [nblocks] device uint32, may be NULL: every block's own count is ADDED to its entry
+ *                       (the cumulative per-block flip number of Sec. 4.2)
+ *   flips               device uint64, overwritten */
+int s24_mask_flips(const uint16_t *mask_new, const uint16_t *mask_old, int64_t nblocks, uint32_t *block_flips,
+                   uint64_t *flips, void *stream);
+
+/* L1-norm gap (Sec. 4.2): gap[r/4][q/4] (device, fp64) = for every 4x4 block of W the kept L1 norm of the
+ * best legal pattern minus that of the second best one (zero when two patterns tie for the best).  W as in
+ * s24_transposable_mask.  The 90 sums are taken in fp64: exact, and the gap correctly rounded, whenever the
+ * block's exponent spread fits fp64 (29 binades for bf16 data, 13 for fp32); beyond that the sums carry
+ * fp64 rounding. */
+int s24_l1_norm_gap(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw, double *gap, void *stream);
+
 /* Instrumentation, not part of the method: registers a DEVICE buffer of two uint64 (8-byte aligned), or
  * NULL to switch the probe off (the default).  While a buffer is registered, workgroup 0 of every
  * large-tile bf16 GEMM launched by s24_spmm_fwd / s24_spmm_bwd_dx / s24_dense_dw / s24_dense_gemm

@@ -36,6 +36,8 @@ _SIGNATURES = {
     "s24_swiglu_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_act_fwd": (_int, [_vp, _vp, _i64, _int, _int, _vp]),
     "s24_act_bwd": (_int, [_vp, _vp, _vp, _i64, _int, _int, _vp]),
+    "s24_mask_flips": (_int, [_vp, _vp, _i64, _vp, _vp, _vp]),
+    "s24_l1_norm_gap": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp]),
     "s24_set_clock_probe": (_int, [_vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
@@ -176,6 +178,19 @@ def act_fwd(Z, H, act):
 def act_bwd(dH, Z, dZ, act):
     _check(lib().s24_act_bwd(_ptr(dH), _ptr(Z), _ptr(dZ), Z.numel(), act, _dt(Z), _stream()), "s24_act_bwd")
     return dZ
+
+
+def mask_flips(mask_new, mask_old, flips, block_flips=None):
+    """flips: int64 tensor of one element (overwritten); block_flips: int32 tensor, one per block (added to)."""
+    _check(lib().s24_mask_flips(_ptr(mask_new), _ptr(mask_old), mask_new.numel(), _ptr(block_flips), _ptr(flips),
+                                _stream()), "s24_mask_flips")
+    return flips
+
+
+def l1_norm_gap(W, gap):
+    r, q = W.shape
+    _check(lib().s24_l1_norm_gap(_ptr(W), _dt(W), r, q, W.stride(0), _ptr(gap), _stream()), "s24_l1_norm_gap")
+    return gap
 
 
 def set_clock_probe(buf):

@@ -568,6 +568,94 @@ int launch(const void *W, int64_t r, int64_t q, int64_t ldw, const uint16_t *mas
     return s24_launch_status();
 }
 
+// ------------------------------------------------------------------ monitors
+// Flip count: || m_new - m_old ||_1 over all mask cells.  Eight blocks (one 16-byte load of each mask) per
+// thread and pass; wave sums by cross-lane adds, one 64-bit atomic per wave.
+__global__ __launch_bounds__(256) void clear_counter_kernel(unsigned long long *counter) { *counter = 0ull; }
+
+__global__ __launch_bounds__(256) void mask_flips_kernel(const uint16_t *__restrict__ mask_new,
+                                                         const uint16_t *__restrict__ mask_old, int64_t nblocks,
+                                                         uint32_t *__restrict__ block_flips,
+                                                         unsigned long long *__restrict__ total)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    unsigned count = 0;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v * 8 < nblocks; v += stride) {
+        const int64_t b0 = v * 8;
+        if (b0 + 8 <= nblocks) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(mask_new + b0), b = *reinterpret_cast<const uint4 *>(mask_old + b0);
+            const uint32_t x[4] = {a.x ^ b.x, a.y ^ b.y, a.z ^ b.z, a.w ^ b.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                count += __builtin_popcount(x[k]);
+                if (block_flips) {
+                    block_flips[b0 + 2 * k] += __builtin_popcount(x[k] & 0xFFFFu);
+                    block_flips[b0 + 2 * k + 1] += __builtin_popcount(x[k] >> 16);
+                }
+            }
+        } else {
+            for (int64_t b = b0; b < nblocks; ++b) {
+                const unsigned c = __builtin_popcount((unsigned)(mask_new[b] ^ mask_old[b]));
+                count += c;
+                if (block_flips) block_flips[b] += c;
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) count += __shfl_down(count, off, 64);
+    if ((threadIdx.x & 63) == 0 && count != 0) atomicAdd(total, (unsigned long long)count);
+}
+
+// L1-norm gap: one block per thread, all 90 kept norms in fp64 (exact while the block's exponent spread
+// stays inside fp64's 53 bits, which it does for any bf16 block spanning up to 29 binades), best and
+// second best tracked on the way.
+template <typename T>
+__global__ __launch_bounds__(256) void l1_gap_kernel(const T *__restrict__ W, int64_t ldw, int br, int bq,
+                                                     double *__restrict__ gap)
+{
+    __shared__ uint16_t s_pat[S24_NUM_PATTERNS];
+    if (threadIdx.x < S24_NUM_PATTERNS) s_pat[threadIdx.x] = g_patterns.mask[threadIdx.x];
+    __syncthreads();
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)br * bq) return;
+    const int bi = (int)(idx / bq), bj = (int)(idx - (int64_t)bi * bq);
+    double a[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const T *row = W + (int64_t)(4 * bi + i) * ldw + 4 * bj;
+        if constexpr (sizeof(T) == 2) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(row);
+            a[4 * i] = fabs((double)s24_bf16_to_f32(v.x & 0xFFFFu));
+            a[4 * i + 1] = fabs((double)s24_bf16_to_f32(v.x >> 16));
+            a[4 * i + 2] = fabs((double)s24_bf16_to_f32(v.y & 0xFFFFu));
+            a[4 * i + 3] = fabs((double)s24_bf16_to_f32(v.y >> 16));
+        } else {
+            const float4 v = *reinterpret_cast<const float4 *>(row);
+            a[4 * i] = fabs((double)v.x);
+            a[4 * i + 1] = fabs((double)v.y);
+            a[4 * i + 2] = fabs((double)v.z);
+            a[4 * i + 3] = fabs((double)v.w);
+        }
+    }
+    double first = 0.0, second = 0.0;
+#pragma unroll 1
+    for (int k = 0; k < S24_NUM_PATTERNS; ++k) {
+        const unsigned m = s_pat[k];
+        double sum = 0.0;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) sum += ((m >> t) & 1u) ? a[t] : 0.0;
+        if (k == 0) {
+            first = sum;
+        } else if (sum > first) {
+            second = first;
+            first = sum;
+        } else if (k == 1 || sum > second) {
+            second = sum;
+        }
+    }
+    gap[idx] = first - second;
+}
+
 // Shape and dtype are checked first; an empty matrix (r or q zero) is accepted
 // whatever the pointers are, since nothing will be read or written.
 int check_weight(const void *W, int dt, int64_t r, int64_t q, int64_t ldw, int64_t gran)
@@ -608,4 +696,43 @@ extern "C" int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, i
     if (dt == S24_BF16)
         return launch<uint16_t>(W, r, q, ldw, mask, mask_out, nullptr, vals, meta, valsT, metaT, true, st);
     return launch<float>(W, r, q, ldw, mask, mask_out, nullptr, vals, meta, valsT, metaT, true, st);
+}
+
+extern "C" int s24_mask_flips(const uint16_t *mask_new, const uint16_t *mask_old, int64_t nblocks, uint32_t *block_flips,
+                              uint64_t *flips, void *stream)
+{
+    S24_REQUIRE(nblocks >= 0, S24_ERR_SHAPE);
+    S24_REQUIRE(flips != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(flips, 8), S24_ERR_ALIGN);
+    if (nblocks > 0) {
+        S24_REQUIRE(mask_new && mask_old, S24_ERR_NULL);
+        S24_REQUIRE(s24_aligned(mask_new, 16) && s24_aligned(mask_old, 16) && s24_aligned(block_flips, 4), S24_ERR_ALIGN);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto *total = reinterpret_cast<unsigned long long *>(flips);
+    hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, st, total);
+    if (nblocks > 0) {
+        const int64_t vecs = (nblocks + 7) / 8;
+        const unsigned grid = (unsigned)((vecs + 255) / 256 < 4096 ? (vecs + 255) / 256 : 4096);
+        hipLaunchKernelGGL(mask_flips_kernel, dim3(grid), dim3(256), 0, st, mask_new, mask_old, nblocks, block_flips, total);
+    }
+    return s24_launch_status();
+}
+
+extern "C" int s24_l1_norm_gap(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw, double *gap, void *stream)
+{
+    const int rc = check_weight(W, dt, r, q, ldw, 4);
+    if (rc != S24_OK || r == 0 || q == 0) return rc;
+    S24_REQUIRE(gap != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(gap, 8), S24_ERR_ALIGN);
+    const int br = (int)(r / 4), bq = (int)(q / 4);
+    const int64_t n = (int64_t)br * bq;
+    S24_REQUIRE((n + 255) / 256 < (1ll << 31), S24_ERR_SHAPE);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (dt == S24_BF16)
+        hipLaunchKernelGGL(l1_gap_kernel<uint16_t>, grid, block, 0, st, static_cast<const uint16_t *>(W), ldw, br, bq, gap);
+    else
+        hipLaunchKernelGGL(l1_gap_kernel<float>, grid, block, 0, st, static_cast<const float *>(W), ldw, br, bq, gap);
+    return s24_launch_status();
 }

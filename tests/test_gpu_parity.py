@@ -325,6 +325,66 @@ def test_dense_dw_decay_equals_the_two_calls_and_the_oracle(s24, case):
                  f"dense_dw_decay {case}")
 
 
+# ------------------------------------------------------------------ monitors
+@pytest.mark.parametrize("shape", [(4, 4), (64, 96), (260, 1000), (1024, 1028)])
+def test_mask_flips(s24, shape):
+    w0 = si.random_matrix(700 + shape[0], shape, 0.02, "bf16")
+    w1 = si.random_matrix(701 + shape[0], shape, 0.02, "bf16")
+    # half of the blocks keep their weights, so some masks do not change at all
+    w1[: shape[0] // 8 * 4] = w0[: shape[0] // 8 * 4]
+    m0, m1 = oracle.transposable_mask(w0), oracle.transposable_mask(w1)
+    flips = torch.full((1,), 12345, dtype=torch.int64, device="cuda")
+    per = np.arange(m0.size, dtype=np.uint32)                      # non-zero start: the counter accumulates
+    d_per = torch.from_numpy(per.view(np.int32).copy()).cuda()
+    # a 16-byte aligned pair of device masks (4x4 alone is 2 bytes: pad the allocation)
+    d0 = torch.zeros(m0.size + 8, dtype=torch.int16, device="cuda")
+    d1 = torch.zeros(m0.size + 8, dtype=torch.int16, device="cuda")
+    d0[: m0.size] = dev(m0).reshape(-1)
+    d1[: m0.size] = dev(m1).reshape(-1)
+    s24.lib()
+    rc = s24.lib().s24_mask_flips(d1.data_ptr(), d0.data_ptr(), m0.size, d_per.data_ptr(), flips.data_ptr(), None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    want_per = per.copy()
+    want = oracle.mask_flips(m1, m0, want_per)
+    assert int(flips.item()) == want
+    assert np.array_equal(d_per.cpu().numpy().view(np.uint32), want_per)
+    # without the per-block counter, and with no blocks at all
+    s24.lib().s24_mask_flips(d1.data_ptr(), d0.data_ptr(), m0.size, None, flips.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert int(flips.item()) == want
+    assert s24.lib().s24_mask_flips(None, None, 0, None, flips.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert int(flips.item()) == 0
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(4, 4), (64, 96), (260, 1000)])
+def test_l1_norm_gap_matches_the_oracle_bit_for_bit(s24, dtype, shape):
+    W = si.random_matrix(720 + shape[0], shape, 0.02, dtype)
+    gap = torch.full((shape[0] // 4, shape[1] // 4), -1.0, dtype=torch.float64, device="cuda")
+    s24.l1_norm_gap(dev_bf16(W), gap)
+    torch.cuda.synchronize()
+    ref = oracle.l1_norm_gap(W)
+    # N(0, 0.02) blocks stay far inside the exponent window in which fp64 sums are exact
+    assert np.array_equal(gap.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("kind", ["few", "equal", "zeros", "range"])
+def test_l1_norm_gap_on_tied_and_wide_range_blocks(s24, kind):
+    W = si.tie_matrix(730, 64, 64, "bf16", kind)
+    gap = torch.empty((16, 16), dtype=torch.float64, device="cuda")
+    s24.l1_norm_gap(dev_bf16(W), gap)
+    torch.cuda.synchronize()
+    got, ref = gap.cpu().numpy(), oracle.l1_norm_gap(W)
+    a = np.abs(si.to_f32(W).astype(np.float64))
+    scale = a.reshape(16, 4, 16, 4).sum(axis=(1, 3))          # an upper bound of every kept norm of the block
+    assert (got >= 0).all()
+    assert np.all(np.abs(got - ref) <= 2.0 ** -50 * scale)     # fp64 rounding of sums of eight terms at most
+    if kind in ("few", "equal", "zeros"):
+        assert np.array_equal(got, ref)
+
+
 # ------------------------------------------------------------------ activations
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("pf", [(1, 8), (37, 264), (256, 1000)])

@@ -95,6 +95,16 @@ def test_gemm_argument_errors(lib):
     assert lib.s24_dense_gemm(P, P, P, 0, 64, 16, 1, None) == OK
 
 
+def test_monitor_argument_errors(lib):
+    assert lib.s24_mask_flips(P, P, -1, None, P, None) == SHAPE
+    assert lib.s24_mask_flips(P, P, 16, None, None, None) == NULL
+    assert lib.s24_mask_flips(P, P, 16, None, P + 4, None) == ALIGN
+    assert lib.s24_l1_norm_gap(P, 1, 6, 8, 8, P, None) == SHAPE
+    assert lib.s24_l1_norm_gap(P, 9, 8, 8, 8, P, None) == DTYPE
+    assert lib.s24_l1_norm_gap(P, 1, 8, 8, 8, None, None) == NULL
+    assert lib.s24_l1_norm_gap(P, 1, 0, 8, 8, None, None) == OK
+
+
 def test_elementwise_argument_errors(lib):
     assert lib.s24_masked_decay_grad(P, P, 1, None, 1e-4, 16, 16, None) == NULL
     assert lib.s24_masked_decay_grad(P, P, 1, P, 1e-4, 16, 24, None) == SHAPE
