@@ -30,6 +30,11 @@ PEAK_DENSE_BF16 = 2500.0      # TFLOP/s, dense bf16 MFMA
 PEAK_SPARSE_BF16 = 5000.0     # TFLOP/s, 2:4 structured-sparse bf16 (dense-equivalent FLOPs)
 PEAK_HBM = 8000.0             # GB/s
 
+# HBM-side bytes per launch (read + written, mean over the kernel's launches in a step) measured with rocprofv3
+# PMC runs of this file (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy):
+# profiles/c4_step_hbm_traffic_pmc.md.  Only for the default configuration of the named workload.
+MEASURED_TRAFFIC_BYTES = {("c4", "dense_dw"): 4.214e9, ("c4", "spmm_fwd"): 3.50e9, ("c4", "spmm_bwd_dx"): 2.21e9}
+
 
 def kernel_model(wl):
     """Algorithmic work of each kernel over one whole step: (kind, amount per step, peak, unit).  Per step and not
@@ -342,8 +347,10 @@ def main():
                          "achieved": round(achieved, 1), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
     dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])
     kd = kernels[dom]
+    default_cfg = ffn.concat == wl.gated and ffn.fuse_decay
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"], "unit": kd["unit"],
-                "frac": kd["frac"], "traffic": None}
+                "frac": kd["frac"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if default_cfg else None}
 
     out = {
         "metric": "2:4 FFN fwd+bwd TFLOP/s (dense-equivalent GEMM FLOPs over the whole step)",
