@@ -169,7 +169,8 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
         for c5, the up-projection otherwise);
     (3) the core clock under each large-tile GEMM kernel, and the clock-scaled matrix-core peak;
     (4) the step replayed from a HIP graph;
-    (5) the step with the mask searched every 40th step only."""
+    (5) the step with the mask searched every 40th step only;
+    (6) the flip-count and L1-norm-gap monitors."""
     import s24_inputs as si
     out = {}
     es = 2 if wl.dtype == "bf16" else 4
@@ -221,6 +222,18 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
             "note": "13 MB matrices are 400 workgroups each, 1.6 per compute unit: a launch per matrix is bound by "
                     "launch-to-launch latency, not by HBM; the same bytes in two launches show the kernel's rate"}
         del stacks
+    # (6) the monitors of Sec. 4.1 / 4.2 on the first weight: flip count between two masks (4 bytes read per block,
+    # one uint64 written) and L1-norm gap (32 bytes read + 8 written per bf16 block, 90 fp64 sums per block)
+    w0 = ws[0]
+    other = torch.roll(w0.mask, 1, 0).contiguous()
+    flips = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ms_f = _time_ms(torch, lambda: s24.mask_flips(w0.mask, other, flips), 10)
+    gap = torch.empty(w0.mask.shape, dtype=torch.float64, device="cuda")
+    ms_g = _time_ms(torch, lambda: s24.l1_norm_gap(w0.W, gap), 5)
+    nb = w0.mask.numel()
+    out["monitors"] = {"mask_flips": {"ms": round(ms_f, 4), "GB/s": round(nb * 4 / ms_f / 1e6, 1)},
+                       "l1_norm_gap": {"ms": round(ms_g, 4), "GB/s": round(nb * (16 * es + 8) / ms_g / 1e6, 1),
+                                       "bound": "alu (90 x 16 fp64 select-adds per block)"}}
     # (4) the whole step replayed from one HIP graph: what the step costs once launch overhead is gone
     graph = ffn.capture(X, dY)
     ms_g = _time_ms(torch, graph.replay, 20)

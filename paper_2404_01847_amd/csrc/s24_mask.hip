@@ -226,11 +226,37 @@ __device__ __noinline__ unsigned slow_best_pattern(Mag16 mag)
 }
 
 // ---------------------------------------------------------------------------
+// Middle path: the 90 sums one by one in fp64, first maximum in id order.  Exact as long as every sum of
+// eight magnitudes fits fp64's 53 bits, i.e. the block spans at most 26 binades of fp32 data (42 of bf16
+// data); used for blocks too wide for the fast path's window, which also has to hold the tie-break bits.
+// ---------------------------------------------------------------------------
+__device__ __noinline__ unsigned mid_best_pattern(Mag16 mag)
+{
+    double a[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) a[t] = (double)__uint_as_float(mag.v[t]);
+    double best = -1.0;
+    unsigned best_id = 0;
+#pragma unroll 1
+    for (unsigned k = 0; k < S24_NUM_PATTERNS; ++k) {
+        const unsigned pm = g_patterns.mask[k];
+        double sum = 0.0;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) sum += ((pm >> t) & 1u) ? a[t] : 0.0;
+        if (sum > best) {
+            best = sum;
+            best_id = k;
+        }
+    }
+    return (unsigned)g_patterns.mask[best_id] | (best_id << 16);
+}
+
+// ---------------------------------------------------------------------------
 // Fast path.  mag[4*i+j] = |w_ij| as fp32 bit patterns.  Returns mask | id<<16.
 // WINDOW = binades below the block maximum within which every element is a
 // multiple of 2048*eps (29 for bf16 data, 13 for fp32 data).
 // ---------------------------------------------------------------------------
-template <int WINDOW>
+template <int WINDOW, int WIDE>
 __device__ __forceinline__ unsigned best_pattern(const uint32_t (&mag)[16], const uint16_t *lut_mask, const uint8_t *lut_id)
 {
     uint32_t mx = 0, mn = 0xFFFFFFFFu;
@@ -245,7 +271,7 @@ __device__ __forceinline__ unsigned best_pattern(const uint32_t (&mag)[16], cons
         Mag16 m16;
 #pragma unroll
         for (int t = 0; t < 16; ++t) m16.v[t] = mag[t];
-        return slow_best_pattern(m16);
+        return (emin + WIDE >= emax) ? mid_best_pattern(m16) : slow_best_pattern(m16);
     }
 
     const double eps = __hiloint2double((int)((emax + 849u) << 20), 0);       // 2^(E-47), E = emax-127
@@ -317,7 +343,7 @@ template <typename T> struct RowOps;
 template <> struct RowOps<uint16_t> {  // bf16
     using Row = uint2;     // four bf16
     using Pair = uint32_t; // two bf16
-    static constexpr int kWindow = 29;
+    static constexpr int kWindow = 29, kWide = 42;
     static __device__ __forceinline__ Row load(const uint16_t *p) { return *reinterpret_cast<const uint2 *>(p); }
     static __device__ __forceinline__ uint32_t bits(const Row &r, int j)
     {
@@ -335,7 +361,7 @@ template <> struct RowOps<uint16_t> {  // bf16
 template <> struct RowOps<float> {
     using Row = uint4;
     using Pair = uint2;
-    static constexpr int kWindow = 13;
+    static constexpr int kWindow = 13, kWide = 26;
     static __device__ __forceinline__ Row load(const float *p) { return *reinterpret_cast<const uint4 *>(p); }
     static __device__ __forceinline__ uint32_t bits(const Row &r, int j)
     {
@@ -415,7 +441,7 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) mag[4 * i + j] = Ops::mag(rows[i], j);
-            const unsigned res = best_pattern<Ops::kWindow>(mag, s_lut_mask, s_lut_id);
+            const unsigned res = best_pattern<Ops::kWindow, Ops::kWide>(mag, s_lut_mask, s_lut_id);
             m = res & 0xFFFFu;
             id = res >> 16;
             if (valid) {
@@ -603,7 +629,14 @@ __global__ __launch_bounds__(256) void mask_flips_kernel(const uint16_t *__restr
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) count += __shfl_down(count, off, 64);
-    if ((threadIdx.x & 63) == 0 && count != 0) atomicAdd(total, (unsigned long long)count);
+    // one atomic per workgroup: thousands of them on one address would cost more than the scan itself
+    __shared__ unsigned s_part[4];
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = count;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long sum = (unsigned long long)s_part[0] + s_part[1] + s_part[2] + s_part[3];
+        if (sum != 0) atomicAdd(total, sum);
+    }
 }
 
 // L1-norm gap: one block per thread, all 90 kept norms in fp64 (exact while the block's exponent spread
@@ -713,7 +746,7 @@ extern "C" int s24_mask_flips(const uint16_t *mask_new, const uint16_t *mask_old
     hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, st, total);
     if (nblocks > 0) {
         const int64_t vecs = (nblocks + 7) / 8;
-        const unsigned grid = (unsigned)((vecs + 255) / 256 < 4096 ? (vecs + 255) / 256 : 4096);
+        const unsigned grid = (unsigned)((vecs + 255) / 256 < 1024 ? (vecs + 255) / 256 : 1024);
         hipLaunchKernelGGL(mask_flips_kernel, dim3(grid), dim3(256), 0, st, mask_new, mask_old, nblocks, block_flips, total);
     }
     return s24_launch_status();
