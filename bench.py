@@ -300,7 +300,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1. "
-                 "DESIGN.md describes how the step would shard over data-parallel ranks.")
+                 "Under data parallelism each rank would run exactly this step on its share of the tokens.")
 
     import torch
     import s24_inputs as si

@@ -12,7 +12,7 @@
  * 1 = bf16 (raw uint16 bit patterns).  Floating-point results are returned in
  * fp64; every input is widened exactly before any arithmetic.
  *
- * Readings taken where the paper is silent (each is listed in the design doc):
+ * Readings taken where the paper is silent:
  *   - order of the 90 block patterns: lexicographic on the 16-character
  *     row-major string m00 m01 ... m33 with '0' < '1';
  *   - argmax tie-break: first (smallest id) maximal pattern;
