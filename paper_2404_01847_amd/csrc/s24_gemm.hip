@@ -486,93 +486,6 @@ __global__ __launch_bounds__(kThreads) void dense_nt_kernel(const uint16_t *__re
     }
 }
 
-// ------------------------------------------------------------------ dense TN (dW)
-// dW[m][n] = sum_t dY[t][m] X[t][n].  Both operands are contiguous along the
-// output axis, not along t, so each thread loads an 8(t) x 8 sub-block (eight
-// 16-byte rows), transposes it in registers and writes eight 16-byte rows of
-// 8 consecutive t into the swizzled LDS tile.  Threads 0..127 stage the dY tile
-// (64 t x 128 m), threads 128..255 the X tile (64 t x 128 n).
-struct Sub8 { uint4 r[8]; };
-
-// Rows at or past T read as zero (their products must vanish); columns past ncols are
-// clamped to the last valid group, their results are never stored.  T >= 1.
-__device__ __forceinline__ void sub8_load(Sub8 &s, const uint16_t *g, int64_t ld, int t0, int T, int col, int ncols)
-{
-    const int c = min(col, ncols - 8);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(g + (int64_t)min(t0 + k, T - 1) * ld + c);
-        s.r[k] = (t0 + k < T) ? v : make_uint4(0, 0, 0, 0);
-    }
-}
-
-// in: r[k] = eight bf16 (columns c..c+7) of row t0+k.  out: o[c] = eight bf16 (t0..t0+7) of column c.
-__device__ __forceinline__ void sub8_transpose_store(const Sub8 &s, unsigned char *buf, int col_local, int tchunk)
-{
-    const uint32_t *w = reinterpret_cast<const uint32_t *>(&s.r[0]);  // w[4*k + d] = columns (2d, 2d+1) of row k
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        uint32_t o[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const uint32_t lo = w[4 * (2 * kk) + c / 2], hi = w[4 * (2 * kk + 1) + c / 2];
-            o[kk] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-        }
-        *reinterpret_cast<uint4 *>(buf + lds_off(col_local + c, tchunk)) = make_uint4(o[0], o[1], o[2], o[3]);
-    }
-}
-
-template <bool ACCUM>
-__global__ __launch_bounds__(kThreads) void dense_tn_kernel(const uint16_t *__restrict__ dY, const uint16_t *__restrict__ X,
-                                                            float *__restrict__ dW, int T, int M, int N)
-{
-    __shared__ __attribute__((aligned(16))) unsigned char s_a[2][BM * 128];
-    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][BN * 128];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int nk = (T + BK - 1) / BK;
-    // staging role of this thread
-    const bool is_a = tid < 128;
-    const int sid = tid & 127;
-    const int scol = (sid & 15) * 8, stc = sid >> 4;  // 16 column groups x 8 t-chunks
-    const uint16_t *src = is_a ? dY : X;
-    const int64_t ld = is_a ? M : N;
-    const int gcol = (is_a ? m0 : n0) + scol, ncols = is_a ? M : N;
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
-    Sub8 sub;
-    sub8_load(sub, src, ld, 8 * stc, T, gcol, ncols);
-    sub8_transpose_store(sub, is_a ? s_a[0] : s_b[0], scol, stc);
-    __syncthreads();
-    for (int kc = 0; kc < nk; ++kc) {
-        const bool more = kc + 1 < nk;
-        if (more) sub8_load(sub, src, ld, (kc + 1) * BK + 8 * stc, T, gcol, ncols);
-        dense_chunk(acc, s_a[kc & 1], s_b[kc & 1], wm, wn, lane);
-        if (more) sub8_transpose_store(sub, is_a ? s_a[(kc + 1) & 1] : s_b[(kc + 1) & 1], scol, stc);
-        __syncthreads();
-    }
-    // accumulator i of lane l: column n = l%32, rows m = 8*(i/4) + 4*(l/32) + i%4
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
-        if (n >= N) continue;
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int m = m0 + 64 * wm + 32 * mi + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
-                if (m >= M) continue;
-                float *dst = dW + (int64_t)m * N + n;
-                *dst = ACCUM ? (*dst + acc[mi][ni][i]) : acc[mi][ni][i];
-            }
-    }
-}
-
 // ------------------------------------------------------------------ dense NT, large tile
 // The dense comparison GEMM in the same tiling family as the sparse kernel:
 // 256 x 256 x 64 workgroup tiles, eight waves of 128 x 64, both operands copied
@@ -688,19 +601,27 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
 // finds the matrix unit busy; the copies of chunk kc+3 are dealt out between the matrix instructions
 // rather than issued in one burst.
 namespace dmatn {
-constexpr int BM = 256, BN = 256, BT = 32, THREADS = 256, WT = 4;   // WT: 32 x 32 blocks per wave and axis
-constexpr int ROWB = BM * 2, OPERAND = BT * ROWB, STAGE = 2 * OPERAND, CPR = ROWB / 16;
-constexpr int NIO = OPERAND / 1024 / 4, NI = 2 * NIO;   // copies per wave, chunk and operand / in total
-static_assert(BM == BN, "one row pitch for both operands");
+constexpr int THREADS = 256;
+// WT = 32 x 32 accumulator blocks per wave and axis: 4 -> 256 x 256 workgroup tiles; 2 -> 128 x 128 tiles for
+// outputs with too few large tiles to fill the chip.  BT = tokens per ring stage: 32 for the large tile (128 KB
+// of LDS); for the small tile 32 (64 KB, two workgroups per CU) when there are more tiles than CUs, else 64 (a
+// small tile has a quarter of the matrix work per token, so the barrier is paid half as often).
+template <int WT, int BT_> struct Cfg {
+    static constexpr int BM = 64 * WT, BN = 64 * WT, BT = BT_;
+    static constexpr int ROWB = BM * 2, OPERAND = BT * ROWB, STAGE = 2 * OPERAND, CPR = ROWB / 16;
+    static constexpr int NIO = OPERAND / 1024 / 4, NI = 2 * NIO;   // copies per wave, chunk and operand / in total
+};
 using big::glb_ptr;
 using big::lds_ptr;
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4i16 *lds_v4i16;
 
+template <int ROWB>
 __device__ __forceinline__ int tr_off(int row, int col)
 {
     return row * ROWB + ((((col >> 3) ^ ((row & 3) << 2))) << 4) + ((col & 7) << 1);
 }
+template <int ROWB>
 __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
 {
     // token rows t..t+3 and t+4..t+7 of this lane group's patch
@@ -713,7 +634,7 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
 // DECAY: the masked decay term is added in the epilogue: dW[m][n] += lambda * Wt[m][n] where bit
 // 4*(m%4) + n%4 of mask[m/4][n/4] is clear, with the same single fused multiply-add the stand-alone
 // decay kernel applies to the stored gradient, so both routes give the same bits.
-template <bool ACCUM, bool DECAY>
+template <int WT, int BT_, bool ACCUM, bool DECAY>
 __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *__restrict__ dY,
                                                                const uint16_t *__restrict__ X, float *__restrict__ dW,
                                                                int T, int M, int N, int tiles_m, int tiles_n,
@@ -721,6 +642,11 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
                                                                const uint16_t *__restrict__ Wt,
                                                                const uint16_t *__restrict__ mask, float lambda)
 {
+    using C = Cfg<WT, BT_>;
+    constexpr int BM = C::BM, BN = C::BN, BT = C::BT, ROWB = C::ROWB, OPERAND = C::OPERAND, STAGE = C::STAGE, CPR = C::CPR;
+    constexpr int NIO = C::NIO, NI = C::NI;
+    constexpr int KS = BT / 16, CPS = NI / KS;   // 16-token steps per chunk, copies issued per step
+    static_assert(KS % 2 == 0 && CPS * KS == NI, "steps alternate between two fragment sets");
     const big::ClockStamp t_start = big::clock_now();
     __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
     __shared__ __attribute__((aligned(16))) unsigned char s1[STAGE];
@@ -750,16 +676,18 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
         voffA[j] = row * M + m0 + 8 * min(c, lastA);
         voffB[j] = row * N + n0 + 8 * min(c, lastB);
     }
-    // which: 1 = the dY tile, 2 = the X tile.  Token rows past T (last chunk only) re-read row T-1.
-    auto issue = [&](unsigned char *st, int kc, int which) {
+    // Copies first .. first+count-1 of a chunk's list (the dY tile's NIO, then the X tile's NIO).  Token rows
+    // past T (last chunk only) re-read row T-1.
+    auto issue = [&](unsigned char *st, int kc, int first, int count) {
         kc = min(kc, nk - 1);
         const char *ya = reinterpret_cast<const char *>(dY + (int64_t)kc * BT * M);
         const char *xb = reinterpret_cast<const char *>(X + (int64_t)kc * BT * N);
         const int lastrow = T - 1 - kc * BT;
 #pragma unroll
-        for (int j = 0; j < NIO; ++j) {
+        for (int c = first; c < first + count; ++c) {
+            const int j = c < NIO ? c : c - NIO;
             const int over = max(((wave * NIO + j) * 64 + lane) / CPR - lastrow, 0);
-            if (which == 1)
+            if (c < NIO)
                 __builtin_amdgcn_global_load_lds((glb_ptr)(ya + (uint32_t)(voffA[j] - over * M) * 2u),
                                                  (lds_ptr)(st + (wave * NIO + j) * 1024), 16, 0, 0);
             else
@@ -779,14 +707,14 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
     int offA[WT], offB[WT];
 #pragma unroll
     for (int i = 0; i < WT; ++i) {
-        offA[i] = tr_off(frow, 32 * WT * wm + 32 * i + fcol);
-        offB[i] = OPERAND + tr_off(frow, 32 * WT * wn + 32 * i + fcol);
+        offA[i] = tr_off<ROWB>(frow, 32 * WT * wm + 32 * i + fcol);
+        offB[i] = OPERAND + tr_off<ROWB>(frow, 32 * WT * wn + 32 * i + fcol);
     }
     auto load_frags = [&](const unsigned char *st, int ks, bf16x8 (&a)[WT], bf16x8 (&b)[WT]) {
 #pragma unroll
-        for (int ni = 0; ni < WT; ++ni) b[ni] = tr_frag(st + offB[ni] + 16 * ks * ROWB);
+        for (int ni = 0; ni < WT; ++ni) b[ni] = tr_frag<ROWB>(st + offB[ni] + 16 * ks * ROWB);
 #pragma unroll
-        for (int mi = 0; mi < WT; ++mi) a[mi] = tr_frag(st + offA[mi] + 16 * ks * ROWB);
+        for (int mi = 0; mi < WT; ++mi) a[mi] = tr_frag<ROWB>(st + offA[mi] + 16 * ks * ROWB);
     };
     auto mma = [&](const bf16x8 (&a)[WT], const bf16x8 (&b)[WT]) {
 #pragma unroll
@@ -795,18 +723,19 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
             for (int ni = 0; ni < WT; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
     };
-    // Issue order of one 16-token step: a matrix instruction, an LDS read of the next step's fragments,
-    // and after every other matrix instruction one copy.
+    // Issue order of one 16-token step: a matrix instruction, then 4/WT LDS reads of the next step's fragments
+    // (4*WT reads against WT*WT matrix instructions), and after every other matrix instruction one copy.
     auto interleave = [&]() {
+        constexpr int RPM = 4 / WT;
+        static_assert(RPM * WT * WT == 4 * WT && 2 * CPS <= WT * WT, "reads and copies fit between the matrix instructions");
 #pragma unroll
         for (int i = 0; i < WT * WT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if ((i & 1) && (i >> 1) < NIO) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+            if ((i & 1) && (i >> 1) < CPS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    static_assert(4 * WT == WT * WT && 2 * NIO <= WT * WT, "one LDS read per matrix instruction");
     // token rows past T must not contribute: clear them in the dY tile of the (last, partial) chunk kc
     auto clear_tail = [&](unsigned char *st, int kc) {
         const int rem = T - kc * BT;
@@ -817,33 +746,31 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
     const bool partial = (T % BT) != 0;
 
     // prologue: chunks 0..2 in flight, chunk 0 landed, its first fragments in registers
-    issue(s0, 0, 1);
-    issue(s0, 0, 2);
+    issue(s0, 0, 0, NI);
     __builtin_amdgcn_sched_barrier(0);
-    issue(s1, 1, 1);
-    issue(s1, 1, 2);
+    issue(s1, 1, 0, NI);
     __builtin_amdgcn_sched_barrier(0);
-    issue(s2, 2, 1);
-    issue(s2, 2, 2);
+    issue(s2, 2, 0, NI);
     __builtin_amdgcn_sched_barrier(0);
     big::wait_and_barrier<2 * NI>();
     if (partial && nk == 1) clear_tail(s0, 0);
-    bf16x8 a0[WT], b0[WT], a1[WT], b1[WT];
-    load_frags(s0, 0, a0, b0);
+    bf16x8 fa[2][WT], fb[2][WT];   // fragments of the current and of the next 16-token step
+    load_frags(s0, 0, fa[0], fb[0]);
 
     // Iteration kc: all but the NI most recent copies (chunk kc+2) are complete, so chunk kc+1 is in LDS for
     // every wave after the barrier, and nobody reads the stage of chunk kc-1 any more: it takes chunk kc+3.
     auto chunk = [&](const unsigned char *cur, unsigned char *nxt, unsigned char *refill, int kc) {
         big::wait_and_barrier<NI>();
         if (partial && kc + 2 == nk) clear_tail(nxt, kc + 1);
-        issue(refill, kc + 3, 1);
-        load_frags(cur, 1, a1, b1);
-        mma(a0, b0);
-        interleave();
-        issue(refill, kc + 3, 2);
-        load_frags(nxt, 0, a0, b0);   // past the last chunk this reads a stage nobody uses; the result is dropped
-        mma(a1, b1);
-        interleave();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            issue(refill, kc + 3, ks * CPS, CPS);
+            // past the last chunk the final prefetch reads a stage nobody uses; the result is dropped
+            if (ks + 1 < KS) load_frags(cur, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+            else load_frags(nxt, 0, fa[0], fb[0]);
+            mma(fa[ks & 1], fb[ks & 1]);
+            interleave();
+        }
     };
     int kc = 0;
     for (; kc + 4 <= nk; kc += 4) {
@@ -857,13 +784,14 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
     if (kc + 2 < nk) chunk(s2, s3, s1, kc + 2);
     big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
     big::clock_report(probe, t_start);
-    // Epilogue through LDS, so that global memory sees 16-byte accesses along rows: each wave parks half of
-    // its tile (128 rows x 64 columns of fp32, 256-byte rows) in its own 32 KB stage, then lane l of pass j
+    // Epilogue through LDS, so that global memory sees 16-byte accesses along rows: each wave parks 64 columns
+    // of its tile at a time (32*WT rows of fp32, 256-byte rows) in its own ring stage, then lane l of pass j
     // owns row (64j + l) / 16, columns 4 * (l % 16) .. +3: one LDS read, one 16-byte store, and for the
     // optional terms one 16-byte load of the old gradient, one 8-byte load of W and one mask word.
+    static_assert(32 * WT * 256 <= STAGE, "a wave's 64-column slice fits one stage");
     unsigned char *est = wave == 0 ? s0 : (wave == 1 ? s1 : (wave == 2 ? s2 : s3));
 #pragma unroll
-    for (int h2 = 0; h2 < 2; ++h2) {
+    for (int h2 = 0; h2 < WT / 2; ++h2) {
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
@@ -878,7 +806,7 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
         asm volatile("" ::: "memory");
         constexpr int BATCH = 8;
 #pragma unroll 1
-        for (int j0 = 0; j0 < 32; j0 += BATCH) {
+        for (int j0 = 0; j0 < 8 * WT; j0 += BATCH) {
             float4 v[BATCH], old[BATCH];
             uint2 wv[BATCH];
             uint32_t keep[BATCH];
@@ -1076,27 +1004,31 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
     bool decay_pending = W != nullptr;
     if (p == 0) {  // empty contraction: dW = beta * dW (the GEMM kernels need at least one token)
         if (!accum) hipLaunchKernelGGL(fill_zero_kernel, dim3(ceil_div(q * r, kThreads)), dim3(kThreads), 0, st, dW, q * r);
-    } else if (dt == S24_BF16 && (int64_t)ceil_div(r, dmatn::BM) * ceil_div(q, dmatn::BN) >= 192) {
-        const int tiles_m = (int)ceil_div(r, dmatn::BM), tiles_n = (int)ceil_div(q, dmatn::BN);
+    } else if (dt == S24_BF16) {
+        // 256 x 256 tiles when they fill the chip, 128 x 128 tiles otherwise
+        const bool large = (int64_t)ceil_div(r, 256) * ceil_div(q, 256) >= 192;
+        const int tile = large ? 256 : 128;
+        const int tiles_m = (int)ceil_div(r, tile), tiles_n = (int)ceil_div(q, tile);
         const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(dmatn::THREADS);
         auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
         const bool fuse = decay_pending && wdt == S24_BF16;
         auto *w = static_cast<const uint16_t *>(fuse ? W : nullptr);
-#define S24_LAUNCH_DW(ACC, DEC)                                                                                      \
-    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<ACC, DEC>), grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q, \
-                       tiles_m, tiles_n, g_clock_probe, w, mask, lambda)
-        if (accum && fuse) S24_LAUNCH_DW(true, true);
-        else if (accum) S24_LAUNCH_DW(true, false);
-        else if (fuse) S24_LAUNCH_DW(false, true);
-        else S24_LAUNCH_DW(false, false);
+#define S24_LAUNCH_DW(WT, BT, ACC, DEC)                                                                                \
+    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<WT, BT, ACC, DEC>), grid, block, 0, st, a, b, dW, (int)p, (int)r,     \
+                       (int)q, tiles_m, tiles_n, g_clock_probe, w, mask, lambda)
+#define S24_LAUNCH_DW_TILE(WT, BT)                              \
+    do {                                                        \
+        if (accum && fuse) S24_LAUNCH_DW(WT, BT, true, true);   \
+        else if (accum) S24_LAUNCH_DW(WT, BT, true, false);     \
+        else if (fuse) S24_LAUNCH_DW(WT, BT, false, true);      \
+        else S24_LAUNCH_DW(WT, BT, false, false);               \
+    } while (0)
+        if (large) S24_LAUNCH_DW_TILE(4, 32);
+        else if (tiles_m * tiles_n > 256) S24_LAUNCH_DW_TILE(2, 32);
+        else S24_LAUNCH_DW_TILE(2, 64);
+#undef S24_LAUNCH_DW_TILE
 #undef S24_LAUNCH_DW
         if (fuse) decay_pending = false;
-    } else if (dt == S24_BF16) {
-        const dim3 grid(ceil_div(r, BM), ceil_div(q, BN)), block(kThreads);
-        S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
-        auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
-        if (accum) hipLaunchKernelGGL(dense_tn_kernel<true>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q);
-        else hipLaunchKernelGGL(dense_tn_kernel<false>, grid, block, 0, st, a, b, dW, (int)p, (int)r, (int)q);
     } else {
         const dim3 grid(ceil_div(r * q, kThreads)), block(kThreads);
         auto *a = static_cast<const float *>(dY), *b = static_cast<const float *>(X);

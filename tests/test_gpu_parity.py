@@ -230,6 +230,23 @@ def test_dense_dw_large_tile_path(s24, p, beta):
     assert_close(host_f64(dW[torch.from_numpy(rows).cuda()]), ref, F32_TOL, f"large dense_dw p={p} beta={beta}")
 
 
+@pytest.mark.parametrize("p", [33, 150])
+@pytest.mark.parametrize("beta", [0.0, 1.0])
+def test_dense_dw_many_small_tiles_path(s24, p, beta):
+    """More 128x128 tiles than compute units, fewer 256x256 tiles than fill the chip: the two-workgroups-per-CU
+    variant (32 tokens per ring stage, ragged last chunk, ragged last tile row and column)."""
+    q, r = 2192, 2160
+    dY = si.random_matrix(470 + p, (p, r), 1e-2, "bf16")
+    X = si.random_matrix(471 + p, (p, q), 1.0, "bf16")
+    dW0 = si.random_matrix(472, (r, q), 1e-3, "f32")
+    dW = dev(dW0).clone()
+    s24.dense_dw(dev_bf16(dY), dev_bf16(X), dW, beta=beta)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 127, 128, r - 1], np.random.default_rng(p).integers(0, r, 24)])).astype(np.int64)
+    ref = oracle.dense_dw(dY, X, beta=beta, dW0=dW0[rows].astype(np.float64), rows=rows)
+    assert_close(host_f64(dW[torch.from_numpy(rows).cuda()]), ref, F32_TOL, f"dense_dw small tiles p={p} beta={beta}")
+
+
 def test_dense_dw_no_tokens(s24):
     dW = torch.full((64, 128), 5.0, dtype=torch.float32, device="cuda")
     # with no tokens the operand pointers are never read: any aligned non-null value will do
@@ -300,7 +317,7 @@ def test_masked_decay(s24, dtype, shape):
 @pytest.mark.parametrize("case", [
     # (p, q, r, dtype, beta): small tiles, fp32 route, and enough 256x256 tiles for the fused epilogue
     (300, 256, 208, "bf16", 0.0), (96, 64, 48, "f32", 1.0),
-    (1000, 3600, 3408, "bf16", 0.0), (777, 3600, 3408, "bf16", 1.0)])
+    (1000, 3600, 3408, "bf16", 0.0), (777, 3600, 3408, "bf16", 1.0), (90, 2192, 2160, "bf16", 1.0)])
 def test_dense_dw_decay_equals_the_two_calls_and_the_oracle(s24, case):
     p, q, r, dtype, beta = case
     lam = 2e-4
