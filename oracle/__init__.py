@@ -40,7 +40,7 @@ def _load():
         for name in ("orc_pack_chunk_major", "orc_pattern_table", "orc_transposable_mask", "orc_compress", "orc_spmm_fwd",
                      "orc_spmm_bwd_dx", "orc_dense_dw", "orc_dense_gemm", "orc_masked_decay",
                      "orc_swiglu_fwd", "orc_swiglu_bwd", "orc_act_fwd", "orc_act_bwd", "orc_num_threads",
-                     "orc_mask_flips", "orc_l1_norm_gap"):
+                     "orc_mask_flips", "orc_l1_norm_gap", "orc_mvue24"):
             getattr(_lib, name).restype = C.c_int
         _lib.orc_round_bf16.restype = None
     return _lib
@@ -117,6 +117,18 @@ def l1_norm_gap(W: np.ndarray) -> np.ndarray:
     gap = np.zeros((r // 4, q // 4), dtype=np.float64)
     _check(_load().orc_l1_norm_gap(_p(W), _dt(W), C.c_int64(r), C.c_int64(q), C.c_int64(q), _p(gap)), "l1_norm_gap")
     return gap
+
+
+def mvue24(dY: np.ndarray, seed: int):
+    """Unbiased 2:4 pruning of dY^T along the tokens: vals[r, p/2] (dtype of dY), meta[r, p/16]."""
+    dY = _c(dY)
+    p, r = dY.shape
+    vals = np.zeros((r, p // 2), dtype=dY.dtype)
+    meta = np.zeros((r, p // 16), dtype=np.uint16)
+    rc = _load().orc_mvue24(_p(dY), _dt(dY), C.c_int64(p), C.c_int64(r), C.c_int64(r), C.c_uint32(seed & 0xFFFFFFFF),
+                            _p(vals), _p(meta))
+    _check(rc, "mvue24")
+    return vals, meta
 
 
 def compress(W: np.ndarray, mask: np.ndarray):

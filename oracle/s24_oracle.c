@@ -203,6 +203,125 @@ int orc_transposable_mask(const void *W, int dt, int64_t r, int64_t q, int64_t l
 }
 
 /* ------------------------------------------------------------------ */
+/* Unbiased 2:4 pruning of the output gradient for the weight-gradient */
+/* GEMM (Eq. 4: grad W = S_z(grad Z^T) X; Eq. 6: S_z = MVUE).          */
+/*                                                                     */
+/* The paper names the estimator and cites it; it does not spell it    */
+/* out.  What is built here follows from the two words: for a group    */
+/* (a_0..a_3) keep two elements, element j with probability pi_j, and  */
+/* store a_j / pi_j, so that the expectation is a_j (unbiased); the    */
+/* total variance sum_j a_j^2 (1/pi_j - 1) under sum_j pi_j = 2,       */
+/* pi_j <= 1 is least for pi_j proportional to |a_j|, capped at 1.     */
+/*   uncapped (2 max|a| <= S = sum|a|): pi_j = 2|a_j|/S, kept value    */
+/*     sign(a_j) S/2;                                                  */
+/*   capped: the largest is kept as it is, one of the other three with */
+/*     pi_j = |a_j|/R (R = their sum), kept value sign(a_j) R.         */
+/* Two elements with these marginals are drawn by systematic sampling: */
+/* one uniform u in [0,1) and the points u, u+1 on the line of the     */
+/* cumulated pi.  All decisions are taken in fp32 in exactly the       */
+/* operation order written below, and u comes from a counter-based     */
+/* integer hash of (seed, feature, token group), so that another       */
+/* implementation can reproduce every bit.                             */
+/* ------------------------------------------------------------------ */
+
+/* fp32 -> bf16 bits, round to nearest even (finite inputs) */
+static uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+static uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+
+/* 23 random bits for (feature, token group): u = bits * 2^-23, so that u + 1 is exact in fp32 */
+static uint32_t mvue_bits(uint32_t seed, uint32_t feature, uint32_t group)
+{
+    return mix32(mix32(group ^ seed) + feature * 0x9E3779B9U) >> 9;
+}
+
+/* one group: a[4] in, kept positions i0 < i1 and their values out */
+static void mvue_group(const float a[4], uint32_t bits, int *i0, int *i1, float *v0, float *v1)
+{
+    float m[4];
+    for (int i = 0; i < 4; ++i) m[i] = fabsf(a[i]);
+    const float S = (m[0] + m[1]) + (m[2] + m[3]);
+    float mx = m[0];
+    int imax = 0;
+    for (int i = 1; i < 4; ++i)
+        if (m[i] > mx) { mx = m[i]; imax = i; }
+    const int capped = 2.0f * mx > S;
+    float R = 0.0f;
+    if (capped) {
+        int first = 1;
+        for (int i = 0; i < 4; ++i) {
+            if (i == imax) continue;
+            R = first ? m[i] : R + m[i];
+            first = 0;
+        }
+    }
+    const float D = capped ? R : S, scale = capped ? 1.0f : 2.0f;
+    const float inv = D > 0.0f ? 1.0f / D : 0.0f;
+    float pi[4];
+    for (int i = 0; i < 4; ++i) {
+        const float t = (scale * m[i]) * inv;
+        pi[i] = t < 1.0f ? t : 1.0f;
+    }
+    if (capped) pi[imax] = 1.0f;
+    const float c1 = pi[0], c2 = c1 + pi[1], c3 = c2 + pi[2];
+    const float u = (float)bits * 0x1p-23f, v = u + 1.0f;
+    int a0 = (u >= c1) + (u >= c2) + (u >= c3);
+    int a1 = (v >= c1) + (v >= c2) + (v >= c3);
+    if (a1 == a0) {            /* only on rounding knife edges and in all-zero groups */
+        if (a0 < 3) a1 = a0 + 1;
+        else { a0 = 2; a1 = 3; }
+    }
+    float val[2];
+    const int idx[2] = {a0, a1};
+    for (int k = 0; k < 2; ++k) {
+        const int j = idx[k];
+        if (m[j] == 0.0f) val[k] = 0.0f;
+        else if (capped) val[k] = (j == imax) ? a[j] : copysignf(R, a[j]);
+        else val[k] = copysignf(0.5f * S, a[j]);
+    }
+    *i0 = a0; *i1 = a1; *v0 = val[0]; *v1 = val[1];
+}
+
+/* dY [p][ld] (dtype dt) -> compressed S_z(dY^T): rows = the r features, contraction axis = the p tokens,
+ * vals [r][p/2] (dtype dt, rounded to nearest even for bf16), meta [r][p/16] as in orc_compress. */
+int orc_mvue24(const void *dY, int dt, int64_t p, int64_t r, int64_t ld, uint32_t seed, void *vals, uint16_t *meta)
+{
+    if (p < 0 || r < 0 || (p % 16) || ld < r) return -1;
+    const int64_t groups = p / 4;
+#pragma omp parallel for schedule(static)
+    for (int64_t f = 0; f < r; ++f) {
+        for (int64_t w = 0; w < p / 16; ++w) meta[f * (p / 16) + w] = 0;
+        for (int64_t g = 0; g < groups; ++g) {
+            float a[4];
+            for (int i = 0; i < 4; ++i) a[i] = (float)widen(dY, dt, (size_t)((4 * g + i) * ld + f));
+            int i0, i1;
+            float v0, v1;
+            mvue_group(a, mvue_bits(seed, (uint32_t)f, (uint32_t)g), &i0, &i1, &v0, &v1);
+            const size_t o = (size_t)(f * (p / 2) + 2 * g);
+            if (dt == 0) {
+                ((float *)vals)[o] = v0;
+                ((float *)vals)[o + 1] = v1;
+            } else {
+                ((uint16_t *)vals)[o] = f32_to_bf16_bits(v0);
+                ((uint16_t *)vals)[o + 1] = f32_to_bf16_bits(v1);
+            }
+            meta[f * (p / 16) + g / 4] |= (uint16_t)((i0 | (i1 << 2)) << (4 * (g % 4)));
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Monitors: flip count (Sec. 4.1, definition of the flip rate) and    */
 /* L1-norm gap of a block (Sec. 4.2).                                  */
 /* ------------------------------------------------------------------ */

@@ -456,3 +456,93 @@ def test_l1_gap_is_consistent_with_the_mask_search():
             others = sorted(sum(blk[t // 4, t % 4] for t in range(16) if (p >> t) & 1) for p in tab)
             assert abs(others[-1] - best) <= 1e-12 * best
             assert abs((others[-1] - others[-2]) - g[bi, bj]) <= 1e-12 * best
+
+
+# ---------------------------------------------------------------- unbiased 2:4 pruning of the output gradient
+def mvue_dense(dY, seed):
+    """Oracle's compressed S_z(dY^T) decoded to a dense [r, p] float64 matrix, plus the kept-position flags."""
+    vals, meta = oracle.mvue24(dY, seed)
+    p, r = dY.shape
+    v = f64(vals).reshape(r, p // 4, 2)
+    nib = ((meta.astype(np.int64)[:, :, None] >> (4 * np.arange(4))) & 0xF).reshape(r, p // 4)
+    i0, i1 = nib & 3, nib >> 2
+    assert (i0 < i1).all()                                       # two distinct kept positions, ascending
+    out = np.zeros((r, p // 4, 4))
+    kept = np.zeros((r, p // 4, 4), dtype=bool)
+    rr, gg = np.meshgrid(np.arange(r), np.arange(p // 4), indexing="ij")
+    out[rr, gg, i0] = v[:, :, 0]
+    out[rr, gg, i1] = v[:, :, 1]
+    kept[rr, gg, i0] = True
+    kept[rr, gg, i1] = True
+    return out.reshape(r, p), kept.reshape(r, p)
+
+
+def test_mvue_deterministic_groups():
+    # Eq. 6 read as: keep two of four, unbiased, least variance.  Groups where nothing is left to chance:
+    col = np.array([3.0, -5.0, 0.0, 0.0,      # two non-zeros: both kept as they are
+                    0.0, 0.0, 0.0, 7.0,       # one non-zero: kept as it is (plus a zero)
+                    0.0, 0.0, 0.0, 0.0,       # nothing
+                    -1.5, 0.0, 2.5, 0.0], dtype=np.float32).reshape(16, 1)
+    for seed in range(5):
+        out, kept = mvue_dense(col, seed)
+        assert np.array_equal(out[0], col[:, 0].astype(np.float64))
+        assert kept.reshape(4, 4).sum(axis=1).tolist() == [2, 2, 2, 2]
+    # equal magnitudes: every element kept with probability 1/2 and doubled
+    col = np.array([2.0, -2.0, 2.0, 2.0] * 4, dtype=np.float32).reshape(16, 1)
+    out, kept = mvue_dense(col, 3)
+    assert np.array_equal(out[0][kept[0]], 2.0 * col[:, 0][kept[0]])
+    assert np.all(out[0][~kept[0]] == 0)
+
+
+@pytest.mark.parametrize("group", [(1.0, 2.0, 3.0, 4.0), (0.3, -0.2, 0.25, -0.1), (5.0, 1.0, -1.5, 0.5), (9.0, 0.0, 2.0, -1.0)])
+def test_mvue_is_unbiased_with_the_least_second_moment(group):
+    """65536 independent draws of one group (the same four numbers in every token group of one feature).
+    Independent of the oracle's formulas: the sample mean must be the group itself, and the summed second
+    moment must equal the minimum of sum_j a_j^2 / pi_j over sum pi = 2, pi <= 1, which Lagrange gives in closed
+    form: S^2 / 2 without a cap, a_max^2 + R^2 with the largest element capped at probability one."""
+    G = 65536
+    a = np.array(group, dtype=np.float32)
+    dY = np.tile(a, G).reshape(4 * G, 1)
+    out, kept = mvue_dense(dY, 7)
+    samples = out[0].reshape(G, 4)
+    m = np.abs(a.astype(np.float64))
+    S, mx = m.sum(), m.max()
+    if 2 * mx <= S:
+        pi = 2 * m / S
+        second = S * S / 2
+    else:
+        R = S - mx
+        pi = np.where(m == mx, 1.0, m / R)
+        second = mx * mx + R * R
+    var = np.where(pi > 0, m * m * (1 / np.maximum(pi, 1e-300) - 1), 0.0)
+    assert np.all(np.abs(samples.mean(axis=0) - a) <= 5 * np.sqrt(var / G) + 1e-6)
+    freq = kept[0].reshape(G, 4).mean(axis=0)
+    assert np.all(np.abs(freq - pi) <= 5 * np.sqrt(pi * (1 - pi) / G) + 1e-6)
+    got_second = (samples ** 2).sum(axis=1).mean()
+    assert abs(got_second - second) <= 0.02 * second
+
+
+def test_mvue_seed_and_dtype_behaviour():
+    dY = si.random_matrix(51, (256, 24), 1e-2, "bf16")
+    v1, m1 = oracle.mvue24(dY, 11)
+    v2, m2 = oracle.mvue24(dY, 11)
+    v3, m3 = oracle.mvue24(dY, 12)
+    assert np.array_equal(v1, v2) and np.array_equal(m1, m2)
+    assert not np.array_equal(m1, m3)
+    # bf16 storage = the fp32 result rounded to nearest even; the draws do not depend on the storage type
+    vf, mf = oracle.mvue24(si.to_f32(dY), 11)
+    assert np.array_equal(mf, m1)
+    assert np.array_equal(oracle.round_bf16(vf.astype(np.float64)), v1)
+
+
+def test_mvue_weight_gradient_is_unbiased():
+    # Eq. 4: the mean over seeds of S_z(dY^T) X approaches dY^T X
+    dY = si.random_matrix(52, (64, 8), 1.0, "f32")
+    X = si.random_matrix(53, (64, 6), 1.0, "f32")
+    exact = f64(dY).T @ f64(X)
+    acc = np.zeros_like(exact)
+    n = 400
+    for seed in range(n):
+        acc += mvue_dense(dY, seed)[0] @ f64(X)
+    err = np.abs(acc / n - exact)
+    assert err.max() <= 6 * np.abs(exact).max() / np.sqrt(n) + 1e-3
