@@ -48,6 +48,10 @@ def kernel_model(wl):
         "spmm_fwd": ("mfma", gemm, PEAK_SPARSE_BF16, "TFLOP/s"),
         "spmm_bwd_dx": ("mfma", gemm, PEAK_SPARSE_BF16, "TFLOP/s"),
         "dense_dw": ("mfma", gemm, PEAK_DENSE_BF16, "TFLOP/s"),
+        # Eq. 4 mode: the pruned output gradients (p x d_ff for every up-type weight, p x d for the down one):
+        # read es per element, write es/2 + 1/8; then the weight gradient as a sparse GEMM
+        "mvue24": ("hbm", ((nw - 1) * p * f + p * d) * (es + es / 2 + 0.125), PEAK_HBM, "GB/s"),
+        "spmm_dw": ("mfma", gemm, PEAK_SPARSE_BF16, "TFLOP/s"),
         # per 4x4 block: read 16 weights; write mask 2, vals 16*es/2, meta 2, valsT 16*es/2, metaT 2
         "mask_compress": ("hbm", blocks * (16 * es + 2 + 8 * es + 2 + 8 * es + 2), PEAK_HBM, "GB/s"),
         # with a given mask: read 16 weights + mask 2; write vals, meta, valsT, metaT
@@ -170,7 +174,8 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     (3) the core clock under each large-tile GEMM kernel, and the clock-scaled matrix-core peak;
     (4) the step replayed from a HIP graph;
     (5) the step with the mask searched every 40th step only;
-    (6) the flip-count and L1-norm-gap monitors."""
+    (6) the flip-count and L1-norm-gap monitors;
+    (7) the step with the sparse weight gradient on the MVUE-pruned output gradient."""
     import s24_inputs as si
     out = {}
     es = 2 if wl.dtype == "bf16" else 4
@@ -234,11 +239,21 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     out["monitors"] = {"mask_flips": {"ms": round(ms_f, 4), "GB/s": round(nb * 4 / ms_f / 1e6, 1)},
                        "l1_norm_gap": {"ms": round(ms_g, 4), "GB/s": round(nb * (16 * es + 8) / ms_g / 1e6, 1),
                                        "bound": "alu (90 x 16 fp64 select-adds per block)"}}
+    # (7) the step with the weight gradient taken from the unbiasedly pruned output gradient (Eq. 4, Eq. 6)
+    if not ffn.mvue:
+        ffn.mvue = True
+        ffn.timings = {}
+        ms_m = _time_ms(torch, lambda: ffn.step(X, dY), 10)
+        tm, ffn.timings, ffn.mvue = ffn.timings, None, False
+        per = {k: round(sum(a.elapsed_time(b) for a, b in v) / 11, 4) for k, v in tm.items() if k in ("mvue24", "spmm_dw")}
+        out["step_with_mvue_sparse_weight_gradient"] = {"ms_per_step": round(ms_m, 4), "TFLOP/s": round(wl.gemm_flops / ms_m / 1e9, 1),
+                                                        "ms_per_step_by_kernel": per}
     # (4) the whole step replayed from one HIP graph: what the step costs once launch overhead is gone
-    graph = ffn.capture(X, dY)
-    ms_g = _time_ms(torch, graph.replay, 20)
-    out["step_as_hip_graph"] = {"ms_per_step": round(ms_g, 4), "TFLOP/s": round(wl.gemm_flops / ms_g / 1e9, 1)}
-    del graph
+    if not ffn.mvue:
+        graph = ffn.capture(X, dY)
+        ms_g = _time_ms(torch, graph.replay, 20)
+        out["step_as_hip_graph"] = {"ms_per_step": round(ms_g, 4), "TFLOP/s": round(wl.gemm_flops / ms_g / 1e9, 1)}
+        del graph
     # (5) the paper's schedule: the mask searched every 40th step, prune + compress with the stored mask on the
     # others (Sec. 5.1); 40 consecutive steps, one of them with the search
     ffn.mask_interval, ffn.steps_done = 40, 0
@@ -293,6 +308,9 @@ def main():
     ap.add_argument("--separate-gate-up", action="store_true",
                     help="gate and up projection as two weights (three mask passes and nine GEMMs for a gated FFN) "
                          "instead of one concatenated [2*d_ff, d_model] weight")
+    ap.add_argument("--mvue", action="store_true",
+                    help="weight gradient from the unbiasedly 2:4-pruned output gradient as a sparse GEMM (Eq. 4, Eq. 6) "
+                         "instead of the dense GEMM")
     ap.add_argument("--no-fuse-decay", action="store_true",
                     help="masked decay as its own kernel after the weight-gradient GEMM instead of inside its epilogue")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -329,7 +347,7 @@ def main():
 
     dev = {k: to_dev(v) for k, v in host.items()}
     ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay,
-                    concat_gate_up=not args.separate_gate_up)
+                    concat_gate_up=not args.separate_gate_up, mvue=args.mvue)
     X, dY = dev["X"], dev["dY"]
 
     for _ in range(args.warmup):
@@ -373,6 +391,7 @@ def main():
         "config": {"workload": f"{wl.name}: FFN d_model={wl.d_model} d_ff={wl.d_ff} tokens={wl.p} act={wl.act} "
                                f"{wl.dtype}, {len(wl.weight_names)} weights, mask+compress every step",
                    "gate_up_as_one_weight": ffn.concat, "decay_in_dw_epilogue": ffn.fuse_decay,
+                   "weight_gradient": "sparse GEMM on the MVUE-pruned output gradient" if ffn.mvue else "dense GEMM",
                    "gemm_flops_per_step": wl.gemm_flops},
         "pct_of_sparse_mfma_peak_whole_step": round(100 * value / PEAK_SPARSE_BF16, 2),
         "roofline": roofline,

@@ -120,6 +120,25 @@ int s24_dense_dw_decay(const void *dY, const void *X, float *dW, const void *W, 
                        const uint16_t *mask, float lambda, int64_t p, int64_t q, int64_t r, float beta,
                        s24_dtype dt, void *stream);
 
+/* Unbiased 2:4 pruning of the output gradient (Eq. 6: S_z = MVUE) into the compressed operand of the sparse
+ * weight-gradient GEMM (Eq. 4).  Of every four consecutive tokens of one feature two are kept, element j with
+ * probability pi_j proportional to |dY_j| (capped at one) and stored as dY_j / pi_j; the pair is drawn by
+ * systematic sampling from one uniform number per group, a counter-based hash of (seed, feature, group), so
+ * the result is a pure function of its arguments.
+ *   dY     [p][ld] device, dtype dt, ld >= r
+ *   vals   [p/64][r][32] (dtype dt), meta [p/64][r][4]: the compressed form of S_z(dY^T), whose rows are the r
+ *          features and whose contraction axis is the p tokens, in the chunk-major storage described above
+ * p multiple of 64. */
+int s24_mvue24(const void *dY, s24_dtype dt, int64_t p, int64_t r, int64_t ld, uint32_t seed, void *vals,
+               uint16_t *meta, void *stream);
+
+/* Sparse weight gradient (Eq. 4): dW[r][q] = beta*dW + S_z(dY^T) . X (+ lambda * W on pruned cells when W is
+ * not NULL, as in s24_dense_dw_decay), contraction over the p tokens against the compressed operand made by
+ * s24_mvue24 (vals [p/64][r][32], meta [p/64][r][4]).  X [p][q], fp32 output.  p multiple of 64; q, r of 16. */
+int s24_spmm_dw(const void *vals, const uint16_t *meta, const void *X, float *dW, const void *W, s24_dtype wdt,
+                const uint16_t *mask, float lambda, int64_t p, int64_t q, int64_t r, float beta, s24_dtype dt,
+                void *stream);
+
 /* Dense comparison GEMM (Eq. 1, first GEMM): Y[p][r] = X[p][q] . W[r][q]^T,
  * same tiling family as the sparse kernels.  q multiple of 32; r of 16. */
 int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r,

@@ -30,6 +30,8 @@ _SIGNATURES = {
     "s24_spmm_bwd_dx": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_dw": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_dw_decay": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _f32, _i64, _i64, _i64, _f32, _int, _vp]),
+    "s24_mvue24": (_int, [_vp, _int, _i64, _i64, _i64, C.c_uint32, _vp, _vp, _vp]),
+    "s24_spmm_dw": (_int, [_vp, _vp, _vp, _vp, _vp, _int, _vp, _f32, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_gemm": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_masked_decay_grad": (_int, [_vp, _vp, _int, _vp, _f32, _i64, _i64, _vp]),
     "s24_swiglu_fwd": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
@@ -140,6 +142,22 @@ def dense_dw_decay(dY, X, dW, W, mask, lam, beta=0.0):
     q = X.shape[1]
     _check(lib().s24_dense_dw_decay(_ptr(dY), _ptr(X), _ptr(dW), _ptr(W), _dt(W), _ptr(mask), lam, p, q, r, beta,
                                     _dt(X), _stream()), "s24_dense_dw_decay")
+    return dW
+
+
+def mvue24(dY, seed, vals, meta):
+    """vals [p/64, r, 32] (dtype of dY) and meta [p/64, r, 4]: the unbiasedly 2:4-pruned dY^T, compressed."""
+    p, r = dY.shape
+    _check(lib().s24_mvue24(_ptr(dY), _dt(dY), p, r, dY.stride(0), seed & 0xFFFFFFFF, _ptr(vals), _ptr(meta), _stream()),
+           "s24_mvue24")
+    return vals, meta
+
+
+def spmm_dw(vals, meta, X, dW, beta=0.0, W=None, mask=None, lam=0.0):
+    p, q = X.shape
+    r = vals.shape[1]          # vals is chunk-major: [p/64, r, 32]
+    _check(lib().s24_spmm_dw(_ptr(vals), _ptr(meta), _ptr(X), _ptr(dW), _ptr(W), _dt(W) if W is not None else _dt(X),
+                             _ptr(mask), lam, p, q, r, beta, _dt(X), _stream()), "s24_spmm_dw")
     return dW
 
 

@@ -846,6 +846,226 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
 }
 }  // namespace dmatn
 
+// ------------------------------------------------------------------ sparse TN (weight gradient from a pruned dY)
+// dW[m][n] = sum_t A[m][t] X[t][n] with A = S_z(dY^T) compressed along the tokens (Eq. 4).  The compressed
+// operand takes the sparse NT kernel's path (chunk-major values and index words copied into the same LDS
+// layout, one 128-bit read per fragment), the token-major X tile takes the dense TN kernel's (rows of 512 bytes
+// copied as they lie, fragments gathered with the transposing LDS read).  One sparse instruction covers the
+// tokens {16h .. 16h+15} and {32+16h .. 32+16h+15} of a 64-token chunk (h = 0, 1), which is how the index
+// words split over a lane pair; its dense fragment is therefore two 8-token runs 32 tokens apart.
+// 256 x 256 tiles, eight waves of 128 (m) x 64 (n), ring of three 50 KB stages, fp32 output through LDS.
+namespace sptn {
+constexpr int BM = 256, BN = 256, THREADS = 512, ROWB = BN * 2, CPR = ROWB / 16;
+constexpr int B_STAGE = 64 * ROWB, A_STAGE = BM * 64, M_STAGE = BM * 8, STAGE = B_STAGE + A_STAGE + M_STAGE;
+using big::a_slot;
+using big::glb_ptr;
+using big::lds_ptr;
+
+template <bool ACCUM, bool DECAY>
+__global__ __launch_bounds__(THREADS) void spmm_tn_big_kernel(const uint16_t *__restrict__ Av,
+                                                              const uint16_t *__restrict__ Am,
+                                                              const uint16_t *__restrict__ X, float *__restrict__ dW,
+                                                              int T, int M, int N, int tiles_m, int tiles_n,
+                                                              unsigned long long *probe, const uint16_t *__restrict__ Wt,
+                                                              const uint16_t *__restrict__ mask, float lambda)
+{
+    const big::ClockStamp t_start = big::clock_now();
+    __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s1[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s2[STAGE];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8;
+    const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (t >= total) return;
+    constexpr int GROUP = 8;
+    const int group_sz = GROUP * tiles_m, grp = t / group_sz, in_grp = t - grp * group_sz;
+    const int gw = min(GROUP, tiles_n - grp * GROUP);
+    const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int nk = T / 64;
+
+    // copies per lane and chunk: four of the X tile (rows 8*wave .. 8*wave+7), two of the values, one index dword
+    int voffB[4];
+    const int lastB = (min(N - n0, BN) >> 3) - 1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int slot = (wave * 4 + j) * 64 + lane, row = slot / CPR, c = (slot % CPR) ^ ((row & 3) << 2);
+        voffB[j] = row * N + n0 + 8 * min(c, lastB);
+    }
+    const uint16_t *ga_[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = 32 * wave + 16 * i + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        ga_[i] = Av + (int64_t)min(m0 + row, M - 1) * 32 + 8 * c;
+    }
+    const uint16_t *gmeta = Am + (int64_t)min(m0 + 32 * wave + (lane >> 1), M - 1) * 4 + 2 * (lane & 1);
+    auto issue = [&](unsigned char *st, int kc) {
+        kc = min(kc, nk - 1);
+        const char *xb = reinterpret_cast<const char *>(X + (int64_t)kc * 64 * N);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_global_load_lds((glb_ptr)(xb + (uint32_t)voffB[j] * 2u), (lds_ptr)(st + (wave * 4 + j) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            __builtin_amdgcn_global_load_lds((glb_ptr)(ga_[i] + (int64_t)kc * M * 32), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_ptr)(gmeta + (int64_t)kc * M * 4), (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), 4, 0, 0);
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+
+    // X fragment addressing: lane group G = lane/16 -> 8-token half G/2, column half G%2
+    const int gi = lane & 15, G = lane >> 4;
+    const int frow = 8 * (G >> 1) + (gi >> 2), fcol = 16 * (G & 1) + 4 * (gi & 3);
+    int offB[2];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) offB[ni] = dmatn::tr_off<ROWB>(frow, 64 * wn + 32 * ni + fcol);
+
+    issue(s0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+
+    auto chunk = [&](const unsigned char *cur, unsigned char *refill, int kc) {
+        big::wait_and_barrier<7>();   // chunk kc landed for every wave; nobody reads `refill` any more
+        issue(refill, kc + 2);
+        const unsigned char *sb = cur, *sa = cur + B_STAGE, *sm = cur + B_STAGE + A_STAGE;
+        const int g = lane >> 5;
+        uint32_t ix[4];
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+            ix[mi] = *reinterpret_cast<const uint32_t *>(sm + (128 * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            bf16x16 b[2];
+            bf16x8 a[4];
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                struct { bf16x8 lo, hi; } pair{dmatn::tr_frag<ROWB>(sb + offB[ni] + 16 * h * ROWB),
+                                               dmatn::tr_frag<ROWB>(sb + offB[ni] + (32 + 16 * h) * ROWB)};
+                b[ni] = __builtin_bit_cast(bf16x16, pair);
+            }
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+                a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(128 * wm + 32 * mi + (lane & 31), 2 * g + h)));
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    if (h == 0)
+                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 0);
+                    else
+                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 1);
+                }
+        }
+        // issue order: the sixteen LDS reads of the first half, then its eight matrix instructions with the
+        // second half's twelve reads and the seven copies of chunk kc+2 dealt out between them
+        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < 4) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i < 7) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kc = 0;
+    for (; kc + 3 <= nk; kc += 3) {
+        chunk(s0, s2, kc);
+        chunk(s1, s0, kc + 1);
+        chunk(s2, s1, kc + 2);
+    }
+    if (kc < nk) chunk(s0, s2, kc);
+    if (kc + 1 < nk) chunk(s1, s0, kc + 1);
+    big::wait_and_barrier<0>();   // copies drained, nobody reads the ring any more: reuse it
+    big::clock_report(probe, t_start);
+    // fp32 output through LDS in 16-byte row segments: a wave parks 64 rows x 64 columns (two of its four row
+    // blocks) at a time in 16 KB of the ring, lane l of pass j owns row (64j + l) / 16, columns 4 * (l % 16) .. +3
+    static_assert(3 * 16384 <= STAGE, "three waves' staging areas per ring stage");
+    unsigned char *est = (wave < 3 ? s0 : (wave < 6 ? s1 : s2)) + (wave % 3) * 16384;
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int mj = 0; mj < 2; ++mj)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = 32 * mj + 8 * (e / 4) + 4 * (lane >> 5) + (e & 3), col = 32 * ni + (lane & 31);
+                    *reinterpret_cast<float *>(est + row * 256 + col * 4) = acc[2 * h2 + mj][ni][e];
+                }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
+        asm volatile("" ::: "memory");
+        constexpr int BATCH = 8;
+#pragma unroll 1
+        for (int j0 = 0; j0 < 16; j0 += BATCH) {
+            float4 v[BATCH], old[BATCH];
+            uint2 wv[BATCH];
+            uint32_t keep[BATCH];
+            bool live[BATCH];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const int idx = (j0 + b) * 64 + lane, row = idx >> 4, c4 = idx & 15;
+                const int m = m0 + 128 * wm + 64 * h2 + row, n = n0 + 64 * wn + 4 * c4;
+                live[b] = m < M && n < N;   // N is a multiple of 16: the four columns are all in or all out
+                const int mc = min(m, M - 1), nc = min(n, N - 4);
+                v[b] = *reinterpret_cast<const float4 *>(est + row * 256 + c4 * 16);
+                if (ACCUM) old[b] = *reinterpret_cast<const float4 *>(dW + (int64_t)mc * N + nc);
+                if (DECAY) {
+                    wv[b] = *reinterpret_cast<const uint2 *>(Wt + (int64_t)mc * N + nc);
+                    keep[b] = mask[(int64_t)(mc >> 2) * (N >> 2) + (nc >> 2)] >> (4 * (mc & 3));
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const int idx = (j0 + b) * 64 + lane, row = idx >> 4, c4 = idx & 15;
+                const int m = m0 + 128 * wm + 64 * h2 + row, n = n0 + 64 * wn + 4 * c4;
+                float4 o = v[b];
+                if (ACCUM) { o.x = old[b].x + o.x; o.y = old[b].y + o.y; o.z = old[b].z + o.z; o.w = old[b].w + o.w; }
+                if (DECAY) {
+                    if (!(keep[b] & 1u)) o.x = fmaf(lambda, s24_bf16_to_f32(wv[b].x & 0xFFFFu), o.x);
+                    if (!(keep[b] & 2u)) o.y = fmaf(lambda, s24_bf16_to_f32(wv[b].x >> 16), o.y);
+                    if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_bf16_to_f32(wv[b].y & 0xFFFFu), o.z);
+                    if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_bf16_to_f32(wv[b].y >> 16), o.w);
+                }
+                if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * N + n) = o;
+            }
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // LDS reads done before the other half overwrites
+        asm volatile("" ::: "memory");
+    }
+}
+}  // namespace sptn
+
+// one thread per output, fp32 data (no fp32 sparse matrix instruction exists)
+template <bool ACCUM>
+__global__ __launch_bounds__(kThreads) void spmm_tn_f32_kernel(const float *__restrict__ Av, const uint16_t *__restrict__ Am,
+                                                               const float *__restrict__ X, float *__restrict__ dW,
+                                                               int64_t T, int64_t M, int64_t N)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= M * N) return;
+    const int64_t m = idx / N, n = idx - m * N;
+    float acc = 0.0f;
+    for (int64_t g = 0; g < T / 4; ++g) {
+        const int64_t cr = (g / 16) * M + m;  // chunk-major storage: (chunk, row)
+        const unsigned nib = (Am[cr * 4 + (g & 15) / 4] >> (4 * (g & 3))) & 0xFu;
+        acc = fmaf(Av[cr * 32 + 2 * (g & 15)], X[(4 * g + (nib & 3u)) * N + n], acc);
+        acc = fmaf(Av[cr * 32 + 2 * (g & 15) + 1], X[(4 * g + (nib >> 2)) * N + n], acc);
+    }
+    dW[idx] = ACCUM ? dW[idx] + acc : acc;
+}
+
 // ------------------------------------------------------------------ fp32 fallbacks (small correctness workload)
 // One thread per output element, plain fp32 FMA; no matrix-core claim.
 template <bool ACCUM>
@@ -1064,6 +1284,54 @@ extern "C" int s24_dense_dw_decay(const void *dY, const void *X, float *dW, cons
     S24_REQUIRE(W && mask, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(W, 16) && s24_aligned(mask, 4), S24_ERR_ALIGN);
     return run_dense_dw(dY, X, dW, p, q, r, beta, dt, W, wdt, mask, lambda, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int s24_spmm_dw(const void *vals, const uint16_t *meta, const void *X, float *dW, const void *W, s24_dtype wdt,
+                           const uint16_t *mask, float lambda, int64_t p, int64_t q, int64_t r, float beta, s24_dtype dt,
+                           void *stream)
+{
+    S24_REQUIRE(p % 64 == 0 && q % 16 == 0 && r % 16 == 0, S24_ERR_SHAPE);
+    S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
+    const int rc = check_gemm(vals, X, dW, p, q, r, dt, q * r);
+    if (rc != S24_OK || q * r == 0) return rc;
+    if (W != nullptr) {
+        S24_REQUIRE(s24_valid_dtype(wdt), S24_ERR_DTYPE);
+        S24_REQUIRE(mask != nullptr, S24_ERR_NULL);
+        S24_REQUIRE(s24_aligned(W, 16) && s24_aligned(mask, 4), S24_ERR_ALIGN);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool accum = beta != 0.0f;
+    bool decay_pending = W != nullptr;
+    if (p == 0) {
+        if (!accum) hipLaunchKernelGGL(fill_zero_kernel, dim3(ceil_div(q * r, kThreads)), dim3(kThreads), 0, st, dW, q * r);
+    } else {
+        S24_REQUIRE(meta != nullptr, S24_ERR_NULL);
+        S24_REQUIRE(s24_aligned(meta, 4), S24_ERR_ALIGN);
+        if (dt == S24_BF16) {
+            const int tiles_m = (int)ceil_div(r, sptn::BM), tiles_n = (int)ceil_div(q, sptn::BN);
+            const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(sptn::THREADS);
+            auto *av = static_cast<const uint16_t *>(vals), *x = static_cast<const uint16_t *>(X);
+            const bool fuse = decay_pending && wdt == S24_BF16;
+            auto *w = static_cast<const uint16_t *>(fuse ? W : nullptr);
+#define S24_LAUNCH_SPDW(ACC, DEC)                                                                                        \
+    hipLaunchKernelGGL((sptn::spmm_tn_big_kernel<ACC, DEC>), grid, block, 0, st, av, meta, x, dW, (int)p, (int)r, (int)q, \
+                       tiles_m, tiles_n, g_clock_probe, w, mask, lambda)
+            if (accum && fuse) S24_LAUNCH_SPDW(true, true);
+            else if (accum) S24_LAUNCH_SPDW(true, false);
+            else if (fuse) S24_LAUNCH_SPDW(false, true);
+            else S24_LAUNCH_SPDW(false, false);
+#undef S24_LAUNCH_SPDW
+            if (fuse) decay_pending = false;
+        } else {
+            const dim3 grid(ceil_div(r * q, kThreads)), block(kThreads);
+            auto *av = static_cast<const float *>(vals), *x = static_cast<const float *>(X);
+            if (accum) hipLaunchKernelGGL(spmm_tn_f32_kernel<true>, grid, block, 0, st, av, meta, x, dW, p, r, q);
+            else hipLaunchKernelGGL(spmm_tn_f32_kernel<false>, grid, block, 0, st, av, meta, x, dW, p, r, q);
+        }
+    }
+    const int rc2 = s24_launch_status();
+    if (rc2 != S24_OK || !decay_pending) return rc2;
+    return s24_masked_decay_grad(dW, W, wdt, mask, lambda, r, q, st);
 }
 
 extern "C" int s24_set_clock_probe(void *two_counters)

@@ -29,6 +29,15 @@ class SparseWeight:
         self.valsT = torch.empty((r // 64, q, 32), dtype=dt, device=dev)
         self.metaT = torch.empty((r // 64, q, 4), dtype=torch.int16, device=dev)
         self.grad = torch.empty((r, q), dtype=torch.float32, device=dev)
+        self.zvals = self.zmeta = None   # compressed pruned output gradient, allocated on first use
+
+    def pruned_grad_buffers(self, p):
+        """Buffers of the unbiasedly pruned output gradient S_z(dY^T) of this weight for p tokens."""
+        if self.zvals is None or self.zvals.shape[0] != p // 64:
+            r = self.W.shape[0]
+            self.zvals = torch.empty((p // 64, r, 32), dtype=self.W.dtype, device=self.W.device)
+            self.zmeta = torch.empty((p // 64, r, 4), dtype=torch.int16, device=self.W.device)
+        return self.zvals, self.zmeta
 
     def refresh(self, call=None, search=True):
         """Rebuild both compressed operands in one pass over W; with `search` the mask is searched in the
@@ -45,10 +54,13 @@ class SparseFFN:
     """Buffers and call sequence of one FFN layer.  act: 'relu' | 'gelu' | 'swiglu'."""
 
     def __init__(self, weights: dict, p: int, act: str, lam: float, fuse_decay: bool = True, mask_interval: int = 1,
-                 concat_gate_up: bool = False):
+                 concat_gate_up: bool = False, mvue: bool = False, seed: int = 0):
         self.act, self.lam, self.p = act, lam, p
+        # Eq. 4 / Eq. 6: the weight gradient from an unbiasedly 2:4-pruned output gradient, as a sparse GEMM
+        self.mvue, self.seed = mvue, seed
         self.mask_interval = mask_interval   # the mask is searched every mask_interval-th step (Sec. 5.1: l = 40)
         self.steps_done = 0
+        self.draws = 0
         self.fuse_decay = fuse_decay   # masked decay inside the weight-gradient GEMM's epilogue
         self.timings = None   # when a dict: kernel name -> list of (start, end) torch.cuda.Event pairs
         self.gated = act == "swiglu"
@@ -109,7 +121,15 @@ class SparseFFN:
         return self.Y
 
     def _dw(self, dYw, Xw, weight):
-        if self.fuse_decay:
+        if self.mvue:
+            zv, zm = weight.pruned_grad_buffers(dYw.shape[0])
+            self.draws += 1   # a fresh draw for every pruned operand of every step
+            self._k('mvue24', s24.mvue24, dYw, self.seed + self.draws, zv, zm)
+            if self.fuse_decay:
+                self._k('spmm_dw', s24.spmm_dw, zv, zm, Xw, weight.grad, 0.0, weight.W, weight.mask, self.lam)
+            else:
+                self._k('spmm_dw', s24.spmm_dw, zv, zm, Xw, weight.grad)
+        elif self.fuse_decay:
             self._k('dense_dw', s24.dense_dw_decay, dYw, Xw, weight.grad, weight.W, weight.mask, self.lam)
         else:
             self._k('dense_dw', s24.dense_dw, dYw, Xw, weight.grad)
@@ -158,6 +178,8 @@ class SparseFFN:
         launches kernels on the current stream.  Worth it where launches, not kernels, bound the step."""
         if self.timings is not None:
             raise RuntimeError("switch the per-kernel timing hooks off before capturing")
+        if self.mvue:
+            raise RuntimeError("the seed of the pruning draw is a launch argument: a replayed graph would repeat the draw")
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):

@@ -342,6 +342,69 @@ def test_dense_dw_decay_equals_the_two_calls_and_the_oracle(s24, case):
                  f"dense_dw_decay {case}")
 
 
+# ------------------------------------------------------------------ unbiased 2:4 pruning of dY and the sparse weight gradient
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(64, 16), (128, 80), (448, 272), (1024, 1040)])
+def test_mvue24_matches_the_oracle_bit_for_bit(s24, dtype, shape):
+    p, r = shape
+    dY = si.random_matrix(800 + p, (p, r), 1e-2, dtype)
+    dY[:8, : r // 2] = 0                                  # all-zero and half-zero groups
+    dY[8:16:2, :] = 0
+    vals = torch.zeros((p // 64, r, 32), dtype=tdtype(dtype), device="cuda")
+    meta = torch.zeros((p // 64, r, 4), dtype=torch.int16, device="cuda")
+    s24.mvue24(dev_bf16(dY), 20240401, vals, meta)
+    torch.cuda.synchronize()
+    want_v, want_m = oracle.pack(*oracle.mvue24(dY, 20240401))
+    assert np.array_equal(host_bits(meta), want_m)
+    assert np.array_equal(host_bits(vals), want_v if dtype == "bf16" else want_v.view(np.float32))
+    # another seed gives another draw
+    s24.mvue24(dev_bf16(dY), 7, vals, meta)
+    torch.cuda.synchronize()
+    want_v2, want_m2 = oracle.pack(*oracle.mvue24(dY, 7))
+    assert np.array_equal(host_bits(meta), want_m2) and not np.array_equal(want_m2, want_m)
+
+
+def test_mvue24_strided_input(s24):
+    p, r = 128, 96
+    full = si.random_matrix(810, (p, 2 * r), 1e-2, "bf16")
+    d = dev_bf16(full)
+    vals = torch.zeros((p // 64, r, 32), dtype=torch.bfloat16, device="cuda")
+    meta = torch.zeros((p // 64, r, 4), dtype=torch.int16, device="cuda")
+    s24.mvue24(d[:, r:], 5, vals, meta)                   # the right half of a [p, 2r] buffer
+    torch.cuda.synchronize()
+    want_v, want_m = oracle.pack(*oracle.mvue24(np.ascontiguousarray(full[:, r:]), 5))
+    assert np.array_equal(host_bits(meta), want_m) and np.array_equal(host_bits(vals), want_v)
+
+
+@pytest.mark.parametrize("case", [
+    # (p, q, r, dtype, beta, decay)
+    (64, 16, 16, "bf16", 0.0, False), (192, 272, 144, "bf16", 1.0, False), (128, 64, 48, "f32", 1.0, True),
+    (448, 1040, 528, "bf16", 0.0, True), (1024, 3600, 3408, "bf16", 1.0, True)])
+def test_spmm_dw_on_the_pruned_gradient(s24, case):
+    """S_z(dY^T) X from the oracle's own pruned operand: the GEMM is checked on its own (its input is
+    the oracle's compressed operand, not the GPU's), with and without accumulation and the decay term."""
+    p, q, r, dtype, beta, decay = case
+    lam = 2e-4
+    dY = si.random_matrix(820 + p, (p, r), 1e-2, dtype)
+    X = si.random_matrix(821 + p, (p, q), 1.0, dtype)
+    W = si.random_matrix(822 + p, (r, q), 0.02, dtype)
+    dW0 = si.random_matrix(823 + p, (r, q), 1e-3, "f32")
+    mask = oracle.transposable_mask(W)
+    vz, mz = oracle.mvue24(dY, 99)
+    vp, mp = oracle.pack(vz, mz)
+    dW = dev(dW0).clone()
+    s24.spmm_dw(dev_bf16(vp), dev(mp), dev_bf16(X), dW, beta=beta,
+                W=dev_bf16(W) if decay else None, mask=dev(mask) if decay else None, lam=lam if decay else 0.0)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 3, r - 1], np.random.default_rng(p).integers(0, r, 20)])).astype(np.int64)
+    # dW^T = X^T . S^T: the oracle's sparse forward GEMM with X^T as the dense operand and S_z(dY^T) as the weight
+    Xt = np.ascontiguousarray(X.T)
+    ref = oracle.spmm_fwd(Xt, vz, mz).T[rows] + beta * dW0[rows].astype(np.float64)
+    if decay:
+        ref = ref + oracle.masked_decay(np.zeros((r, q), np.float32), W, mask, lam)[rows]
+    assert_close(host_f64(dW[torch.from_numpy(rows).cuda()]), ref, F32_TOL, f"spmm_dw {case}")
+
+
 # ------------------------------------------------------------------ monitors
 @pytest.mark.parametrize("shape", [(4, 4), (64, 96), (260, 1000), (1024, 1028)])
 def test_mask_flips(s24, shape):

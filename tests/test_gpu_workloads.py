@@ -308,3 +308,33 @@ def test_gate_and_up_as_one_weight_matches_the_separate_weights():
     x, y = host_f64(a.dX), host_f64(b.dX)
     assert np.linalg.norm(x - y) <= BF16_TOL[1] * np.linalg.norm(x)
     assert np.abs(x - y).max() <= 2.0 ** -6 * np.abs(x).max()
+
+
+def test_step_with_the_sparse_weight_gradient():
+    """Eq. 4 mode of the layer: every weight gradient is S_z(dY^T) X (+ decay) for the draw the layer made.
+    The GPU's pruned operand is compared bit for bit with the oracle's for the same seed, on an input that
+    comes from the seeded generator (dY of the down projection), and its gradient with the oracle's GEMM."""
+    from paper_2404_01847_amd.ffn import SparseFFN
+    wl = si.Workload("m", 256, 128, 256, "gelu", "bf16", 14)
+    host = si.make(wl)
+    d = {k: dev_bf16(v) for k, v in host.items()}
+    ffn = SparseFFN({n: d[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, mvue=True, seed=1000)
+    ffn.step(d["X"], d["dY"])
+    torch.cuda.synchronize()
+    # first pruned operand of the step: dY for W2 (seed + 1)
+    w2 = ffn.w["W2"]
+    vz, mz = oracle.mvue24(host["dY"], 1001)
+    vp, mp = oracle.pack(vz, mz)
+    assert np.array_equal(host_bits(w2.zmeta), mp) and np.array_equal(host_bits(w2.zvals), vp)
+    # its gradient: S_z(dY^T) H + decay, with H as the GPU computed it upstream fed to nothing but the comparison of
+    # shapes; the oracle side uses its own chain for H
+    mask1 = oracle.transposable_mask(host["W1"])
+    c1 = oracle.compress(host["W1"], mask1)
+    Z = oracle.round_bf16(oracle.spmm_fwd(host["X"], c1[0], c1[1]))
+    H = oracle.round_bf16(oracle.act_fwd(Z, oracle.ACT_GELU_ERF))
+    mask2 = oracle.transposable_mask(host["W2"])
+    ref = oracle.spmm_fwd(np.ascontiguousarray(H.T), vz, mz).T
+    ref = ref + oracle.masked_decay(np.zeros(host["W2"].shape, np.float32), host["W2"], mask2, wl.lam)
+    assert_close(host_f64(w2.grad), ref, (2e-2, 5e-3), "W2 gradient from the pruned dY")
+    with pytest.raises(RuntimeError):
+        ffn.capture(d["X"], d["dY"])

@@ -95,6 +95,20 @@ def test_gemm_argument_errors(lib):
     assert lib.s24_dense_gemm(P, P, P, 0, 64, 16, 1, None) == OK
 
 
+def test_mvue_argument_errors(lib):
+    assert lib.s24_mvue24(P, 1, 96, 16, 16, 1, P, P, None) == SHAPE            # p % 64
+    assert lib.s24_mvue24(P, 1, 64, 16, 8, 1, P, P, None) == SHAPE             # ld < r
+    assert lib.s24_mvue24(P, 4, 64, 16, 16, 1, P, P, None) == DTYPE
+    assert lib.s24_mvue24(P, 1, 64, 16, 16, 1, None, P, None) == NULL
+    assert lib.s24_mvue24(P, 1, 64, 16, 16, 1, P + 8, P, None) == ALIGN
+    assert lib.s24_mvue24(P, 1, 0, 16, 16, 1, None, None, None) == OK
+    assert lib.s24_spmm_dw(P, P, P, P, None, 1, None, 0.0, 96, 16, 16, 0.0, 1, None) == SHAPE
+    assert lib.s24_spmm_dw(P, P, P, P, None, 1, None, 0.0, 64, 16, 16, 0.5, 1, None) == UNSUP
+    assert lib.s24_spmm_dw(P, None, P, P, None, 1, None, 0.0, 64, 16, 16, 0.0, 1, None) == NULL
+    assert lib.s24_spmm_dw(P, P, P, P, P, 1, None, 1e-4, 64, 16, 16, 0.0, 1, None) == NULL    # decay without a mask
+    assert lib.s24_spmm_dw(P, P, P, P, None, 1, None, 0.0, 64, 16, 0, 0.0, 1, None) == OK
+
+
 def test_monitor_argument_errors(lib):
     assert lib.s24_mask_flips(P, P, -1, None, P, None) == SHAPE
     assert lib.s24_mask_flips(P, P, 16, None, None, None) == NULL
