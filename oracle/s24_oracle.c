@@ -215,7 +215,8 @@ int orc_transposable_mask(const void *W, int dt, int64_t r, int64_t q, int64_t l
 /*   uncapped (2 max|a| <= S = sum|a|): pi_j = 2|a_j|/S, kept value    */
 /*     sign(a_j) S/2;                                                  */
 /*   capped: the largest is kept as it is, one of the other three with */
-/*     pi_j = |a_j|/R (R = their sum), kept value sign(a_j) R.         */
+/*     pi_j = |a_j|/R (R = S - max|a|, their sum), kept value          */
+/*     sign(a_j) R.                                                    */
 /* Two elements with these marginals are drawn by systematic sampling: */
 /* one uniform u in [0,1) and the points u, u+1 on the line of the     */
 /* cumulated pi.  All decisions are taken in fp32 in exactly the       */
@@ -251,45 +252,30 @@ static void mvue_group(const float a[4], uint32_t bits, int *i0, int *i1, float 
     float m[4];
     for (int i = 0; i < 4; ++i) m[i] = fabsf(a[i]);
     const float S = (m[0] + m[1]) + (m[2] + m[3]);
-    float mx = m[0];
-    int imax = 0;
-    for (int i = 1; i < 4; ++i)
-        if (m[i] > mx) { mx = m[i]; imax = i; }
-    const int capped = 2.0f * mx > S;
-    float R = 0.0f;
-    if (capped) {
-        int first = 1;
-        for (int i = 0; i < 4; ++i) {
-            if (i == imax) continue;
-            R = first ? m[i] : R + m[i];
-            first = 0;
-        }
-    }
+    const float m01 = m[0] > m[1] ? m[0] : m[1], m23 = m[2] > m[3] ? m[2] : m[3];
+    const float mx = m01 > m23 ? m01 : m23;
+    const int capped = 2.0f * mx > S;          /* then mx is larger than the other three together: it is unique */
+    const float R = S - mx;                    /* the others' sum, as fp32 gives it */
     const float D = capped ? R : S, scale = capped ? 1.0f : 2.0f;
     const float inv = D > 0.0f ? 1.0f / D : 0.0f;
-    float pi[4];
+    float pi[4], mag[4];
     for (int i = 0; i < 4; ++i) {
         const float t = (scale * m[i]) * inv;
         pi[i] = t < 1.0f ? t : 1.0f;
+        mag[i] = capped ? R : 0.5f * S;
+        if (capped && m[i] == mx) { pi[i] = 1.0f; mag[i] = m[i]; }
     }
-    if (capped) pi[imax] = 1.0f;
     const float c1 = pi[0], c2 = c1 + pi[1], c3 = c2 + pi[2];
     const float u = (float)bits * 0x1p-23f, v = u + 1.0f;
     int a0 = (u >= c1) + (u >= c2) + (u >= c3);
     int a1 = (v >= c1) + (v >= c2) + (v >= c3);
-    if (a1 == a0) {            /* only on rounding knife edges and in all-zero groups */
+    if (a1 == a0) {            /* only on rounding knife edges and in groups with fewer than two non-zeros */
         if (a0 < 3) a1 = a0 + 1;
         else { a0 = 2; a1 = 3; }
     }
-    float val[2];
-    const int idx[2] = {a0, a1};
-    for (int k = 0; k < 2; ++k) {
-        const int j = idx[k];
-        if (m[j] == 0.0f) val[k] = 0.0f;
-        else if (capped) val[k] = (j == imax) ? a[j] : copysignf(R, a[j]);
-        else val[k] = copysignf(0.5f * S, a[j]);
-    }
-    *i0 = a0; *i1 = a1; *v0 = val[0]; *v1 = val[1];
+    *i0 = a0; *i1 = a1;
+    *v0 = m[a0] == 0.0f ? 0.0f : copysignf(mag[a0], a[a0]);
+    *v1 = m[a1] == 0.0f ? 0.0f : copysignf(mag[a1], a[a1]);
 }
 
 /* dY [p][ld] (dtype dt) -> compressed S_z(dY^T): rows = the r features, contraction axis = the p tokens,

@@ -5,8 +5,8 @@
 // consecutive tokens of one feature two are kept, element j with probability pi_j and stored as a_j / pi_j
 // (unbiased); sum_j a_j^2 / pi_j under sum pi = 2, pi <= 1 is least for pi_j proportional to |a_j|, capped
 // at one.  Without a cap (2 max|a| <= S = sum |a|) a kept element becomes sign(a_j) S / 2; with a cap the
-// largest element is always kept as it is and one of the others, with probability |a_j| / R (R their sum),
-// becomes sign(a_j) R.  The pair is drawn by systematic sampling with one uniform number u per group, taken
+// largest element is always kept as it is and one of the others, with probability |a_j| / R (R = S - max|a|,
+// their sum), becomes sign(a_j) R.  The pair is drawn by systematic sampling with one uniform number u per group, taken
 // from a counter-based integer hash of (seed, feature, token group).  Every decision is an fp32 operation
 // written with explicit round-to-nearest intrinsics in a fixed order, so the result is a pure function of the
 // inputs and the seed, reproducible bit for bit by any implementation that follows the same order.
@@ -30,41 +30,29 @@ __device__ __forceinline__ Kept mvue_group(const float (&a)[4], uint32_t bits)
 #pragma unroll
     for (int i = 0; i < 4; ++i) m[i] = fabsf(a[i]);
     const float S = __fadd_rn(__fadd_rn(m[0], m[1]), __fadd_rn(m[2], m[3]));
-    float mx = m[0];
-    int imax = 0;
-#pragma unroll
-    for (int i = 1; i < 4; ++i)
-        if (m[i] > mx) { mx = m[i]; imax = i; }
-    const bool capped = __fmul_rn(2.0f, mx) > S;
-    // sum of the three others in index order
-    const float o0 = imax == 0 ? m[1] : m[0];
-    const float o1 = imax <= 1 ? m[2] : m[1];
-    const float o2 = imax <= 2 ? m[3] : m[2];
-    const float R = capped ? __fadd_rn(__fadd_rn(o0, o1), o2) : 0.0f;
+    const float mx = fmaxf(fmaxf(m[0], m[1]), fmaxf(m[2], m[3]));
+    const bool capped = __fmul_rn(2.0f, mx) > S;   // then mx exceeds the other three together: it is unique
+    const float R = __fsub_rn(S, mx);              // the others' sum, as fp32 gives it
     const float D = capped ? R : S, scale = capped ? 1.0f : 2.0f;
     const float inv = D > 0.0f ? __fdiv_rn(1.0f, D) : 0.0f;
-    float pi[4];
+    const float common = capped ? R : __fmul_rn(0.5f, S);
+    float pi[4], val[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const float t = __fmul_rn(__fmul_rn(scale, m[i]), inv);
-        pi[i] = t < 1.0f ? t : 1.0f;
-        if (capped && i == imax) pi[i] = 1.0f;
+        const bool top = capped && m[i] == mx;
+        pi[i] = top ? 1.0f : fminf(__fmul_rn(__fmul_rn(scale, m[i]), inv), 1.0f);
+        val[i] = m[i] == 0.0f ? 0.0f : copysignf(top ? m[i] : common, a[i]);
     }
     const float c1 = pi[0], c2 = __fadd_rn(c1, pi[1]), c3 = __fadd_rn(c2, pi[2]);
     const float u = __fmul_rn((float)bits, 0x1p-23f), v = __fadd_rn(u, 1.0f);
     int i0 = (u >= c1) + (u >= c2) + (u >= c3);
     int i1 = (v >= c1) + (v >= c2) + (v >= c3);
-    if (i1 == i0) {   // only on rounding knife edges and in all-zero groups
+    if (i1 == i0) {   // only on rounding knife edges and in groups with fewer than two non-zeros
         if (i0 < 3) i1 = i0 + 1;
         else { i0 = 2; i1 = 3; }
     }
-    auto value = [&](int j) {
-        const float aj = j == 0 ? a[0] : (j == 1 ? a[1] : (j == 2 ? a[2] : a[3]));
-        if (aj == 0.0f) return 0.0f;
-        if (capped) return j == imax ? aj : copysignf(R, aj);
-        return copysignf(__fmul_rn(0.5f, S), aj);
-    };
-    return {i0, i1, value(i0), value(i1)};
+    auto pick = [&](int j) { return j == 0 ? val[0] : (j == 1 ? val[1] : (j == 2 ? val[2] : val[3])); };
+    return {i0, i1, pick(i0), pick(i1)};
 }
 
 template <typename T> struct Elem;
@@ -82,23 +70,29 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void mvue24_kernel(const T *__restrict__ dY, int64_t ld, int r, int chunks,
                                                           uint32_t seed, T *__restrict__ vals, uint16_t *__restrict__ meta)
 {
-    const int f = (int)blockIdx.x * 64 + (threadIdx.x & 63);
-    const int c = (int)blockIdx.y * 4 + (threadIdx.x >> 6);
-    if (f >= r || c >= chunks) return;
-    const T *src = dY + (int64_t)c * 64 * ld + f;
+    const int lane = threadIdx.x & 63;
+    const int f = (int)blockIdx.x * 64 + lane;
+    const int c = (int)blockIdx.y * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
+    if (c >= chunks) return;
+    // wave-uniform row pointers plus the lane's column: no per-load address arithmetic; lanes past the last
+    // feature re-read the last one and store nothing
+    const T *src = dY + (int64_t)c * 64 * ld + (int)blockIdx.x * 64;
+    const uint32_t row_bytes = (uint32_t)ld * (uint32_t)sizeof(T);   // 63 rows stay below 4 GB (checked on the host)
+    const uint32_t col_bytes = (uint32_t)min(lane, r - 1 - (int)blockIdx.x * 64) * (uint32_t)sizeof(T);
     float out[32];
     uint32_t words[2] = {0u, 0u};
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
         float a[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = Elem<T>::load(src + (int64_t)(4 * g + i) * ld);
+        for (int i = 0; i < 4; ++i) a[i] = Elem<T>::load(reinterpret_cast<const T *>(reinterpret_cast<const char *>(src) + (col_bytes + (uint32_t)(4 * g + i) * row_bytes)));
         const uint32_t bits = mix32(mix32((uint32_t)(16 * c + g) ^ seed) + (uint32_t)f * 0x9E3779B9U) >> 9;
         const Kept k = mvue_group(a, bits);
         out[2 * g] = k.v0;
         out[2 * g + 1] = k.v1;
         words[g >> 3] |= (uint32_t)(k.i0 | (k.i1 << 2)) << (4 * (g & 7));
     }
+    if (f >= r) return;
     const int64_t o = (int64_t)c * r + f;
     if constexpr (sizeof(T) == 2) {
         uint4 *dst = reinterpret_cast<uint4 *>(vals + o * 32);
@@ -121,7 +115,7 @@ extern "C" int s24_mvue24(const void *dY, s24_dtype dt, int64_t p, int64_t r, in
 {
     S24_REQUIRE(s24_valid_dtype(dt), S24_ERR_DTYPE);
     S24_REQUIRE(p >= 0 && r >= 0 && p % 64 == 0 && ld >= r, S24_ERR_SHAPE);
-    S24_REQUIRE(p < (1ll << 31) && r < (1ll << 31) && p / 256 + 1 <= 65535, S24_ERR_SHAPE);
+    S24_REQUIRE(p < (1ll << 31) && r < (1ll << 31) && p / 256 + 1 <= 65535 && ld < (1ll << 24), S24_ERR_SHAPE);
     if (p == 0 || r == 0) return S24_OK;
     S24_REQUIRE(dY && vals && meta, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(dY, s24_elem_size(dt)) && s24_aligned(vals, 16) && s24_aligned(meta, 8), S24_ERR_ALIGN);
