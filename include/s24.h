@@ -97,6 +97,14 @@ int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
 int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y,
                  int64_t p, int64_t q, int64_t r, s24_dtype dt, void *stream);
 
+/* Forward of a gated layer in one pass (Eq. 2 + Sec. 5.2): the compressed operand holds the stacked weight
+ * [W_gate; W_up] (2f rows of q, gate rows first: vals [q/64][2f][32], meta [q/64][2f][4]).  Writes
+ * GU[p][2f] = X . (M.*W)^T (its halves are G = Z_1 and U = Z_2, both needed by the backward pass) and
+ * H[p][f] = silu(G) .* U with G and U rounded to the storage type first, i.e. the same bits as s24_spmm_fwd
+ * followed by s24_swiglu_fwd on the halves.  q multiple of 64; f multiple of 16. */
+int s24_spmm_fwd_swiglu(const void *X, const void *vals, const uint16_t *meta, void *GU, void *H, int64_t p,
+                        int64_t q, int64_t f, s24_dtype dt, void *stream);
+
 /* Backward sparse GEMM for the input gradient (Eq. 3):
  * dX[p][q] = beta*dX + dY[p][r] . (M.*W), contraction over r against the
  * compressed transpose (valsT [r/64][q][32], metaT [r/64][q][4]); legal because the

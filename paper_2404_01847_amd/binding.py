@@ -27,6 +27,7 @@ _SIGNATURES = {
     "s24_transposable_mask": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp]),
     "s24_compress": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "s24_spmm_fwd": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "s24_spmm_fwd_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_spmm_bwd_dx": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_dw": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_dw_decay": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _f32, _i64, _i64, _i64, _f32, _int, _vp]),
@@ -120,6 +121,15 @@ def spmm_fwd(X, vals, meta, Y):
     r = vals.shape[1]          # vals is chunk-major: [q/64, r, 32]
     _check(lib().s24_spmm_fwd(_ptr(X), _ptr(vals), _ptr(meta), _ptr(Y), p, q, r, _dt(X), _stream()), "s24_spmm_fwd")
     return Y
+
+
+def spmm_fwd_swiglu(X, vals, meta, GU, H):
+    """vals/meta: the stacked [W_gate; W_up] compressed; GU [p, 2f] (its halves are G and U), H [p, f]."""
+    p, q = X.shape
+    f = vals.shape[1] // 2
+    _check(lib().s24_spmm_fwd_swiglu(_ptr(X), _ptr(vals), _ptr(meta), _ptr(GU), _ptr(H), p, q, f, _dt(X), _stream()),
+           "s24_spmm_fwd_swiglu")
+    return GU, H
 
 
 def spmm_bwd_dx(dY, valsT, metaT, dX, beta=0.0):

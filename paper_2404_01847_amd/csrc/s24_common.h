@@ -32,3 +32,12 @@ __device__ __forceinline__ uint32_t s24_pack_bf16x2(float lo, float hi)
 {
     return s24_f32_to_bf16(lo) | (s24_f32_to_bf16(hi) << 16);
 }
+
+// silu(g) * u in fp32, shared by the stand-alone SwiGLU kernel and the GEMM epilogue that applies it
+// 1 / (1 + 2^(-x log2 e)) with the hardware exponential and reciprocal (about 2 ulp in fp32, far inside what the
+// bf16 or fp32 outputs of the activation kernels need; saturates to 0 and 1 for large |x|)
+__device__ __forceinline__ float s24_sigmoid(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * x));
+}
+__device__ __forceinline__ float s24_silu_mul(float g, float u) { return g * s24_sigmoid(g) * u; }

@@ -46,7 +46,7 @@ template <> struct Vec8<float> {
     }
 };
 
-__device__ __forceinline__ float sigmoidf(float x) { return 1.0f / (1.0f + expf(-x)); }
+__device__ __forceinline__ float sigmoidf(float x) { return s24_sigmoid(x); }
 
 // ---- masked decay: G += lambda * W where the mask prunes -------------------
 template <typename T>
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kThreads) void swiglu_fwd_kernel(const T *__restric
     Vec8<T>::load(G + in_off, g);
     Vec8<T>::load(U + in_off, u);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) h[k] = g[k] * sigmoidf(g[k]) * u[k];
+    for (int k = 0; k < 8; ++k) h[k] = s24_silu_mul(g[k], u[k]);
     Vec8<T>::store(H + idx * 8, h);
 }
 

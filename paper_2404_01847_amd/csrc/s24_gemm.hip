@@ -223,8 +223,7 @@ __device__ __forceinline__ void clock_report(unsigned long long *probe, const Cl
 // units 2c and 2c+1 from one aligned slot, in swapped order on odd rows.
 // `estage` is EWAVE bytes of LDS private to the wave and no longer used for anything else.
 constexpr int EWAVE = 64 * 256;
-__device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned char *estage, uint16_t *__restrict__ Out,
-                                             int N, int M, int n_base, int m_base, int lane)
+__device__ __forceinline__ void stage_tile(const f32x16 (&acc)[4][2], unsigned char *estage, int lane)
 {
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
@@ -237,6 +236,18 @@ __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned
                     make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g4], acc[mi][ni][4 * g4 + 1]),
                                s24_pack_bf16x2(acc[mi][ni][4 * g4 + 2], acc[mi][ni][4 * g4 + 3]));
             }
+}
+// 16-byte chunk c (eight bf16, columns 8c .. 8c+7) of row nl of a staged tile
+__device__ __forceinline__ uint4 staged_chunk(const unsigned char *estage, int nl, int c)
+{
+    const int x = nl & 31;
+    const uint4 v = *reinterpret_cast<const uint4 *>(estage + nl * 256 + ((((2 * c) ^ x) & ~1) << 3));
+    return (x & 1) ? make_uint4(v.z, v.w, v.x, v.y) : v;
+}
+__device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned char *estage, uint16_t *__restrict__ Out,
+                                             int N, int M, int n_base, int m_base, int lane)
+{
+    stage_tile(acc, estage, lane);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
     asm volatile("" ::: "memory");
@@ -245,19 +256,23 @@ __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned
         const int nl = 4 * j + (lane >> 4), c = lane & 15;
         const int n = n_base + nl, m = m_base + 8 * c;
         if (n >= N || m >= M) continue;   // M is a multiple of 16 (and of 8): a chunk is all in or all out
-        const int x = nl & 31;
-        const uint4 v = *reinterpret_cast<const uint4 *>(estage + nl * 256 + ((((2 * c) ^ x) & ~1) << 3));
-        *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + m) = (x & 1) ? make_uint4(v.z, v.w, v.x, v.y) : v;
+        *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + m) = staged_chunk(estage, nl, c);
     }
 }
 
-template <bool ACCUM>
+// SWIGLU (forward of a gated layer, Sec. 5.2): the compressed operand holds the gate rows [0, F) and the up rows
+// [F, 2F) of one stacked weight (M = 2F).  A workgroup tile then takes 128 gate features and the 128 up features
+// of the same indices, its epilogue pairs them and writes G and U (the halves of Out, row stride M) and
+// H = silu(G) * U (row stride F), all bf16, G and U rounded before H is formed as the stand-alone kernel sees them.
+template <bool ACCUM, bool SWIGLU = false>
 __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
                                                               uint16_t *__restrict__ Out, int N, int K, int M,
-                                                              int tiles_m, int tiles_n, unsigned long long *probe)
+                                                              int tiles_m, int tiles_n, unsigned long long *probe,
+                                                              uint16_t *__restrict__ H = nullptr, int F = 0)
 {
+    static_assert(!(ACCUM && SWIGLU), "the gated epilogue overwrites");
     const ClockStamp t_start = clock_now();
     // One array per ring stage: the compiler then knows which stage a direct-to-LDS
     // copy writes and does not make reads of the other stages wait for it.
@@ -277,8 +292,13 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     const int group_sz = GROUP * tiles_m, grp = t / group_sz, in_grp = t - grp * group_sz;
     const int gw = min(GROUP, tiles_n - grp * GROUP);
     const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int m0 = SWIGLU ? tm * 128 : tm * BM, n0 = tn * BN;   // SWIGLU: m0 = first feature of the tile
     const int nk = K / 64;
+    // row of the compressed operand behind tile row i (clamped at the edge; such rows are never stored)
+    auto a_row = [&](int i) {
+        if (SWIGLU) return (i < 128 ? 0 : F) + min(m0 + (i & 127), F - 1);
+        return min(m0 + i, M - 1);
+    };
 
     // per-lane source pointers of the direct-to-LDS copies (elements), advanced by one chunk per stage
     const uint16_t *gb[4];
@@ -293,10 +313,10 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     for (int i = 0; i < 2; ++i) {
         const int row = 32 * wave + 16 * i + (lane >> 2);
         const int c = (lane & 3) ^ ((row >> 2) & 3);
-        ga_[i] = Av + (int64_t)min(m0 + row, M - 1) * 32 + 8 * c;
+        ga_[i] = Av + (int64_t)a_row(row) * 32 + 8 * c;
     }
     // index words: one 4-byte direct-to-LDS copy per lane and chunk (row 32*wave + lane/2, dword lane%2)
-    const uint16_t *gmeta = Am + (int64_t)min(m0 + 32 * wave + (lane >> 1), M - 1) * 4 + 2 * (lane & 1);
+    const uint16_t *gmeta = Am + (int64_t)a_row(32 * wave + (lane >> 1)) * 4 + 2 * (lane & 1);
     // Every call issues exactly seven copies per lane (four of the dense operand, two of the
     // values, one of the index words), so the wait counts below are constants; past the last
     // chunk it re-reads the last one into a stage nobody will read again.
@@ -407,8 +427,32 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         return;
     }
     static_assert(3 * EWAVE <= STAGE, "three wave tiles must fit one ring stage");
-    staged_store(acc, (wave < 3 ? s0 : (wave < 6 ? s1 : s2)) + (wave % 3) * EWAVE, Out, N, M, n0 + 64 * wn,
-                 m0 + 128 * wm, lane);
+    auto region = [&](int w) { return (w < 3 ? s0 : (w < 6 ? s1 : s2)) + (w % 3) * EWAVE; };
+    if constexpr (!SWIGLU) {
+        staged_store(acc, region(wave), Out, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
+    } else {
+        // waves (0, wn) and (1, wn) hold the gate and the up tile of the same 64 tokens x 128 features: both park
+        // their bf16 tiles, then each takes 32 of the 64 token rows and writes G, U and H in 16-byte pieces
+        stage_tile(acc, region(wave), lane);
+        wait_and_barrier<0>();
+        const unsigned char *sg = region(2 * wn), *su = region(2 * wn + 1);
+#pragma unroll 2
+        for (int j = 0; j < 8; ++j) {
+            const int idx = j * 64 + lane, nl = 32 * wm + (idx >> 4), c = idx & 15;
+            const int n = n0 + 64 * wn + nl, f = m0 + 8 * c;
+            if (n >= N || f >= F) continue;   // F is a multiple of 8: a chunk is all in or all out
+            const uint4 g = staged_chunk(sg, nl, c), u = staged_chunk(su, nl, c);
+            const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, uw[4] = {u.x, u.y, u.z, u.w};
+            uint32_t hw[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                hw[k] = s24_pack_bf16x2(s24_silu_mul(__uint_as_float(gw[k] << 16), __uint_as_float(uw[k] << 16)),
+                                        s24_silu_mul(__uint_as_float(gw[k] & 0xFFFF0000u), __uint_as_float(uw[k] & 0xFFFF0000u)));
+            *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + f) = g;
+            *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + F + f) = u;
+            *reinterpret_cast<uint4 *>(H + (int64_t)n * F + f) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+        }
+    }
 }
 }  // namespace big
 
@@ -1189,6 +1233,30 @@ extern "C" int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t
     S24_REQUIRE(metaT != nullptr, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(metaT, 4), S24_ERR_ALIGN);
     return launch_spmm(dY, valsT, metaT, dX, p, r, q, beta, dt, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int s24_spmm_fwd_swiglu(const void *X, const void *vals, const uint16_t *meta, void *GU, void *H, int64_t p,
+                                   int64_t q, int64_t f, s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(q % 64 == 0 && f % 16 == 0 && q > 0, S24_ERR_SHAPE);
+    const int rc = check_gemm(X, vals, GU, p, q, 2 * f, dt, p * f);
+    if (rc != S24_OK || p * f == 0) return rc;
+    S24_REQUIRE(meta != nullptr && H != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(meta, 4) && s24_aligned(H, 16), S24_ERR_ALIGN);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int tiles_m = (int)ceil_div(f, 128), tiles_n = (int)ceil_div(p, big::BN);
+    if (dt == S24_BF16 && (int64_t)tiles_m * tiles_n >= 192) {
+        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
+        hipLaunchKernelGGL((big::spmm_nt_big_kernel<false, true>), grid, block, 0, st, static_cast<const uint16_t *>(X),
+                           static_cast<const uint16_t *>(vals), meta, static_cast<uint16_t *>(GU), (int)p, (int)q,
+                           (int)(2 * f), tiles_m, tiles_n, g_clock_probe, static_cast<uint16_t *>(H), (int)f);
+        return s24_launch_status();
+    }
+    // shapes the fused epilogue does not cover: the GEMM into [p][2f], then the stand-alone activation on its halves
+    const int rc2 = launch_spmm(X, vals, meta, GU, p, q, 2 * f, 0.0f, dt, st);
+    if (rc2 != S24_OK) return rc2;
+    const size_t es = s24_elem_size(dt);
+    return s24_swiglu_fwd(GU, static_cast<const char *>(GU) + f * es, H, p, f, 2 * f, dt, st);
 }
 
 extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r, s24_dtype dt,

@@ -54,10 +54,11 @@ class SparseFFN:
     """Buffers and call sequence of one FFN layer.  act: 'relu' | 'gelu' | 'swiglu'."""
 
     def __init__(self, weights: dict, p: int, act: str, lam: float, fuse_decay: bool = True, mask_interval: int = 1,
-                 concat_gate_up: bool = False, mvue: bool = False, seed: int = 0):
+                 concat_gate_up: bool = False, mvue: bool = False, seed: int = 0, fuse_swiglu: bool = True):
         self.act, self.lam, self.p = act, lam, p
         # Eq. 4 / Eq. 6: the weight gradient from an unbiasedly 2:4-pruned output gradient, as a sparse GEMM
         self.mvue, self.seed = mvue, seed
+        self.fuse_swiglu = fuse_swiglu   # with one gate+up weight: SwiGLU in the epilogue of its forward GEMM
         self.mask_interval = mask_interval   # the mask is searched every mask_interval-th step (Sec. 5.1: l = 40)
         self.steps_done = 0
         self.draws = 0
@@ -105,7 +106,10 @@ class SparseFFN:
 
     def forward(self, X):
         w = self.w
-        if self.concat:
+        if self.concat and self.fuse_swiglu:
+            self._k('spmm_fwd', s24.spmm_fwd_swiglu, X, w["Wgu"].vals, w["Wgu"].meta, self.GU, self.H)
+            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["Wd"].vals, w["Wd"].meta, self.Y)
+        elif self.concat:
             self._k('spmm_fwd', s24.spmm_fwd, X, w["Wgu"].vals, w["Wgu"].meta, self.GU)
             self._k('swiglu_fwd', s24.swiglu_fwd, self.G, self.U, self.H)
             self._k('spmm_fwd', s24.spmm_fwd, self.H, w["Wd"].vals, w["Wd"].meta, self.Y)

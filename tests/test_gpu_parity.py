@@ -197,6 +197,37 @@ def test_spmm_one_hot_reproduces_masked_weight_exactly(s24):
     assert np.array_equal(host_f64(Y), ref)       # products with 1 and sums with 0 are exact
 
 
+# ------------------------------------------------------------------ gated forward in one pass
+@pytest.mark.parametrize("case", [
+    # (p, q, f): the fallback (two kernels) and the fused epilogue (>= 192 tiles of 256 tokens x 128 features),
+    # the latter with a ragged last token tile and a ragged last feature tile
+    (96, 64, 48), (300, 128, 272), (1000, 128, 6272), (777, 192, 6224)])
+def test_spmm_fwd_swiglu_equals_the_two_calls_and_the_oracle(s24, case):
+    p, q, f = case
+    X = si.random_matrix(900 + p, (p, q), 1.0, "bf16")
+    W = si.random_matrix(901 + p, (2 * f, q), 0.02, "bf16")        # stacked [W_gate; W_up]
+    mask = oracle.transposable_mask(W)
+    vals, meta, _, _ = oracle.compress(W, mask)
+    vp, mp = oracle.pack(vals, meta)
+    d_X, d_v, d_m = dev_bf16(X), dev_bf16(vp), dev(mp)
+    GU = torch.full((p, 2 * f), 7.0, dtype=torch.bfloat16, device="cuda")
+    H = torch.full((p, f), 7.0, dtype=torch.bfloat16, device="cuda")
+    s24.spmm_fwd_swiglu(d_X, d_v, d_m, GU, H)
+    GU2 = torch.empty_like(GU)
+    H2 = torch.empty_like(H)
+    s24.spmm_fwd(d_X, d_v, d_m, GU2)
+    s24.swiglu_fwd(GU2[:, :f], GU2[:, f:], H2)
+    torch.cuda.synchronize()
+    assert torch.equal(GU.view(torch.int16), GU2.view(torch.int16))            # same bits as the two calls
+    assert torch.equal(H.view(torch.int16), H2.view(torch.int16))
+    rows = np.unique(np.concatenate([[0, p - 1], np.random.default_rng(p).integers(0, p, 12)])).astype(np.int64)
+    Z = oracle.spmm_fwd(X, vals, meta, rows=rows)
+    assert_close(host_f64(GU[torch.from_numpy(rows).cuda()]), Z, BF16_TOL, f"GU {case}")
+    Zb = oracle.round_bf16(Z)
+    Href = oracle.swiglu_fwd(np.ascontiguousarray(Zb[:, :f]), np.ascontiguousarray(Zb[:, f:]))
+    assert_close(host_f64(H[torch.from_numpy(rows).cuda()]), Href, (2e-2, 5e-3), f"H {case}")
+
+
 # ------------------------------------------------------------------ dense GEMMs
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("pqr", [(1, 16, 16), (64, 128, 128), (300, 208, 272), (1000, 144, 400)])
