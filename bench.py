@@ -311,6 +311,8 @@ def main():
     ap.add_argument("--mvue", action="store_true",
                     help="weight gradient from the unbiasedly 2:4-pruned output gradient as a sparse GEMM (Eq. 4, Eq. 6) "
                          "instead of the dense GEMM")
+    ap.add_argument("--no-fuse-swiglu", action="store_true",
+                    help="SwiGLU forward and backward as their own kernels instead of GEMM epilogues")
     ap.add_argument("--no-fuse-decay", action="store_true",
                     help="masked decay as its own kernel after the weight-gradient GEMM instead of inside its epilogue")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -347,7 +349,7 @@ def main():
 
     dev = {k: to_dev(v) for k, v in host.items()}
     ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay,
-                    concat_gate_up=not args.separate_gate_up, mvue=args.mvue)
+                    concat_gate_up=not args.separate_gate_up, mvue=args.mvue, fuse_swiglu=not args.no_fuse_swiglu)
     X, dY = dev["X"], dev["dY"]
 
     for _ in range(args.warmup):
@@ -391,6 +393,7 @@ def main():
         "config": {"workload": f"{wl.name}: FFN d_model={wl.d_model} d_ff={wl.d_ff} tokens={wl.p} act={wl.act} "
                                f"{wl.dtype}, {len(wl.weight_names)} weights, mask+compress every step",
                    "gate_up_as_one_weight": ffn.concat, "decay_in_dw_epilogue": ffn.fuse_decay,
+                   "swiglu_in_gemm_epilogues": bool(ffn.concat and ffn.fuse_swiglu),
                    "weight_gradient": "sparse GEMM on the MVUE-pruned output gradient" if ffn.mvue else "dense GEMM",
                    "gemm_flops_per_step": wl.gemm_flops},
         "pct_of_sparse_mfma_peak_whole_step": round(100 * value / PEAK_SPARSE_BF16, 2),

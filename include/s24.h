@@ -113,6 +113,15 @@ int s24_spmm_fwd_swiglu(const void *X, const void *vals, const uint16_t *meta, v
 int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, void *dX,
                     int64_t p, int64_t q, int64_t r, float beta, s24_dtype dt, void *stream);
 
+/* Input gradient of the down projection of a gated layer with the backward of the activation in the same pass
+ * (Eq. 3 + Sec. 5.2): dH = dY[p][r] . (M.*W_down) (valsT [r/64][f][32], metaT [r/64][f][4]) is formed tile by
+ * tile, rounded to the storage type and consumed on the spot:  dGU[p][2f] = [dH .* U .* silu'(G) | dH .* silu(G)]
+ * with G and U the halves of GU[p][2f].  Same bits as s24_spmm_bwd_dx followed by s24_swiglu_bwd.  Only the
+ * large-tile bf16 kernel has this epilogue: other dtypes, and outputs of fewer than 192 tiles of 256 x 256, return
+ * S24_ERR_UNSUPPORTED and leave everything untouched (use the two calls).  r multiple of 64; f of 16. */
+int s24_spmm_bwd_dx_swiglu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
+                           int64_t p, int64_t f, int64_t r, s24_dtype dt, void *stream);
+
 /* Dense weight gradient (Eq. 1, third GEMM; straight-through estimator):
  * dW[r][q] = beta*dW + dY[p][r]^T . X[p][q], fp32 output, beta 0 or 1
  * (1 accumulates over micro-batches).  q, r multiples of 16. */

@@ -29,6 +29,7 @@ _SIGNATURES = {
     "s24_spmm_fwd": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_spmm_fwd_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_spmm_bwd_dx": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
+    "s24_spmm_bwd_dx_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_dense_dw": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_dw_decay": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _f32, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_mvue24": (_int, [_vp, _int, _i64, _i64, _i64, C.c_uint32, _vp, _vp, _vp]),
@@ -138,6 +139,16 @@ def spmm_bwd_dx(dY, valsT, metaT, dX, beta=0.0):
     _check(lib().s24_spmm_bwd_dx(_ptr(dY), _ptr(valsT), _ptr(metaT), _ptr(dX), p, q, r, beta, _dt(dY), _stream()),
            "s24_spmm_bwd_dx")
     return dX
+
+
+def spmm_bwd_dx_swiglu(dY, valsT, metaT, GU, dGU):
+    """dGU [p, 2f] from dY [p, r], the compressed transpose of the down weight and GU [p, 2f]; raises S24Error
+    with status -6 (unsupported) for shapes that only the two-call route covers."""
+    p, r = dY.shape
+    f = valsT.shape[1]
+    _check(lib().s24_spmm_bwd_dx_swiglu(_ptr(dY), _ptr(valsT), _ptr(metaT), _ptr(GU), _ptr(dGU), p, f, r, _dt(dY),
+                                        _stream()), "s24_spmm_bwd_dx_swiglu")
+    return dGU
 
 
 def dense_dw(dY, X, dW, beta=0.0):

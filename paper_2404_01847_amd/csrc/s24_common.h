@@ -41,3 +41,12 @@ __device__ __forceinline__ float s24_sigmoid(float x)
     return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * x));
 }
 __device__ __forceinline__ float s24_silu_mul(float g, float u) { return g * s24_sigmoid(g) * u; }
+
+// backward of h = silu(g) * u for an incoming dh: dg = dh u s (1 + g (1 - s)), du = dh silu(g), s = sigmoid(g)
+__device__ __forceinline__ void s24_swiglu_grad(float dh, float g, float u, float &dg, float &du)
+{
+    const float s = s24_sigmoid(g);
+    const float gs = g * s;
+    dg = dh * u * (s + gs * (1.0f - s));
+    du = dh * gs;
+}

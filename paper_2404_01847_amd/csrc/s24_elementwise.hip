@@ -46,7 +46,6 @@ template <> struct Vec8<float> {
     }
 };
 
-__device__ __forceinline__ float sigmoidf(float x) { return s24_sigmoid(x); }
 
 // ---- masked decay: G += lambda * W where the mask prunes -------------------
 template <typename T>
@@ -102,12 +101,7 @@ __global__ __launch_bounds__(kThreads) void swiglu_bwd_kernel(const T *__restric
     Vec8<T>::load(G + off, g);
     Vec8<T>::load(U + off, u);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const float s = sigmoidf(g[k]);
-        const float gs = g[k] * s;                     // silu(g)
-        dg[k] = d[k] * u[k] * (s + gs * (1.0f - s));   // s (1 + g (1 - s))
-        du[k] = d[k] * gs;
-    }
+    for (int k = 0; k < 8; ++k) s24_swiglu_grad(d[k], g[k], u[k], dg[k], du[k]);
     Vec8<T>::store(dG + off, dg);
     Vec8<T>::store(dU + off, du);
 }

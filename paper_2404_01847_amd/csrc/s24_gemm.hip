@@ -264,15 +264,19 @@ __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned
 // [F, 2F) of one stacked weight (M = 2F).  A workgroup tile then takes 128 gate features and the 128 up features
 // of the same indices, its epilogue pairs them and writes G and U (the halves of Out, row stride M) and
 // H = silu(G) * U (row stride F), all bf16, G and U rounded before H is formed as the stand-alone kernel sees them.
-template <bool ACCUM, bool SWIGLU = false>
+// GATE_BWD (input gradient of the down projection of a gated layer): the tile of dH = dY (M.*W_down) is not
+// written; its bf16 rounding goes straight into the backward of the activation, dG = dH U s (1 + G (1 - s)),
+// dU = dH silu(G), with G and U read from, and dG and dU written to, the halves of [N][2M] buffers.
+template <bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false>
 __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
                                                               uint16_t *__restrict__ Out, int N, int K, int M,
                                                               int tiles_m, int tiles_n, unsigned long long *probe,
-                                                              uint16_t *__restrict__ H = nullptr, int F = 0)
+                                                              uint16_t *__restrict__ H = nullptr, int F = 0,
+                                                              const uint16_t *__restrict__ GU = nullptr)
 {
-    static_assert(!(ACCUM && SWIGLU), "the gated epilogue overwrites");
+    static_assert(!(ACCUM && (SWIGLU || GATE_BWD)) && !(SWIGLU && GATE_BWD), "the gated epilogues overwrite");
     const ClockStamp t_start = clock_now();
     // One array per ring stage: the compiler then knows which stage a direct-to-LDS
     // copy writes and does not make reads of the other stages wait for it.
@@ -428,7 +432,45 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     }
     static_assert(3 * EWAVE <= STAGE, "three wave tiles must fit one ring stage");
     auto region = [&](int w) { return (w < 3 ? s0 : (w < 6 ? s1 : s2)) + (w % 3) * EWAVE; };
-    if constexpr (!SWIGLU) {
+    if constexpr (GATE_BWD) {
+        unsigned char *est = region(wave);
+        stage_tile(acc, est, lane);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
+        asm volatile("" ::: "memory");
+        const int n_base = n0 + 64 * wn, m_base = m0 + 128 * wm;
+        // the accumulators are dead now: all 32 loads of G and U go out before anything is computed
+        const int c = lane & 15, m = min(m_base + 8 * c, M - 8);
+        uint4 g[16], u[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int64_t o = (int64_t)min(n_base + 4 * j + (lane >> 4), N - 1) * 2 * M + m;
+            g[j] = *reinterpret_cast<const uint4 *>(GU + o);
+            u[j] = *reinterpret_cast<const uint4 *>(GU + o + M);
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int nl = 4 * j + (lane >> 4), n = n_base + nl;
+            const uint4 dh = staged_chunk(est, nl, c);
+            const uint32_t dw[4] = {dh.x, dh.y, dh.z, dh.w}, gw[4] = {g[j].x, g[j].y, g[j].z, g[j].w};
+            const uint32_t uw[4] = {u[j].x, u[j].y, u[j].z, u[j].w};
+            uint32_t dgw[4], duw[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float dg0, du0, dg1, du1;
+                s24_swiglu_grad(__uint_as_float(dw[k] << 16), __uint_as_float(gw[k] << 16), __uint_as_float(uw[k] << 16), dg0, du0);
+                s24_swiglu_grad(__uint_as_float(dw[k] & 0xFFFF0000u), __uint_as_float(gw[k] & 0xFFFF0000u),
+                                __uint_as_float(uw[k] & 0xFFFF0000u), dg1, du1);
+                dgw[k] = s24_pack_bf16x2(dg0, dg1);
+                duw[k] = s24_pack_bf16x2(du0, du1);
+            }
+            if (n < N && m_base + 8 * c < M) {   // M is a multiple of 16: a chunk is all in or all out
+                const int64_t o = (int64_t)n * 2 * M + m;
+                *reinterpret_cast<uint4 *>(Out + o) = make_uint4(dgw[0], dgw[1], dgw[2], dgw[3]);
+                *reinterpret_cast<uint4 *>(Out + o + M) = make_uint4(duw[0], duw[1], duw[2], duw[3]);
+            }
+        }
+    } else if constexpr (!SWIGLU) {
         staged_store(acc, region(wave), Out, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
     } else {
         // waves (0, wn) and (1, wn) hold the gate and the up tile of the same 64 tokens x 128 features: both park
@@ -1257,6 +1299,25 @@ extern "C" int s24_spmm_fwd_swiglu(const void *X, const void *vals, const uint16
     if (rc2 != S24_OK) return rc2;
     const size_t es = s24_elem_size(dt);
     return s24_swiglu_fwd(GU, static_cast<const char *>(GU) + f * es, H, p, f, 2 * f, dt, st);
+}
+
+extern "C" int s24_spmm_bwd_dx_swiglu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
+                                      int64_t p, int64_t f, int64_t r, s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(r % 64 == 0 && f % 16 == 0 && r > 0, S24_ERR_SHAPE);
+    const int rc = check_gemm(dY, valsT, dGU, p, f, r, dt, p * f);
+    if (rc != S24_OK || p * f == 0) return rc;
+    S24_REQUIRE(metaT != nullptr && GU != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(metaT, 4) && s24_aligned(GU, 16), S24_ERR_ALIGN);
+    const int tiles_m = (int)ceil_div(f, big::BM), tiles_n = (int)ceil_div(p, big::BN);
+    // only the large-tile bf16 kernel carries this epilogue; other shapes take s24_spmm_bwd_dx + s24_swiglu_bwd
+    S24_REQUIRE(dt == S24_BF16 && (int64_t)tiles_m * tiles_n >= 192, S24_ERR_UNSUPPORTED);
+    const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
+    hipLaunchKernelGGL((big::spmm_nt_big_kernel<false, false, true>), grid, block, 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint16_t *>(dY), static_cast<const uint16_t *>(valsT), metaT,
+                       static_cast<uint16_t *>(dGU), (int)p, (int)r, (int)f, tiles_m, tiles_n, g_clock_probe, nullptr, 0,
+                       static_cast<const uint16_t *>(GU));
+    return s24_launch_status();
 }
 
 extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r, s24_dtype dt,

@@ -59,6 +59,7 @@ class SparseFFN:
         # Eq. 4 / Eq. 6: the weight gradient from an unbiasedly 2:4-pruned output gradient, as a sparse GEMM
         self.mvue, self.seed = mvue, seed
         self.fuse_swiglu = fuse_swiglu   # with one gate+up weight: SwiGLU in the epilogue of its forward GEMM
+        self.fuse_gate_bwd = None        # and its backward in the epilogue of the dH GEMM where the shape allows (probed)
         self.mask_interval = mask_interval   # the mask is searched every mask_interval-th step (Sec. 5.1: l = 40)
         self.steps_done = 0
         self.draws = 0
@@ -141,9 +142,19 @@ class SparseFFN:
     def backward(self, X, dY):
         w = self.w
         if self.concat:
-            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["Wd"].valsT, w["Wd"].metaT, self.dH)
+            fused = False
+            if self.fuse_swiglu and self.fuse_gate_bwd is not False:
+                try:
+                    self._k('spmm_bwd_dx', s24.spmm_bwd_dx_swiglu, dY, w["Wd"].valsT, w["Wd"].metaT, self.GU, self.dGU)
+                    fused = self.fuse_gate_bwd = True
+                except s24.S24Error as e:
+                    if e.status != -6:   # anything but "this shape takes the two-call route"
+                        raise
+                    self.fuse_gate_bwd = False
+            if not fused:
+                self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["Wd"].valsT, w["Wd"].metaT, self.dH)
+                self._k('swiglu_bwd', s24.swiglu_bwd, self.dH, self.G, self.U, self.dG, self.dU)
             self._dw(dY, self.H, w["Wd"])
-            self._k('swiglu_bwd', s24.swiglu_bwd, self.dH, self.G, self.U, self.dG, self.dU)
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dGU, w["Wgu"].valsT, w["Wgu"].metaT, self.dX)
             self._dw(self.dGU, X, w["Wgu"])
         elif self.gated:

@@ -228,6 +228,46 @@ def test_spmm_fwd_swiglu_equals_the_two_calls_and_the_oracle(s24, case):
     assert_close(host_f64(H[torch.from_numpy(rows).cuda()]), Href, (2e-2, 5e-3), f"H {case}")
 
 
+@pytest.mark.parametrize("case", [(2000, 6272, 128), (1800, 6224, 192)])    # (p, f, r): >= 192 tiles of 256 x 256
+def test_spmm_bwd_dx_swiglu_equals_the_two_calls_and_the_oracle(s24, case):
+    p, f, r = case
+    dY = si.random_matrix(910 + p, (p, r), 1e-2, "bf16")
+    Wd = si.random_matrix(911 + p, (r, f), 0.02, "bf16")
+    GU = si.random_matrix(912 + p, (p, 2 * f), 1.0, "bf16")
+    mask = oracle.transposable_mask(Wd)
+    _, _, valsT, metaT = oracle.compress(Wd, mask)
+    vtp, mtp = oracle.pack(valsT, metaT)
+    d_dY, d_v, d_m, d_GU = dev_bf16(dY), dev_bf16(vtp), dev(mtp), dev_bf16(GU)
+    dGU = torch.full((p, 2 * f), 7.0, dtype=torch.bfloat16, device="cuda")
+    s24.spmm_bwd_dx_swiglu(d_dY, d_v, d_m, d_GU, dGU)
+    dH = torch.empty((p, f), dtype=torch.bfloat16, device="cuda")
+    dGU2 = torch.empty_like(dGU)
+    s24.spmm_bwd_dx(d_dY, d_v, d_m, dH)
+    s24.swiglu_bwd(dH, d_GU[:, :f], d_GU[:, f:], dGU2[:, :f], dGU2[:, f:])
+    torch.cuda.synchronize()
+    assert torch.equal(dGU.view(torch.int16), dGU2.view(torch.int16))          # same bits as the two calls
+    rows = np.unique(np.concatenate([[0, p - 1], np.random.default_rng(p).integers(0, p, 12)])).astype(np.int64)
+    dHr = oracle.round_bf16(oracle.spmm_bwd_dx(dY, valsT, metaT, rows=rows))
+    G, U = np.ascontiguousarray(GU[rows][:, :f]), np.ascontiguousarray(GU[rows][:, f:])
+    dG, dU = oracle.swiglu_bwd(dHr, G, U)
+    got = host_f64(dGU[torch.from_numpy(rows).cuda()])
+    assert_close(got[:, :f], dG, (2e-2, 5e-3), f"dG {case}")
+    assert_close(got[:, f:], dU, (2e-2, 5e-3), f"dU {case}")
+
+
+def test_spmm_bwd_dx_swiglu_declines_small_shapes(s24):
+    p, f, r = 64, 64, 64
+    z = torch.zeros((p, 2 * f), dtype=torch.bfloat16, device="cuda")
+    before = z.clone()
+    v = torch.zeros((1, f, 32), dtype=torch.bfloat16, device="cuda")
+    m = torch.zeros((1, f, 4), dtype=torch.int16, device="cuda")
+    with pytest.raises(s24.S24Error) as e:
+        s24.spmm_bwd_dx_swiglu(torch.zeros((p, r), dtype=torch.bfloat16, device="cuda"), v, m, z, z)
+    assert e.value.status == -6
+    torch.cuda.synchronize()
+    assert torch.equal(z, before)
+
+
 # ------------------------------------------------------------------ dense GEMMs
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("pqr", [(1, 16, 16), (64, 128, 128), (300, 208, 272), (1000, 144, 400)])

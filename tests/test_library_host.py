@@ -85,6 +85,10 @@ def test_gemm_argument_errors(lib):
     assert lib.s24_spmm_fwd_swiglu(P, P, P, P, P, 4, 64, 24, 1, None) == SHAPE      # f % 16
     assert lib.s24_spmm_fwd_swiglu(P, P, P, P, None, 4, 64, 16, 1, None) == NULL
     assert lib.s24_spmm_fwd_swiglu(P, P, P, P, P, 0, 64, 16, 1, None) == OK
+    assert lib.s24_spmm_bwd_dx_swiglu(P, P, P, P, P, 4, 16, 96, 1, None) == SHAPE   # r % 64
+    assert lib.s24_spmm_bwd_dx_swiglu(P, P, P, None, P, 4, 16, 64, 1, None) == NULL
+    assert lib.s24_spmm_bwd_dx_swiglu(P, P, P, P, P, 4, 16, 64, 1, None) == UNSUP   # too few tiles for the fused kernel
+    assert lib.s24_spmm_bwd_dx_swiglu(P, P, P, P, P, 4, 16, 64, 0, None) == UNSUP   # fp32
     assert lib.s24_spmm_bwd_dx(P, P, P, P, 4, 16, 96, 0.0, 1, None) == SHAPE  # r % 64
     assert lib.s24_spmm_bwd_dx(P, P, P, P, 4, 16, 64, 0.5, 1, None) == UNSUP  # beta must be 0 or 1
     assert lib.s24_dense_dw(P, P, P, 4, 24, 16, 0.0, 1, None) == SHAPE
