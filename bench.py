@@ -66,7 +66,7 @@ def kernel_model(wl):
     return m
 
 
-def cpu_baseline(wl, tensors_host, budget_tokens=16):
+def cpu_baseline(wl, tensors_host, budget_tokens=None):
     """The oracle, as it stands, on a bounded sample: every weight-side stage
     (mask, compress, decay) at full size, every token-side stage (GEMMs,
     activation) on the first `budget_tokens` tokens, extrapolated linearly in
@@ -75,6 +75,10 @@ def cpu_baseline(wl, tensors_host, budget_tokens=16):
     import oracle
     import s24_inputs as si
     t = tensors_host
+    if budget_tokens is None:
+        # about 10 s of oracle GEMM work on 16 host threads (6 d d_ff FLOPs per token and weight, some 40 GFLOP/s
+        # in fp64): the token sample shrinks with the layer's size
+        budget_tokens = max(16, min(wl.p, int(4.0e11 / (6.0 * len(wl.weight_names) * wl.d_model * wl.d_ff))))
     n = min(budget_tokens, wl.p)
     X, dY = np.ascontiguousarray(t["X"][:n]), np.ascontiguousarray(t["dY"][:n])
     t0 = time.perf_counter()
