@@ -15,8 +15,10 @@ import subprocess
 
 import numpy as np
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 ACT_RELU, ACT_GELU_ERF = 0, 1
+GATE_SILU, GATE_GELU_ERF = 0, 1
+ROW_MAJOR, COL_MAJOR = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "s24_oracle.c")
@@ -40,9 +42,10 @@ def _load():
         for name in ("orc_pack_chunk_major", "orc_pattern_table", "orc_transposable_mask", "orc_compress", "orc_spmm_fwd",
                      "orc_spmm_bwd_dx", "orc_dense_dw", "orc_dense_gemm", "orc_masked_decay",
                      "orc_swiglu_fwd", "orc_swiglu_bwd", "orc_act_fwd", "orc_act_bwd", "orc_num_threads",
-                     "orc_mask_flips", "orc_l1_norm_gap", "orc_mvue24"):
+                     "orc_mask_flips", "orc_l1_norm_gap", "orc_mvue24", "orc_glu_fwd", "orc_glu_bwd", "orc_bias_grad"):
             getattr(_lib, name).restype = C.c_int
         _lib.orc_round_bf16.restype = None
+        _lib.orc_round_f16.restype = None
     return _lib
 
 
@@ -51,7 +54,9 @@ def _dt(a: np.ndarray) -> int:
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError(f"expected float32 or uint16(bf16 bits), got {a.dtype}")
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError(f"expected float32, float16 or uint16(bf16 bits), got {a.dtype}")
 
 
 def _p(a):
@@ -262,3 +267,72 @@ def round_bf16(x) -> np.ndarray:
     out = np.zeros(x.shape, dtype=np.uint16)
     _load().orc_round_bf16(_p(x), C.c_int64(x.size), _p(out))
     return out
+
+
+def round_f16(x) -> np.ndarray:
+    """fp64 -> fp32 -> binary16 (round-to-nearest-even at each step), returned as numpy float16."""
+    x = _c(x, np.float64)
+    out = np.zeros(x.shape, dtype=np.uint16)
+    _load().orc_round_f16(_p(x), C.c_int64(x.size), _p(out))
+    return out.view(np.float16)
+
+
+def round_like(x, like: np.ndarray) -> np.ndarray:
+    """fp64 -> the storage type of `like` (float32, float16, or uint16 holding bf16 bits)."""
+    if like.dtype == np.float32:
+        return np.asarray(x, dtype=np.float64).astype(np.float32)
+    return round_f16(x) if like.dtype == np.float16 else round_bf16(x)
+
+
+def _strided(Z, layout):
+    """(array, leading dimension) of a logical [p][n] matrix held row-major (layout 0) or column-major (1)."""
+    Z = _c(Z)
+    return Z, Z.shape[1]   # a column-major [p][n] matrix is passed as the [n][p] array that stores it: ld = p
+
+
+def glu_fwd(Z, gate, layout=0):
+    """Sec. 5.2 step 3.  Z is [p][2r] (layout 0) or its column-major storage given as the [2r][p] array (1)."""
+    Z, ld = _strided(Z, layout)
+    p, n = (Z.shape[1], Z.shape[0]) if layout == COL_MAJOR else Z.shape
+    r = n // 2
+    H = np.zeros((p, r), dtype=np.float64)
+    _check(_load().orc_glu_fwd(_p(Z), _dt(Z), C.c_int(layout), C.c_int64(ld), C.c_int64(p), C.c_int64(r), C.c_int(gate),
+                               _p(H)), "glu_fwd")
+    return H
+
+
+def glu_bwd(dH, Z, gate, layout=0, layout_h=0):
+    """dZ as a dense row-major [p][2r] fp64 array; dH is [p][r] (layout_h 0) or given as [r][p] (layout_h 1)."""
+    Z, ld = _strided(Z, layout)
+    dH, ldh = _strided(dH, layout_h)
+    p, n = (Z.shape[1], Z.shape[0]) if layout == COL_MAJOR else Z.shape
+    r = n // 2
+    dZ = np.zeros((p, n), dtype=np.float64)
+    _check(_load().orc_glu_bwd(_p(dH), C.c_int(layout_h), C.c_int64(ldh), _p(Z), _dt(Z), C.c_int(layout), C.c_int64(ld),
+                               C.c_int64(p), C.c_int64(r), C.c_int(gate), _p(dZ)), "glu_bwd")
+    return dZ
+
+
+def bias_grad(dZ, layout=0):
+    """Column sums of the logical [p][n] matrix dZ (given as [n][p] when layout is 1)."""
+    dZ, ld = _strided(dZ, layout)
+    p, n = (dZ.shape[1], dZ.shape[0]) if layout == COL_MAJOR else dZ.shape
+    db = np.zeros(n, dtype=np.float64)
+    _check(_load().orc_bias_grad(_p(dZ), _dt(dZ), C.c_int(layout), C.c_int64(ld), C.c_int64(p), C.c_int64(n), _p(db)),
+           "bias_grad")
+    return db
+
+
+def spmm_fwd_bias(X, vals, meta, bias, rows=None):
+    """Sec. 5.2 step 2: Z = X (M.*W)^T + d, the bias widened exactly and added in fp64."""
+    Y = spmm_fwd(X, vals, meta, rows)
+    b = widen(bias)
+    return Y + b[None, :]
+
+
+def widen(a: np.ndarray) -> np.ndarray:
+    """Exact fp64 values of a float32 / float16 / bf16-bits array (numpy's own conversions)."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)

@@ -9,8 +9,10 @@
  *
  * Conventions (paper Sec. 3.1): X is p x q (tokens x in-features), W is r x q
  * (out-features x in-features), Z/Y is p x r; all row-major.  dtype 0 = fp32,
- * 1 = bf16 (raw uint16 bit patterns).  Floating-point results are returned in
- * fp64; every input is widened exactly before any arithmetic.
+ * 1 = bf16 (raw uint16 bit patterns), 2 = IEEE binary16 (raw uint16 bit
+ * patterns; the paper's own precision is fp16 mixed precision, Sec. 6).
+ * Floating-point results are returned in fp64; every input is widened exactly
+ * before any arithmetic.
  *
  * Readings taken where the paper is silent:
  *   - order of the 90 block patterns: lexicographic on the 16-character
@@ -37,13 +39,29 @@
 #include <omp.h>
 #endif
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
 enum { ORC_ACT_RELU = 0, ORC_ACT_GELU_ERF = 1 };
+enum { ORC_GATE_SILU = 0, ORC_GATE_GELU_ERF = 1 };
+enum { ORC_ROW_MAJOR = 0, ORC_COL_MAJOR = 1 };
+
+/* IEEE 754 binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits.
+ * e = 0: +-f * 2^-24;  e = 31: infinity (f = 0) or NaN;  else +-(1024 + f) * 2^(e-25). */
+static double half_bits_to_double(uint16_t h)
+{
+    const int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 0) v = ldexp((double)f, -24);
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = ldexp((double)(1024 + f), e - 25);
+    return sign ? -v : v;
+}
 
 static double widen(const void *base, int dt, size_t idx)
 {
     if (dt == ORC_F32)
         return (double)((const float *)base)[idx];
+    if (dt == ORC_F16)
+        return half_bits_to_double(((const uint16_t *)base)[idx]);
     uint32_t u = ((uint32_t)((const uint16_t *)base)[idx]) << 16;
     float f;
     memcpy(&f, &u, sizeof f);
@@ -225,6 +243,8 @@ int orc_transposable_mask(const void *W, int dt, int64_t r, int64_t q, int64_t l
 /* implementation can reproduce every bit.                             */
 /* ------------------------------------------------------------------ */
 
+static uint16_t f32_to_half_bits(float f);   /* defined with orc_round_f16 below */
+
 /* fp32 -> bf16 bits, round to nearest even (finite inputs) */
 static uint16_t f32_to_bf16_bits(float f)
 {
@@ -279,7 +299,7 @@ static void mvue_group(const float a[4], uint32_t bits, int *i0, int *i1, float 
 }
 
 /* dY [p][ld] (dtype dt) -> compressed S_z(dY^T): rows = the r features, contraction axis = the p tokens,
- * vals [r][p/2] (dtype dt, rounded to nearest even for bf16), meta [r][p/16] as in orc_compress. */
+ * vals [r][p/2] (dtype dt, rounded to nearest even for bf16 and binary16), meta [r][p/16] as in orc_compress. */
 int orc_mvue24(const void *dY, int dt, int64_t p, int64_t r, int64_t ld, uint32_t seed, void *vals, uint16_t *meta)
 {
     if (p < 0 || r < 0 || (p % 16) || ld < r) return -1;
@@ -297,6 +317,9 @@ int orc_mvue24(const void *dY, int dt, int64_t p, int64_t r, int64_t ld, uint32_
             if (dt == 0) {
                 ((float *)vals)[o] = v0;
                 ((float *)vals)[o + 1] = v1;
+            } else if (dt == ORC_F16) {
+                ((uint16_t *)vals)[o] = f32_to_half_bits(v0);
+                ((uint16_t *)vals)[o + 1] = f32_to_half_bits(v1);
             } else {
                 ((uint16_t *)vals)[o] = f32_to_bf16_bits(v0);
                 ((uint16_t *)vals)[o + 1] = f32_to_bf16_bits(v1);
@@ -634,6 +657,107 @@ int orc_act_bwd(const void *dH, const void *Z, int dt, int64_t n, int act, doubl
         dZ[k] = d * dz;
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Gated activation on the output Z = [Z1 | Z2] of the concatenated    */
+/* gate/up GEMM (Sec. 5.2 step 3): H = act(Z1) .* Z2, act = GELU (the   */
+/* paper's GEGLU) or SiLU (SwiGLU).  Z is p x 2r, H is p x r; each is   */
+/* stored row-major (element (t,c) at t*ld + c) or, as the activations  */
+/* of the paper's sparse GEMMs are (App. A.2), column-major (c*ld + t). */
+/* The biases of Sec. 5.2 belong to step 2: they are part of Z.         */
+/* ------------------------------------------------------------------ */
+static size_t at(int layout, int64_t ld, int64_t t, int64_t c)
+{
+    return (size_t)(layout == ORC_COL_MAJOR ? c * ld + t : t * ld + c);
+}
+
+static double gate_value(int gate, double x)
+{
+    return gate == ORC_GATE_SILU ? x * sigmoid(x) : 0.5 * x * (1.0 + erf(x / sqrt(2.0)));
+}
+
+static double gate_slope(int gate, double x)
+{
+    if (gate == ORC_GATE_SILU) {
+        double s = sigmoid(x);
+        return s * (1.0 + x * (1.0 - s));
+    }
+    return 0.5 * (1.0 + erf(x / sqrt(2.0))) + x * 0.39894228040143267794 * exp(-0.5 * x * x);
+}
+
+/* H (dense p x r, row-major fp64) = act(Z1) .* Z2 */
+int orc_glu_fwd(const void *Z, int dt, int layout, int64_t ldz, int64_t p, int64_t r, int gate, double *H)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < p; ++t)
+        for (int64_t c = 0; c < r; ++c) {
+            double z1 = widen(Z, dt, at(layout, ldz, t, c)), z2 = widen(Z, dt, at(layout, ldz, t, r + c));
+            H[t * r + c] = gate_value(gate, z1) * z2;
+        }
+    return 0;
+}
+
+/* dZ (dense p x 2r, row-major fp64) = [dH .* Z2 .* act'(Z1) | dH .* act(Z1)]; dH is p x r in its own layout */
+int orc_glu_bwd(const void *dH, int layout_h, int64_t ldh, const void *Z, int dt, int layout, int64_t ldz, int64_t p,
+                int64_t r, int gate, double *dZ)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < p; ++t)
+        for (int64_t c = 0; c < r; ++c) {
+            double z1 = widen(Z, dt, at(layout, ldz, t, c)), z2 = widen(Z, dt, at(layout, ldz, t, r + c));
+            double d = widen(dH, dt, at(layout_h, ldh, t, c));
+            dZ[t * 2 * r + c] = d * z2 * gate_slope(gate, z1);
+            dZ[t * 2 * r + r + c] = d * gate_value(gate, z1);
+        }
+    return 0;
+}
+
+/* Gradient of the bias d of Z = X W^T + d (Sec. 5.2 step 2): db[c] = sum over tokens of dZ[t][c]. */
+int orc_bias_grad(const void *dZ, int dt, int layout, int64_t ld, int64_t p, int64_t n, double *db)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < n; ++c) {
+        double s = 0.0;
+        for (int64_t t = 0; t < p; ++t) s += widen(dZ, dt, at(layout, ld, t, c));
+        db[c] = s;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Round fp64 -> binary16 the way a GPU epilogue does from its fp32    */
+/* accumulator: fp64 -> fp32 (the C cast, round to nearest even), then */
+/* fp32 -> binary16, round to nearest even, overflow to infinity,      */
+/* gradual underflow.                                                  */
+/* ------------------------------------------------------------------ */
+static uint16_t f32_to_half_bits(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    const uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    const uint32_t a = u & 0x7FFFFFFFu;
+    if (a > 0x7F800000u) return (uint16_t)(sign | 0x7E00u);            /* NaN */
+    if (a >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);           /* >= 65520 rounds to infinity */
+    /* the nearest multiple of the target spacing: 2^(e-10) for |x| in [2^e, 2^(e+1)), e >= -14; 2^-24 below */
+    double m = fabs((double)f);
+    int e;
+    (void)frexp(m, &e);                  /* m = frac * 2^e, frac in [0.5, 1): binade exponent is e - 1 */
+    int q = (e - 1 < -14 ? -14 : e - 1) - 10;
+    double scaled = ldexp(m, -q);        /* exact */
+    double n = nearbyint(scaled);        /* default rounding mode: to nearest, ties to even */
+    double v = ldexp(n, q);              /* a binary16 value, possibly the next binade's first */
+    /* encode v */
+    if (v == 0.0) return sign;
+    (void)frexp(v, &e);
+    if (e - 1 < -14) return (uint16_t)(sign | (uint16_t)ldexp(v, 24));
+    return (uint16_t)(sign | (uint16_t)(((e - 1 + 15) << 10) + ((int)ldexp(v, 10 - (e - 1)) - 1024)));
+}
+
+void orc_round_f16(const double *x, int64_t n, uint16_t *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < n; ++k) out[k] = f32_to_half_bits((float)x[k]);
 }
 
 /* ------------------------------------------------------------------ */

@@ -9,7 +9,8 @@ layers); they stand in for the language-model layers the paper trains, whose
 datasets and weights are not available here.  Every tensor is drawn on the
 host with torch.Generator('cpu').manual_seed(seed), as randn * std in fp32,
 in the fixed order: weights (W1, W2 | Wg, Wu, Wd), X, dY; bf16 workloads then
-round to bf16 (nearest-even).  bf16 tensors are returned as uint16 bit arrays.
+round to bf16 (nearest-even).  bf16 tensors are returned as uint16 bit arrays,
+fp16 ("f16", IEEE binary16) tensors as numpy float16 arrays.
 """
 from __future__ import annotations
 
@@ -26,7 +27,7 @@ class Workload:
     d_model: int
     d_ff: int
     act: str        # "relu" | "gelu" | "swiglu"
-    dtype: str      # "f32" | "bf16"
+    dtype: str      # "f32" | "bf16" | "f16"
     seed: int
     std_w: float = 0.02
     std_x: float = 1.0
@@ -75,9 +76,17 @@ def to_f32(a: np.ndarray) -> np.ndarray:
     return bf16_bits_to_f32(a) if a.dtype == np.uint16 else a.astype(np.float32, copy=False)
 
 
+def _store(t: torch.Tensor, dtype: str) -> np.ndarray:
+    """fp32 tensor -> the array type of `dtype` (nearest-even where it narrows)."""
+    if dtype == "bf16":
+        return f32_to_bf16_bits(t)
+    if dtype == "f16":
+        return t.to(torch.float16).numpy()
+    return t.numpy()
+
+
 def _draw(gen, shape, std, dtype):
-    t = torch.randn(shape, generator=gen, dtype=torch.float32) * std
-    return f32_to_bf16_bits(t) if dtype == "bf16" else t.numpy()
+    return _store(torch.randn(shape, generator=gen, dtype=torch.float32) * std, dtype)
 
 
 def make(wl: Workload, p: int | None = None, only_weights: bool = False) -> dict:
@@ -122,7 +131,10 @@ def tie_matrix(seed: int, r: int, q: int, dtype: str, kind: str) -> np.ndarray:
     kind "range":  entries 2^e with e uniform in [-120, 100] (far beyond any
                    fixed-point window), random signs and 1..3 leading digits
     kind "subnormal": bf16/fp32 subnormals mixed with normals
+    For "f16" the same kinds stay inside binary16: "tiny" scales by 2^-12, "range" takes
+    e in [-24, 13], "subnormal" mixes multiples of 2^-24 with multiples of 2^-17.
     """
+    half = dtype == "f16"
     g = torch.Generator(device="cpu").manual_seed(seed)
     sign = (torch.randint(0, 2, (r, q), generator=g) * 2 - 1).float()
     if kind == "few":
@@ -140,15 +152,15 @@ def tie_matrix(seed: int, r: int, q: int, dtype: str, kind: str) -> np.ndarray:
         for t in range(16):
             sel = (pick == t)
             blk = x[t // 4::4, t % 4::4]
-            blk[sel] = blk[sel] * 2.0 ** -30
+            blk[sel] = blk[sel] * (2.0 ** -12 if half else 2.0 ** -30)
     elif kind == "range":
         m = torch.randint(1, 8, (r, q), generator=g).float()
-        e = torch.randint(-120, 101, (r, q), generator=g).double()
+        e = (torch.randint(-24, 14, (r, q), generator=g) if half else torch.randint(-120, 101, (r, q), generator=g)).double()
         x = (sign.double() * m.double() * torch.pow(torch.tensor(2.0, dtype=torch.float64), e)).float()
     elif kind == "subnormal":
         m = torch.randint(0, 128, (r, q), generator=g).double()
-        e = torch.where(torch.randint(0, 4, (r, q), generator=g) == 0, -126.0, -133.0)
+        e = torch.where(torch.randint(0, 4, (r, q), generator=g) == 0, -17.0 if half else -126.0, -24.0 if half else -133.0)
         x = (sign.double() * m * torch.pow(torch.tensor(2.0, dtype=torch.float64), e.double())).float()
     else:
         raise ValueError(kind)
-    return f32_to_bf16_bits(x) if dtype == "bf16" else x.numpy().copy()
+    return _store(x, dtype).copy()

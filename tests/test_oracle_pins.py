@@ -94,14 +94,14 @@ def check_against_brute_force(W, legal_blocks, **kw):
             assert legal_blocks[int(index[bi, bj])] == want
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_mask_matches_exact_brute_force_random(dtype, legal_blocks):
     W = si.random_matrix(11, (32, 48), 0.02, dtype)
     check_against_brute_force(W, legal_blocks)
     check_against_brute_force(W, legal_blocks, exact_wide=True)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal"])
 def test_mask_matches_exact_brute_force_ties(dtype, kind, legal_blocks):
     W = si.tie_matrix(5, 16, 32, dtype, kind)
@@ -109,7 +109,7 @@ def test_mask_matches_exact_brute_force_ties(dtype, kind, legal_blocks):
     check_against_brute_force(W, legal_blocks, exact_wide=True)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_mask_fast_and_wide_paths_agree(dtype):
     for kind in ["few", "equal", "zeros", "tiny", "range", "subnormal"]:
         W = si.tie_matrix(9, 64, 128, dtype, kind)
@@ -198,7 +198,7 @@ def decode(vals, meta, width):
     return out
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_compress_decodes_to_masked_weight_bitwise(dtype):
     W = si.random_matrix(12, (32, 64), 0.02, dtype)
     W[3, 5] = 0          # a kept or pruned exact zero must not disturb the indices
@@ -215,7 +215,7 @@ def test_compress_decodes_to_masked_weight_bitwise(dtype):
         assert nibs <= legal
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_pack_is_the_documented_permutation(dtype):
     W = si.random_matrix(13, (80, 192), 0.02, dtype)
     mask = oracle.transposable_mask(W)
@@ -236,7 +236,7 @@ def test_compress_rejects_illegal_mask():
 
 
 # ---------------------------------------------------------------- GEMMs
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_sparse_gemms_equal_dense_gemm_on_masked_weight(dtype):
     p, q, r = 24, 64, 48
     W = si.random_matrix(20, (r, q), 0.02, dtype)
@@ -274,7 +274,7 @@ def test_sparse_gemm_one_hot_rows_reproduce_masked_weight():
     assert not np.array_equal(Wm[:, :16], Wm[:, :16].T)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_dense_gemms_match_library(dtype):
     p, q, r = 40, 24, 16
     X = si.random_matrix(30, (p, q), 1.0, dtype)
@@ -292,7 +292,7 @@ def test_dense_gemms_match_library(dtype):
 
 
 # ---------------------------------------------------------------- masked decay (Eq. 10)
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_masked_decay_touches_only_pruned_cells(dtype):
     r, q, lam = 32, 48, np.float32(2e-4)
     W = si.random_matrix(40, (r, q), 0.02, dtype)
@@ -353,7 +353,7 @@ def test_swiglu_bwd_matches_autograd_and_finite_differences():
     assert (dg0 == 0.5).all() and (du0 == 0).all()
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_relu_and_gelu_match_library(dtype):
     z = si.random_matrix(60, (6, 40), 1.5, dtype)
     d = si.random_matrix(61, (6, 40), 1.0, dtype)
@@ -369,7 +369,7 @@ def test_relu_and_gelu_match_library(dtype):
     np.testing.assert_allclose(oracle.act_bwd(d, z, oracle.ACT_GELU_ERF), tz2.grad.numpy(), rtol=1e-12, atol=1e-15)
     # GELU(0) = 0, GELU'(0) = 1/2
     zero = np.zeros((1, 4), dtype=z.dtype)
-    one = si.f32_to_bf16_bits(torch.ones(1, 4)) if dtype == "bf16" else np.ones((1, 4), dtype=np.float32)
+    one = si.f32_to_bf16_bits(torch.ones(1, 4)) if dtype == "bf16" else np.ones((1, 4), dtype=z.dtype)
     assert (oracle.act_fwd(zero, oracle.ACT_GELU_ERF) == 0).all()
     assert (oracle.act_bwd(one, zero, oracle.ACT_GELU_ERF) == 0.5).all()
 
@@ -407,7 +407,7 @@ def test_flip_count_equals_numpy_on_expanded_masks():
     assert 0 < want <= 64 * 96
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 def test_l1_gap_equals_exact_rational_enumeration(legal_blocks, dtype):
     # Sec. 4.2: g = ||m1 . w||_1 - ||m2 . w||_1 with m1, m2 the masks of largest and second largest kept norm
     W = si.random_matrix(41, (16, 24), 0.02, dtype)
@@ -546,3 +546,115 @@ def test_mvue_weight_gradient_is_unbiased():
         acc += mvue_dense(dY, seed)[0] @ f64(X)
     err = np.abs(acc / n - exact)
     assert err.max() <= 6 * np.abs(exact).max() / np.sqrt(n) + 1e-3
+
+
+# ---------------------------------------------------------------- binary16 (the paper's own precision, Sec. 6)
+def test_f16_inputs_are_widened_exactly():
+    # every one of the 65536 bit patterns, read back through a one-row column sum, against numpy's conversion
+    h = np.arange(65536, dtype=np.uint16).view(np.float16).reshape(1, -1)
+    got = oracle.bias_grad(h)
+    want = h[0].astype(np.float64)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+
+
+def test_round_f16_matches_numpy_and_torch():
+    rng = np.random.default_rng(17)
+    x = rng.standard_normal(20000) * np.exp(rng.uniform(-22, 12, 20000))
+    x[:10] = [0.0, -0.0, 1.00048828125, 1.00146484375, 65504.0, 65519.99, 65520.0, 2.0 ** -25, 1.5 * 2.0 ** -25, -1e9]
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float32).astype(np.float16)
+    got = oracle.round_f16(x)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    wt = torch.from_numpy(x).float().to(torch.float16).numpy()
+    assert np.array_equal(got.view(np.uint16), wt.view(np.uint16))
+    # ties to even, overflow to infinity, half the smallest subnormal to zero
+    assert got[2] == 1.0 and got[3] == np.float16(1.001953125) and got[4] == 65504 and got[5] == 65504
+    assert np.isinf(got[6]) and got[7] == 0 and got[8] == np.float16(2.0 ** -24) and got[9] == -np.inf
+
+
+def test_mvue_f16_rounds_kept_values_to_binary16():
+    dY = si.random_matrix(70, (32, 8), 0.05, "f16")
+    v16, m16 = oracle.mvue24(dY, 5)
+    v32, m32 = oracle.mvue24(dY.astype(np.float32), 5)
+    assert v16.dtype == np.float16 and np.array_equal(m16, m32)      # same decisions: both decide in fp32
+    assert np.array_equal(v16.view(np.uint16), v32.astype(np.float16).view(np.uint16))
+
+
+# ---------------------------------------------------------------- gated activation on Z = [Z1 | Z2] (Sec. 5.2 step 3)
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("gate", ["gelu", "silu"])
+def test_glu_matches_library_in_both_layouts(dtype, gate):
+    p, r = 12, 24
+    Z = si.random_matrix(80, (p, 2 * r), 1.5, dtype)
+    D = si.random_matrix(81, (p, r), 1.0, dtype)
+    g = oracle.GATE_GELU_ERF if gate == "gelu" else oracle.GATE_SILU
+    fn = (lambda t: torch.nn.functional.gelu(t, approximate="none")) if gate == "gelu" else torch.nn.functional.silu
+    tz = torch.from_numpy(f64(Z)).requires_grad_()
+    th = fn(tz[:, :r]) * tz[:, r:]
+    th.backward(torch.from_numpy(f64(D)))
+    H = oracle.glu_fwd(Z, g)
+    np.testing.assert_allclose(H, th.detach().numpy(), rtol=1e-13, atol=1e-300)
+    dZ = oracle.glu_bwd(D, Z, g)
+    np.testing.assert_allclose(dZ, tz.grad.numpy(), rtol=1e-12, atol=1e-15)
+    # column-major storage of the same matrices is the row-major storage of their transposes
+    Zc, Dc = np.ascontiguousarray(Z.T), np.ascontiguousarray(D.T)
+    assert np.array_equal(oracle.glu_fwd(Zc, g, layout=oracle.COL_MAJOR), H)
+    assert np.array_equal(oracle.glu_bwd(Dc, Zc, g, layout=oracle.COL_MAJOR, layout_h=oracle.COL_MAJOR), dZ)
+    assert np.array_equal(oracle.glu_bwd(D, Zc, g, layout=oracle.COL_MAJOR), dZ)
+    # the gate is the FIRST half: swapping the halves changes the result
+    Zs = np.concatenate([Z[:, r:], Z[:, :r]], axis=1)
+    assert not np.allclose(oracle.glu_fwd(Zs, g), H)
+
+
+def test_glu_special_values_and_the_swiglu_special_case():
+    # GELU(1) = Phi(1), GELU(-1) = -(1 - Phi(1)), GELU(0) = 0, GELU'(0) = 1/2; Phi(1) to 16 digits
+    phi1 = 0.8413447460685429
+    Z = np.array([[1.0, -1.0, 0.0, 40.0, 2.0, 3.0, 5.0, 0.5]], dtype=np.float32)
+    H = oracle.glu_fwd(Z, oracle.GATE_GELU_ERF)[0]
+    np.testing.assert_allclose(H[:2], [2.0 * phi1, -3.0 * (1.0 - phi1)], rtol=1e-14)
+    assert H[2] == 0.0 and H[3] == 20.0
+    dZ = oracle.glu_bwd(np.ones((1, 4), dtype=np.float32), Z, oracle.GATE_GELU_ERF)[0]
+    assert dZ[2] == 0.5 * 5.0 and dZ[6] == 0.0 and dZ[7] == 40.0 and dZ[3] == 0.5
+    np.testing.assert_allclose(dZ[4], phi1, rtol=1e-14)
+    # central differences of the forward function
+    Zr = si.random_matrix(82, (3, 16), 1.0, "f32")
+    Dr = si.random_matrix(83, (3, 8), 1.0, "f32")
+    an = oracle.glu_bwd(Dr, Zr, oracle.GATE_GELU_ERF)
+    eps = 2.0 ** -10
+    for c in range(16):
+        Zp, Zm = Zr.copy(), Zr.copy()
+        Zp[:, c] += eps
+        Zm[:, c] -= eps
+        fd = (oracle.glu_fwd(Zp, oracle.GATE_GELU_ERF) - oracle.glu_fwd(Zm, oracle.GATE_GELU_ERF)) / (Zp[:, c] - Zm[:, c]).astype(np.float64)[:, None]
+        np.testing.assert_allclose(an[:, c], (fd * f64(Dr))[:, c % 8], rtol=1e-5, atol=1e-7)
+    # with the SiLU gate it is the SwiGLU of the two halves
+    Zb = si.random_matrix(84, (5, 32), 2.0, "bf16")
+    Db = si.random_matrix(85, (5, 16), 1.0, "bf16")
+    G, U = np.ascontiguousarray(Zb[:, :16]), np.ascontiguousarray(Zb[:, 16:])
+    assert np.array_equal(oracle.glu_fwd(Zb, oracle.GATE_SILU), oracle.swiglu_fwd(G, U))
+    dG, dU = oracle.swiglu_bwd(Db, G, U)
+    np.testing.assert_allclose(oracle.glu_bwd(Db, Zb, oracle.GATE_SILU), np.concatenate([dG, dU], axis=1), rtol=1e-14, atol=0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_bias_gradient_is_the_column_sum_and_bias_shifts_every_row(dtype):
+    dZ = si.random_matrix(86, (37, 24), 1.0, dtype)
+    want = np.array([sum(Fraction(float(v)) for v in f64(dZ)[:, c]) for c in range(24)], dtype=object)
+    got = oracle.bias_grad(dZ)
+    assert all(abs(Fraction(float(g)) - w) <= abs(w) * Fraction(1, 2 ** 45) + Fraction(1, 2 ** 60) for g, w in zip(got, want))
+    assert np.array_equal(oracle.bias_grad(np.ascontiguousarray(dZ.T), layout=oracle.COL_MAJOR), got)
+    ones = np.ones((5, 8), dtype=np.float32)
+    assert (oracle.bias_grad(ones) == 5.0).all()
+    # Z = X W^T + d: every row moves by d, and d = 0 gives the plain product
+    p, q, r = 8, 64, 16
+    W = si.random_matrix(87, (r, q), 0.02, dtype)
+    X = si.random_matrix(88, (p, q), 1.0, dtype)
+    d = si.random_matrix(89, (r,), 0.5, dtype)
+    mask = oracle.transposable_mask(W)
+    vals, meta, _, _ = oracle.compress(W, mask)
+    Y = oracle.spmm_fwd(X, vals, meta)
+    Z = oracle.spmm_fwd_bias(X, vals, meta, d)
+    np.testing.assert_allclose(Z - Y, np.broadcast_to(f64(d), (p, r)), rtol=0, atol=1e-15)
+    assert np.array_equal(oracle.spmm_fwd_bias(X, vals, meta, np.zeros_like(d)), Y)
