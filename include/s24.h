@@ -32,7 +32,14 @@
  *                o is the row's kept value 32c+j)  and  meta[K/64][R][4]  (word
  *                4c+j of the row).  One chunk of one row is exactly what one
  *                lane pair feeds to two sparse matrix-core instructions.
- *   dtypes       S24_BF16 buffers hold raw bfloat16; S24_F32 buffers hold float.
+ *   dtypes       S24_BF16 buffers hold raw bfloat16, S24_F16 buffers IEEE binary16 (the paper trains in fp16
+ *                mixed precision, Sec. 6), S24_F32 buffers float.  Both 16-bit types run the same kernels on
+ *                the matrix cores (fp32 accumulation, one rounding to the storage type); S24_F32 runs plain
+ *                fp32 kernels kept for checking.  binary16 results overflow to infinity like any IEEE
+ *                conversion: scaling the loss is the caller's business.
+ *   layouts      a logical [p][n] activation matrix is S24_ROW_MAJOR (element (t, c) at t*ld + c) or
+ *                S24_COL_MAJOR (at c*ld + t, the layout the paper's sparse GEMMs emit, App. A.2).  The GEMMs of
+ *                this library read and write row-major; the gated activation and the bias gradient take both.
  */
 #ifndef S24_H
 #define S24_H
@@ -53,8 +60,10 @@ typedef enum {
     S24_ERR_UNSUPPORTED = -6  /* valid request that this build does not implement */
 } s24_status;
 
-typedef enum { S24_F32 = 0, S24_BF16 = 1 } s24_dtype;
+typedef enum { S24_F32 = 0, S24_BF16 = 1, S24_F16 = 2 } s24_dtype;   /* S24_F16: IEEE binary16, the paper's own precision (Sec. 6) */
 typedef enum { S24_ACT_RELU = 0, S24_ACT_GELU_ERF = 1 } s24_act;
+typedef enum { S24_GATE_SILU = 0, S24_GATE_GELU_ERF = 1 } s24_gate;     /* SwiGLU / GEGLU (Sec. 5.2) */
+typedef enum { S24_ROW_MAJOR = 0, S24_COL_MAJOR = 1 } s24_layout;       /* element (t, c) at t*ld + c / c*ld + t */
 
 #define S24_NUM_PATTERNS 90
 
@@ -96,6 +105,25 @@ int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
  * p >= 1; q multiple of 64; r multiple of 16. */
 int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y,
                  int64_t p, int64_t q, int64_t r, s24_dtype dt, void *stream);
+
+/* Z = X (M.*W)^T + d (Sec. 5.2 step 2): s24_spmm_fwd with the bias d[r] (dtype dt, 8-byte aligned, may be NULL)
+ * added to the fp32 accumulator before the one rounding to the storage type. */
+int s24_spmm_fwd_bias(const void *X, const void *vals, const uint16_t *meta, const void *bias, void *Y,
+                      int64_t p, int64_t q, int64_t r, s24_dtype dt, void *stream);
+
+/* The three steps of Sec. 5.2 in one pass, for either gate: the compressed operand holds the stacked weight
+ * [W_gate; W_up] as in s24_spmm_fwd_swiglu, bias is the stacked d[2f] or NULL.  Writes
+ * GU[p][2f] = Z = X (M.*W)^T + d and H[p][f] = act(Z_1) .* Z_2 (act = GELU for S24_GATE_GELU_ERF, the paper's
+ * GEGLU; SiLU for S24_GATE_SILU), Z rounded to the storage type before H is formed: the same bits as
+ * s24_spmm_fwd_bias followed by s24_glu_fwd.  q multiple of 64; f multiple of 16. */
+int s24_spmm_fwd_glu(const void *X, const void *vals, const uint16_t *meta, const void *bias, void *GU, void *H,
+                     int64_t p, int64_t q, int64_t f, s24_gate gate, s24_dtype dt, void *stream);
+
+/* s24_spmm_bwd_dx_swiglu for either gate: dGU[p][2f] = [dH .* Z_2 .* act'(Z_1) | dH .* act(Z_1)] with
+ * dH = dY (M.*W_down) consumed tile by tile.  Same bits as s24_spmm_bwd_dx followed by s24_glu_bwd; the same
+ * S24_ERR_UNSUPPORTED rule (fp32, or fewer than 192 output tiles of 256 x 256). */
+int s24_spmm_bwd_dx_glu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
+                        int64_t p, int64_t f, int64_t r, s24_gate gate, s24_dtype dt, void *stream);
 
 /* Forward of a gated layer in one pass (Eq. 2 + Sec. 5.2): the compressed operand holds the stacked weight
  * [W_gate; W_up] (2f rows of q, gate rows first: vals [q/64][2f][32], meta [q/64][2f][4]).  Writes
@@ -179,6 +207,27 @@ int s24_swiglu_fwd(const void *G, const void *U, void *H, int64_t p, int64_t f, 
  * with row stride ld_gu like G and U. */
 int s24_swiglu_bwd(const void *dH, const void *G, const void *U, void *dG, void *dU,
                    int64_t p, int64_t f, int64_t ld_gu, s24_dtype dt, void *stream);
+
+/* Gated activation on the output of the concatenated GEMM (Sec. 5.2 step 3): Z is [p][2f] = [Z_1 | Z_2] with
+ * leading dimension ldz in layout lz, H is [p][f] with ldh in layout lh;  H = act(Z_1) .* Z_2.  The four layout
+ * pairs are all served: equal layouts by a streaming kernel, different ones through 64 x 64 LDS tiles, so
+ * that a column-major Z (what the paper's Table 4 measures) can feed a row-major consumer without a
+ * separate transpose.  f and both leading dimensions multiples of 8 elements; p a multiple of 8 unless both
+ * layouts are row-major; Z and H 16-byte aligned. */
+int s24_glu_fwd(const void *Z, s24_layout lz, int64_t ldz, void *H, s24_layout lh, int64_t ldh, int64_t p, int64_t f,
+                s24_gate gate, s24_dtype dt, void *stream);
+
+/* Backward of s24_glu_fwd: dZ (layout and leading dimension of Z) = [dH .* Z_2 .* act'(Z_1) | dH .* act(Z_1)];
+ * gelu'(z) = Phi(z) + z phi(z), silu'(z) = s(z)(1 + z(1 - s(z))).  dH is [p][f] with ldh in layout lh. */
+int s24_glu_bwd(const void *dH, s24_layout lh, int64_t ldh, const void *Z, s24_layout lz, int64_t ldz, void *dZ,
+                int64_t p, int64_t f, s24_gate gate, s24_dtype dt, void *stream);
+
+/* Gradient of the bias of Sec. 5.2 step 2:  db[c] = beta*db[c] + sum over the p tokens of dZ[t][c], c < n.
+ * dZ is [p][n] with leading dimension ld in the given layout; db is fp32 on the device; beta is 0 or 1.  The sum
+ * runs in fp32 in a fixed order (no atomics): the result is reproducible.  n, ld multiples of 8; p a multiple of
+ * 8 for a column-major dZ. */
+int s24_bias_grad(const void *dZ, s24_layout layout, int64_t ld, int64_t p, int64_t n, float *db, float beta,
+                  s24_dtype dt, void *stream);
 
 /* Ungated activations of the smaller workloads: H = act(Z), n elements.
  * GELU is the erf form.  n multiple of 8. */

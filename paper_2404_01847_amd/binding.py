@@ -1,7 +1,7 @@
 """ctypes binding of libs24.so: argument marshalling only.
 
 Every function takes torch tensors that already live on the GPU (bf16 data as
-torch.bfloat16, masks/metadata as int16/uint16 views, pattern ids as uint8),
+torch.bfloat16, binary16 as torch.float16, masks/metadata as int16/uint16 views, pattern ids as uint8),
 passes their data pointers and the current HIP stream to the C entry point of
 the same name, and raises S24Error on a non-zero status.  Nothing is computed
 here and nothing falls back to PyTorch.
@@ -13,8 +13,10 @@ import os
 
 import torch
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 ACT_RELU, ACT_GELU_ERF = 0, 1
+GATE_SILU, GATE_GELU_ERF = 0, 1
+ROW_MAJOR, COL_MAJOR = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libs24.so")
@@ -27,6 +29,12 @@ _SIGNATURES = {
     "s24_transposable_mask": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp]),
     "s24_compress": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "s24_spmm_fwd": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "s24_spmm_fwd_bias": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "s24_spmm_fwd_glu": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp]),
+    "s24_spmm_bwd_dx_glu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp]),
+    "s24_glu_fwd": (_int, [_vp, _int, _i64, _vp, _int, _i64, _i64, _i64, _int, _int, _vp]),
+    "s24_glu_bwd": (_int, [_vp, _int, _i64, _vp, _int, _i64, _vp, _i64, _i64, _int, _int, _vp]),
+    "s24_bias_grad": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _f32, _int, _vp]),
     "s24_spmm_fwd_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_spmm_bwd_dx": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_spmm_bwd_dx_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
@@ -89,9 +97,11 @@ def _ptr(t):
 def _dt(t: torch.Tensor) -> int:
     if t.dtype == torch.bfloat16:
         return BF16
+    if t.dtype == torch.float16:
+        return F16
     if t.dtype == torch.float32:
         return F32
-    raise TypeError(f"s24 supports float32 and bfloat16 tensors, got {t.dtype}")
+    raise TypeError(f"s24 supports float32, float16 and bfloat16 tensors, got {t.dtype}")
 
 
 def _stream():
@@ -122,6 +132,63 @@ def spmm_fwd(X, vals, meta, Y):
     r = vals.shape[1]          # vals is chunk-major: [q/64, r, 32]
     _check(lib().s24_spmm_fwd(_ptr(X), _ptr(vals), _ptr(meta), _ptr(Y), p, q, r, _dt(X), _stream()), "s24_spmm_fwd")
     return Y
+
+
+def spmm_fwd_bias(X, vals, meta, bias, Y):
+    """Y = X (M.*W)^T + bias; bias [r] in the dtype of X, or None."""
+    p, q = X.shape
+    r = vals.shape[1]
+    _check(lib().s24_spmm_fwd_bias(_ptr(X), _ptr(vals), _ptr(meta), _ptr(bias), _ptr(Y), p, q, r, _dt(X), _stream()),
+           "s24_spmm_fwd_bias")
+    return Y
+
+
+def spmm_fwd_glu(X, vals, meta, bias, GU, H, gate):
+    """spmm_fwd_swiglu for either gate (GATE_SILU / GATE_GELU_ERF) and an optional stacked bias [2f]."""
+    p, q = X.shape
+    f = vals.shape[1] // 2
+    _check(lib().s24_spmm_fwd_glu(_ptr(X), _ptr(vals), _ptr(meta), _ptr(bias), _ptr(GU), _ptr(H), p, q, f, gate, _dt(X),
+                                  _stream()), "s24_spmm_fwd_glu")
+    return GU, H
+
+
+def spmm_bwd_dx_glu(dY, valsT, metaT, GU, dGU, gate):
+    p, r = dY.shape
+    f = valsT.shape[1]
+    _check(lib().s24_spmm_bwd_dx_glu(_ptr(dY), _ptr(valsT), _ptr(metaT), _ptr(GU), _ptr(dGU), p, f, r, gate, _dt(dY),
+                                     _stream()), "s24_spmm_bwd_dx_glu")
+    return dGU
+
+
+def _ld(t, layout):
+    """Leading dimension of a 2-D tensor that stores a logical [p][n] matrix: a column-major matrix is passed as
+    the [n, p] tensor holding it, so the stride of the first axis is the leading dimension either way."""
+    return t.stride(0)
+
+
+def glu_fwd(Z, H, gate, layout_z=ROW_MAJOR, layout_h=ROW_MAJOR):
+    """H = act(Z_1) .* Z_2.  Z: [p, 2f] tensor (row-major) or the [2f, p] tensor that holds a column-major Z;
+    H likewise [p, f] or [f, p]."""
+    p, f = (H.shape[1], H.shape[0]) if layout_h == COL_MAJOR else H.shape
+    _check(lib().s24_glu_fwd(_ptr(Z), layout_z, _ld(Z, layout_z), _ptr(H), layout_h, _ld(H, layout_h), p, f, gate, _dt(Z),
+                             _stream()), "s24_glu_fwd")
+    return H
+
+
+def glu_bwd(dH, Z, dZ, gate, layout_h=ROW_MAJOR, layout_z=ROW_MAJOR):
+    """dZ (shaped and laid out like Z) from dH ([p, f], or [f, p] for a column-major dH)."""
+    p, f = (dH.shape[1], dH.shape[0]) if layout_h == COL_MAJOR else dH.shape
+    _check(lib().s24_glu_bwd(_ptr(dH), layout_h, _ld(dH, layout_h), _ptr(Z), layout_z, _ld(Z, layout_z), _ptr(dZ), p, f,
+                             gate, _dt(Z), _stream()), "s24_glu_bwd")
+    return dZ
+
+
+def bias_grad(dZ, db, beta=0.0, layout=ROW_MAJOR):
+    """db [n] (float32) = beta*db + column sums of the logical [p][n] matrix dZ ([n, p] tensor if column-major)."""
+    p, n = (dZ.shape[1], dZ.shape[0]) if layout == COL_MAJOR else dZ.shape
+    _check(lib().s24_bias_grad(_ptr(dZ), layout, _ld(dZ, layout), p, n, _ptr(db), beta, _dt(dZ), _stream()),
+           "s24_bias_grad")
+    return db
 
 
 def spmm_fwd_swiglu(X, vals, meta, GU, H):

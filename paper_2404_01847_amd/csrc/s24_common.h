@@ -1,5 +1,5 @@
 // Shared host/device helpers of the s24 library (argument checks, launch
-// plumbing, bf16 conversions).  gfx950 only.
+// plumbing, bf16 / binary16 conversions, the activation arithmetic).  gfx950 only.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -12,7 +12,9 @@
     } while (0)
 
 static inline bool s24_aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-static inline bool s24_valid_dtype(int dt) { return dt == S24_F32 || dt == S24_BF16; }
+static inline bool s24_valid_dtype(int dt) { return dt == S24_F32 || dt == S24_BF16 || dt == S24_F16; }
+static inline bool s24_valid_gate(int g) { return g == S24_GATE_SILU || g == S24_GATE_GELU_ERF; }
+static inline bool s24_valid_layout(int l) { return l == S24_ROW_MAJOR || l == S24_COL_MAJOR; }
 static inline size_t s24_elem_size(int dt) { return dt == S24_F32 ? 4 : 2; }
 
 // Call after a kernel launch: turns a refused launch into S24_ERR_LAUNCH.
@@ -33,6 +35,40 @@ __device__ __forceinline__ uint32_t s24_pack_bf16x2(float lo, float hi)
     return s24_f32_to_bf16(lo) | (s24_f32_to_bf16(hi) << 16);
 }
 
+// Storage types of the kernels: uint16_t holds bf16 bits, s24_half is IEEE binary16, float is itself.
+// s24_num<T> converts between 16-bit storage and the fp32 the arithmetic runs in: one value from its 16 bits,
+// the low / high half of a dword, and back (round to nearest even; binary16 overflows to infinity).
+typedef _Float16 s24_half;
+template <typename T> struct s24_num;
+template <> struct s24_num<uint16_t> {
+    static __device__ __forceinline__ float widen(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+    static __device__ __forceinline__ float lo(uint32_t d) { return __uint_as_float(d << 16); }
+    static __device__ __forceinline__ float hi(uint32_t d) { return __uint_as_float(d & 0xFFFF0000u); }
+    static __device__ __forceinline__ uint32_t narrow(float f) { return s24_f32_to_bf16(f); }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) { return s24_pack_bf16x2(a, b); }
+};
+template <> struct s24_num<s24_half> {
+    static __device__ __forceinline__ float widen(uint32_t bits16)
+    {
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+    }
+    static __device__ __forceinline__ float lo(uint32_t d) { return widen(d & 0xFFFFu); }
+    static __device__ __forceinline__ float hi(uint32_t d) { return widen(d >> 16); }
+    // The conversion is pinned to the one instruction that rounds an fp32 value to binary16.  Written as a C++
+    // cast the compiler merges it with the multiplication before it into a mixed-precision instruction in some
+    // kernels and not in others, and the two do not always agree in the last bit; with the instruction fixed,
+    // every kernel that forms the same fp32 value stores the same bits.
+    static __device__ __forceinline__ uint32_t narrow(float f)
+    {
+        uint32_t h = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm("v_cvt_f16_f32 %0, %1" : "=v"(h) : "v"(f));
+#endif
+        return h & 0xFFFFu;
+    }
+    static __device__ __forceinline__ uint32_t pack2(float a, float b) { return narrow(a) | (narrow(b) << 16); }
+};
+
 // silu(g) * u in fp32, shared by the stand-alone SwiGLU kernel and the GEMM epilogue that applies it
 // 1 / (1 + 2^(-x log2 e)) with the hardware exponential and reciprocal (about 2 ulp in fp32, far inside what the
 // bf16 or fp32 outputs of the activation kernels need; saturates to 0 and 1 for large |x|)
@@ -49,4 +85,28 @@ __device__ __forceinline__ void s24_swiglu_grad(float dh, float g, float u, floa
     const float gs = g * s;
     dg = dh * u * (s + gs * (1.0f - s));
     du = dh * gs;
+}
+
+// GELU in its erf form and its slope Phi(x) + x phi(x), shared by the ungated activation kernels, the gated
+// stand-alone kernels and the GEMM epilogues
+__device__ __forceinline__ float s24_gelu(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float s24_gelu_slope(float x)
+{
+    return 0.5f * (1.0f + erff(x * 0.70710678118654752f)) + x * 0.39894228040143268f * expf(-0.5f * x * x);
+}
+
+// Gated activation h = act(g) * u with act chosen at compile time (GATE: 0 = SiLU, 1 = GELU), and its backward
+template <int GATE> __device__ __forceinline__ float s24_glu(float g, float u)
+{
+    if (GATE == S24_GATE_SILU) return s24_silu_mul(g, u);
+    return s24_gelu(g) * u;
+}
+template <int GATE> __device__ __forceinline__ void s24_glu_grad(float dh, float g, float u, float &dg, float &du)
+{
+    if (GATE == S24_GATE_SILU) {
+        s24_swiglu_grad(dh, g, u, dg, du);
+    } else {
+        dg = dh * u * s24_gelu_slope(g);
+        du = dh * s24_gelu(g);
+    }
 }

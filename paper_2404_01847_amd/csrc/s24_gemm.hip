@@ -22,6 +22,33 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(16))) _Float16 f16x16;
+
+// The 16-bit kernels move operands as raw bits (fragments are typed bf16x8 / bf16x16 whatever they hold); the
+// element type T (uint16_t = bf16 bits, s24_half = IEEE binary16) only selects the matrix instruction and the
+// conversions of the epilogues.
+template <typename T> struct Mma;
+template <> struct Mma<uint16_t> {
+    static __device__ __forceinline__ f32x16 dense(bf16x8 a, bf16x8 b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    template <int ABID> static __device__ __forceinline__ f32x16 sparse(bf16x8 a, bf16x16 b, f32x16 c, int idx)
+    {
+        return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a, b, c, idx, 0, ABID);
+    }
+};
+template <> struct Mma<s24_half> {
+    static __device__ __forceinline__ f32x16 dense(bf16x8 a, bf16x8 b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+    template <int ABID> static __device__ __forceinline__ f32x16 sparse(bf16x8 a, bf16x16 b, f32x16 c, int idx)
+    {
+        return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x16, b), c, idx, 0, ABID);
+    }
+};
 
 constexpr int BM = 128, BN = 128, BK = 64;  // workgroup tile; BK in elements of k
 constexpr int kThreads = 256;
@@ -85,10 +112,10 @@ __device__ __forceinline__ void sparse_a_load(SparseA &a, const uint16_t *Av, co
     }
 }
 
-template <bool ACCUM>
+template <typename T, bool ACCUM>
 __global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__restrict__ B, const uint16_t *__restrict__ Av,
                                                            const uint16_t *__restrict__ Am, uint16_t *__restrict__ Out,
-                                                           int N, int K, int M)
+                                                           int N, int K, int M, const uint16_t *__restrict__ bias)
 {
     __shared__ __attribute__((aligned(16))) unsigned char s_b[2][BN * 128];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -124,10 +151,8 @@ __global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__res
             const bf16x16 b1 = as_bf16x16(lds_read(buf, row, 2 + gb), lds_read(buf, row, 6 + gb));
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) {
-                acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(as_bf16x8(a_cur.v[mi][0]), b0, acc[mi][ni],
-                                                                        (int)a_cur.idx[mi], 0, 0);
-                acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(as_bf16x8(a_cur.v[mi][1]), b1, acc[mi][ni],
-                                                                        (int)a_cur.idx[mi], 0, 1);
+                acc[mi][ni] = Mma<T>::template sparse<0>(as_bf16x8(a_cur.v[mi][0]), b0, acc[mi][ni], (int)a_cur.idx[mi]);
+                acc[mi][ni] = Mma<T>::template sparse<1>(as_bf16x8(a_cur.v[mi][1]), b1, acc[mi][ni], (int)a_cur.idx[mi]);
             }
         }
         if (more) tile_store(breg, s_b[(kc + 1) & 1], tid);
@@ -150,14 +175,21 @@ __global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__res
                 float v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][4 * g + e];
+                if (bias != nullptr) {   // Z = X W^T + d (Sec. 5.2 step 2), added before the rounding
+                    const uint2 b = *reinterpret_cast<const uint2 *>(bias + m);
+                    v[0] += s24_num<T>::lo(b.x);
+                    v[1] += s24_num<T>::hi(b.x);
+                    v[2] += s24_num<T>::lo(b.y);
+                    v[3] += s24_num<T>::hi(b.y);
+                }
                 if (ACCUM) {
                     const uint2 old = *dst;
-                    v[0] += s24_bf16_to_f32(old.x & 0xFFFFu);
-                    v[1] += s24_bf16_to_f32(old.x >> 16);
-                    v[2] += s24_bf16_to_f32(old.y & 0xFFFFu);
-                    v[3] += s24_bf16_to_f32(old.y >> 16);
+                    v[0] += s24_num<T>::lo(old.x);
+                    v[1] += s24_num<T>::hi(old.x);
+                    v[2] += s24_num<T>::lo(old.y);
+                    v[3] += s24_num<T>::hi(old.y);
                 }
-                *dst = make_uint2(s24_pack_bf16x2(v[0], v[1]), s24_pack_bf16x2(v[2], v[3]));
+                *dst = make_uint2(s24_num<T>::pack2(v[0], v[1]), s24_num<T>::pack2(v[2], v[3]));
             }
         }
     }
@@ -223,6 +255,7 @@ __device__ __forceinline__ void clock_report(unsigned long long *probe, const Cl
 // units 2c and 2c+1 from one aligned slot, in swapped order on odd rows.
 // `estage` is EWAVE bytes of LDS private to the wave and no longer used for anything else.
 constexpr int EWAVE = 64 * 256;
+template <typename T>
 __device__ __forceinline__ void stage_tile(const f32x16 (&acc)[4][2], unsigned char *estage, int lane)
 {
 #pragma unroll
@@ -233,9 +266,28 @@ __device__ __forceinline__ void stage_tile(const f32x16 (&acc)[4][2], unsigned c
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int nl = 32 * ni + (lane & 31), u = 8 * mi + 2 * g4 + (lane >> 5);
                 *reinterpret_cast<uint2 *>(estage + nl * 256 + ((u ^ (nl & 31)) << 3)) =
-                    make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g4], acc[mi][ni][4 * g4 + 1]),
-                               s24_pack_bf16x2(acc[mi][ni][4 * g4 + 2], acc[mi][ni][4 * g4 + 3]));
+                    make_uint2(s24_num<T>::pack2(acc[mi][ni][4 * g4], acc[mi][ni][4 * g4 + 1]),
+                               s24_num<T>::pack2(acc[mi][ni][4 * g4 + 2], acc[mi][ni][4 * g4 + 3]));
             }
+}
+// Z = X W^T + d (Sec. 5.2 step 2): adds the bias of output feature m to the wave's 128 (m) x 64 (n) accumulator
+// tile before it is rounded.  `bias` points at the entry of the tile's first feature; features at or past `limit`
+// (edge tiles; never stored) read the last four valid entries instead.
+template <typename T>
+__device__ __forceinline__ void add_bias(f32x16 (&acc)[4][2], const uint16_t *__restrict__ bias, int limit, int lane)
+{
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const int m = min(32 * mi + 8 * g4 + 4 * (lane >> 5), limit - 4);
+            const uint2 b = *reinterpret_cast<const uint2 *>(bias + m);
+            const float b4[4] = {s24_num<T>::lo(b.x), s24_num<T>::hi(b.x), s24_num<T>::lo(b.y), s24_num<T>::hi(b.y)};
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[mi][ni][4 * g4 + e] += b4[e];
+        }
 }
 // 16-byte chunk c (eight bf16, columns 8c .. 8c+7) of row nl of a staged tile
 __device__ __forceinline__ uint4 staged_chunk(const unsigned char *estage, int nl, int c)
@@ -244,10 +296,11 @@ __device__ __forceinline__ uint4 staged_chunk(const unsigned char *estage, int n
     const uint4 v = *reinterpret_cast<const uint4 *>(estage + nl * 256 + ((((2 * c) ^ x) & ~1) << 3));
     return (x & 1) ? make_uint4(v.z, v.w, v.x, v.y) : v;
 }
+template <typename T>
 __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned char *estage, uint16_t *__restrict__ Out,
                                              int N, int M, int n_base, int m_base, int lane)
 {
-    stage_tile(acc, estage, lane);
+    stage_tile<T>(acc, estage, lane);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
     asm volatile("" ::: "memory");
@@ -263,18 +316,21 @@ __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned
 // SWIGLU (forward of a gated layer, Sec. 5.2): the compressed operand holds the gate rows [0, F) and the up rows
 // [F, 2F) of one stacked weight (M = 2F).  A workgroup tile then takes 128 gate features and the 128 up features
 // of the same indices, its epilogue pairs them and writes G and U (the halves of Out, row stride M) and
-// H = silu(G) * U (row stride F), all bf16, G and U rounded before H is formed as the stand-alone kernel sees them.
+// H = act(G) * U (row stride F, act = SiLU or GELU by GATE), G and U rounded to the storage type before H is formed,
+// as the stand-alone kernel sees them.  A bias d[2F] (Sec. 5.2 step 2), if given, is added before that rounding.
 // GATE_BWD (input gradient of the down projection of a gated layer): the tile of dH = dY (M.*W_down) is not
-// written; its bf16 rounding goes straight into the backward of the activation, dG = dH U s (1 + G (1 - s)),
-// dU = dH silu(G), with G and U read from, and dG and dU written to, the halves of [N][2M] buffers.
-template <bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false>
+// written; its rounding to the storage type goes straight into the backward of the activation, dG = dH U act'(G),
+// dU = dH act(G), with G and U read from, and dG and dU written to, the halves of [N][2M] buffers.
+// T is the storage type of every 16-bit buffer (bf16 bits or binary16).
+template <typename T, bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false, int GATE = S24_GATE_SILU>
 __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
                                                               uint16_t *__restrict__ Out, int N, int K, int M,
                                                               int tiles_m, int tiles_n, unsigned long long *probe,
                                                               uint16_t *__restrict__ H = nullptr, int F = 0,
-                                                              const uint16_t *__restrict__ GU = nullptr)
+                                                              const uint16_t *__restrict__ GU = nullptr,
+                                                              const uint16_t *__restrict__ bias = nullptr)
 {
     static_assert(!(ACCUM && (SWIGLU || GATE_BWD)) && !(SWIGLU && GATE_BWD), "the gated epilogues overwrite");
     const ClockStamp t_start = clock_now();
@@ -379,9 +435,9 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni) {
                     if (h == 0)
-                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 0);
+                        acc[mi][ni] = Mma<T>::template sparse<0>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
                     else
-                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 1);
+                        acc[mi][ni] = Mma<T>::template sparse<1>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
                 }
         }
         // Issue order: the twelve LDS reads of the first half, then its eight matrix instructions with the
@@ -422,19 +478,23 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
                     if (m >= M) continue;
                     uint2 *dst = reinterpret_cast<uint2 *>(Out + (int64_t)n * M + m);
                     const uint2 old = *dst;
-                    *dst = make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g4] + s24_bf16_to_f32(old.x & 0xFFFFu),
-                                                      acc[mi][ni][4 * g4 + 1] + s24_bf16_to_f32(old.x >> 16)),
-                                      s24_pack_bf16x2(acc[mi][ni][4 * g4 + 2] + s24_bf16_to_f32(old.y & 0xFFFFu),
-                                                      acc[mi][ni][4 * g4 + 3] + s24_bf16_to_f32(old.y >> 16)));
+                    *dst = make_uint2(s24_num<T>::pack2(acc[mi][ni][4 * g4] + s24_num<T>::lo(old.x),
+                                                        acc[mi][ni][4 * g4 + 1] + s24_num<T>::hi(old.x)),
+                                      s24_num<T>::pack2(acc[mi][ni][4 * g4 + 2] + s24_num<T>::lo(old.y),
+                                                        acc[mi][ni][4 * g4 + 3] + s24_num<T>::hi(old.y)));
                 }
         }
         return;
     }
     static_assert(3 * EWAVE <= STAGE, "three wave tiles must fit one ring stage");
     auto region = [&](int w) { return (w < 3 ? s0 : (w < 6 ? s1 : s2)) + (w % 3) * EWAVE; };
+    if (!GATE_BWD && bias != nullptr) {   // wave-uniform
+        if (SWIGLU) add_bias<T>(acc, bias + (wm ? F : 0) + m0, F - m0, lane);
+        else add_bias<T>(acc, bias + m0 + 128 * wm, M - (m0 + 128 * wm), lane);
+    }
     if constexpr (GATE_BWD) {
         unsigned char *est = region(wave);
-        stage_tile(acc, est, lane);
+        stage_tile<T>(acc, est, lane);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
         asm volatile("" ::: "memory");
@@ -458,11 +518,10 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float dg0, du0, dg1, du1;
-                s24_swiglu_grad(__uint_as_float(dw[k] << 16), __uint_as_float(gw[k] << 16), __uint_as_float(uw[k] << 16), dg0, du0);
-                s24_swiglu_grad(__uint_as_float(dw[k] & 0xFFFF0000u), __uint_as_float(gw[k] & 0xFFFF0000u),
-                                __uint_as_float(uw[k] & 0xFFFF0000u), dg1, du1);
-                dgw[k] = s24_pack_bf16x2(dg0, dg1);
-                duw[k] = s24_pack_bf16x2(du0, du1);
+                s24_glu_grad<GATE>(s24_num<T>::lo(dw[k]), s24_num<T>::lo(gw[k]), s24_num<T>::lo(uw[k]), dg0, du0);
+                s24_glu_grad<GATE>(s24_num<T>::hi(dw[k]), s24_num<T>::hi(gw[k]), s24_num<T>::hi(uw[k]), dg1, du1);
+                dgw[k] = s24_num<T>::pack2(dg0, dg1);
+                duw[k] = s24_num<T>::pack2(du0, du1);
             }
             if (n < N && m_base + 8 * c < M) {   // M is a multiple of 16: a chunk is all in or all out
                 const int64_t o = (int64_t)n * 2 * M + m;
@@ -471,11 +530,11 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
             }
         }
     } else if constexpr (!SWIGLU) {
-        staged_store(acc, region(wave), Out, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
+        staged_store<T>(acc, region(wave), Out, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
     } else {
         // waves (0, wn) and (1, wn) hold the gate and the up tile of the same 64 tokens x 128 features: both park
         // their bf16 tiles, then each takes 32 of the 64 token rows and writes G, U and H in 16-byte pieces
-        stage_tile(acc, region(wave), lane);
+        stage_tile<T>(acc, region(wave), lane);
         wait_and_barrier<0>();
         const unsigned char *sg = region(2 * wn), *su = region(2 * wn + 1);
 #pragma unroll 2
@@ -488,8 +547,8 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
             uint32_t hw[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                hw[k] = s24_pack_bf16x2(s24_silu_mul(__uint_as_float(gw[k] << 16), __uint_as_float(uw[k] << 16)),
-                                        s24_silu_mul(__uint_as_float(gw[k] & 0xFFFF0000u), __uint_as_float(uw[k] & 0xFFFF0000u)));
+                hw[k] = s24_num<T>::pack2(s24_glu<GATE>(s24_num<T>::lo(gw[k]), s24_num<T>::lo(uw[k])),
+                                          s24_glu<GATE>(s24_num<T>::hi(gw[k]), s24_num<T>::hi(uw[k])));
             *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + f) = g;
             *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + F + f) = u;
             *reinterpret_cast<uint4 *>(H + (int64_t)n * F + f) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
@@ -502,6 +561,7 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
 // Both operands in LDS as k-contiguous swizzled tiles.  MFMA step i of a lane
 // with k-group g = lane/32 uses chunk 4*g + i of its row, i.e. k in
 // [32*g + 8*i, 32*g + 8*i + 8) of the 64-wide chunk, for A and B alike.
+template <typename T>
 __device__ __forceinline__ void dense_chunk(f32x16 (&acc)[2][2], const unsigned char *sa, const unsigned char *sb, int wm,
                                             int wn, int lane)
 {
@@ -517,11 +577,12 @@ __device__ __forceinline__ void dense_chunk(f32x16 (&acc)[2][2], const unsigned 
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+                acc[mi][ni] = Mma<T>::dense(a[mi], b[ni], acc[mi][ni]);
     }
 }
 
 // Y[n][m] = sum_k X[n][k] W[m][k]  (n tokens, m out-features)
+template <typename T>
 __global__ __launch_bounds__(kThreads) void dense_nt_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W,
                                                             uint16_t *__restrict__ Y, int N, int K, int M)
 {
@@ -548,7 +609,7 @@ __global__ __launch_bounds__(kThreads) void dense_nt_kernel(const uint16_t *__re
             tile_load(ra, W, K, m0, M, (kc + 1) * BK, tid);
             tile_load(rb, X, K, n0, N, (kc + 1) * BK, tid);
         }
-        dense_chunk(acc, s_a[kc & 1], s_b[kc & 1], wm, wn, lane);
+        dense_chunk<T>(acc, s_a[kc & 1], s_b[kc & 1], wm, wn, lane);
         if (more) {
             tile_store(ra, s_a[(kc + 1) & 1], tid);
             tile_store(rb, s_b[(kc + 1) & 1], tid);
@@ -566,8 +627,8 @@ __global__ __launch_bounds__(kThreads) void dense_nt_kernel(const uint16_t *__re
                 const int m = m0 + 64 * wm + 32 * mi + 8 * g + 4 * (lane >> 5);
                 if (m >= M) continue;
                 *reinterpret_cast<uint2 *>(Y + (int64_t)n * M + m) =
-                    make_uint2(s24_pack_bf16x2(acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1]),
-                               s24_pack_bf16x2(acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]));
+                    make_uint2(s24_num<T>::pack2(acc[mi][ni][4 * g], acc[mi][ni][4 * g + 1]),
+                               s24_num<T>::pack2(acc[mi][ni][4 * g + 2], acc[mi][ni][4 * g + 3]));
             }
     }
 }
@@ -584,6 +645,7 @@ using big::glb_ptr;
 using big::lds_ptr;
 using big::wait_vm_lgkm0;
 
+template <typename T>
 __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *__restrict__ X,
                                                                const uint16_t *__restrict__ W, uint16_t *__restrict__ Y,
                                                                int N, int K, int M, int tiles_m, int tiles_n, unsigned long long *probe)
@@ -645,7 +707,7 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
             for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = Mma<T>::dense(a[mi], b[ni], acc[mi][ni]);
         }
         // Issue order: the six LDS reads of the first 16-wide step, then one matrix instruction at a time with
         // the other steps' eighteen reads after the first eighteen and one copy of chunk kc+1 after every fourth.
@@ -666,7 +728,7 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
     if (kc < nk) chunk(s0, s1, kc);
     big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
     big::clock_report(probe, t_start);
-    big::staged_store(acc, (wave < 4 ? s0 : s1) + (wave & 3) * big::EWAVE, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
+    big::staged_store<T>(acc, (wave < 4 ? s0 : s1) + (wave & 3) * big::EWAVE, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
 }
 }  // namespace bignt
 
@@ -720,7 +782,7 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
 // DECAY: the masked decay term is added in the epilogue: dW[m][n] += lambda * Wt[m][n] where bit
 // 4*(m%4) + n%4 of mask[m/4][n/4] is clear, with the same single fused multiply-add the stand-alone
 // decay kernel applies to the stored gradient, so both routes give the same bits.
-template <int WT, int BT_, bool ACCUM, bool DECAY>
+template <typename ET, int WT, int BT_, bool ACCUM, bool DECAY>
 __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *__restrict__ dY,
                                                                const uint16_t *__restrict__ X, float *__restrict__ dW,
                                                                int T, int M, int N, int tiles_m, int tiles_n,
@@ -807,7 +869,7 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
         for (int mi = 0; mi < WT; ++mi)
 #pragma unroll
             for (int ni = 0; ni < WT; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+                acc[mi][ni] = Mma<ET>::dense(a[mi], b[ni], acc[mi][ni]);
     };
     // Issue order of one 16-token step: a matrix instruction, then 4/WT LDS reads of the next step's fragments
     // (4*WT reads against WT*WT matrix instructions), and after every other matrix instruction one copy.
@@ -917,10 +979,10 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
                 float4 o = v[b];
                 if (ACCUM) { o.x = old[b].x + o.x; o.y = old[b].y + o.y; o.z = old[b].z + o.z; o.w = old[b].w + o.w; }
                 if (DECAY) {
-                    if (!(keep[b] & 1u)) o.x = fmaf(lambda, s24_bf16_to_f32(wv[b].x & 0xFFFFu), o.x);
-                    if (!(keep[b] & 2u)) o.y = fmaf(lambda, s24_bf16_to_f32(wv[b].x >> 16), o.y);
-                    if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_bf16_to_f32(wv[b].y & 0xFFFFu), o.z);
-                    if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_bf16_to_f32(wv[b].y >> 16), o.w);
+                    if (!(keep[b] & 1u)) o.x = fmaf(lambda, s24_num<ET>::lo(wv[b].x), o.x);
+                    if (!(keep[b] & 2u)) o.y = fmaf(lambda, s24_num<ET>::hi(wv[b].x), o.y);
+                    if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_num<ET>::lo(wv[b].y), o.z);
+                    if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_num<ET>::hi(wv[b].y), o.w);
                 }
                 if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * N + n) = o;
             }
@@ -947,7 +1009,7 @@ using big::a_slot;
 using big::glb_ptr;
 using big::lds_ptr;
 
-template <bool ACCUM, bool DECAY>
+template <typename ET, bool ACCUM, bool DECAY>
 __global__ __launch_bounds__(THREADS) void spmm_tn_big_kernel(const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
                                                               const uint16_t *__restrict__ X, float *__restrict__ dW,
@@ -1045,9 +1107,9 @@ __global__ __launch_bounds__(THREADS) void spmm_tn_big_kernel(const uint16_t *__
 #pragma unroll
                 for (int ni = 0; ni < 2; ++ni) {
                     if (h == 0)
-                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 0);
+                        acc[mi][ni] = Mma<ET>::template sparse<0>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
                     else
-                        acc[mi][ni] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[mi], b[ni], acc[mi][ni], (int)ix[mi], 0, 1);
+                        acc[mi][ni] = Mma<ET>::template sparse<1>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
                 }
         }
         // issue order: the sixteen LDS reads of the first half, then its eight matrix instructions with the
@@ -1118,10 +1180,10 @@ __global__ __launch_bounds__(THREADS) void spmm_tn_big_kernel(const uint16_t *__
                 float4 o = v[b];
                 if (ACCUM) { o.x = old[b].x + o.x; o.y = old[b].y + o.y; o.z = old[b].z + o.z; o.w = old[b].w + o.w; }
                 if (DECAY) {
-                    if (!(keep[b] & 1u)) o.x = fmaf(lambda, s24_bf16_to_f32(wv[b].x & 0xFFFFu), o.x);
-                    if (!(keep[b] & 2u)) o.y = fmaf(lambda, s24_bf16_to_f32(wv[b].x >> 16), o.y);
-                    if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_bf16_to_f32(wv[b].y & 0xFFFFu), o.z);
-                    if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_bf16_to_f32(wv[b].y >> 16), o.w);
+                    if (!(keep[b] & 1u)) o.x = fmaf(lambda, s24_num<ET>::lo(wv[b].x), o.x);
+                    if (!(keep[b] & 2u)) o.y = fmaf(lambda, s24_num<ET>::hi(wv[b].x), o.y);
+                    if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_num<ET>::lo(wv[b].y), o.z);
+                    if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_num<ET>::hi(wv[b].y), o.w);
                 }
                 if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * N + n) = o;
             }
@@ -1157,7 +1219,7 @@ __global__ __launch_bounds__(kThreads) void spmm_tn_f32_kernel(const float *__re
 template <bool ACCUM>
 __global__ __launch_bounds__(kThreads) void spmm_nt_f32_kernel(const float *__restrict__ B, const float *__restrict__ Av,
                                                                const uint16_t *__restrict__ Am, float *__restrict__ Out,
-                                                               int64_t N, int64_t K, int64_t M)
+                                                               int64_t N, int64_t K, int64_t M, const float *__restrict__ bias)
 {
     const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (idx >= N * M) return;
@@ -1169,6 +1231,7 @@ __global__ __launch_bounds__(kThreads) void spmm_nt_f32_kernel(const float *__re
         acc = fmaf(Av[cr * 32 + 2 * (g & 15)], B[n * K + 4 * g + (nib & 3u)], acc);
         acc = fmaf(Av[cr * 32 + 2 * (g & 15) + 1], B[n * K + 4 * g + (nib >> 2)], acc);
     }
+    if (bias != nullptr) acc += bias[m];
     Out[idx] = ACCUM ? Out[idx] + acc : acc;
 }
 
@@ -1217,37 +1280,57 @@ int check_gemm(const void *a, const void *b, const void *c, int64_t p, int64_t q
     return S24_OK;
 }
 
+// Runs `...` with T bound to the storage type of a 16-bit dtype.
+#define S24_WITH_16BIT_TYPE(dt, ...)      \
+    do {                                  \
+        if ((dt) == S24_BF16) {           \
+            using T = uint16_t;           \
+            __VA_ARGS__;                  \
+        } else {                          \
+            using T = s24_half;           \
+            __VA_ARGS__;                  \
+        }                                 \
+    } while (0)
+
+inline bool fills_chip_256(int64_t m, int64_t n) { return (int64_t)ceil_div(m, 256) * ceil_div(n, 256) >= 192; }
+
+// Out[N][M] = beta * Out + B[N][K] . A^T (+ bias[M], only with beta = 0)
 int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, int64_t N, int64_t K, int64_t M, float beta,
-                int dt, hipStream_t st)
+                int dt, hipStream_t st, const void *bias = nullptr)
 {
     if (N == 0 || M == 0) return S24_OK;
     const bool accum = beta != 0.0f;
-    if (dt == S24_BF16 && (int64_t)ceil_div(M, big::BM) * ceil_div(N, big::BN) >= 192) {
+    if (dt == S24_F32) {
+        const dim3 grid(ceil_div(N * M, kThreads)), block(kThreads);
+        auto *b = static_cast<const float *>(B), *av = static_cast<const float *>(Av);
+        auto *o = static_cast<float *>(Out);
+        auto *d = static_cast<const float *>(bias);
+        if (accum) hipLaunchKernelGGL(spmm_nt_f32_kernel<true>, grid, block, 0, st, b, av, Am, o, N, K, M, d);
+        else hipLaunchKernelGGL(spmm_nt_f32_kernel<false>, grid, block, 0, st, b, av, Am, o, N, K, M, d);
+        return s24_launch_status();
+    }
+    auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av), *d = static_cast<const uint16_t *>(bias);
+    auto *o = static_cast<uint16_t *>(Out);
+    if (fills_chip_256(M, N)) {
         // enough 256x256 tiles to fill the chip: large-tile kernel
         const int tiles_m = (int)ceil_div(M, big::BM), tiles_n = (int)ceil_div(N, big::BN);
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
         const dim3 grid(per_xcd * 8), block(big::THREADS);
-        auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av);
-        auto *o = static_cast<uint16_t *>(Out);
-        if (accum)
-            hipLaunchKernelGGL(big::spmm_nt_big_kernel<true>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
-                               tiles_m, tiles_n, g_clock_probe);
-        else
-            hipLaunchKernelGGL(big::spmm_nt_big_kernel<false>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
-                               tiles_m, tiles_n, g_clock_probe);
-    } else if (dt == S24_BF16) {
+        S24_WITH_16BIT_TYPE(dt, {
+            if (accum)
+                hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, true>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
+                                   tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, d);
+            else
+                hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
+                                   tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, d);
+        });
+    } else {
         const dim3 grid(ceil_div(M, BM), ceil_div(N, BN)), block(kThreads);
         S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
-        auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av);
-        auto *o = static_cast<uint16_t *>(Out);
-        if (accum) hipLaunchKernelGGL(spmm_nt_kernel<true>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M);
-        else hipLaunchKernelGGL(spmm_nt_kernel<false>, grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M);
-    } else {
-        const dim3 grid(ceil_div(N * M, kThreads)), block(kThreads);
-        auto *b = static_cast<const float *>(B), *av = static_cast<const float *>(Av);
-        auto *o = static_cast<float *>(Out);
-        if (accum) hipLaunchKernelGGL(spmm_nt_f32_kernel<true>, grid, block, 0, st, b, av, Am, o, N, K, M);
-        else hipLaunchKernelGGL(spmm_nt_f32_kernel<false>, grid, block, 0, st, b, av, Am, o, N, K, M);
+        S24_WITH_16BIT_TYPE(dt, {
+            if (accum) hipLaunchKernelGGL((spmm_nt_kernel<T, true>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M, d);
+            else hipLaunchKernelGGL((spmm_nt_kernel<T, false>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M, d);
+        });
     }
     return s24_launch_status();
 }
@@ -1257,12 +1340,18 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
 extern "C" int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y, int64_t p, int64_t q, int64_t r,
                             s24_dtype dt, void *stream)
 {
+    return s24_spmm_fwd_bias(X, vals, meta, nullptr, Y, p, q, r, dt, stream);
+}
+
+extern "C" int s24_spmm_fwd_bias(const void *X, const void *vals, const uint16_t *meta, const void *bias, void *Y, int64_t p,
+                                 int64_t q, int64_t r, s24_dtype dt, void *stream)
+{
     S24_REQUIRE(q % 64 == 0 && r % 16 == 0 && q > 0, S24_ERR_SHAPE);
     const int rc = check_gemm(X, vals, Y, p, q, r, dt, p * r);
     if (rc != S24_OK || p * r == 0) return rc;
     S24_REQUIRE(meta != nullptr, S24_ERR_NULL);
-    S24_REQUIRE(s24_aligned(meta, 4), S24_ERR_ALIGN);
-    return launch_spmm(X, vals, meta, Y, p, q, r, 0.0f, dt, static_cast<hipStream_t>(stream));
+    S24_REQUIRE(s24_aligned(meta, 4) && s24_aligned(bias, 8), S24_ERR_ALIGN);
+    return launch_spmm(X, vals, meta, Y, p, q, r, 0.0f, dt, static_cast<hipStream_t>(stream), bias);
 }
 
 extern "C" int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, void *dX, int64_t p, int64_t q,
@@ -1277,47 +1366,74 @@ extern "C" int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t
     return launch_spmm(dY, valsT, metaT, dX, p, r, q, beta, dt, static_cast<hipStream_t>(stream));
 }
 
-extern "C" int s24_spmm_fwd_swiglu(const void *X, const void *vals, const uint16_t *meta, void *GU, void *H, int64_t p,
-                                   int64_t q, int64_t f, s24_dtype dt, void *stream)
+extern "C" int s24_spmm_fwd_glu(const void *X, const void *vals, const uint16_t *meta, const void *bias, void *GU, void *H,
+                                int64_t p, int64_t q, int64_t f, s24_gate gate, s24_dtype dt, void *stream)
 {
+    S24_REQUIRE(s24_valid_gate(gate), S24_ERR_DTYPE);
     S24_REQUIRE(q % 64 == 0 && f % 16 == 0 && q > 0, S24_ERR_SHAPE);
     const int rc = check_gemm(X, vals, GU, p, q, 2 * f, dt, p * f);
     if (rc != S24_OK || p * f == 0) return rc;
     S24_REQUIRE(meta != nullptr && H != nullptr, S24_ERR_NULL);
-    S24_REQUIRE(s24_aligned(meta, 4) && s24_aligned(H, 16), S24_ERR_ALIGN);
+    S24_REQUIRE(s24_aligned(meta, 4) && s24_aligned(H, 16) && s24_aligned(bias, 8), S24_ERR_ALIGN);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int tiles_m = (int)ceil_div(f, 128), tiles_n = (int)ceil_div(p, big::BN);
-    if (dt == S24_BF16 && (int64_t)tiles_m * tiles_n >= 192) {
+    if (dt != S24_F32 && (int64_t)tiles_m * tiles_n >= 192) {
         const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
-        hipLaunchKernelGGL((big::spmm_nt_big_kernel<false, true>), grid, block, 0, st, static_cast<const uint16_t *>(X),
-                           static_cast<const uint16_t *>(vals), meta, static_cast<uint16_t *>(GU), (int)p, (int)q,
-                           (int)(2 * f), tiles_m, tiles_n, g_clock_probe, static_cast<uint16_t *>(H), (int)f);
+        auto *x = static_cast<const uint16_t *>(X), *av = static_cast<const uint16_t *>(vals), *d = static_cast<const uint16_t *>(bias);
+        auto *gu = static_cast<uint16_t *>(GU), *h = static_cast<uint16_t *>(H);
+#define S24_LAUNCH_FWD_GLU(G)                                                                                              \
+    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, true, false, G>), grid, block, 0, st, x, av, meta, gu, (int)p, \
+                       (int)q, (int)(2 * f), tiles_m, tiles_n, g_clock_probe, h, (int)f, nullptr, d)
+        S24_WITH_16BIT_TYPE(dt, {
+            if (gate == S24_GATE_SILU) S24_LAUNCH_FWD_GLU(S24_GATE_SILU);
+            else S24_LAUNCH_FWD_GLU(S24_GATE_GELU_ERF);
+        });
+#undef S24_LAUNCH_FWD_GLU
         return s24_launch_status();
     }
     // shapes the fused epilogue does not cover: the GEMM into [p][2f], then the stand-alone activation on its halves
-    const int rc2 = launch_spmm(X, vals, meta, GU, p, q, 2 * f, 0.0f, dt, st);
+    const int rc2 = launch_spmm(X, vals, meta, GU, p, q, 2 * f, 0.0f, dt, st, bias);
     if (rc2 != S24_OK) return rc2;
-    const size_t es = s24_elem_size(dt);
-    return s24_swiglu_fwd(GU, static_cast<const char *>(GU) + f * es, H, p, f, 2 * f, dt, st);
+    return s24_glu_fwd(GU, S24_ROW_MAJOR, 2 * f, H, S24_ROW_MAJOR, f, p, f, gate, dt, st);
 }
 
-extern "C" int s24_spmm_bwd_dx_swiglu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
-                                      int64_t p, int64_t f, int64_t r, s24_dtype dt, void *stream)
+extern "C" int s24_spmm_fwd_swiglu(const void *X, const void *vals, const uint16_t *meta, void *GU, void *H, int64_t p,
+                                   int64_t q, int64_t f, s24_dtype dt, void *stream)
 {
+    return s24_spmm_fwd_glu(X, vals, meta, nullptr, GU, H, p, q, f, S24_GATE_SILU, dt, stream);
+}
+
+extern "C" int s24_spmm_bwd_dx_glu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
+                                   int64_t p, int64_t f, int64_t r, s24_gate gate, s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(s24_valid_gate(gate), S24_ERR_DTYPE);
     S24_REQUIRE(r % 64 == 0 && f % 16 == 0 && r > 0, S24_ERR_SHAPE);
     const int rc = check_gemm(dY, valsT, dGU, p, f, r, dt, p * f);
     if (rc != S24_OK || p * f == 0) return rc;
     S24_REQUIRE(metaT != nullptr && GU != nullptr, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(metaT, 4) && s24_aligned(GU, 16), S24_ERR_ALIGN);
     const int tiles_m = (int)ceil_div(f, big::BM), tiles_n = (int)ceil_div(p, big::BN);
-    // only the large-tile bf16 kernel carries this epilogue; other shapes take s24_spmm_bwd_dx + s24_swiglu_bwd
-    S24_REQUIRE(dt == S24_BF16 && (int64_t)tiles_m * tiles_n >= 192, S24_ERR_UNSUPPORTED);
+    // only the large-tile 16-bit kernel carries this epilogue; other shapes take s24_spmm_bwd_dx + s24_glu_bwd
+    S24_REQUIRE(dt != S24_F32 && (int64_t)tiles_m * tiles_n >= 192, S24_ERR_UNSUPPORTED);
     const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
-    hipLaunchKernelGGL((big::spmm_nt_big_kernel<false, false, true>), grid, block, 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint16_t *>(dY), static_cast<const uint16_t *>(valsT), metaT,
-                       static_cast<uint16_t *>(dGU), (int)p, (int)r, (int)f, tiles_m, tiles_n, g_clock_probe, nullptr, 0,
-                       static_cast<const uint16_t *>(GU));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto *dy = static_cast<const uint16_t *>(dY), *av = static_cast<const uint16_t *>(valsT), *gu = static_cast<const uint16_t *>(GU);
+    auto *o = static_cast<uint16_t *>(dGU);
+#define S24_LAUNCH_BWD_GLU(G)                                                                                              \
+    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, true, G>), grid, block, 0, st, dy, av, metaT, o, (int)p, \
+                       (int)r, (int)f, tiles_m, tiles_n, g_clock_probe, nullptr, 0, gu, nullptr)
+    S24_WITH_16BIT_TYPE(dt, {
+        if (gate == S24_GATE_SILU) S24_LAUNCH_BWD_GLU(S24_GATE_SILU);
+        else S24_LAUNCH_BWD_GLU(S24_GATE_GELU_ERF);
+    });
+#undef S24_LAUNCH_BWD_GLU
     return s24_launch_status();
+}
+
+extern "C" int s24_spmm_bwd_dx_swiglu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
+                                      int64_t p, int64_t f, int64_t r, s24_dtype dt, void *stream)
+{
+    return s24_spmm_bwd_dx_glu(dY, valsT, metaT, GU, dGU, p, f, r, S24_GATE_SILU, dt, stream);
 }
 
 extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r, s24_dtype dt,
@@ -1327,19 +1443,22 @@ extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, 
     const int rc = check_gemm(X, W, Y, p, q, r, dt, p * r);
     if (rc != S24_OK || p * r == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt == S24_BF16 && (int64_t)ceil_div(r, bignt::BM) * ceil_div(p, bignt::BN) >= 192) {
-        const int tiles_m = (int)ceil_div(r, bignt::BM), tiles_n = (int)ceil_div(p, bignt::BN);
-        hipLaunchKernelGGL(bignt::dense_nt_big_kernel, dim3(((tiles_m * tiles_n + 7) / 8) * 8), dim3(bignt::THREADS), 0, st,
-                           static_cast<const uint16_t *>(X), static_cast<const uint16_t *>(W), static_cast<uint16_t *>(Y),
-                           (int)p, (int)q, (int)r, tiles_m, tiles_n, g_clock_probe);
-    } else if (dt == S24_BF16) {
-        const dim3 grid(ceil_div(r, BM), ceil_div(p, BN)), block(kThreads);
-        S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
-        hipLaunchKernelGGL(dense_nt_kernel, grid, block, 0, st, static_cast<const uint16_t *>(X),
-                           static_cast<const uint16_t *>(W), static_cast<uint16_t *>(Y), (int)p, (int)q, (int)r);
-    } else {
+    if (dt == S24_F32) {
         hipLaunchKernelGGL(dense_nt_f32_kernel, dim3(ceil_div(p * r, kThreads)), dim3(kThreads), 0, st,
                            static_cast<const float *>(X), static_cast<const float *>(W), static_cast<float *>(Y), p, q, r);
+        return s24_launch_status();
+    }
+    auto *x = static_cast<const uint16_t *>(X), *w = static_cast<const uint16_t *>(W);
+    auto *y = static_cast<uint16_t *>(Y);
+    if (fills_chip_256(r, p)) {
+        const int tiles_m = (int)ceil_div(r, bignt::BM), tiles_n = (int)ceil_div(p, bignt::BN);
+        S24_WITH_16BIT_TYPE(dt, hipLaunchKernelGGL(bignt::dense_nt_big_kernel<T>, dim3(((tiles_m * tiles_n + 7) / 8) * 8),
+                                                   dim3(bignt::THREADS), 0, st, x, w, y, (int)p, (int)q, (int)r, tiles_m,
+                                                   tiles_n, g_clock_probe));
+    } else {
+        const dim3 grid(ceil_div(r, BM), ceil_div(p, BN)), block(kThreads);
+        S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
+        S24_WITH_16BIT_TYPE(dt, hipLaunchKernelGGL(dense_nt_kernel<T>, grid, block, 0, st, x, w, y, (int)p, (int)q, (int)r));
     }
     return s24_launch_status();
 }
@@ -1353,17 +1472,17 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
     bool decay_pending = W != nullptr;
     if (p == 0) {  // empty contraction: dW = beta * dW (the GEMM kernels need at least one token)
         if (!accum) hipLaunchKernelGGL(fill_zero_kernel, dim3(ceil_div(q * r, kThreads)), dim3(kThreads), 0, st, dW, q * r);
-    } else if (dt == S24_BF16) {
+    } else if (dt != S24_F32) {
         // 256 x 256 tiles when they fill the chip, 128 x 128 tiles otherwise
-        const bool large = (int64_t)ceil_div(r, 256) * ceil_div(q, 256) >= 192;
+        const bool large = fills_chip_256(r, q);
         const int tile = large ? 256 : 128;
         const int tiles_m = (int)ceil_div(r, tile), tiles_n = (int)ceil_div(q, tile);
         const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(dmatn::THREADS);
         auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
-        const bool fuse = decay_pending && wdt == S24_BF16;
+        const bool fuse = decay_pending && wdt == dt;   // the epilogue reads W in the operands' own 16-bit type
         auto *w = static_cast<const uint16_t *>(fuse ? W : nullptr);
 #define S24_LAUNCH_DW(WT, BT, ACC, DEC)                                                                                \
-    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<WT, BT, ACC, DEC>), grid, block, 0, st, a, b, dW, (int)p, (int)r,     \
+    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<T, WT, BT, ACC, DEC>), grid, block, 0, st, a, b, dW, (int)p, (int)r,  \
                        (int)q, tiles_m, tiles_n, g_clock_probe, w, mask, lambda)
 #define S24_LAUNCH_DW_TILE(WT, BT)                              \
     do {                                                        \
@@ -1372,9 +1491,11 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
         else if (fuse) S24_LAUNCH_DW(WT, BT, false, true);      \
         else S24_LAUNCH_DW(WT, BT, false, false);               \
     } while (0)
-        if (large) S24_LAUNCH_DW_TILE(4, 32);
-        else if (tiles_m * tiles_n > 256) S24_LAUNCH_DW_TILE(2, 32);
-        else S24_LAUNCH_DW_TILE(2, 64);
+        S24_WITH_16BIT_TYPE(dt, {
+            if (large) S24_LAUNCH_DW_TILE(4, 32);
+            else if (tiles_m * tiles_n > 256) S24_LAUNCH_DW_TILE(2, 32);
+            else S24_LAUNCH_DW_TILE(2, 64);
+        });
 #undef S24_LAUNCH_DW_TILE
 #undef S24_LAUNCH_DW
         if (fuse) decay_pending = false;
@@ -1436,19 +1557,21 @@ extern "C" int s24_spmm_dw(const void *vals, const uint16_t *meta, const void *X
     } else {
         S24_REQUIRE(meta != nullptr, S24_ERR_NULL);
         S24_REQUIRE(s24_aligned(meta, 4), S24_ERR_ALIGN);
-        if (dt == S24_BF16) {
+        if (dt != S24_F32) {
             const int tiles_m = (int)ceil_div(r, sptn::BM), tiles_n = (int)ceil_div(q, sptn::BN);
             const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(sptn::THREADS);
             auto *av = static_cast<const uint16_t *>(vals), *x = static_cast<const uint16_t *>(X);
-            const bool fuse = decay_pending && wdt == S24_BF16;
+            const bool fuse = decay_pending && wdt == dt;
             auto *w = static_cast<const uint16_t *>(fuse ? W : nullptr);
-#define S24_LAUNCH_SPDW(ACC, DEC)                                                                                        \
-    hipLaunchKernelGGL((sptn::spmm_tn_big_kernel<ACC, DEC>), grid, block, 0, st, av, meta, x, dW, (int)p, (int)r, (int)q, \
+#define S24_LAUNCH_SPDW(ACC, DEC)                                                                                           \
+    hipLaunchKernelGGL((sptn::spmm_tn_big_kernel<T, ACC, DEC>), grid, block, 0, st, av, meta, x, dW, (int)p, (int)r, (int)q, \
                        tiles_m, tiles_n, g_clock_probe, w, mask, lambda)
-            if (accum && fuse) S24_LAUNCH_SPDW(true, true);
-            else if (accum) S24_LAUNCH_SPDW(true, false);
-            else if (fuse) S24_LAUNCH_SPDW(false, true);
-            else S24_LAUNCH_SPDW(false, false);
+            S24_WITH_16BIT_TYPE(dt, {
+                if (accum && fuse) S24_LAUNCH_SPDW(true, true);
+                else if (accum) S24_LAUNCH_SPDW(true, false);
+                else if (fuse) S24_LAUNCH_SPDW(false, true);
+                else S24_LAUNCH_SPDW(false, false);
+            });
 #undef S24_LAUNCH_SPDW
             if (fuse) decay_pending = false;
         } else {

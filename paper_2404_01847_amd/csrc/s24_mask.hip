@@ -358,6 +358,23 @@ template <> struct RowOps<uint16_t> {  // bf16
     static __device__ __forceinline__ Pair pair(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
 };
 
+// IEEE binary16: the same 16-bit moves as bf16; a magnitude widens to fp32 exactly (binary16 subnormals are fp32
+// normals).  An element with fp32 exponent e is a multiple of 2^(e-10), so the fast path's window is 26 binades,
+// and eight of them sum exactly in fp64 over 39 binades, which is all binary16 has: no block needs the slow path.
+template <> struct RowOps<s24_half> {
+    using Row = uint2;
+    using Pair = uint32_t;
+    static constexpr int kWindow = 26, kWide = 39;
+    static __device__ __forceinline__ Row load(const s24_half *p) { return *reinterpret_cast<const uint2 *>(p); }
+    static __device__ __forceinline__ uint32_t bits(const Row &r, int j) { return RowOps<uint16_t>::bits(r, j); }
+    static __device__ __forceinline__ uint32_t mag(const Row &r, int j)  // compile-time j
+    {
+        const uint32_t d = (j < 2) ? r.x : r.y;
+        return __float_as_uint(s24_num<s24_half>::widen(((j & 1) ? (d >> 16) : d) & 0x7FFFu));
+    }
+    static __device__ __forceinline__ Pair pair(uint32_t lo, uint32_t hi) { return lo | (hi << 16); }
+};
+
 template <> struct RowOps<float> {
     using Row = uint4;
     using Pair = uint2;
@@ -658,10 +675,10 @@ __global__ __launch_bounds__(256) void l1_gap_kernel(const T *__restrict__ W, in
         const T *row = W + (int64_t)(4 * bi + i) * ldw + 4 * bj;
         if constexpr (sizeof(T) == 2) {
             const uint2 v = *reinterpret_cast<const uint2 *>(row);
-            a[4 * i] = fabs((double)s24_bf16_to_f32(v.x & 0xFFFFu));
-            a[4 * i + 1] = fabs((double)s24_bf16_to_f32(v.x >> 16));
-            a[4 * i + 2] = fabs((double)s24_bf16_to_f32(v.y & 0xFFFFu));
-            a[4 * i + 3] = fabs((double)s24_bf16_to_f32(v.y >> 16));
+            a[4 * i] = fabs((double)s24_num<T>::lo(v.x));
+            a[4 * i + 1] = fabs((double)s24_num<T>::hi(v.x));
+            a[4 * i + 2] = fabs((double)s24_num<T>::lo(v.y));
+            a[4 * i + 3] = fabs((double)s24_num<T>::hi(v.y));
         } else {
             const float4 v = *reinterpret_cast<const float4 *>(row);
             a[4 * i] = fabs((double)v.x);
@@ -714,6 +731,8 @@ extern "C" int s24_transposable_mask(const void *W, s24_dtype dt, int64_t r, int
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dt == S24_BF16)
         return launch<uint16_t>(W, r, q, ldw, nullptr, mask, index, nullptr, nullptr, nullptr, nullptr, false, st);
+    if (dt == S24_F16)
+        return launch<s24_half>(W, r, q, ldw, nullptr, mask, index, nullptr, nullptr, nullptr, nullptr, false, st);
     return launch<float>(W, r, q, ldw, nullptr, mask, index, nullptr, nullptr, nullptr, nullptr, false, st);
 }
 
@@ -728,6 +747,8 @@ extern "C" int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dt == S24_BF16)
         return launch<uint16_t>(W, r, q, ldw, mask, mask_out, nullptr, vals, meta, valsT, metaT, true, st);
+    if (dt == S24_F16)
+        return launch<s24_half>(W, r, q, ldw, mask, mask_out, nullptr, vals, meta, valsT, metaT, true, st);
     return launch<float>(W, r, q, ldw, mask, mask_out, nullptr, vals, meta, valsT, metaT, true, st);
 }
 
@@ -765,6 +786,8 @@ extern "C" int s24_l1_norm_gap(const void *W, s24_dtype dt, int64_t r, int64_t q
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
     if (dt == S24_BF16)
         hipLaunchKernelGGL(l1_gap_kernel<uint16_t>, grid, block, 0, st, static_cast<const uint16_t *>(W), ldw, br, bq, gap);
+    else if (dt == S24_F16)
+        hipLaunchKernelGGL(l1_gap_kernel<s24_half>, grid, block, 0, st, static_cast<const s24_half *>(W), ldw, br, bq, gap);
     else
         hipLaunchKernelGGL(l1_gap_kernel<float>, grid, block, 0, st, static_cast<const float *>(W), ldw, br, bq, gap);
     return s24_launch_status();

@@ -59,6 +59,9 @@ template <typename T> struct Elem;
 template <> struct Elem<uint16_t> {
     static __device__ __forceinline__ float load(const uint16_t *p) { return s24_bf16_to_f32(*p); }
 };
+template <> struct Elem<s24_half> {
+    static __device__ __forceinline__ float load(const s24_half *p) { return (float)*p; }
+};
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float *p) { return *p; }
 };
@@ -98,8 +101,8 @@ __global__ __launch_bounds__(kThreads) void mvue24_kernel(const T *__restrict__ 
         uint4 *dst = reinterpret_cast<uint4 *>(vals + o * 32);
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            dst[k] = make_uint4(s24_pack_bf16x2(out[8 * k], out[8 * k + 1]), s24_pack_bf16x2(out[8 * k + 2], out[8 * k + 3]),
-                                s24_pack_bf16x2(out[8 * k + 4], out[8 * k + 5]), s24_pack_bf16x2(out[8 * k + 6], out[8 * k + 7]));
+            dst[k] = make_uint4(s24_num<T>::pack2(out[8 * k], out[8 * k + 1]), s24_num<T>::pack2(out[8 * k + 2], out[8 * k + 3]),
+                                s24_num<T>::pack2(out[8 * k + 4], out[8 * k + 5]), s24_num<T>::pack2(out[8 * k + 6], out[8 * k + 7]));
     } else {
         float4 *dst = reinterpret_cast<float4 *>(vals + o * 32);
 #pragma unroll
@@ -125,6 +128,9 @@ extern "C" int s24_mvue24(const void *dY, s24_dtype dt, int64_t p, int64_t r, in
     if (dt == S24_BF16)
         hipLaunchKernelGGL(mvue24_kernel<uint16_t>, grid, block, 0, st, static_cast<const uint16_t *>(dY), ld, (int)r, chunks,
                            seed, static_cast<uint16_t *>(vals), meta);
+    else if (dt == S24_F16)
+        hipLaunchKernelGGL(mvue24_kernel<s24_half>, grid, block, 0, st, static_cast<const s24_half *>(dY), ld, (int)r, chunks,
+                           seed, static_cast<s24_half *>(vals), meta);
     else
         hipLaunchKernelGGL(mvue24_kernel<float>, grid, block, 0, st, static_cast<const float *>(dY), ld, (int)r, chunks, seed,
                            static_cast<float *>(vals), meta);

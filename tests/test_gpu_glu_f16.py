@@ -1,0 +1,332 @@
+"""GPU parity for the gated-activation family of Sec. 5.2 (GEGLU / SwiGLU on row- and column-major operands, the
+bias of step 2 and its gradient, both gates in the GEMM epilogues) and for the binary16 instantiation of the
+large-tile matrix-core kernels.  Same bar as tests/test_gpu_parity.py: index and bit-pattern work exact, floating
+point within the tolerance of tests/util.py."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import s24_inputs as si
+from util import assert_close, bits, dev, dev_bf16, host_bits, host_f64, tol_for, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+# results of an activation applied to already rounded inputs carry one more rounding than a GEMM output; binary16
+# gradients of size 1e-5 .. 1e-4 lie among the subnormals (spacing 6e-8), which costs them relative accuracy,
+# so their element bound is the general 1e-2 while the normwise bound stays five times tighter than bf16's
+ACT_TOL = {"bf16": (2e-2, 5e-3), "f16": (1e-2, 1e-3), "f32": (1e-3, 2e-5)}
+
+
+@pytest.fixture(scope="module")
+def s24():
+    import paper_2404_01847_amd as lib
+    lib.lib()   # fail loudly here if libs24.so is missing
+    assert torch.cuda.is_available()
+    return lib
+
+
+def gates(s24, gate):
+    return (s24.GATE_GELU_ERF, oracle.GATE_GELU_ERF) if gate == "gelu" else (s24.GATE_SILU, oracle.GATE_SILU)
+
+
+def sample_rows(p, seed, n=12):
+    return np.unique(np.concatenate([[0, p - 1], np.random.default_rng(seed).integers(0, p, n)])).astype(np.int64)
+
+
+# ------------------------------------------------------------------ stand-alone gated activation, four layout pairs
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("gate", ["gelu", "silu"])
+@pytest.mark.parametrize("layouts", ["RR", "CC", "CR", "RC"])
+@pytest.mark.parametrize("pf", [(8, 8), (200, 264), (328, 72)])     # several 64 x 64 tiles with ragged edges
+def test_glu_fwd_bwd_all_layouts(s24, dtype, gate, layouts, pf):
+    p, f = pf
+    g_lib, g_orc = gates(s24, gate)
+    lz, lh = (s24.COL_MAJOR if c == "C" else s24.ROW_MAJOR for c in layouts)
+    z = si.random_matrix(1000 + p, (p, 2 * f), 1.5, dtype)
+    z[0, :4] = 0
+    d = si.random_matrix(1001 + f, (p, f), 1e-2 if dtype != "f32" else 1.0, dtype)
+    Zs = np.ascontiguousarray(z.T) if lz else z           # the tensor that stores Z
+    Ds = np.ascontiguousarray(d.T) if lh else d
+    Z, D = dev_bf16(Zs), dev_bf16(Ds)
+    H = torch.full(Ds.shape, 7.0, dtype=torch_dtype(dtype), device="cuda")
+    dZ = torch.full(Zs.shape, 7.0, dtype=torch_dtype(dtype), device="cuda")
+    s24.glu_fwd(Z, H, g_lib, layout_z=lz, layout_h=lh)
+    s24.glu_bwd(D, Z, dZ, g_lib, layout_h=lh, layout_z=lz)
+    torch.cuda.synchronize()
+    h = host_f64(H)
+    dz = host_f64(dZ)
+    assert_close(h.T if lh else h, oracle.glu_fwd(z, g_orc), ACT_TOL[dtype], f"glu_fwd {gate} {layouts} {pf}")
+    assert_close(dz.T if lz else dz, oracle.glu_bwd(d, z, g_orc), ACT_TOL[dtype], f"glu_bwd {gate} {layouts} {pf}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_glu_layouts_agree_bit_for_bit_and_strides_are_honoured(s24, dtype):
+    """The four layout pairs run the same arithmetic: their results are the same numbers.  Leading dimensions
+    larger than the extent (a window of a wider buffer) leave the rest of the buffer alone."""
+    p, f = 136, 200
+    z = si.random_matrix(1010, (p, 2 * f), 1.5, dtype)
+    Zr = dev_bf16(z)
+    Zc = dev_bf16(np.ascontiguousarray(z.T))
+    outs = []
+    for lz, lh in [(0, 0), (1, 1), (1, 0), (0, 1)]:
+        H = torch.zeros((f, p) if lh else (p, f), dtype=torch_dtype(dtype), device="cuda")
+        s24.glu_fwd(Zc if lz else Zr, H, s24.GATE_GELU_ERF, layout_z=lz, layout_h=lh)
+        outs.append(H.t().contiguous() if lh else H)
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(bits(o), bits(outs[0]))
+    # H written into the middle columns of a wider row-major buffer
+    wide = torch.full((p, f + 48), 3.0, dtype=torch_dtype(dtype), device="cuda")
+    s24.glu_fwd(Zc, wide[:, 16:16 + f], s24.GATE_GELU_ERF, layout_z=s24.COL_MAJOR, layout_h=s24.ROW_MAJOR)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(wide[:, 16:16 + f].contiguous()), bits(outs[0]))
+    assert (wide[:, :16] == 3.0).all() and (wide[:, 16 + f:] == 3.0).all()
+
+
+def test_glu_silu_is_the_swiglu_entry_point(s24):
+    p, f = 77, 136
+    z = si.random_matrix(1020, (p, 2 * f), 1.5, "bf16")
+    d = si.random_matrix(1021, (p, f), 1e-2, "bf16")
+    Z, D = dev_bf16(z), dev_bf16(d)
+    H1, H2 = torch.zeros((p, f), dtype=torch.bfloat16, device="cuda"), torch.zeros((p, f), dtype=torch.bfloat16, device="cuda")
+    dZ1, dZ2 = torch.zeros_like(Z), torch.zeros_like(Z)
+    s24.glu_fwd(Z, H1, s24.GATE_SILU)
+    s24.swiglu_fwd(Z[:, :f], Z[:, f:], H2)
+    s24.glu_bwd(D, Z, dZ1, s24.GATE_SILU)
+    s24.swiglu_bwd(D, Z[:, :f], Z[:, f:], dZ2[:, :f], dZ2[:, f:])
+    torch.cuda.synchronize()
+    assert torch.equal(bits(H1), bits(H2)) and torch.equal(bits(dZ1), bits(dZ2))
+
+
+def test_glu_table4_shape_column_major_binary16(s24):
+    """The paper's Table 4 input at its smallest width (32 x 512 tokens, d = 768, fp16, column-major), checked on
+    sampled tokens."""
+    p, n = 32 * 512, 768
+    f = n // 2
+    z = si.random_matrix(1030, (p, n), 1.0, "f16")
+    Z = dev_bf16(np.ascontiguousarray(z.T))
+    Hc = torch.zeros((f, p), dtype=torch.float16, device="cuda")
+    Hr = torch.zeros((p, f), dtype=torch.float16, device="cuda")
+    s24.glu_fwd(Z, Hc, s24.GATE_GELU_ERF, layout_z=s24.COL_MAJOR, layout_h=s24.COL_MAJOR)
+    s24.glu_fwd(Z, Hr, s24.GATE_GELU_ERF, layout_z=s24.COL_MAJOR, layout_h=s24.ROW_MAJOR)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(Hc.t().contiguous()), bits(Hr))
+    rows = sample_rows(p, 5, 40)
+    ref = oracle.glu_fwd(np.ascontiguousarray(z[rows]), oracle.GATE_GELU_ERF)
+    assert_close(host_f64(Hr[torch.from_numpy(rows).cuda()]), ref, ACT_TOL["f16"], "table-4 shape")
+
+
+# ------------------------------------------------------------------ bias gradient
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("layout", ["R", "C"])
+@pytest.mark.parametrize("pn", [(8, 8), (1000, 200), (4104, 72)])
+@pytest.mark.parametrize("beta", [0.0, 1.0])
+def test_bias_grad(s24, dtype, layout, pn, beta):
+    p, n = pn
+    dz = si.random_matrix(1100 + p, (p, n), 1e-2, dtype)
+    col = layout == "C"
+    D = dev_bf16(np.ascontiguousarray(dz.T) if col else dz)
+    db0 = np.random.default_rng(n).standard_normal(n).astype(np.float32)
+    db = torch.from_numpy(db0.copy()).cuda()
+    s24.bias_grad(D, db, beta=beta, layout=s24.COL_MAJOR if col else s24.ROW_MAJOR)
+    torch.cuda.synchronize()
+    ref = oracle.bias_grad(dz) + beta * db0.astype(np.float64)
+    # fp32 running sums of p terms of size ~1e-2: error ~ p * 2^-24 * |term| per column, far inside this bound
+    assert_close(db.cpu().numpy().astype(np.float64), ref, (1e-3, 2e-5), f"bias_grad {layout} {pn}")
+
+
+def test_bias_grad_is_reproducible_and_no_tokens_gives_beta_db(s24):
+    dz = si.random_matrix(1110, (3000, 264), 1.0, "bf16")
+    D = dev_bf16(dz)
+    a, b = torch.zeros(264, device="cuda"), torch.ones(264, device="cuda")
+    s24.bias_grad(D, a)
+    s24.bias_grad(D, b)            # beta = 0 overwrites
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    e = torch.full((16,), 5.0, device="cuda")
+    s24.bias_grad(torch.zeros((0, 16), dtype=torch.bfloat16, device="cuda"), e, beta=1.0)
+    torch.cuda.synchronize()
+    assert (e == 5.0).all()
+    s24.bias_grad(torch.zeros((0, 16), dtype=torch.bfloat16, device="cuda"), e, beta=0.0)
+    torch.cuda.synchronize()
+    assert (e == 0.0).all()
+
+
+# ------------------------------------------------------------------ Z = X W^T + d
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("pqr", [(1, 64, 16), (300, 256, 208), (77, 192, 400)])
+def test_spmm_fwd_bias_small_tiles(s24, dtype, pqr):
+    p, q, r = pqr
+    W = si.random_matrix(1200 + r, (r, q), 0.02, dtype)
+    X = si.random_matrix(1201 + p, (p, q), 1.0, dtype)
+    b = si.random_matrix(1202, (r,), 0.5, dtype)
+    mask = oracle.transposable_mask(W)
+    vals, meta, _, _ = oracle.compress(W, mask)
+    vp, mp = oracle.pack(vals, meta)
+    Y = torch.full((p, r), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    s24.spmm_fwd_bias(dev_bf16(X), dev_bf16(vp), dev(mp), dev_bf16(b), Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y), oracle.spmm_fwd_bias(X, vals, meta, b), tol_for(dtype), f"spmm_fwd_bias {pqr}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_spmm_fwd_bias_large_tiles_and_null_bias(s24, dtype):
+    p, q, r = 6100, 128, 2000          # >= 192 tiles of 256 x 256, ragged in both directions
+    W = si.random_matrix(1210, (r, q), 0.02, dtype)
+    X = si.random_matrix(1211, (p, q), 1.0, dtype)
+    b = si.random_matrix(1212, (r,), 0.5, dtype)
+    mask = oracle.transposable_mask(W)
+    vals, meta, _, _ = oracle.compress(W, mask)
+    vp, mp = oracle.pack(vals, meta)
+    d_X, d_v, d_m = dev_bf16(X), dev_bf16(vp), dev(mp)
+    Y = torch.full((p, r), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    Y0, Y1 = torch.empty_like(Y), torch.empty_like(Y)
+    s24.spmm_fwd_bias(d_X, d_v, d_m, dev_bf16(b), Y)
+    s24.spmm_fwd_bias(d_X, d_v, d_m, None, Y0)
+    s24.spmm_fwd(d_X, d_v, d_m, Y1)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(Y0), bits(Y1))
+    rows = sample_rows(p, 3, 30)
+    ridx = torch.from_numpy(rows).cuda()
+    assert_close(host_f64(Y[ridx]), oracle.spmm_fwd_bias(X, vals, meta, b, rows=rows), tol_for(dtype), "bias, large tiles")
+    assert_close(host_f64(Y1[ridx]), oracle.spmm_fwd(X, vals, meta, rows=rows), tol_for(dtype), "no bias, large tiles")
+
+
+# ------------------------------------------------------------------ steps 1-3 of Sec. 5.2 in one pass, both gates
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gate", ["gelu", "silu"])
+@pytest.mark.parametrize("case", [(300, 128, 272), (777, 192, 6224)])     # fallback route / fused epilogue, ragged
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_spmm_fwd_glu_equals_the_separate_calls_and_the_oracle(s24, dtype, gate, case, with_bias):
+    p, q, f = case
+    g_lib, g_orc = gates(s24, gate)
+    X = si.random_matrix(1300 + p, (p, q), 1.0, dtype)
+    W = si.random_matrix(1301 + p, (2 * f, q), 0.02, dtype)        # stacked [W_gate; W_up]
+    b = si.random_matrix(1302, (2 * f,), 0.5, dtype) if with_bias else None
+    mask = oracle.transposable_mask(W)
+    vals, meta, _, _ = oracle.compress(W, mask)
+    vp, mp = oracle.pack(vals, meta)
+    d_X, d_v, d_m = dev_bf16(X), dev_bf16(vp), dev(mp)
+    d_b = dev_bf16(b) if with_bias else None
+    GU = torch.full((p, 2 * f), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    H = torch.full((p, f), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    s24.spmm_fwd_glu(d_X, d_v, d_m, d_b, GU, H, g_lib)
+    GU2, H2 = torch.empty_like(GU), torch.empty_like(H)
+    s24.spmm_fwd_bias(d_X, d_v, d_m, d_b, GU2)
+    s24.glu_fwd(GU2, H2, g_lib)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(GU), bits(GU2))            # same bits as the separate calls
+    assert torch.equal(bits(H), bits(H2))
+    rows = sample_rows(p, p)
+    ridx = torch.from_numpy(rows).cuda()
+    Z = oracle.spmm_fwd_bias(X, vals, meta, b, rows=rows) if with_bias else oracle.spmm_fwd(X, vals, meta, rows=rows)
+    assert_close(host_f64(GU[ridx]), Z, tol_for(dtype), f"Z {case}")
+    Href = oracle.glu_fwd(oracle.round_like(Z, X), g_orc)
+    assert_close(host_f64(H[ridx]), Href, ACT_TOL[dtype], f"H {case}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gate", ["gelu", "silu"])
+def test_spmm_bwd_dx_glu_equals_the_separate_calls_and_the_oracle(s24, dtype, gate):
+    p, f, r = 1800, 6224, 192          # >= 192 tiles of 256 x 256, ragged
+    g_lib, g_orc = gates(s24, gate)
+    dY = si.random_matrix(1400, (p, r), 1e-2, dtype)
+    Wd = si.random_matrix(1401, (r, f), 0.02, dtype)
+    GU = si.random_matrix(1402, (p, 2 * f), 1.0, dtype)
+    mask = oracle.transposable_mask(Wd)
+    _, _, valsT, metaT = oracle.compress(Wd, mask)
+    vtp, mtp = oracle.pack(valsT, metaT)
+    d_dY, d_v, d_m, d_GU = dev_bf16(dY), dev_bf16(vtp), dev(mtp), dev_bf16(GU)
+    dGU = torch.full((p, 2 * f), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    s24.spmm_bwd_dx_glu(d_dY, d_v, d_m, d_GU, dGU, g_lib)
+    dH = torch.empty((p, f), dtype=torch_dtype(dtype), device="cuda")
+    dGU2 = torch.empty_like(dGU)
+    s24.spmm_bwd_dx(d_dY, d_v, d_m, dH)
+    s24.glu_bwd(dH, d_GU, dGU2, g_lib)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(dGU), bits(dGU2))
+    rows = sample_rows(p, 7)
+    dHr = oracle.round_like(oracle.spmm_bwd_dx(dY, valsT, metaT, rows=rows), dY)
+    ref = oracle.glu_bwd(dHr, np.ascontiguousarray(GU[rows]), g_orc)
+    assert_close(host_f64(dGU[torch.from_numpy(rows).cuda()]), ref, ACT_TOL[dtype], f"dGU {gate}")
+
+
+# ------------------------------------------------------------------ binary16 on the large-tile matrix-core kernels
+@pytest.mark.parametrize("k", [64, 192, 320])
+def test_f16_spmm_large_tile_path(s24, k):
+    p, r = 6100, 2000
+    W = si.random_matrix(1500 + k, (r, k), 0.02, "f16")
+    X = si.random_matrix(1501 + k, (p, k), 1.0, "f16")
+    mask = oracle.transposable_mask(W)
+    vals, meta, _, _ = oracle.compress(W, mask)
+    vp, mp = oracle.pack(vals, meta)
+    rows = sample_rows(p, k, 40)
+    ridx = torch.from_numpy(rows).cuda()
+    Y = torch.full((p, r), 3.0, dtype=torch.float16, device="cuda")
+    s24.spmm_fwd(dev_bf16(X), dev_bf16(vp), dev(mp), Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y[ridx]), oracle.spmm_fwd(X, vals, meta, rows=rows), tol_for("f16"), f"f16 spmm_fwd k={k}")
+    dX0 = si.random_matrix(1502, (p, r), 1e-2, "f16")
+    dX = dev_bf16(dX0).clone()
+    s24.spmm_bwd_dx(dev_bf16(X), dev_bf16(vp), dev(mp), dX, beta=1.0)
+    torch.cuda.synchronize()
+    ref = oracle.spmm_bwd_dx(X, vals, meta, beta=1.0, dX0=si.to_f32(dX0[rows]).astype(np.float64), rows=rows)
+    assert_close(host_f64(dX[ridx]), ref, tol_for("f16"), f"f16 spmm_bwd_dx k={k}")
+
+
+@pytest.mark.parametrize("p", [64, 200])
+@pytest.mark.parametrize("shape", [(3408, 3600), (1040, 1296), (2160, 2192)])   # 256-tiles; 128-tiles, 64 and 32 tokens per stage
+@pytest.mark.parametrize("beta", [0.0, 1.0])
+def test_f16_dense_dw_with_decay_all_tile_shapes(s24, p, shape, beta):
+    r, q = shape
+    lam = 2e-4
+    dY = si.random_matrix(1600 + p, (p, r), 1e-2, "f16")
+    X = si.random_matrix(1601 + p, (p, q), 1.0, "f16")
+    W = si.random_matrix(1602, (r, q), 0.02, "f16")
+    dW0 = si.random_matrix(1603, (r, q), 1e-3, "f32")
+    mask = oracle.transposable_mask(W)
+    d_dY, d_X, d_W, d_mask = dev_bf16(dY), dev_bf16(X), dev_bf16(W), dev(mask)
+    fused = dev(dW0).clone()
+    s24.dense_dw_decay(d_dY, d_X, fused, d_W, d_mask, lam, beta=beta)
+    two = dev(dW0).clone()
+    s24.dense_dw(d_dY, d_X, two, beta=beta)
+    s24.masked_decay_grad(two, d_W, d_mask, lam)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.view(torch.int32), two.view(torch.int32))
+    rows = np.unique(np.concatenate([[0, 3, 4, r - 1], np.random.default_rng(p).integers(0, r, 20)])).astype(np.int64)
+    g = oracle.dense_dw(dY, X, beta=beta, dW0=dW0[rows].astype(np.float64), rows=rows)
+    g = g + oracle.masked_decay(np.zeros((r, q), np.float32), W, mask, lam)[rows]
+    assert_close(host_f64(fused[torch.from_numpy(rows).cuda()]), g, tol_for("f32"), f"f16 dense_dw_decay {shape} p={p}")
+
+
+def test_f16_dense_gemm_and_spmm_dw_large(s24):
+    p, q, r = 6100, 128, 2000
+    X = si.random_matrix(1700, (p, q), 1.0, "f16")
+    W = si.random_matrix(1701, (r, q), 0.02, "f16")
+    Y = torch.zeros((p, r), dtype=torch.float16, device="cuda")
+    s24.dense_gemm(dev_bf16(X), dev_bf16(W), Y)
+    torch.cuda.synchronize()
+    rows = sample_rows(p, 1, 30)
+    assert_close(host_f64(Y[torch.from_numpy(rows).cuda()]), oracle.dense_gemm(X, W, rows=rows), tol_for("f16"), "f16 dense_gemm")
+    # fully sparse weight gradient (Eq. 4) on binary16 operands
+    p2, q2, r2 = 448, 528, 272
+    dY = si.random_matrix(1702, (p2, r2), 1e-2, "f16")
+    X2 = si.random_matrix(1703, (p2, q2), 1.0, "f16")
+    vals = torch.zeros((p2 // 64, r2, 32), dtype=torch.float16, device="cuda")
+    meta = torch.zeros((p2 // 64, r2, 4), dtype=torch.int16, device="cuda")
+    s24.mvue24(dev_bf16(dY), 11, vals, meta)
+    dW = torch.zeros((r2, q2), dtype=torch.float32, device="cuda")
+    s24.spmm_dw(vals, meta, dev_bf16(X2), dW)
+    torch.cuda.synchronize()
+    ov, om = oracle.mvue24(dY, 11)
+    want_v, want_m = oracle.pack(ov, om)
+    assert np.array_equal(host_bits(vals).view(np.uint16), want_v.view(np.uint16)) and np.array_equal(host_bits(meta), want_m)
+    # the pruned gradient, decoded, times X
+    dense = np.zeros((r2, p2))
+    v64 = ov.astype(np.float64)
+    for g in range(p2 // 4):
+        nib = (om[:, g // 4] >> (4 * (g % 4))) & 0xF
+        dense[np.arange(r2), 4 * g + (nib & 3)] = v64[:, 2 * g]
+        dense[np.arange(r2), 4 * g + (nib >> 2)] = v64[:, 2 * g + 1]
+    assert_close(dW.cpu().numpy().astype(np.float64), dense @ X2.astype(np.float64), tol_for("f16"), "f16 spmm_dw")

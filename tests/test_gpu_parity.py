@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import s24_inputs as si
-from util import BF16_TOL, F32_TOL, assert_close, dev, dev_bf16, host_bits, host_f64
+from util import BF16_TOL, F32_TOL, assert_close, dev, dev_bf16, host_bits, host_f64, tol_for, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -22,11 +22,11 @@ def s24():
 
 
 def tdtype(dtype):
-    return torch.bfloat16 if dtype == "bf16" else torch.float32
+    return torch_dtype(dtype)
 
 
 def tol(dtype):
-    return BF16_TOL if dtype == "bf16" else F32_TOL
+    return tol_for(dtype)
 
 
 def gpu_mask(s24, W, want_index=True):
@@ -65,7 +65,7 @@ def test_pattern_table_matches_oracle(s24):
 
 
 # ------------------------------------------------------------------ mask search
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("shape", [(4, 4), (128, 128), (260, 388), (516, 132), (64, 1024)])
 def test_mask_random_bit_exact(s24, dtype, shape):
     W = si.random_matrix(100 + shape[0], shape, 0.02, dtype)
@@ -75,7 +75,7 @@ def test_mask_random_bit_exact(s24, dtype, shape):
     assert np.array_equal(got_i, want_i)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal"])
 def test_mask_ties_and_wide_ranges_bit_exact(s24, dtype, kind):
     W = si.tie_matrix(77, 192, 320, dtype, kind)
@@ -98,7 +98,7 @@ def test_mask_strided_weight_and_empty(s24):
 
 
 # ------------------------------------------------------------------ compress
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("shape", [(64, 64), (128, 128), (320, 448), (576, 192)])
 @pytest.mark.parametrize("fused", [False, True])
 def test_compress_bit_exact(s24, dtype, shape, fused):
@@ -132,7 +132,7 @@ def compressed(W):
     return (mask,) + oracle.compress(W, mask)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("pqr", [(1, 64, 16), (128, 128, 128), (300, 256, 208), (77, 192, 400), (513, 64, 144)])
 def test_spmm_fwd(s24, dtype, pqr):
     p, q, r = pqr
@@ -145,7 +145,7 @@ def test_spmm_fwd(s24, dtype, pqr):
     assert_close(host_f64(Y), oracle.spmm_fwd(X, vals, meta), tol(dtype), f"spmm_fwd {pqr}")
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("pqr", [(1, 16, 64), (128, 128, 128), (300, 208, 256), (77, 400, 192)])
 @pytest.mark.parametrize("beta", [0.0, 1.0])
 def test_spmm_bwd_dx(s24, dtype, pqr, beta):
@@ -269,7 +269,7 @@ def test_spmm_bwd_dx_swiglu_declines_small_shapes(s24):
 
 
 # ------------------------------------------------------------------ dense GEMMs
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("pqr", [(1, 16, 16), (64, 128, 128), (300, 208, 272), (1000, 144, 400)])
 @pytest.mark.parametrize("beta", [0.0, 1.0])
 def test_dense_dw(s24, dtype, pqr, beta):
@@ -338,7 +338,7 @@ def test_dense_dw_rank_one_is_exact(s24):
     assert np.array_equal(host_f64(dW), oracle.dense_dw(dY, X))    # bf16 x bf16 fits fp32 exactly
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("pqr", [(1, 64, 16), (128, 128, 128), (300, 256, 208)])
 def test_dense_gemm(s24, dtype, pqr):
     p, q, r = pqr
@@ -364,7 +364,7 @@ def test_dense_gemm_large_tile_path(s24, k):
 
 
 # ------------------------------------------------------------------ masked decay
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("shape", [(16, 16), (260, 400), (128, 1024)])
 def test_masked_decay(s24, dtype, shape):
     lam = 2e-4
@@ -414,7 +414,7 @@ def test_dense_dw_decay_equals_the_two_calls_and_the_oracle(s24, case):
 
 
 # ------------------------------------------------------------------ unbiased 2:4 pruning of dY and the sparse weight gradient
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("shape", [(64, 16), (128, 80), (448, 272), (1024, 1040)])
 def test_mvue24_matches_the_oracle_bit_for_bit(s24, dtype, shape):
     p, r = shape
@@ -427,7 +427,8 @@ def test_mvue24_matches_the_oracle_bit_for_bit(s24, dtype, shape):
     torch.cuda.synchronize()
     want_v, want_m = oracle.pack(*oracle.mvue24(dY, 20240401))
     assert np.array_equal(host_bits(meta), want_m)
-    assert np.array_equal(host_bits(vals), want_v if dtype == "bf16" else want_v.view(np.float32))
+    word = np.uint32 if dtype == "f32" else np.uint16
+    assert np.array_equal(host_bits(vals).view(word), want_v.view(word))
     # another seed gives another draw
     s24.mvue24(dev_bf16(dY), 7, vals, meta)
     torch.cuda.synchronize()
@@ -509,7 +510,7 @@ def test_mask_flips(s24, shape):
     assert int(flips.item()) == 0
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("shape", [(4, 4), (64, 96), (260, 1000)])
 def test_l1_norm_gap_matches_the_oracle_bit_for_bit(s24, dtype, shape):
     W = si.random_matrix(720 + shape[0], shape, 0.02, dtype)
@@ -537,7 +538,7 @@ def test_l1_norm_gap_on_tied_and_wide_range_blocks(s24, kind):
 
 
 # ------------------------------------------------------------------ activations
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("pf", [(1, 8), (37, 264), (256, 1000)])
 def test_swiglu_fwd_bwd(s24, dtype, pf):
     p, f = pf
@@ -578,7 +579,7 @@ def test_swiglu_halves_of_one_buffer_and_extremes(s24):
     assert_close(out[:, f:], ru, BF16_TOL, "swiglu_bwd dU halves")
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("act", ["relu", "gelu"])
 def test_act_fwd_bwd(s24, dtype, act):
     code = {"relu": (s24.ACT_RELU, oracle.ACT_RELU), "gelu": (s24.ACT_GELU_ERF, oracle.ACT_GELU_ERF)}[act]

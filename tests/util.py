@@ -7,14 +7,14 @@ import s24_inputs as si
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
-    """numpy (float32, or uint16 = bf16 bits / mask words, or uint8) -> CUDA tensor."""
+    """numpy (float32, float16, or uint16 = bf16 bits / mask words, or uint8) -> CUDA tensor."""
     if a.dtype == np.uint16:
         return torch.from_numpy(a.view(np.int16).copy()).cuda()
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
 def dev_bf16(a: np.ndarray) -> torch.Tensor:
-    """bf16 bit array (uint16) -> CUDA bfloat16 tensor; float32 arrays pass through."""
+    """bf16 bit array (uint16) -> CUDA bfloat16 tensor; float32 and float16 arrays pass through."""
     t = dev(a)
     return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
 
@@ -46,8 +46,25 @@ def errors(got: np.ndarray, ref: np.ndarray):
 
 # bf16 in / fp32 accumulate: max relative error 1e-2, normwise 5e-3
 BF16_TOL = (1e-2, 5e-3)
+# binary16 in / fp32 accumulate: the same bar holds with room to spare (11 significant bits instead of 8); the
+# tighter figures are what one rounding to binary16 of an fp32-accumulated sum allows, with some slack for
+# results that land among the subnormals
+F16_TOL = (4e-3, 1e-3)
 # fp32 data path (small correctness workload): accumulation-order noise only
 F32_TOL = (1e-3, 2e-5)
+
+
+def tol_for(dtype: str):
+    return {"bf16": BF16_TOL, "f16": F16_TOL, "f32": F32_TOL}[dtype]
+
+
+def torch_dtype(dtype: str):
+    return {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dtype]
+
+
+def bits(t: torch.Tensor) -> torch.Tensor:
+    """Integer view of a tensor for bit-exact comparison."""
+    return t.view(torch.int32) if t.dtype == torch.float32 else t.view(torch.int16)
 
 
 def assert_close(got, ref, tol, what=""):
