@@ -40,7 +40,7 @@ def kernel_model(wl):
     """Algorithmic work of each kernel over one whole step: (kind, amount per step, peak, unit).  Per step and not
     per launch because the launches of one kernel differ in size when gate and up projection are one weight."""
     p, d, f = wl.p, wl.d_model, wl.d_ff
-    es = 2 if wl.dtype == "bf16" else 4
+    es = 4 if wl.dtype == "f32" else 2
     nw = len(wl.weight_names)
     blocks = nw * d * f / 16
     gemm = nw * 2.0 * p * d * f
@@ -62,6 +62,8 @@ def kernel_model(wl):
         "swiglu_bwd": ("hbm", p * f * 5 * es, PEAK_HBM, "GB/s"),
         "act_fwd": ("hbm", p * f * 2 * es, PEAK_HBM, "GB/s"),
         "act_bwd": ("hbm", p * f * 3 * es, PEAK_HBM, "GB/s"),
+        # bias gradients (only with --geglu-bias): every output gradient read once
+        "bias_grad": ("hbm", ((nw - 1) * p * f + p * d) * es, PEAK_HBM, "GB/s"),
     }
     return m
 
@@ -90,15 +92,18 @@ def cpu_baseline(wl, tensors_host, budget_tokens=None):
         r, q = t[name].shape
         oracle.masked_decay(np.zeros((r, q), np.float32), t[name], comp[name][0], wl.lam)
     t_weights = time.perf_counter() - t0
-    rnd = oracle.round_bf16 if wl.dtype == "bf16" else (lambda a: a.astype(np.float32))
+    rnd = lambda a: oracle.round_like(a, X)
     t0 = time.perf_counter()
     if wl.gated:
         G = rnd(oracle.spmm_fwd(X, comp["Wg"][1], comp["Wg"][2]))
         U = rnd(oracle.spmm_fwd(X, comp["Wu"][1], comp["Wu"][2]))
-        H = rnd(oracle.swiglu_fwd(G, U))
+        gate = oracle.GATE_GELU_ERF if wl.act == "geglu" else oracle.GATE_SILU
+        Z = np.concatenate([G, U], axis=1)
+        H = rnd(oracle.glu_fwd(Z, gate))
         oracle.spmm_fwd(H, comp["Wd"][1], comp["Wd"][2])
         dH = rnd(oracle.spmm_bwd_dx(dY, comp["Wd"][3], comp["Wd"][4]))
-        dG, dU = (rnd(a) for a in oracle.swiglu_bwd(dH, G, U))
+        dZ = rnd(oracle.glu_bwd(dH, Z, gate))
+        dG, dU = np.ascontiguousarray(dZ[:, :wl.d_ff]), np.ascontiguousarray(dZ[:, wl.d_ff:])
         oracle.spmm_bwd_dx(dG, comp["Wg"][3], comp["Wg"][4])
         oracle.spmm_bwd_dx(dU, comp["Wu"][3], comp["Wu"][4])
         oracle.dense_dw(dY, H)
@@ -182,7 +187,7 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     (7) the step with the sparse weight gradient on the MVUE-pruned output gradient."""
     import s24_inputs as si
     out = {}
-    es = 2 if wl.dtype == "bf16" else 4
+    es = 4 if wl.dtype == "f32" else 2
     from paper_2404_01847_amd.ffn import SparseWeight
     # the layer's weights one by one (also where the timed step holds gate and up projection as one weight)
     named = {}
@@ -206,7 +211,7 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
         stacks = []
         for which in range(2):
             a = np.concatenate([si.sweep_weight(layer, which, wl) for layer in range(36)], axis=0)
-            t = torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+            t = torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if a.dtype == np.uint16 else torch.from_numpy(a).cuda()
             stacks.append((t, torch.empty((t.shape[0] // 4, t.shape[1] // 4), dtype=torch.int16, device="cuda")))
         rows = [wl.d_ff, wl.d_model]
 
@@ -264,7 +269,8 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     ms_40 = _time_ms(torch, lambda: ffn.step(X, dY), 40)
     ffn.mask_interval, ffn.steps_done = 1, 0
     out["step_with_mask_every_40_steps"] = {"ms_per_step": round(ms_40, 4), "TFLOP/s": round(wl.gemm_flops / ms_40 / 1e9, 1)}
-    if wl.dtype == "bf16":
+    out["gated_activation_sec_5_2"] = gated_activation_measurements(torch, s24)
+    if wl.dtype != "f32":
         names = list(named) if wl.name == "c5" else list(named)[:1]
         cmp_ = []
         for name in names:
@@ -301,6 +307,44 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     return out
 
 
+def gated_activation_measurements(torch, s24):
+    """Sec. 5.2 / Table 4: GEGLU on the paper's inputs, 32 x 512 tokens by d features (so f = d/2 gated features) in
+    binary16, stored column-major as the paper's sparse GEMMs leave them.  Three routes: column-major in and out
+    (the paper's kernel), column-major in and row-major out (the layout this library's GEMMs consume; the change of
+    layout rides on the same pass through 64 x 64 LDS tiles), row-major in and out.  GB/s counts the algorithmic
+    bytes: Z read once, H written once (3 f p elements).  Also the backward kernel and the bias gradient at the
+    widest input."""
+    out = {"input": "32 x 512 x d, binary16", "rows": []}
+    p = 32 * 512
+    for d in (768, 1024, 1280, 1600, 2048, 4096, 8192):
+        f = d // 2
+        Zc = torch.empty((d, p), dtype=torch.float16, device="cuda").normal_()
+        Zr = torch.empty((p, d), dtype=torch.float16, device="cuda").normal_()
+        Hc = torch.empty((f, p), dtype=torch.float16, device="cuda")
+        Hr = torch.empty((p, f), dtype=torch.float16, device="cuda")
+        nbytes = 3.0 * f * p * 2
+        row = {"d": d}
+        for tag, z, h, lz, lh in (("col_to_col", Zc, Hc, 1, 1), ("col_to_row", Zc, Hr, 1, 0), ("row_to_row", Zr, Hr, 0, 0)):
+            ms = _time_ms(torch, lambda: s24.glu_fwd(z, h, s24.GATE_GELU_ERF, layout_z=lz, layout_h=lh), 20)
+            row[tag] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1)}
+        out["rows"].append(row)
+    # backward and bias gradient at d = 8192 (dH read, Z read, dZ written: 5 f p elements; bias gradient: 2 f p read)
+    dHc = torch.empty((f, p), dtype=torch.float16, device="cuda").normal_()
+    dHr = torch.empty((p, f), dtype=torch.float16, device="cuda").normal_()
+    dZc, dZr = torch.empty_like(Zc), torch.empty_like(Zr)
+    ms_c = _time_ms(torch, lambda: s24.glu_bwd(dHc, Zc, dZc, s24.GATE_GELU_ERF, layout_h=1, layout_z=1), 20)
+    ms_r = _time_ms(torch, lambda: s24.glu_bwd(dHr, Zr, dZr, s24.GATE_GELU_ERF), 20)
+    ms_x = _time_ms(torch, lambda: s24.glu_bwd(dHr, Zc, dZc, s24.GATE_GELU_ERF, layout_h=0, layout_z=1), 20)
+    out["backward_d8192"] = {k: {"ms": round(ms, 4), "GB/s": round(5.0 * f * p * 2 / ms / 1e6, 1)}
+                             for k, ms in (("col", ms_c), ("row", ms_r), ("row_dH_col_Z", ms_x))}
+    db = torch.empty(d, dtype=torch.float32, device="cuda")
+    ms_br = _time_ms(torch, lambda: s24.bias_grad(dZr, db), 20)
+    ms_bc = _time_ms(torch, lambda: s24.bias_grad(dZc, db, layout=s24.COL_MAJOR), 20)
+    out["bias_grad_d8192"] = {"row_major": {"ms": round(ms_br, 4), "GB/s": round(2.0 * d * p / ms_br / 1e6, 1)},
+                              "col_major": {"ms": round(ms_bc, 4), "GB/s": round(2.0 * d * p / ms_bc / 1e6, 1)}}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -319,6 +363,12 @@ def main():
                     help="SwiGLU forward and backward as their own kernels instead of GEMM epilogues")
     ap.add_argument("--no-fuse-decay", action="store_true",
                     help="masked decay as its own kernel after the weight-gradient GEMM instead of inside its epilogue")
+    ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
+                    help="storage type of the 16-bit workloads (default: the workload's own, bf16); f16 is IEEE binary16, "
+                         "the precision the paper trains in")
+    ap.add_argument("--geglu-bias", action="store_true",
+                    help="gated workloads only: the layer of Sec. 5.2 as written, GELU gate and biases on both projections "
+                         "(bias add in the GEMM epilogues, bias gradients as their own kernel)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device-to-device copy five times (reference for HBM byte counters) and exit")
     args = ap.parse_args()
@@ -343,7 +393,14 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}))
         return
+    import dataclasses
     wl = si.WORKLOADS[args.workload]
+    if args.dtype and wl.dtype != "f32":
+        wl = dataclasses.replace(wl, dtype=args.dtype)
+    if args.geglu_bias:
+        if not wl.gated or args.separate_gate_up:
+            sys.exit("bench.py: --geglu-bias needs a gated workload (c4, c5) with gate and up projection as one weight")
+        wl = dataclasses.replace(wl, act="geglu")
     host = si.make(wl)
 
     def to_dev(a):
@@ -352,8 +409,13 @@ def main():
         return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
 
     dev = {k: to_dev(v) for k, v in host.items()}
+    biases = None
+    if args.geglu_bias:
+        biases = {"Wgu": to_dev(si.random_matrix(7001, (2 * wl.d_ff,), 0.3, wl.dtype)),
+                  "Wd": to_dev(si.random_matrix(7002, (wl.d_model,), 0.3, wl.dtype))}
     ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay,
-                    concat_gate_up=not args.separate_gate_up, mvue=args.mvue, fuse_swiglu=not args.no_fuse_swiglu)
+                    concat_gate_up=not args.separate_gate_up, mvue=args.mvue, fuse_swiglu=not args.no_fuse_swiglu,
+                    biases=biases)
     X, dY = dev["X"], dev["dY"]
 
     for _ in range(args.warmup):
@@ -384,7 +446,7 @@ def main():
                          "achieved": round(achieved, 1), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
     dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])
     kd = kernels[dom]
-    default_cfg = ffn.concat == wl.gated and ffn.fuse_decay
+    default_cfg = ffn.concat == wl.gated and ffn.fuse_decay and not args.dtype and not args.geglu_bias
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"], "unit": kd["unit"],
                 "frac": kd["frac"],
                 "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if default_cfg else None}

@@ -218,38 +218,64 @@ __global__ __launch_bounds__(kThreads) void glu_bwd_transpose_kernel(const T *__
 }
 
 // ---- bias gradient (Sec. 5.2 step 2: d of Z = X W^T + d): sums over tokens --------------------------------------
-// Row-major dZ[p][n]: a workgroup of 16 waves owns 64 columns; half a wave reads one 64-column row segment (two
-// columns per lane), so a wave takes two rows at a time and the 16 waves walk the rows 32 apart.  Partial sums meet
-// in LDS in a fixed order: the result does not depend on scheduling.
+// Row-major dZ[p][n]: a workgroup of 16 waves owns 64 columns.  A lane reads 16 bytes (eight 16-bit or four fp32
+// columns), so one wave-wide load covers the 64-column segments of 8 (4) consecutive rows, the 16 waves walk the
+// rows 128 (64) at a time, four loads in flight per wave.  Lanes that hold the same columns are summed by a
+// butterfly, the waves' partial sums meet in LDS in a fixed order: the result does not depend on scheduling.
 constexpr int kBiasThreads = 1024;
 template <typename T>
 __global__ __launch_bounds__(kBiasThreads) void bias_grad_rows_kernel(const T *__restrict__ dZ, int64_t ld, int64_t p,
                                                                       int64_t n, float *__restrict__ db, float beta)
 {
-    __shared__ float s_part[32][64];
-    const int tid = threadIdx.x, lane = tid & 63, slot = tid >> 5;   // slot: which of 32 row phases
-    const int64_t c = (int64_t)blockIdx.x * 64 + 2 * (lane & 31);
-    float s0 = 0.f, s1 = 0.f;
-    if (c < n) {   // n is even: a column pair is all in or all out
-        for (int64_t t = slot; t < p; t += 32) {
-            if constexpr (sizeof(T) == 2) {
-                const uint32_t d = *reinterpret_cast<const uint32_t *>(dZ + t * ld + c);
-                s0 += s24_num<T>::lo(d);
-                s1 += s24_num<T>::hi(d);
-            } else {
-                const float2 d = *reinterpret_cast<const float2 *>(dZ + t * ld + c);
-                s0 += d.x;
-                s1 += d.y;
+    constexpr int VEC = 16 / (int)sizeof(T), LPR = 64 / VEC, RPW = 64 / LPR;   // columns per lane, lanes per row, rows per load
+    constexpr int64_t STEP = (kBiasThreads / 64) * RPW;
+    __shared__ float s_part[kBiasThreads / 64][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cl = VEC * (lane % LPR);
+    const int64_t c = (int64_t)blockIdx.x * 64 + cl;
+    float acc[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = 0.f;
+    auto add_row = [&](const uint4 &v) {
+        if constexpr (sizeof(T) == 2) {
+            const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                acc[2 * k] += s24_num<T>::lo(d[k]);
+                acc[2 * k + 1] += s24_num<T>::hi(d[k]);
             }
+        } else {
+            acc[0] += __uint_as_float(v.x);
+            acc[1] += __uint_as_float(v.y);
+            acc[2] += __uint_as_float(v.z);
+            acc[3] += __uint_as_float(v.w);
         }
+    };
+    if (c < n) {   // n is a multiple of 8: a lane's columns are all in or all out
+        const T *src = dZ + c;
+        int64_t t = wave * RPW + lane / LPR;
+        for (; t + 3 * STEP < p; t += 4 * STEP) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4 *>(src + (t + u * STEP) * ld);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) add_row(v[u]);
+        }
+        for (; t < p; t += STEP) add_row(*reinterpret_cast<const uint4 *>(src + t * ld));
     }
-    s_part[slot][2 * (lane & 31)] = s0;
-    s_part[slot][2 * (lane & 31) + 1] = s1;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] += __shfl_xor(acc[k], off, 64);
+    if (lane < LPR) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) s_part[wave][cl + k] = acc[k];
+    }
     __syncthreads();
     if (tid < 64 && (int64_t)blockIdx.x * 64 + tid < n) {
         float sum = 0.f;
 #pragma unroll
-        for (int k = 0; k < 32; ++k) sum += s_part[k][tid];
+        for (int k = 0; k < kBiasThreads / 64; ++k) sum += s_part[k][tid];
         float *o = db + (int64_t)blockIdx.x * 64 + tid;
         *o = beta != 0.0f ? *o + sum : sum;
     }

@@ -13,6 +13,7 @@ import torch
 from . import binding as s24
 
 _ACT = {"relu": s24.ACT_RELU, "gelu": s24.ACT_GELU_ERF}
+_GATE = {"swiglu": s24.GATE_SILU, "geglu": s24.GATE_GELU_ERF}
 
 
 class SparseWeight:
@@ -51,10 +52,14 @@ class SparseWeight:
 
 
 class SparseFFN:
-    """Buffers and call sequence of one FFN layer.  act: 'relu' | 'gelu' | 'swiglu'."""
+    """Buffers and call sequence of one FFN layer.  act: 'relu' | 'gelu' | 'swiglu' | 'geglu' (the last one needs
+    concat_gate_up).  `biases` maps weight names (after concatenation: 'Wgu', 'Wd'; else 'Wg', 'Wu', 'Wd' or
+    'W1', 'W2') to bias vectors in the weights' dtype: Z = X W^T + d as in Sec. 5.2 step 2; their gradients are
+    left in `bias_grad[name]` (fp32)."""
 
     def __init__(self, weights: dict, p: int, act: str, lam: float, fuse_decay: bool = True, mask_interval: int = 1,
-                 concat_gate_up: bool = False, mvue: bool = False, seed: int = 0, fuse_swiglu: bool = True):
+                 concat_gate_up: bool = False, mvue: bool = False, seed: int = 0, fuse_swiglu: bool = True,
+                 biases: dict | None = None):
         self.act, self.lam, self.p = act, lam, p
         # Eq. 4 / Eq. 6: the weight gradient from an unbiasedly 2:4-pruned output gradient, as a sparse GEMM
         self.mvue, self.seed = mvue, seed
@@ -65,7 +70,10 @@ class SparseFFN:
         self.draws = 0
         self.fuse_decay = fuse_decay   # masked decay inside the weight-gradient GEMM's epilogue
         self.timings = None   # when a dict: kernel name -> list of (start, end) torch.cuda.Event pairs
-        self.gated = act == "swiglu"
+        self.gated = act in _GATE
+        self.gate = _GATE.get(act)
+        if act == "geglu" and not concat_gate_up:
+            raise ValueError("the GEGLU kernels take Z = [Z_1 | Z_2] as one buffer: use concat_gate_up=True")
         # gate and up projection held as one [2*d_ff, d_model] weight (Sec. 5.2): one mask/compress pass, one
         # forward GEMM into a [p, 2*d_ff] buffer whose halves are Z_1 and Z_2, one input-gradient GEMM over
         # the 2*d_ff contraction instead of two accumulated ones, one weight-gradient GEMM
@@ -76,6 +84,9 @@ class SparseFFN:
         else:
             names = ("Wg", "Wu", "Wd") if self.gated else ("W1", "W2")
         self.w = {n: SparseWeight(weights[n]) for n in names}
+        self.bias = {n: (biases or {}).get(n) for n in names}
+        self.bias_grad = {n: torch.empty(b.numel(), dtype=torch.float32, device=b.device)
+                          for n, b in self.bias.items() if b is not None}
         d = weights[names[0]].shape[1]
         f = weights[names[-1]].shape[1]
         up = self.w[names[0]].W
@@ -105,27 +116,42 @@ class SparseFFN:
         for w in self.w.values():
             w.refresh(self._k, search)
 
+    def _fwd(self, Xw, name, out):
+        """out = Xw (M.*W)^T, plus the weight's bias if it has one."""
+        w = self.w[name]
+        if self.bias[name] is None:
+            self._k('spmm_fwd', s24.spmm_fwd, Xw, w.vals, w.meta, out)
+        else:
+            self._k('spmm_fwd', s24.spmm_fwd_bias, Xw, w.vals, w.meta, self.bias[name], out)
+
     def forward(self, X):
         w = self.w
         if self.concat and self.fuse_swiglu:
-            self._k('spmm_fwd', s24.spmm_fwd_swiglu, X, w["Wgu"].vals, w["Wgu"].meta, self.GU, self.H)
-            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["Wd"].vals, w["Wd"].meta, self.Y)
+            if self.gate == s24.GATE_SILU and self.bias["Wgu"] is None:
+                self._k('spmm_fwd', s24.spmm_fwd_swiglu, X, w["Wgu"].vals, w["Wgu"].meta, self.GU, self.H)
+            else:
+                self._k('spmm_fwd', s24.spmm_fwd_glu, X, w["Wgu"].vals, w["Wgu"].meta, self.bias["Wgu"], self.GU, self.H,
+                        self.gate)
+            self._fwd(self.H, "Wd", self.Y)
         elif self.concat:
-            self._k('spmm_fwd', s24.spmm_fwd, X, w["Wgu"].vals, w["Wgu"].meta, self.GU)
-            self._k('swiglu_fwd', s24.swiglu_fwd, self.G, self.U, self.H)
-            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["Wd"].vals, w["Wd"].meta, self.Y)
+            self._fwd(X, "Wgu", self.GU)
+            self._k('swiglu_fwd', s24.glu_fwd, self.GU, self.H, self.gate)
+            self._fwd(self.H, "Wd", self.Y)
         elif self.gated:
-            self._k('spmm_fwd', s24.spmm_fwd, X, w["Wg"].vals, w["Wg"].meta, self.G)
-            self._k('spmm_fwd', s24.spmm_fwd, X, w["Wu"].vals, w["Wu"].meta, self.U)
+            self._fwd(X, "Wg", self.G)
+            self._fwd(X, "Wu", self.U)
             self._k('swiglu_fwd', s24.swiglu_fwd, self.G, self.U, self.H)
-            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["Wd"].vals, w["Wd"].meta, self.Y)
+            self._fwd(self.H, "Wd", self.Y)
         else:
-            self._k('spmm_fwd', s24.spmm_fwd, X, w["W1"].vals, w["W1"].meta, self.Z)
+            self._fwd(X, "W1", self.Z)
             self._k('act_fwd', s24.act_fwd, self.Z, self.H, _ACT[self.act])
-            self._k('spmm_fwd', s24.spmm_fwd, self.H, w["W2"].vals, w["W2"].meta, self.Y)
+            self._fwd(self.H, "W2", self.Y)
         return self.Y
 
     def _dw(self, dYw, Xw, weight):
+        for name, w in self.w.items():   # the bias gradient of this weight: column sums of its output gradient
+            if w is weight and self.bias[name] is not None:
+                self._k('bias_grad', s24.bias_grad, dYw, self.bias_grad[name])
         if self.mvue:
             zv, zm = weight.pruned_grad_buffers(dYw.shape[0])
             self.draws += 1   # a fresh draw for every pruned operand of every step
@@ -145,7 +171,8 @@ class SparseFFN:
             fused = False
             if self.fuse_swiglu and self.fuse_gate_bwd is not False:
                 try:
-                    self._k('spmm_bwd_dx', s24.spmm_bwd_dx_swiglu, dY, w["Wd"].valsT, w["Wd"].metaT, self.GU, self.dGU)
+                    self._k('spmm_bwd_dx', s24.spmm_bwd_dx_glu, dY, w["Wd"].valsT, w["Wd"].metaT, self.GU, self.dGU,
+                            self.gate)
                     fused = self.fuse_gate_bwd = True
                 except s24.S24Error as e:
                     if e.status != -6:   # anything but "this shape takes the two-call route"
@@ -153,7 +180,7 @@ class SparseFFN:
                     self.fuse_gate_bwd = False
             if not fused:
                 self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["Wd"].valsT, w["Wd"].metaT, self.dH)
-                self._k('swiglu_bwd', s24.swiglu_bwd, self.dH, self.G, self.U, self.dG, self.dU)
+                self._k('swiglu_bwd', s24.glu_bwd, self.dH, self.GU, self.dGU, self.gate)
             self._dw(dY, self.H, w["Wd"])
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dGU, w["Wgu"].valsT, w["Wgu"].metaT, self.dX)
             self._dw(self.dGU, X, w["Wgu"])

@@ -26,7 +26,7 @@ class Workload:
     p: int          # tokens (batch x sequence, flattened)
     d_model: int
     d_ff: int
-    act: str        # "relu" | "gelu" | "swiglu"
+    act: str        # "relu" | "gelu" | "swiglu" | "geglu"
     dtype: str      # "f32" | "bf16" | "f16"
     seed: int
     std_w: float = 0.02
@@ -36,7 +36,7 @@ class Workload:
 
     @property
     def gated(self) -> bool:
-        return self.act == "swiglu"
+        return self.act in ("swiglu", "geglu")
 
     @property
     def weight_names(self):

@@ -74,8 +74,7 @@ def oracle_chain(wl, t, rnd):
 
 def run_chain(s24, wl, t, tol_act, tol_grad):
     from paper_2404_01847_amd.ffn import SparseFFN
-    bf16 = wl.dtype == "bf16"
-    rnd = (lambda a: oracle.round_bf16(a)) if bf16 else (lambda a: a.astype(np.float32))
+    rnd = lambda a: oracle.round_like(a, t["X"])
     ref = oracle_chain(wl, t, rnd)
     ffn = SparseFFN({n: dev_bf16(t[n]) for n in wl.weight_names}, t["X"].shape[0], wl.act, wl.lam)
     X, dY = dev_bf16(t["X"]), dev_bf16(t["dY"])
@@ -104,6 +103,61 @@ def test_reduced_bf16_whole_step(s24, act):
     # the chain compounds bf16 roundings: a 1-ulp flip upstream moves a downstream value by up to its own
     # rounding step, so the element bound is doubled here; the normwise bound stays
     run_chain(s24, wl, si.make(wl), (2e-2, 5e-3), (2e-2, 5e-3))
+
+
+@pytest.mark.parametrize("act", ["gelu", "swiglu"])
+def test_reduced_binary16_whole_step(s24, act):
+    # the same small layers in IEEE binary16, the paper's own precision: three more significant bits than bf16, so
+    # the normwise bound is five times tighter; the element bound is the doubled one of the bf16 chain for the
+    # same reason (a flipped rounding upstream moves a near-cancelled element downstream by its own rounding step)
+    # Output gradients of unit scale: binary16 training scales the loss precisely so that the gradients of a layer
+    # like this one (1e-5 .. 1e-4 at the workloads' 1e-2) do not fall among the subnormals, where they keep
+    # only a few bits.
+    wl = si.Workload("mini16_" + act, 200, 128, 448, act, "f16", 18, std_dy=1.0)
+    run_chain(s24, wl, si.make(wl), (2e-2, 1e-3), (2e-2, 1e-3))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_geglu_layer_with_biases_whole_step(s24, dtype):
+    """Sec. 5.2 as written: concatenated gate/up weight and bias, Z = X W^T + d, GELU(Z_1) .* Z_2, and the
+    backward of all of it including the bias gradients, against an oracle chain that rounds where the kernels do."""
+    from paper_2404_01847_amd.ffn import SparseFFN
+    wl = si.Workload("mini_geglu", 200, 128, 448, "geglu", dtype, 19, std_dy=1.0 if dtype == "f16" else 1e-2)
+    t = si.make(wl)
+    p, d, f = 200, wl.d_model, wl.d_ff
+    Wgu = np.concatenate([t["Wg"], t["Wu"]], axis=0)
+    bgu = si.random_matrix(191, (2 * f,), 0.3, dtype)
+    bd = si.random_matrix(192, (d,), 0.3, dtype)
+    rnd = lambda a: oracle.round_like(a, t["X"])
+    mgu, md = oracle.transposable_mask(Wgu), oracle.transposable_mask(t["Wd"])
+    cgu, cd = oracle.compress(Wgu, mgu), oracle.compress(t["Wd"], md)
+    X, dY = t["X"], t["dY"]
+    Z = rnd(oracle.spmm_fwd_bias(X, cgu[0], cgu[1], bgu))
+    H = rnd(oracle.glu_fwd(Z, oracle.GATE_GELU_ERF))
+    Y = oracle.spmm_fwd_bias(H, cd[0], cd[1], bd)
+    dH = rnd(oracle.spmm_bwd_dx(dY, cd[2], cd[3]))
+    dZ = rnd(oracle.glu_bwd(dH, Z, oracle.GATE_GELU_ERF))
+    dX = oracle.spmm_bwd_dx(dZ, cgu[2], cgu[3])
+
+    ffn = SparseFFN({n: dev_bf16(t[n]) for n in wl.weight_names}, p, "geglu", wl.lam, concat_gate_up=True,
+                    biases={"Wgu": dev_bf16(bgu), "Wd": dev_bf16(bd)})
+    ffn.step(dev_bf16(X), dev_bf16(dY))
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(ffn.w["Wgu"].mask), mgu) and np.array_equal(host_bits(ffn.w["Wd"].mask), md)
+    tol = (2e-2, 5e-3) if dtype == "bf16" else (2e-2, 1e-3)
+    widen = lambda a: a if a.dtype == np.float64 else si.to_f32(a).astype(np.float64)
+    for name, want in (("GU", Z), ("H", H), ("Y", Y), ("dGU", dZ), ("dX", dX)):
+        assert_close(host_f64(getattr(ffn, name)), widen(want), tol, f"geglu {dtype} {name}")
+    # Weight and bias gradients: sums over tokens in which a rounding flipped upstream shows at full size in the
+    # near-cancelled elements, so they are checked against the oracle applied to the kernels' own inputs (what
+    # the GPU stored for dZ and H); the chain values above already tie those inputs to the oracle.
+    dZ_gpu, H_gpu = host_bits(ffn.dGU), host_bits(ffn.H)
+    g_gu = oracle.masked_decay(oracle.dense_dw(dZ_gpu, X).astype(np.float32), Wgu, mgu, wl.lam)
+    g_d = oracle.masked_decay(oracle.dense_dw(dY, H_gpu).astype(np.float32), t["Wd"], md, wl.lam)
+    assert_close(host_f64(ffn.w["Wgu"].grad), g_gu, F32_TOL, "geglu grad Wgu")
+    assert_close(host_f64(ffn.w["Wd"].grad), g_d, F32_TOL, "geglu grad Wd")
+    assert_close(host_f64(ffn.bias_grad["Wgu"]), oracle.bias_grad(dZ_gpu), F32_TOL, "geglu bias grad gu")
+    assert_close(host_f64(ffn.bias_grad["Wd"]), oracle.bias_grad(dY), F32_TOL, "geglu bias grad d")
 
 
 # ------------------------------------------------------------------ full-size workloads

@@ -143,6 +143,54 @@ def test_elementwise_argument_errors(lib):
     assert lib.s24_act_fwd(P, P, 0, 0, 1, None) == OK
 
 
+def test_gated_family_argument_errors(lib):
+    R, Cm = 0, 1
+    # s24_glu_fwd(Z, lz, ldz, H, lh, ldh, p, f, gate, dt, stream)
+    assert lib.s24_glu_fwd(P, R, 32, P, R, 16, 4, 12, 1, 2, None) == SHAPE             # f % 8
+    assert lib.s24_glu_fwd(P, R, 24, P, R, 16, 4, 16, 1, 2, None) == SHAPE             # ldz < 2f
+    assert lib.s24_glu_fwd(P, Cm, 8, P, R, 16, 4, 16, 1, 2, None) == SHAPE             # column-major needs p % 8
+    assert lib.s24_glu_fwd(P, Cm, 4, P, Cm, 8, 8, 16, 1, 2, None) == SHAPE             # ldz < p
+    assert lib.s24_glu_fwd(P, 2, 32, P, R, 16, 4, 16, 1, 2, None) == DTYPE             # layout enum
+    assert lib.s24_glu_fwd(P, R, 32, P, R, 16, 4, 16, 5, 2, None) == DTYPE             # gate enum
+    assert lib.s24_glu_fwd(P, R, 32, P, R, 16, 4, 16, 1, 3, None) == DTYPE
+    assert lib.s24_glu_fwd(None, R, 32, P, R, 16, 4, 16, 1, 2, None) == NULL
+    assert lib.s24_glu_fwd(P + 8, R, 32, P, R, 16, 4, 16, 1, 2, None) == ALIGN
+    assert lib.s24_glu_fwd(None, R, 32, None, R, 16, 0, 16, 1, 2, None) == OK
+    # s24_glu_bwd(dH, lh, ldh, Z, lz, ldz, dZ, p, f, gate, dt, stream)
+    assert lib.s24_glu_bwd(P, R, 16, P, R, 32, None, 4, 16, 0, 1, None) == NULL
+    assert lib.s24_glu_bwd(P, R, 8, P, R, 32, P, 4, 16, 0, 1, None) == SHAPE           # ldh < f
+    assert lib.s24_glu_bwd(P, Cm, 8, P, R, 32, P, 4, 16, 0, 1, None) == SHAPE          # mixed layouts need p % 8
+    assert lib.s24_glu_bwd(P, R, 16, P, R, 32, P + 2, 4, 16, 0, 1, None) == ALIGN
+    # s24_bias_grad(dZ, layout, ld, p, n, db, beta, dt, stream)
+    assert lib.s24_bias_grad(P, R, 16, 4, 12, P, 0.0, 1, None) == SHAPE                # n % 8
+    assert lib.s24_bias_grad(P, R, 8, 4, 16, P, 0.0, 1, None) == SHAPE                 # ld < n
+    assert lib.s24_bias_grad(P, Cm, 8, 4, 16, P, 0.0, 1, None) == SHAPE                # column-major needs p % 8
+    assert lib.s24_bias_grad(P, R, 16, 4, 16, P, 0.5, 1, None) == UNSUP
+    assert lib.s24_bias_grad(P, R, 16, 4, 16, None, 0.0, 1, None) == NULL
+    assert lib.s24_bias_grad(P, R, 16, 4, 16, P + 2, 0.0, 1, None) == ALIGN
+    assert lib.s24_bias_grad(P, R, 16, 4, 16, P, 0.0, 8, None) == DTYPE
+    assert lib.s24_bias_grad(None, R, 16, 4, 0, None, 0.0, 1, None) == OK
+    # s24_spmm_fwd_bias(X, vals, meta, bias, Y, p, q, r, dt, stream)
+    assert lib.s24_spmm_fwd_bias(P, P, P, P, P, 4, 96, 16, 2, None) == SHAPE
+    assert lib.s24_spmm_fwd_bias(P, P, P, P + 4, P, 4, 64, 16, 2, None) == ALIGN       # bias 8-byte aligned
+    assert lib.s24_spmm_fwd_bias(P, P, None, None, P, 4, 64, 16, 2, None) == NULL
+    assert lib.s24_spmm_fwd_bias(P, P, P, None, P, 0, 64, 16, 2, None) == OK
+    # s24_spmm_fwd_glu(X, vals, meta, bias, GU, H, p, q, f, gate, dt, stream)
+    assert lib.s24_spmm_fwd_glu(P, P, P, None, P, P, 4, 64, 24, 1, 2, None) == SHAPE   # f % 16
+    assert lib.s24_spmm_fwd_glu(P, P, P, None, P, P, 4, 64, 16, 3, 2, None) == DTYPE   # gate
+    assert lib.s24_spmm_fwd_glu(P, P, P, None, P, None, 4, 64, 16, 1, 2, None) == NULL
+    assert lib.s24_spmm_fwd_glu(P, P, P, None, P, P, 0, 64, 16, 1, 2, None) == OK
+    # s24_spmm_bwd_dx_glu(dY, valsT, metaT, GU, dGU, p, f, r, gate, dt, stream)
+    assert lib.s24_spmm_bwd_dx_glu(P, P, P, P, P, 4, 16, 96, 1, 2, None) == SHAPE
+    assert lib.s24_spmm_bwd_dx_glu(P, P, P, P, P, 4, 16, 64, 7, 2, None) == DTYPE
+    assert lib.s24_spmm_bwd_dx_glu(P, P, P, P, P, 4, 16, 64, 1, 2, None) == UNSUP      # too few tiles
+    assert lib.s24_spmm_bwd_dx_glu(P, P, P, P, P, 4, 16, 64, 1, 0, None) == UNSUP      # fp32
+    # binary16 is a valid dtype everywhere a dtype is taken
+    assert lib.s24_transposable_mask(P, 2, 6, 8, 8, P, None, None) == SHAPE
+    assert lib.s24_spmm_fwd(P, P, P, P, 0, 64, 16, 2, None) == OK
+    assert lib.s24_mvue24(P, 2, 0, 16, 16, 1, None, None, None) == OK
+
+
 def test_binding_refuses_to_run_without_library(monkeypatch, tmp_path):
     from paper_2404_01847_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
