@@ -345,6 +345,88 @@ def gated_activation_measurements(torch, s24):
     return out
 
 
+def block_level_measurements(torch, s24, wl, ffn, X, dY, weights):
+    """The paper's block-level comparison (Sec. 6, speed-up of a single FFN layer and of a single transformer block,
+    forward + backward): the 2:4 FFN step of this library next to the same layer run densely through the library's own
+    dense GEMMs, and both next to the rest of the block (two layer norms, QKV and output projections, causal attention),
+    which is dense in either case and is run here by PyTorch's stock operators, since attention is not part of this
+    library.  Reported: the three times and the two speed-ups they imply."""
+    F = torch.nn.functional
+    p, d, f = wl.p, wl.d_model, wl.d_ff
+    dt = X.dtype
+    reps = 10
+    ms_sparse = _time_ms(torch, lambda: ffn.step(X, dY), reps)
+    # the dense layer: same call sequence with s24_dense_gemm in place of the sparse GEMMs (the input-gradient GEMMs
+    # read transposed copies of the weights, made once), no mask search, no compress, no decay
+    if wl.gated:
+        Wup = torch.cat([weights["Wg"], weights["Wu"]], dim=0).contiguous()
+        Wdn = weights["Wd"]
+    else:
+        Wup, Wdn = weights["W1"], weights["W2"]
+    WupT, WdnT = Wup.t().contiguous(), Wdn.t().contiguous()
+    nz = Wup.shape[0]
+    new = lambda *shape: torch.empty(shape, dtype=dt, device=X.device)
+    Z, H, Y, dH, dZ, dX = new(p, nz), new(p, f), new(p, d), new(p, f), new(p, nz), new(p, d)
+    gUp = torch.empty(Wup.shape, dtype=torch.float32, device=X.device)
+    gDn = torch.empty(Wdn.shape, dtype=torch.float32, device=X.device)
+    gate = s24.GATE_GELU_ERF if wl.act == "geglu" else s24.GATE_SILU
+    act = s24.ACT_RELU if wl.act == "relu" else s24.ACT_GELU_ERF
+
+    def dense_step():
+        s24.dense_gemm(X, Wup, Z)
+        if wl.gated:
+            s24.glu_fwd(Z, H, gate)
+        else:
+            s24.act_fwd(Z, H, act)
+        s24.dense_gemm(H, Wdn, Y)
+        s24.dense_gemm(dY, WdnT, dH)
+        s24.dense_dw(dY, H, gDn)
+        if wl.gated:
+            s24.glu_bwd(dH, Z, dZ, gate)
+        else:
+            s24.act_bwd(dH, Z, dZ, act)
+        s24.dense_gemm(dZ, WupT, dX)
+        s24.dense_dw(dZ, X, gUp)
+
+    ms_dense = _time_ms(torch, dense_step, reps)
+    out = {"ffn_sparse_ms": round(ms_sparse, 4), "ffn_dense_ms": round(ms_dense, 4),
+           "ffn_speedup": round(ms_dense / ms_sparse, 3),
+           "ffn_dense_note": "the same layer through s24_dense_gemm / s24_dense_dw (dense MFMA kernels of this library, "
+                             "transposed weight copies prepared outside the timed region)"}
+    # the rest of the block, dense in both cases: PyTorch operators (not this library's code)
+    try:
+        hd = 128 if d % 128 == 0 and d >= 2048 else 64
+        heads = d // hd
+        seq = 2048 if p % 2048 == 0 and d >= 4096 else 1024
+        batch = p // seq
+        g = torch.Generator(device="cuda").manual_seed(11)
+        mk = lambda *shape: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(dt).requires_grad_()
+        Wqkv, Wo = mk(3 * d, d), mk(d, d)
+        ln1w, ln1b, ln2w, ln2b = (torch.ones(d, device="cuda", dtype=dt).requires_grad_() for _ in range(4))
+        xin = X.detach().clone().requires_grad_()
+        gout = dY.detach().clone()
+
+        def attention_part():
+            h = F.layer_norm(xin, (d,), ln1w, ln1b)
+            qkv = F.linear(h, Wqkv).view(batch, seq, 3, heads, hd).permute(2, 0, 3, 1, 4)
+            a = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2], is_causal=True)
+            y = xin + F.linear(a.transpose(1, 2).reshape(p, d), Wo)
+            z = F.layer_norm(y, (d,), ln2w, ln2b)   # the FFN's input; its gradient arrives from the FFN
+            torch.autograd.backward([z, y], [gout, gout])
+            for t in (xin, Wqkv, Wo, ln1w, ln1b, ln2w, ln2b):
+                t.grad = None
+
+        ms_attn = _time_ms(torch, attention_part, 5)
+        out.update({"rest_of_block_ms": round(ms_attn, 4),
+                    "rest_of_block": f"PyTorch: 2 layer norms, QKV and output projections, causal attention, "
+                                     f"{heads} heads x {hd}, {batch} x {seq} tokens, forward + backward",
+                    "block_sparse_ms": round(ms_attn + ms_sparse, 4), "block_dense_ms": round(ms_attn + ms_dense, 4),
+                    "block_speedup": round((ms_attn + ms_dense) / (ms_attn + ms_sparse), 3)})
+    except Exception as e:   # the comparison above stands on its own if PyTorch's attention is unavailable here
+        out["rest_of_block_error"] = f"{type(e).__name__}: {e}"[:300]
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -369,6 +451,9 @@ def main():
     ap.add_argument("--geglu-bias", action="store_true",
                     help="gated workloads only: the layer of Sec. 5.2 as written, GELU gate and biases on both projections "
                          "(bias add in the GEMM epilogues, bias gradients as their own kernel)")
+    ap.add_argument("--block", action="store_true",
+                    help="also time the same layer run densely and the dense rest of a transformer block (PyTorch attention): "
+                         "the FFN-level and block-level speed-ups of the paper's Sec. 6")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device-to-device copy five times (reference for HBM byte counters) and exit")
     args = ap.parse_args()
@@ -432,6 +517,10 @@ def main():
     value = wl.gemm_flops / (ms_per_step * 1e-3) / 1e12
 
     extras = None if args.no_extras else side_measurements(torch, s24, wl, ffn, X, dY, {n: dev[n] for n in wl.weight_names})
+
+    if args.block:
+        extras = dict(extras or {})
+        extras["block_level"] = block_level_measurements(torch, s24, wl, ffn, X, dY, {n: dev[n] for n in wl.weight_names})
 
     model = kernel_model(wl)
     kernels = {}
