@@ -277,7 +277,7 @@ template <typename T>
 __device__ __forceinline__ void add_bias(f32x16 (&acc)[4][2], const uint16_t *__restrict__ bias, int limit, int lane)
 {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             const int m = min(32 * mi + 8 * g4 + 4 * (lane >> 5), limit - 4);
@@ -288,6 +288,9 @@ __device__ __forceinline__ void add_bias(f32x16 (&acc)[4][2], const uint16_t *__
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[mi][ni][4 * g4 + e] += b4[e];
         }
+        // four loads in flight at a time: all sixteen at once would not fit beside the 128 accumulators
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 // 16-byte chunk c (eight bf16, columns 8c .. 8c+7) of row nl of a staged tile
 __device__ __forceinline__ uint4 staged_chunk(const unsigned char *estage, int nl, int c)
@@ -322,7 +325,9 @@ __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned
 // written; its rounding to the storage type goes straight into the backward of the activation, dG = dH U act'(G),
 // dU = dH act(G), with G and U read from, and dG and dU written to, the halves of [N][2M] buffers.
 // T is the storage type of every 16-bit buffer (bf16 bits or binary16).
-template <typename T, bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false, int GATE = S24_GATE_SILU>
+// BIAS compiles the bias add into the plain forward kernel (the gated forward tests the pointer at run time; the
+// plain kernel without a bias keeps its register budget, which the extra loads would push into scratch).
+template <typename T, bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false, int GATE = S24_GATE_SILU, bool BIAS = false>
 __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
@@ -488,9 +493,10 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     }
     static_assert(3 * EWAVE <= STAGE, "three wave tiles must fit one ring stage");
     auto region = [&](int w) { return (w < 3 ? s0 : (w < 6 ? s1 : s2)) + (w % 3) * EWAVE; };
-    if (!GATE_BWD && bias != nullptr) {   // wave-uniform
-        if (SWIGLU) add_bias<T>(acc, bias + (wm ? F : 0) + m0, F - m0, lane);
-        else add_bias<T>(acc, bias + m0 + 128 * wm, M - (m0 + 128 * wm), lane);
+    if constexpr (SWIGLU) {
+        if (bias != nullptr) add_bias<T>(acc, bias + (wm ? F : 0) + m0, F - m0, lane);   // wave-uniform
+    } else if constexpr (BIAS) {
+        add_bias<T>(acc, bias + m0 + 128 * wm, M - (m0 + 128 * wm), lane);   // launched only with a bias
     }
     if constexpr (GATE_BWD) {
         unsigned char *est = region(wave);
@@ -1319,10 +1325,13 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
         S24_WITH_16BIT_TYPE(dt, {
             if (accum)
                 hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, true>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
-                                   tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, d);
+                                   tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, nullptr);
+            else if (d != nullptr)
+                hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, true>), grid, block, 0, st, b,
+                                   av, Am, o, (int)N, (int)K, (int)M, tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, d);
             else
                 hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M,
-                                   tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, d);
+                                   tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, nullptr);
         });
     } else {
         const dim3 grid(ceil_div(M, BM), ceil_div(N, BN)), block(kThreads);
