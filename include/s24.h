@@ -125,6 +125,19 @@ int s24_spmm_fwd_glu(const void *X, const void *vals, const uint16_t *meta, cons
 int s24_spmm_bwd_dx_glu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
                         int64_t p, int64_t f, int64_t r, s24_gate gate, s24_dtype dt, void *stream);
 
+/* Forward of an ungated layer with its activation in the same pass (Eq. 2; the ReLU / GELU layers of the
+ * GPT-2-shaped workloads): Z[p][r] = X (M.*W)^T + bias (bias may be NULL) and H[p][r] = act(Z), Z rounded to the
+ * storage type before H is formed: the same bits as s24_spmm_fwd_bias followed by s24_act_fwd. */
+int s24_spmm_fwd_act(const void *X, const void *vals, const uint16_t *meta, const void *bias, void *Z, void *H,
+                     int64_t p, int64_t q, int64_t r, s24_act act, s24_dtype dt, void *stream);
+
+/* Input gradient of the second projection of an ungated layer with the backward of the activation in the same pass
+ * (Eq. 3): dZ[p][f] = (dY[p][r] (M.*W_2)) .* act'(Z), the product rounded to the storage type before the
+ * multiplication: the same bits as s24_spmm_bwd_dx followed by s24_act_bwd.  Same S24_ERR_UNSUPPORTED rule as
+ * s24_spmm_bwd_dx_glu.  r multiple of 64; f of 16. */
+int s24_spmm_bwd_dx_act(const void *dY, const void *valsT, const uint16_t *metaT, const void *Z, void *dZ,
+                        int64_t p, int64_t f, int64_t r, s24_act act, s24_dtype dt, void *stream);
+
 /* Forward of a gated layer in one pass (Eq. 2 + Sec. 5.2): the compressed operand holds the stacked weight
  * [W_gate; W_up] (2f rows of q, gate rows first: vals [q/64][2f][32], meta [q/64][2f][4]).  Writes
  * GU[p][2f] = X . (M.*W)^T (its halves are G = Z_1 and U = Z_2, both needed by the backward pass) and

@@ -35,6 +35,8 @@ _SIGNATURES = {
     "s24_glu_fwd": (_int, [_vp, _int, _i64, _vp, _int, _i64, _i64, _i64, _int, _int, _vp]),
     "s24_glu_bwd": (_int, [_vp, _int, _i64, _vp, _int, _i64, _vp, _i64, _i64, _int, _int, _vp]),
     "s24_bias_grad": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _f32, _int, _vp]),
+    "s24_spmm_fwd_act": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp]),
+    "s24_spmm_bwd_dx_act": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp]),
     "s24_spmm_fwd_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_spmm_bwd_dx": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_spmm_bwd_dx_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
@@ -189,6 +191,24 @@ def bias_grad(dZ, db, beta=0.0, layout=ROW_MAJOR):
     _check(lib().s24_bias_grad(_ptr(dZ), layout, _ld(dZ, layout), p, n, _ptr(db), beta, _dt(dZ), _stream()),
            "s24_bias_grad")
     return db
+
+
+def spmm_fwd_act(X, vals, meta, bias, Z, H, act):
+    """Z = X (M.*W)^T + bias (bias may be None) and H = act(Z) in one pass."""
+    p, q = X.shape
+    r = vals.shape[1]
+    _check(lib().s24_spmm_fwd_act(_ptr(X), _ptr(vals), _ptr(meta), _ptr(bias), _ptr(Z), _ptr(H), p, q, r, act, _dt(X),
+                                  _stream()), "s24_spmm_fwd_act")
+    return Z, H
+
+
+def spmm_bwd_dx_act(dY, valsT, metaT, Z, dZ, act):
+    """dZ = (dY (M.*W_2)) .* act'(Z); raises S24Error with status -6 for shapes that only the two-call route covers."""
+    p, r = dY.shape
+    f = valsT.shape[1]
+    _check(lib().s24_spmm_bwd_dx_act(_ptr(dY), _ptr(valsT), _ptr(metaT), _ptr(Z), _ptr(dZ), p, f, r, act, _dt(dY),
+                                     _stream()), "s24_spmm_bwd_dx_act")
+    return dZ
 
 
 def spmm_fwd_swiglu(X, vals, meta, GU, H):

@@ -316,6 +316,21 @@ __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned
     }
 }
 
+// Ungated activation and its slope, chosen at compile time (the same arithmetic as the stand-alone kernels)
+template <int ACT> __device__ __forceinline__ float act_value(float z)
+{
+    if (ACT == S24_ACT_RELU) return z > 0.0f ? z : 0.0f;
+    return s24_gelu(z);
+}
+template <int ACT> __device__ __forceinline__ float act_slope(float z)
+{
+    if (ACT == S24_ACT_RELU) return z > 0.0f ? 1.0f : 0.0f;
+    return s24_gelu_slope(z);
+}
+
+// ACT_MODE 1 (forward of an ungated layer): the rounded tile Z is written to Out and H = act(Z) beside it, as the
+// stand-alone activation kernel would form it from the stored Z.  ACT_MODE 2 (input gradient of the second
+// projection): the rounded tile of dH is not written but multiplied by act'(Z), Z read from `GU`, into Out = dZ.
 // SWIGLU (forward of a gated layer, Sec. 5.2): the compressed operand holds the gate rows [0, F) and the up rows
 // [F, 2F) of one stacked weight (M = 2F).  A workgroup tile then takes 128 gate features and the 128 up features
 // of the same indices, its epilogue pairs them and writes G and U (the halves of Out, row stride M) and
@@ -327,7 +342,8 @@ __device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned
 // T is the storage type of every 16-bit buffer (bf16 bits or binary16).
 // BIAS compiles the bias add into the plain forward kernel (the gated forward tests the pointer at run time; the
 // plain kernel without a bias keeps its register budget, which the extra loads would push into scratch).
-template <typename T, bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false, int GATE = S24_GATE_SILU, bool BIAS = false>
+template <typename T, bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false, int GATE = S24_GATE_SILU, bool BIAS = false,
+          int ACT_MODE = 0, int ACT = S24_ACT_RELU>
 __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
@@ -338,6 +354,7 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
                                                               const uint16_t *__restrict__ bias = nullptr)
 {
     static_assert(!(ACCUM && (SWIGLU || GATE_BWD)) && !(SWIGLU && GATE_BWD), "the gated epilogues overwrite");
+    static_assert(ACT_MODE == 0 || !(ACCUM || SWIGLU || GATE_BWD), "one epilogue at a time");
     const ClockStamp t_start = clock_now();
     // One array per ring stage: the compiler then knows which stage a direct-to-LDS
     // copy writes and does not make reads of the other stages wait for it.
@@ -534,6 +551,52 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
                 *reinterpret_cast<uint4 *>(Out + o) = make_uint4(dgw[0], dgw[1], dgw[2], dgw[3]);
                 *reinterpret_cast<uint4 *>(Out + o + M) = make_uint4(duw[0], duw[1], duw[2], duw[3]);
             }
+        }
+    } else if constexpr (ACT_MODE == 2) {
+        unsigned char *est = region(wave);
+        stage_tile<T>(acc, est, lane);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
+        asm volatile("" ::: "memory");
+        const int n_base = n0 + 64 * wn, m_base = m0 + 128 * wm;
+        const int c = lane & 15, m = min(m_base + 8 * c, M - 8);
+        uint4 z[16];   // the accumulators are dead: all loads of Z go out before anything is computed
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            z[j] = *reinterpret_cast<const uint4 *>(GU + (int64_t)min(n_base + 4 * j + (lane >> 4), N - 1) * M + m);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int nl = 4 * j + (lane >> 4), n = n_base + nl;
+            const uint4 dh = staged_chunk(est, nl, c);
+            const uint32_t dw[4] = {dh.x, dh.y, dh.z, dh.w}, zw[4] = {z[j].x, z[j].y, z[j].z, z[j].w};
+            uint32_t o[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                o[k] = s24_num<T>::pack2(s24_num<T>::lo(dw[k]) * act_slope<ACT>(s24_num<T>::lo(zw[k])),
+                                         s24_num<T>::hi(dw[k]) * act_slope<ACT>(s24_num<T>::hi(zw[k])));
+            if (n < N && m_base + 8 * c < M)   // M is a multiple of 16: a chunk is all in or all out
+                *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + m) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    } else if constexpr (ACT_MODE == 1) {
+        unsigned char *est = region(wave);
+        stage_tile<T>(acc, est, lane);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));
+        asm volatile("" ::: "memory");
+        const int n_base = n0 + 64 * wn, m_base = m0 + 128 * wm;
+#pragma unroll 4
+        for (int j = 0; j < 16; ++j) {
+            const int nl = 4 * j + (lane >> 4), c = lane & 15;
+            const int n = n_base + nl, m = m_base + 8 * c;
+            if (n >= N || m >= M) continue;
+            const uint4 zc = staged_chunk(est, nl, c);
+            const uint32_t zw[4] = {zc.x, zc.y, zc.z, zc.w};
+            uint32_t h[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                h[k] = s24_num<T>::pack2(act_value<ACT>(s24_num<T>::lo(zw[k])), act_value<ACT>(s24_num<T>::hi(zw[k])));
+            *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + m) = zc;
+            *reinterpret_cast<uint4 *>(H + (int64_t)n * M + m) = make_uint4(h[0], h[1], h[2], h[3]);
         }
     } else if constexpr (!SWIGLU) {
         staged_store<T>(acc, region(wave), Out, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
@@ -1443,6 +1506,66 @@ extern "C" int s24_spmm_bwd_dx_swiglu(const void *dY, const void *valsT, const u
                                       int64_t p, int64_t f, int64_t r, s24_dtype dt, void *stream)
 {
     return s24_spmm_bwd_dx_glu(dY, valsT, metaT, GU, dGU, p, f, r, S24_GATE_SILU, dt, stream);
+}
+
+extern "C" int s24_spmm_fwd_act(const void *X, const void *vals, const uint16_t *meta, const void *bias, void *Z, void *H,
+                                int64_t p, int64_t q, int64_t r, s24_act act, s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(act == S24_ACT_RELU || act == S24_ACT_GELU_ERF, S24_ERR_DTYPE);
+    S24_REQUIRE(q % 64 == 0 && r % 16 == 0 && q > 0, S24_ERR_SHAPE);
+    const int rc = check_gemm(X, vals, Z, p, q, r, dt, p * r);
+    if (rc != S24_OK || p * r == 0) return rc;
+    S24_REQUIRE(meta != nullptr && H != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(meta, 4) && s24_aligned(H, 16) && s24_aligned(bias, 8), S24_ERR_ALIGN);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt != S24_F32 && fills_chip_256(r, p)) {
+        const int tiles_m = (int)ceil_div(r, big::BM), tiles_n = (int)ceil_div(p, big::BN);
+        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
+        auto *x = static_cast<const uint16_t *>(X), *av = static_cast<const uint16_t *>(vals), *d = static_cast<const uint16_t *>(bias);
+        auto *z = static_cast<uint16_t *>(Z), *h = static_cast<uint16_t *>(H);
+#define S24_LAUNCH_FWD_ACT(A, BIASED)                                                                                          \
+    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, BIASED, 1, A>), grid, block, 0, st, x, av, \
+                       meta, z, (int)p, (int)q, (int)r, tiles_m, tiles_n, g_clock_probe, h, 0, nullptr, d)
+        S24_WITH_16BIT_TYPE(dt, {
+            if (act == S24_ACT_RELU && d != nullptr) S24_LAUNCH_FWD_ACT(S24_ACT_RELU, true);
+            else if (act == S24_ACT_RELU) S24_LAUNCH_FWD_ACT(S24_ACT_RELU, false);
+            else if (d != nullptr) S24_LAUNCH_FWD_ACT(S24_ACT_GELU_ERF, true);
+            else S24_LAUNCH_FWD_ACT(S24_ACT_GELU_ERF, false);
+        });
+#undef S24_LAUNCH_FWD_ACT
+        return s24_launch_status();
+    }
+    // shapes the fused epilogue does not cover: the GEMM, then the stand-alone activation
+    const int rc2 = launch_spmm(X, vals, meta, Z, p, q, r, 0.0f, dt, st, bias);
+    if (rc2 != S24_OK) return rc2;
+    return s24_act_fwd(Z, H, p * r, act, dt, st);
+}
+
+extern "C" int s24_spmm_bwd_dx_act(const void *dY, const void *valsT, const uint16_t *metaT, const void *Z, void *dZ,
+                                   int64_t p, int64_t f, int64_t r, s24_act act, s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(act == S24_ACT_RELU || act == S24_ACT_GELU_ERF, S24_ERR_DTYPE);
+    S24_REQUIRE(r % 64 == 0 && f % 16 == 0 && r > 0, S24_ERR_SHAPE);
+    const int rc = check_gemm(dY, valsT, dZ, p, f, r, dt, p * f);
+    if (rc != S24_OK || p * f == 0) return rc;
+    S24_REQUIRE(metaT != nullptr && Z != nullptr, S24_ERR_NULL);
+    S24_REQUIRE(s24_aligned(metaT, 4) && s24_aligned(Z, 16), S24_ERR_ALIGN);
+    // only the large-tile 16-bit kernel carries this epilogue; other shapes take s24_spmm_bwd_dx + s24_act_bwd
+    S24_REQUIRE(dt != S24_F32 && fills_chip_256(f, p), S24_ERR_UNSUPPORTED);
+    const int tiles_m = (int)ceil_div(f, big::BM), tiles_n = (int)ceil_div(p, big::BN);
+    const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto *dy = static_cast<const uint16_t *>(dY), *av = static_cast<const uint16_t *>(valsT), *z = static_cast<const uint16_t *>(Z);
+    auto *o = static_cast<uint16_t *>(dZ);
+#define S24_LAUNCH_BWD_ACT(A)                                                                                                 \
+    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, false, 2, A>), grid, block, 0, st, dy, av, \
+                       metaT, o, (int)p, (int)r, (int)f, tiles_m, tiles_n, g_clock_probe, nullptr, 0, z, nullptr)
+    S24_WITH_16BIT_TYPE(dt, {
+        if (act == S24_ACT_RELU) S24_LAUNCH_BWD_ACT(S24_ACT_RELU);
+        else S24_LAUNCH_BWD_ACT(S24_ACT_GELU_ERF);
+    });
+#undef S24_LAUNCH_BWD_ACT
+    return s24_launch_status();
 }
 
 extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r, s24_dtype dt,

@@ -63,7 +63,7 @@ class SparseFFN:
         self.act, self.lam, self.p = act, lam, p
         # Eq. 4 / Eq. 6: the weight gradient from an unbiasedly 2:4-pruned output gradient, as a sparse GEMM
         self.mvue, self.seed = mvue, seed
-        self.fuse_swiglu = fuse_swiglu   # with one gate+up weight: SwiGLU in the epilogue of its forward GEMM
+        self.fuse_swiglu = fuse_swiglu   # the activation in the epilogue of the first projection's forward GEMM
         self.fuse_gate_bwd = None        # and its backward in the epilogue of the dH GEMM where the shape allows (probed)
         self.mask_interval = mask_interval   # the mask is searched every mask_interval-th step (Sec. 5.1: l = 40)
         self.steps_done = 0
@@ -142,6 +142,10 @@ class SparseFFN:
             self._fwd(X, "Wu", self.U)
             self._k('swiglu_fwd', s24.swiglu_fwd, self.G, self.U, self.H)
             self._fwd(self.H, "Wd", self.Y)
+        elif self.fuse_swiglu:   # the activation in the epilogue of the first projection's GEMM
+            self._k('spmm_fwd', s24.spmm_fwd_act, X, w["W1"].vals, w["W1"].meta, self.bias["W1"], self.Z, self.H,
+                    _ACT[self.act])
+            self._fwd(self.H, "W2", self.Y)
         else:
             self._fwd(X, "W1", self.Z)
             self._k('act_fwd', s24.act_fwd, self.Z, self.H, _ACT[self.act])
@@ -193,9 +197,20 @@ class SparseFFN:
             self._dw(self.dG, X, w["Wg"])
             self._dw(self.dU, X, w["Wu"])
         else:
-            self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["W2"].valsT, w["W2"].metaT, self.dH)
+            fused = False
+            if self.fuse_swiglu and self.fuse_gate_bwd is not False:
+                try:
+                    self._k('spmm_bwd_dx', s24.spmm_bwd_dx_act, dY, w["W2"].valsT, w["W2"].metaT, self.Z, self.dZ,
+                            _ACT[self.act])
+                    fused = self.fuse_gate_bwd = True
+                except s24.S24Error as e:
+                    if e.status != -6:   # anything but "this shape takes the two-call route"
+                        raise
+                    self.fuse_gate_bwd = False
+            if not fused:
+                self._k('spmm_bwd_dx', s24.spmm_bwd_dx, dY, w["W2"].valsT, w["W2"].metaT, self.dH)
+                self._k('act_bwd', s24.act_bwd, self.dH, self.Z, self.dZ, _ACT[self.act])
             self._dw(dY, self.H, w["W2"])
-            self._k('act_bwd', s24.act_bwd, self.dH, self.Z, self.dZ, _ACT[self.act])
             self._k('spmm_bwd_dx', s24.spmm_bwd_dx, self.dZ, w["W1"].valsT, w["W1"].metaT, self.dX)
             self._dw(self.dZ, X, w["W1"])
         return self.dX

@@ -252,6 +252,72 @@ def test_spmm_bwd_dx_glu_equals_the_separate_calls_and_the_oracle(s24, dtype, ga
     assert_close(host_f64(dGU[torch.from_numpy(rows).cuda()]), ref, ACT_TOL[dtype], f"dGU {gate}")
 
 
+# ------------------------------------------------------------------ ungated activation in the GEMM epilogues
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("act", ["relu", "gelu"])
+@pytest.mark.parametrize("case", [(300, 128, 272), (2100, 192, 6224)])     # fallback route / fused epilogue, ragged
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_spmm_fwd_act_equals_the_separate_calls_and_the_oracle(s24, dtype, act, case, with_bias):
+    p, q, r = case
+    if dtype == "f32" and p > 1000:
+        pytest.skip("fp32 runs the plain kernels at every size: covered by the small case")
+    a_lib, a_orc = (s24.ACT_RELU, oracle.ACT_RELU) if act == "relu" else (s24.ACT_GELU_ERF, oracle.ACT_GELU_ERF)
+    X = si.random_matrix(1800 + p, (p, q), 1.0, dtype)
+    W = si.random_matrix(1801 + p, (r, q), 0.02, dtype)
+    b = si.random_matrix(1802, (r,), 0.5, dtype) if with_bias else None
+    mask = oracle.transposable_mask(W)
+    vals, meta, _, _ = oracle.compress(W, mask)
+    vp, mp = oracle.pack(vals, meta)
+    d_X, d_v, d_m = dev_bf16(X), dev_bf16(vp), dev(mp)
+    d_b = dev_bf16(b) if with_bias else None
+    Z = torch.full((p, r), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    H = torch.full((p, r), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    s24.spmm_fwd_act(d_X, d_v, d_m, d_b, Z, H, a_lib)
+    Z2, H2 = torch.empty_like(Z), torch.empty_like(H)
+    s24.spmm_fwd_bias(d_X, d_v, d_m, d_b, Z2)
+    s24.act_fwd(Z2, H2, a_lib)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(Z), bits(Z2)) and torch.equal(bits(H), bits(H2))       # same bits as the separate calls
+    rows = sample_rows(p, p)
+    ridx = torch.from_numpy(rows).cuda()
+    Zr = oracle.spmm_fwd_bias(X, vals, meta, b, rows=rows) if with_bias else oracle.spmm_fwd(X, vals, meta, rows=rows)
+    assert_close(host_f64(Z[ridx]), Zr, tol_for(dtype), f"Z {case}")
+    assert_close(host_f64(H[ridx]), oracle.act_fwd(oracle.round_like(Zr, X), a_orc), ACT_TOL[dtype], f"H {case}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("act", ["relu", "gelu"])
+def test_spmm_bwd_dx_act_equals_the_separate_calls_and_the_oracle(s24, dtype, act):
+    p, f, r = 1800, 6224, 192          # >= 192 tiles of 256 x 256, ragged
+    a_lib, a_orc = (s24.ACT_RELU, oracle.ACT_RELU) if act == "relu" else (s24.ACT_GELU_ERF, oracle.ACT_GELU_ERF)
+    dY = si.random_matrix(1900, (p, r), 1e-2, dtype)
+    W2 = si.random_matrix(1901, (r, f), 0.02, dtype)
+    Zh = si.random_matrix(1902, (p, f), 1.0, dtype)
+    Zh[0, :6] = 0                                  # relu'(0) = 0
+    mask = oracle.transposable_mask(W2)
+    _, _, valsT, metaT = oracle.compress(W2, mask)
+    vtp, mtp = oracle.pack(valsT, metaT)
+    d_dY, d_v, d_m, d_Z = dev_bf16(dY), dev_bf16(vtp), dev(mtp), dev_bf16(Zh)
+    dZ = torch.full((p, f), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    s24.spmm_bwd_dx_act(d_dY, d_v, d_m, d_Z, dZ, a_lib)
+    dH, dZ2 = torch.empty_like(dZ), torch.empty_like(dZ)
+    s24.spmm_bwd_dx(d_dY, d_v, d_m, dH)
+    s24.act_bwd(dH, d_Z, dZ2, a_lib)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(dZ), bits(dZ2))
+    rows = sample_rows(p, 9)
+    dHr = oracle.round_like(oracle.spmm_bwd_dx(dY, valsT, metaT, rows=rows), dY)
+    ref = oracle.act_bwd(dHr, np.ascontiguousarray(Zh[rows]), a_orc)
+    assert_close(host_f64(dZ[torch.from_numpy(rows).cuda()]), ref, ACT_TOL[dtype], f"dZ {act}")
+    # small shapes decline and leave the output alone
+    small = torch.zeros((64, 64), dtype=torch_dtype(dtype), device="cuda")
+    v = torch.zeros((1, 64, 32), dtype=torch_dtype(dtype), device="cuda")
+    m = torch.zeros((1, 64, 4), dtype=torch.int16, device="cuda")
+    with pytest.raises(s24.S24Error) as e:
+        s24.spmm_bwd_dx_act(small, v, m, small, small, a_lib)
+    assert e.value.status == -6
+
+
 # ------------------------------------------------------------------ binary16 on the large-tile matrix-core kernels
 @pytest.mark.parametrize("k", [64, 192, 320])
 def test_f16_spmm_large_tile_path(s24, k):

@@ -185,6 +185,15 @@ def test_gated_family_argument_errors(lib):
     assert lib.s24_spmm_bwd_dx_glu(P, P, P, P, P, 4, 16, 64, 7, 2, None) == DTYPE
     assert lib.s24_spmm_bwd_dx_glu(P, P, P, P, P, 4, 16, 64, 1, 2, None) == UNSUP      # too few tiles
     assert lib.s24_spmm_bwd_dx_glu(P, P, P, P, P, 4, 16, 64, 1, 0, None) == UNSUP      # fp32
+    # s24_spmm_fwd_act(X, vals, meta, bias, Z, H, p, q, r, act, dt, stream)
+    assert lib.s24_spmm_fwd_act(P, P, P, None, P, P, 4, 96, 16, 1, 1, None) == SHAPE
+    assert lib.s24_spmm_fwd_act(P, P, P, None, P, P, 4, 64, 16, 4, 1, None) == DTYPE   # activation enum
+    assert lib.s24_spmm_fwd_act(P, P, P, None, P, None, 4, 64, 16, 1, 1, None) == NULL
+    assert lib.s24_spmm_fwd_act(P, P, P, None, P, P, 0, 64, 16, 1, 1, None) == OK
+    # s24_spmm_bwd_dx_act(dY, valsT, metaT, Z, dZ, p, f, r, act, dt, stream)
+    assert lib.s24_spmm_bwd_dx_act(P, P, P, P, P, 4, 16, 96, 1, 1, None) == SHAPE
+    assert lib.s24_spmm_bwd_dx_act(P, P, P, None, P, 4, 16, 64, 1, 1, None) == NULL
+    assert lib.s24_spmm_bwd_dx_act(P, P, P, P, P, 4, 16, 64, 1, 1, None) == UNSUP
     # binary16 is a valid dtype everywhere a dtype is taken
     assert lib.s24_transposable_mask(P, 2, 6, 8, 8, P, None, None) == SHAPE
     assert lib.s24_spmm_fwd(P, P, P, P, 0, 64, 16, 2, None) == OK
