@@ -851,10 +851,14 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
 // DECAY: the masked decay term is added in the epilogue: dW[m][n] += lambda * Wt[m][n] where bit
 // 4*(m%4) + n%4 of mask[m/4][n/4] is clear, with the same single fused multiply-add the stand-alone
 // decay kernel applies to the stored gradient, so both routes give the same bits.
+// The operands may be windows of larger matrices: M and N are the extents of this launch's output, ldy, ldx and ldw
+// the row strides (elements) of dY, of X and of dW / Wt (the mask's row stride is ldw / 4; a window starts at a
+// multiple of four rows and columns).
 template <typename ET, int WT, int BT_, bool ACCUM, bool DECAY>
 __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *__restrict__ dY,
                                                                const uint16_t *__restrict__ X, float *__restrict__ dW,
-                                                               int T, int M, int N, int tiles_m, int tiles_n,
+                                                               int T, int M, int N, int ldy, int ldx, int ldw,
+                                                               int tiles_m, int tiles_n,
                                                                unsigned long long *probe,
                                                                const uint16_t *__restrict__ Wt,
                                                                const uint16_t *__restrict__ mask, float lambda)
@@ -890,25 +894,25 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
 #pragma unroll
     for (int j = 0; j < NIO; ++j) {
         const int slot = (wave * NIO + j) * 64 + lane, row = slot / CPR, c = (slot % CPR) ^ ((row & 3) << 2);
-        voffA[j] = row * M + m0 + 8 * min(c, lastA);
-        voffB[j] = row * N + n0 + 8 * min(c, lastB);
+        voffA[j] = row * ldy + m0 + 8 * min(c, lastA);
+        voffB[j] = row * ldx + n0 + 8 * min(c, lastB);
     }
     // Copies first .. first+count-1 of a chunk's list (the dY tile's NIO, then the X tile's NIO).  Token rows
     // past T (last chunk only) re-read row T-1.
     auto issue = [&](unsigned char *st, int kc, int first, int count) {
         kc = min(kc, nk - 1);
-        const char *ya = reinterpret_cast<const char *>(dY + (int64_t)kc * BT * M);
-        const char *xb = reinterpret_cast<const char *>(X + (int64_t)kc * BT * N);
+        const char *ya = reinterpret_cast<const char *>(dY + (int64_t)kc * BT * ldy);
+        const char *xb = reinterpret_cast<const char *>(X + (int64_t)kc * BT * ldx);
         const int lastrow = T - 1 - kc * BT;
 #pragma unroll
         for (int c = first; c < first + count; ++c) {
             const int j = c < NIO ? c : c - NIO;
             const int over = max(((wave * NIO + j) * 64 + lane) / CPR - lastrow, 0);
             if (c < NIO)
-                __builtin_amdgcn_global_load_lds((glb_ptr)(ya + (uint32_t)(voffA[j] - over * M) * 2u),
+                __builtin_amdgcn_global_load_lds((glb_ptr)(ya + (uint32_t)(voffA[j] - over * ldy) * 2u),
                                                  (lds_ptr)(st + (wave * NIO + j) * 1024), 16, 0, 0);
             else
-                __builtin_amdgcn_global_load_lds((glb_ptr)(xb + (uint32_t)(voffB[j] - over * N) * 2u),
+                __builtin_amdgcn_global_load_lds((glb_ptr)(xb + (uint32_t)(voffB[j] - over * ldx) * 2u),
                                                  (lds_ptr)(st + OPERAND + (wave * NIO + j) * 1024), 16, 0, 0);
         }
     };
@@ -1035,10 +1039,10 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
                 live[b] = m < M && n < N;   // N is a multiple of 16: the four columns are all in or all out
                 const int mc = min(m, M - 1), nc = min(n, N - 4);
                 v[b] = *reinterpret_cast<const float4 *>(est + row * 256 + c4 * 16);
-                if (ACCUM) old[b] = *reinterpret_cast<const float4 *>(dW + (int64_t)mc * N + nc);
+                if (ACCUM) old[b] = *reinterpret_cast<const float4 *>(dW + (int64_t)mc * ldw + nc);
                 if (DECAY) {
-                    wv[b] = *reinterpret_cast<const uint2 *>(Wt + (int64_t)mc * N + nc);
-                    keep[b] = mask[(int64_t)(mc >> 2) * (N >> 2) + (nc >> 2)] >> (4 * (mc & 3));
+                    wv[b] = *reinterpret_cast<const uint2 *>(Wt + (int64_t)mc * ldw + nc);
+                    keep[b] = mask[(int64_t)(mc >> 2) * (ldw >> 2) + (nc >> 2)] >> (4 * (mc & 3));
                 }
             }
 #pragma unroll
@@ -1053,7 +1057,7 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
                     if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_num<ET>::lo(wv[b].y), o.z);
                     if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_num<ET>::hi(wv[b].y), o.w);
                 }
-                if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * N + n) = o;
+                if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * ldw + n) = o;
             }
         }
         asm volatile("" ::: "memory");
@@ -1605,17 +1609,20 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
     if (p == 0) {  // empty contraction: dW = beta * dW (the GEMM kernels need at least one token)
         if (!accum) hipLaunchKernelGGL(fill_zero_kernel, dim3(ceil_div(q * r, kThreads)), dim3(kThreads), 0, st, dW, q * r);
     } else if (dt != S24_F32) {
-        // 256 x 256 tiles when they fill the chip, 128 x 128 tiles otherwise
-        const bool large = fills_chip_256(r, q);
-        const int tile = large ? 256 : 128;
-        const int tiles_m = (int)ceil_div(r, tile), tiles_n = (int)ceil_div(q, tile);
-        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(dmatn::THREADS);
         auto *a = static_cast<const uint16_t *>(dY), *b = static_cast<const uint16_t *>(X);
         const bool fuse = decay_pending && wdt == dt;   // the epilogue reads W in the operands' own 16-bit type
         auto *w = static_cast<const uint16_t *>(fuse ? W : nullptr);
-#define S24_LAUNCH_DW(WT, BT, ACC, DEC)                                                                                \
-    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<T, WT, BT, ACC, DEC>), grid, block, 0, st, a, b, dW, (int)p, (int)r,  \
-                       (int)q, tiles_m, tiles_n, g_clock_probe, w, mask, lambda)
+        // One launch over the window [m_off, m_off + mm) x [n_off, n_off + nn) of the output, in tiles of `tile`
+        auto launch = [&](int tile, int64_t m_off, int64_t mm, int64_t n_off, int64_t nn) {
+            const int tiles_m = (int)ceil_div(mm, tile), tiles_n = (int)ceil_div(nn, tile);
+            const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(dmatn::THREADS);
+            const uint16_t *aw = a + m_off, *bw = b + n_off;
+            float *ow = dW + m_off * q + n_off;
+            const uint16_t *ww = w ? w + m_off * q + n_off : nullptr;
+            const uint16_t *mw = fuse ? mask + (m_off / 4) * (q / 4) + n_off / 4 : nullptr;
+#define S24_LAUNCH_DW(WT, BT, ACC, DEC)                                                                                 \
+    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<T, WT, BT, ACC, DEC>), grid, block, 0, st, aw, bw, ow, (int)p, (int)mm, \
+                       (int)nn, (int)r, (int)q, (int)q, tiles_m, tiles_n, g_clock_probe, ww, mw, lambda)
 #define S24_LAUNCH_DW_TILE(WT, BT)                              \
     do {                                                        \
         if (accum && fuse) S24_LAUNCH_DW(WT, BT, true, true);   \
@@ -1623,13 +1630,43 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
         else if (fuse) S24_LAUNCH_DW(WT, BT, false, true);      \
         else S24_LAUNCH_DW(WT, BT, false, false);               \
     } while (0)
-        S24_WITH_16BIT_TYPE(dt, {
-            if (large) S24_LAUNCH_DW_TILE(4, 32);
-            else if (tiles_m * tiles_n > 256) S24_LAUNCH_DW_TILE(2, 32);
-            else S24_LAUNCH_DW_TILE(2, 64);
-        });
+            S24_WITH_16BIT_TYPE(dt, {
+                if (tile == 256) S24_LAUNCH_DW_TILE(4, 32);
+                else if (tiles_m * tiles_n > 256) S24_LAUNCH_DW_TILE(2, 32);
+                else S24_LAUNCH_DW_TILE(2, 64);
+            });
 #undef S24_LAUNCH_DW_TILE
 #undef S24_LAUNCH_DW
+        };
+        // 256 x 256 tiles when they fill the chip, 128 x 128 tiles otherwise.  A grid of large tiles that is not a
+        // whole number of rounds over the 256 compute units leaves the chip part empty in its last round (c4's
+        // 1376 tiles: 5.375 rounds).  Where whole tile rows or columns can be cut off so that the rest is an exact
+        // number of rounds and the cut-off strip is at most half a round of large tiles, the slab runs in large
+        // tiles and the strip in small ones (at most 512 of them: one resident set, two workgroups per compute
+        // unit), which costs 0.56 of a round instead of a whole one; a longer strip (c4's other weight, 0.69 of a
+        // round) measured no better than the idle tail it replaces and stays in the single launch.  Every output
+        // element belongs to exactly one launch either way, so nothing about the result changes.
+        const int tm256 = (int)ceil_div(r, 256), tn256 = (int)ceil_div(q, 256), total = tm256 * tn256;
+        if (total < 192) {
+            launch(128, 0, r, 0, q);
+        } else {
+            int cut_m = 0, cut_n = 0;   // tile rows / columns kept in the large-tile slab (0: no such cut)
+            if (total % 256 != 0) {
+                for (int k = tm256 - 1; k >= 1 && !cut_m; --k)
+                    if ((k * tn256) % 256 == 0 && (tm256 - k) * tn256 <= 128) cut_m = k;
+                for (int k = tn256 - 1; k >= 1 && !cut_n; --k)
+                    if ((k * tm256) % 256 == 0 && (tn256 - k) * tm256 <= 128) cut_n = k;
+            }
+            if (cut_m && (!cut_n || cut_m * tn256 >= cut_n * tm256)) {
+                launch(256, 0, 256ll * cut_m, 0, q);
+                launch(128, 256ll * cut_m, r - 256ll * cut_m, 0, q);
+            } else if (cut_n) {
+                launch(256, 0, r, 0, 256ll * cut_n);
+                launch(128, 0, r, 256ll * cut_n, q - 256ll * cut_n);
+            } else {
+                launch(256, 0, r, 0, q);
+            }
+        }
         if (fuse) decay_pending = false;
     } else {
         const dim3 grid(ceil_div(r * q, kThreads)), block(kThreads);

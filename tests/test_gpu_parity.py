@@ -318,6 +318,34 @@ def test_dense_dw_many_small_tiles_path(s24, p, beta):
     assert_close(host_f64(dW[torch.from_numpy(rows).cuda()]), ref, F32_TOL, f"dense_dw small tiles p={p} beta={beta}")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("rq", [(4096, 4336), (4240, 4096)])     # 16 x 17 and 17 x 16 large tiles, ragged strip
+@pytest.mark.parametrize("beta", [0.0, 1.0])
+def test_dense_dw_round_exact_slab_plus_small_tile_strip(s24, dtype, rq, beta):
+    """Tile grids that are not a whole number of rounds over the compute units are cut into a slab of whole rounds
+    (large tiles) and a strip (small tiles), along either axis: rows and columns on both sides of the cut, the
+    ragged edge, accumulation and the decay term against the oracle, and the same bits as the unfused route."""
+    r, q = rq
+    p, lam = 150, 2e-4
+    dY = si.random_matrix(480 + r, (p, r), 1e-2, dtype)
+    X = si.random_matrix(481 + q, (p, q), 1.0, dtype)
+    W = si.random_matrix(482, (r, q), 0.02, dtype)
+    dW0 = si.random_matrix(483, (r, q), 1e-3, "f32")
+    mask = oracle.transposable_mask(W)
+    d_dY, d_X, d_W, d_mask = dev_bf16(dY), dev_bf16(X), dev_bf16(W), dev(mask)
+    fused = dev(dW0).clone()
+    s24.dense_dw_decay(d_dY, d_X, fused, d_W, d_mask, lam, beta=beta)
+    two = dev(dW0).clone()
+    s24.dense_dw(d_dY, d_X, two, beta=beta)
+    s24.masked_decay_grad(two, d_W, d_mask, lam)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.view(torch.int32), two.view(torch.int32))
+    rows = np.unique(np.concatenate([[0, 4095, r - 1, r - 2, 2048, 4000], np.random.default_rng(r).integers(0, r, 16)])).astype(np.int64)
+    g = oracle.dense_dw(dY, X, beta=beta, dW0=dW0[rows].astype(np.float64), rows=rows)
+    g = g + oracle.masked_decay(np.zeros((r, q), np.float32), W, mask, lam)[rows]
+    assert_close(host_f64(fused[torch.from_numpy(rows).cuda()]), g, F32_TOL, f"dense_dw slab+strip {rq} beta={beta}")
+
+
 def test_dense_dw_no_tokens(s24):
     dW = torch.full((64, 128), 5.0, dtype=torch.float32, device="cuda")
     # with no tokens the operand pointers are never read: any aligned non-null value will do
