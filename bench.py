@@ -443,6 +443,8 @@ def main():
                          "instead of the dense GEMM")
     ap.add_argument("--no-fuse-swiglu", action="store_true",
                     help="SwiGLU forward and backward as their own kernels instead of GEMM epilogues")
+    ap.add_argument("--no-batch-dw", action="store_true",
+                    help="one launch per weight-gradient GEMM instead of one pass over the tiles of all of them")
     ap.add_argument("--no-fuse-decay", action="store_true",
                     help="masked decay as its own kernel after the weight-gradient GEMM instead of inside its epilogue")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
@@ -500,7 +502,7 @@ def main():
                   "Wd": to_dev(si.random_matrix(7002, (wl.d_model,), 0.3, wl.dtype))}
     ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay,
                     concat_gate_up=not args.separate_gate_up, mvue=args.mvue, fuse_swiglu=not args.no_fuse_swiglu,
-                    biases=biases)
+                    biases=biases, batch_dw=not args.no_batch_dw)
     X, dY = dev["X"], dev["dY"]
 
     for _ in range(args.warmup):
@@ -549,6 +551,7 @@ def main():
                                f"{wl.dtype}, {len(wl.weight_names)} weights, mask+compress every step",
                    "gate_up_as_one_weight": ffn.concat, "decay_in_dw_epilogue": ffn.fuse_decay,
                    "swiglu_in_gemm_epilogues": bool(ffn.concat and ffn.fuse_swiglu),
+                   "weight_gradients_in_one_pass": bool(ffn.batch_dw and not ffn.mvue),
                    "weight_gradient": "sparse GEMM on the MVUE-pruned output gradient" if ffn.mvue else "dense GEMM",
                    "gemm_flops_per_step": wl.gemm_flops},
         "pct_of_sparse_mfma_peak_whole_step": round(100 * value / PEAK_SPARSE_BF16, 2),

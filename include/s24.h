@@ -178,6 +178,26 @@ int s24_dense_dw_decay(const void *dY, const void *X, float *dW, const void *W, 
                        const uint16_t *mask, float lambda, int64_t p, int64_t q, int64_t r, float beta,
                        s24_dtype dt, void *stream);
 
+/* Several weight gradients in one pass (Eq. 1 + Eq. 10 for up to four weights of a layer, e.g. the two or three of
+ * an FFN): the same result, bit for bit, as s24_dense_dw_decay (W != NULL) or s24_dense_dw (W == NULL) on each
+ * problem with the same beta, but the tiles of all problems share one grid, so that the compute units which the
+ * last, partial round of one GEMM would leave idle take tiles of the next, and if the joint tile count exceeds a
+ * whole number of rounds by at most half a round, that excess is cut off as whole tile columns or rows of one
+ * problem and run in small tiles.  `problems` is a HOST array of `count` <= 4 entries, read during the call:
+ *   dY [p][r], X [p][q] (dtype dt), dW [r][q] fp32, W [r][q] (dtype dt) or NULL, mask [r/4][q/4] (with W), lambda.
+ * Problems that do not fit the shared grid (fp32, no tokens, small outputs, decay on some but not all) are run one
+ * after the other instead.  All problems are validated before the first launch. */
+typedef struct {
+    const void *dY;
+    const void *X;
+    float *dW;
+    const void *W;
+    const uint16_t *mask;
+    int64_t p, q, r;
+    float lambda;
+} s24_dw_problem;
+int s24_dense_dw_batch(const s24_dw_problem *problems, int count, float beta, s24_dtype dt, void *stream);
+
 /* Unbiased 2:4 pruning of the output gradient (Eq. 6: S_z = MVUE) into the compressed operand of the sparse
  * weight-gradient GEMM (Eq. 4).  Of every four consecutive tokens of one feature two are kept, element j with
  * probability pi_j proportional to |dY_j| (capped at one) and stored as dY_j / pi_j; the pair is drawn by

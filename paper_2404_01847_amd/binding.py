@@ -42,6 +42,7 @@ _SIGNATURES = {
     "s24_spmm_bwd_dx_swiglu": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
     "s24_dense_dw": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_dw_decay": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _f32, _i64, _i64, _i64, _f32, _int, _vp]),
+    "s24_dense_dw_batch": (_int, [_vp, _int, _f32, _int, _vp]),
     "s24_mvue24": (_int, [_vp, _int, _i64, _i64, _i64, C.c_uint32, _vp, _vp, _vp]),
     "s24_spmm_dw": (_int, [_vp, _vp, _vp, _vp, _vp, _int, _vp, _f32, _i64, _i64, _i64, _f32, _int, _vp]),
     "s24_dense_gemm": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
@@ -251,6 +252,22 @@ def dense_dw_decay(dY, X, dW, W, mask, lam, beta=0.0):
     _check(lib().s24_dense_dw_decay(_ptr(dY), _ptr(X), _ptr(dW), _ptr(W), _dt(W), _ptr(mask), lam, p, q, r, beta,
                                     _dt(X), _stream()), "s24_dense_dw_decay")
     return dW
+
+
+class _DwProblem(C.Structure):
+    _fields_ = [("dY", _vp), ("X", _vp), ("dW", _vp), ("W", _vp), ("mask", _vp), ("p", _i64), ("q", _i64), ("r", _i64),
+                ("lam", _f32)]
+
+
+def dense_dw_batch(problems, beta=0.0):
+    """problems: up to four tuples (dY, X, dW, W, mask, lam) with W and mask None for no decay term; the weight
+    gradients of all of them in one pass (same bits as dense_dw_decay / dense_dw on each)."""
+    arr = (_DwProblem * len(problems))()
+    for k, (dY, X, dW, W, mask, lam) in enumerate(problems):
+        p, r = dY.shape
+        arr[k] = _DwProblem(_ptr(dY), _ptr(X), _ptr(dW), _ptr(W), _ptr(mask), p, X.shape[1], r, lam)
+    _check(lib().s24_dense_dw_batch(C.cast(arr, C.c_void_p), len(problems), beta, _dt(problems[0][0]), _stream()),
+           "s24_dense_dw_batch")
 
 
 def mvue24(dY, seed, vals, meta):

@@ -851,17 +851,25 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *p)
 // DECAY: the masked decay term is added in the epilogue: dW[m][n] += lambda * Wt[m][n] where bit
 // 4*(m%4) + n%4 of mask[m/4][n/4] is clear, with the same single fused multiply-add the stand-alone
 // decay kernel applies to the stored gradient, so both routes give the same bits.
-// The operands may be windows of larger matrices: M and N are the extents of this launch's output, ldy, ldx and ldw
-// the row strides (elements) of dY, of X and of dW / Wt (the mask's row stride is ldw / 4; a window starts at a
-// multiple of four rows and columns).
+// One launch covers up to four weight gradients (DwBatch): their tiles share one grid, so that the compute units
+// left idle by the last, partial round of one problem take tiles of the next.  The operands of a problem may be
+// windows of larger matrices: M and N are the extents of the window's output, ldy, ldx and ldw the row strides
+// (elements) of dY, of X and of dW / Wt (the mask's row stride is ldw / 4; a window starts at a multiple of four
+// rows and columns).
+struct DwWindow {
+    const uint16_t *dY, *X, *Wt, *mask;
+    float *dW;
+    int T, M, N, ldy, ldx, ldw, tiles_m, tiles_n;
+    float lambda;
+};
+constexpr int kMaxBatch = 4;
+struct DwBatch {
+    DwWindow w[kMaxBatch];
+    int first_tile[kMaxBatch + 1];   // first_tile[i] .. first_tile[i+1]-1 are the tiles of problem i; unused entries repeat the total
+};
+
 template <typename ET, int WT, int BT_, bool ACCUM, bool DECAY>
-__global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *__restrict__ dY,
-                                                               const uint16_t *__restrict__ X, float *__restrict__ dW,
-                                                               int T, int M, int N, int ldy, int ldx, int ldw,
-                                                               int tiles_m, int tiles_n,
-                                                               unsigned long long *probe,
-                                                               const uint16_t *__restrict__ Wt,
-                                                               const uint16_t *__restrict__ mask, float lambda)
+__global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch batch, unsigned long long *probe)
 {
     using C = Cfg<WT, BT_>;
     constexpr int BM = C::BM, BN = C::BN, BT = C::BT, ROWB = C::ROWB, OPERAND = C::OPERAND, STAGE = C::STAGE, CPR = C::CPR;
@@ -876,9 +884,21 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const uint16_t *_
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
-    const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8;
-    const int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    // Workgroups are dealt round-robin to the eight XCDs; each XCD takes one contiguous slab of the tile list
+    const int total = batch.first_tile[kMaxBatch], per_xcd = (total + 7) / 8;
+    int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
     if (t >= total) return;
+    int which = 0;   // wave-uniform: the problem this tile belongs to
+#pragma unroll
+    for (int i = 1; i < kMaxBatch; ++i)
+        if (t >= batch.first_tile[i]) which = i;
+    t -= batch.first_tile[which];
+    const DwWindow &win = batch.w[which];
+    const uint16_t *__restrict__ dY = win.dY, *__restrict__ X = win.X, *__restrict__ Wt = win.Wt, *__restrict__ mask = win.mask;
+    float *__restrict__ dW = win.dW;
+    const int T = win.T, M = win.M, N = win.N, ldy = win.ldy, ldx = win.ldx, ldw = win.ldw;
+    const int tiles_m = win.tiles_m, tiles_n = win.tiles_n;
+    const float lambda = win.lambda;
     constexpr int GROUP = 8;
     const int group_sz = GROUP * tiles_m, grp = t / group_sz, in_grp = t - grp * group_sz;
     const int gw = min(GROUP, tiles_n - grp * GROUP);
@@ -1600,6 +1620,57 @@ extern "C" int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, 
 }
 
 namespace {
+// One weight gradient as the batched kernel sees it (16-bit operands; W == nullptr: no decay term)
+struct DwProblem {
+    const uint16_t *dY, *X;
+    float *dW;
+    const uint16_t *W, *mask;
+    int64_t p, q, r;
+    float lambda;
+};
+// The window [m_off, m_off + mm) x [n_off, n_off + nn) of a problem's output, in tiles of `tile`
+dmatn::DwWindow dw_window(const DwProblem &pr, int tile, int64_t m_off, int64_t mm, int64_t n_off, int64_t nn)
+{
+    dmatn::DwWindow w{};
+    w.dY = pr.dY + m_off;
+    w.X = pr.X + n_off;
+    w.dW = pr.dW + m_off * pr.q + n_off;
+    w.Wt = pr.W ? pr.W + m_off * pr.q + n_off : nullptr;
+    w.mask = pr.W ? pr.mask + (m_off / 4) * (pr.q / 4) + n_off / 4 : nullptr;
+    w.T = (int)pr.p;
+    w.M = (int)mm;
+    w.N = (int)nn;
+    w.ldy = (int)pr.r;
+    w.ldx = (int)pr.q;
+    w.ldw = (int)pr.q;
+    w.tiles_m = (int)ceil_div(mm, tile);
+    w.tiles_n = (int)ceil_div(nn, tile);
+    w.lambda = pr.lambda;
+    return w;
+}
+// tile: 256 (large), or 128 (small; 32 tokens per stage when there are more tiles than compute units, else 64)
+void launch_dw_batch(const dmatn::DwBatch &batch, int tile, bool accum, bool decay, int dt, hipStream_t st)
+{
+    const int total = batch.first_tile[dmatn::kMaxBatch];
+    const dim3 grid(((total + 7) / 8) * 8), block(dmatn::THREADS);
+#define S24_LAUNCH_DW(WT, BT, ACC, DEC) \
+    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<T, WT, BT, ACC, DEC>), grid, block, 0, st, batch, g_clock_probe)
+#define S24_LAUNCH_DW_TILE(WT, BT)                               \
+    do {                                                         \
+        if (accum && decay) S24_LAUNCH_DW(WT, BT, true, true);   \
+        else if (accum) S24_LAUNCH_DW(WT, BT, true, false);      \
+        else if (decay) S24_LAUNCH_DW(WT, BT, false, true);      \
+        else S24_LAUNCH_DW(WT, BT, false, false);                \
+    } while (0)
+    S24_WITH_16BIT_TYPE(dt, {
+        if (tile == 256) S24_LAUNCH_DW_TILE(4, 32);
+        else if (total > 256) S24_LAUNCH_DW_TILE(2, 32);
+        else S24_LAUNCH_DW_TILE(2, 64);
+    });
+#undef S24_LAUNCH_DW_TILE
+#undef S24_LAUNCH_DW
+}
+
 // Shared by s24_dense_dw and s24_dense_dw_decay.  W == nullptr: no decay term.
 int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q, int64_t r, float beta, int dt,
                  const void *W, int wdt, const uint16_t *mask, float lambda, hipStream_t st)
@@ -1614,29 +1685,12 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
         auto *w = static_cast<const uint16_t *>(fuse ? W : nullptr);
         // One launch over the window [m_off, m_off + mm) x [n_off, n_off + nn) of the output, in tiles of `tile`
         auto launch = [&](int tile, int64_t m_off, int64_t mm, int64_t n_off, int64_t nn) {
-            const int tiles_m = (int)ceil_div(mm, tile), tiles_n = (int)ceil_div(nn, tile);
-            const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(dmatn::THREADS);
-            const uint16_t *aw = a + m_off, *bw = b + n_off;
-            float *ow = dW + m_off * q + n_off;
-            const uint16_t *ww = w ? w + m_off * q + n_off : nullptr;
-            const uint16_t *mw = fuse ? mask + (m_off / 4) * (q / 4) + n_off / 4 : nullptr;
-#define S24_LAUNCH_DW(WT, BT, ACC, DEC)                                                                                 \
-    hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<T, WT, BT, ACC, DEC>), grid, block, 0, st, aw, bw, ow, (int)p, (int)mm, \
-                       (int)nn, (int)r, (int)q, (int)q, tiles_m, tiles_n, g_clock_probe, ww, mw, lambda)
-#define S24_LAUNCH_DW_TILE(WT, BT)                              \
-    do {                                                        \
-        if (accum && fuse) S24_LAUNCH_DW(WT, BT, true, true);   \
-        else if (accum) S24_LAUNCH_DW(WT, BT, true, false);     \
-        else if (fuse) S24_LAUNCH_DW(WT, BT, false, true);      \
-        else S24_LAUNCH_DW(WT, BT, false, false);               \
-    } while (0)
-            S24_WITH_16BIT_TYPE(dt, {
-                if (tile == 256) S24_LAUNCH_DW_TILE(4, 32);
-                else if (tiles_m * tiles_n > 256) S24_LAUNCH_DW_TILE(2, 32);
-                else S24_LAUNCH_DW_TILE(2, 64);
-            });
-#undef S24_LAUNCH_DW_TILE
-#undef S24_LAUNCH_DW
+            const DwProblem pr{a, b, dW, w, fuse ? mask : nullptr, p, q, r, lambda};
+            dmatn::DwBatch batch{};
+            batch.w[0] = dw_window(pr, tile, m_off, mm, n_off, nn);
+            const int tiles = batch.w[0].tiles_m * batch.w[0].tiles_n;
+            for (int i = 1; i <= dmatn::kMaxBatch; ++i) batch.first_tile[i] = tiles;
+            launch_dw_batch(batch, tile, accum, fuse, dt, st);
         };
         // 256 x 256 tiles when they fill the chip, 128 x 128 tiles otherwise.  A grid of large tiles that is not a
         // whole number of rounds over the 256 compute units leaves the chip part empty in its last round (c4's
@@ -1703,6 +1757,83 @@ extern "C" int s24_dense_dw_decay(const void *dY, const void *X, float *dW, cons
     S24_REQUIRE(W && mask, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(W, 16) && s24_aligned(mask, 4), S24_ERR_ALIGN);
     return run_dense_dw(dY, X, dW, p, q, r, beta, dt, W, wdt, mask, lambda, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int s24_dense_dw_batch(const s24_dw_problem *problems, int count, float beta, s24_dtype dt, void *stream)
+{
+    S24_REQUIRE(s24_valid_dtype(dt), S24_ERR_DTYPE);
+    S24_REQUIRE(count >= 0 && count <= dmatn::kMaxBatch, S24_ERR_SHAPE);
+    S24_REQUIRE(beta == 0.0f || beta == 1.0f, S24_ERR_UNSUPPORTED);
+    if (count == 0) return S24_OK;
+    S24_REQUIRE(problems != nullptr, S24_ERR_NULL);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // every problem is checked before anything is launched
+    bool shared_grid = dt != S24_F32;
+    int64_t total = 0;
+    for (int i = 0; i < count; ++i) {
+        const s24_dw_problem &pr = problems[i];
+        S24_REQUIRE(pr.q % 16 == 0 && pr.r % 16 == 0, S24_ERR_SHAPE);
+        const int rc = check_gemm(pr.dY, pr.X, pr.dW, pr.p, pr.q, pr.r, dt, pr.q * pr.r);
+        if (rc != S24_OK) return rc;
+        if (pr.W != nullptr && pr.q * pr.r != 0) {
+            S24_REQUIRE(pr.mask != nullptr, S24_ERR_NULL);
+            S24_REQUIRE(s24_aligned(pr.W, 16) && s24_aligned(pr.mask, 4), S24_ERR_ALIGN);
+        }
+        const int64_t tiles = (int64_t)ceil_div(pr.r, 256) * ceil_div(pr.q, 256);
+        // one grid for all of them: 16-bit data, tokens to contract, every problem large enough for the large tile,
+        // and the decay term on all of them or on none
+        shared_grid = shared_grid && pr.p > 0 && tiles >= 64 && (pr.W != nullptr) == (problems[0].W != nullptr);
+        total += tiles;
+    }
+    if (!shared_grid || total < 192 || count == 1) {
+        for (int i = 0; i < count; ++i) {
+            const s24_dw_problem &pr = problems[i];
+            if (pr.q * pr.r == 0) continue;
+            const int rc = run_dense_dw(pr.dY, pr.X, pr.dW, pr.p, pr.q, pr.r, beta, dt, pr.W, dt, pr.mask, pr.lambda, st);
+            if (rc != S24_OK) return rc;
+        }
+        return S24_OK;
+    }
+    const bool accum = beta != 0.0f, decay = problems[0].W != nullptr;
+    DwProblem prs[dmatn::kMaxBatch];
+    for (int i = 0; i < count; ++i) {
+        const s24_dw_problem &pr = problems[i];
+        prs[i] = DwProblem{static_cast<const uint16_t *>(pr.dY), static_cast<const uint16_t *>(pr.X), pr.dW,
+                           static_cast<const uint16_t *>(pr.W), pr.mask, pr.p, pr.q, pr.r, pr.lambda};
+    }
+    // The tiles of all problems make one list.  If its length is not a whole number of rounds over the 256 compute
+    // units, look for a problem from which whole tile columns (or rows) amounting to exactly the excess, and to at
+    // most half a round, can be cut: that strip runs in small tiles afterwards, the rest in whole rounds.
+    int cut = -1, cut_cols = 0, cut_rows = 0;
+    const int excess = (int)(total % 256);
+    if (excess != 0 && excess <= 128) {
+        for (int i = 0; i < count && cut < 0; ++i) {
+            const int tm = (int)ceil_div(prs[i].r, 256), tn = (int)ceil_div(prs[i].q, 256);
+            if (excess % tm == 0 && excess / tm < tn) { cut = i; cut_cols = excess / tm; }
+            else if (excess % tn == 0 && excess / tn < tm) { cut = i; cut_rows = excess / tn; }
+        }
+    }
+    dmatn::DwBatch batch{};
+    int first = 0;
+    for (int i = 0; i < count; ++i) {
+        // the cut removes the LAST tile rows / columns, the ragged edge included: what stays is a multiple of 256
+        const int64_t keep_m = i == cut && cut_rows ? 256ll * ((int64_t)ceil_div(prs[i].r, 256) - cut_rows) : prs[i].r;
+        const int64_t keep_n = i == cut && cut_cols ? 256ll * ((int64_t)ceil_div(prs[i].q, 256) - cut_cols) : prs[i].q;
+        batch.w[i] = dw_window(prs[i], 256, 0, keep_m, 0, keep_n);
+        batch.first_tile[i] = first;
+        first += batch.w[i].tiles_m * batch.w[i].tiles_n;
+    }
+    for (int i = count; i <= dmatn::kMaxBatch; ++i) batch.first_tile[i] = first;
+    launch_dw_batch(batch, 256, accum, decay, dt, st);
+    if (cut >= 0) {
+        dmatn::DwBatch strip{};
+        const int64_t m_off = cut_rows ? batch.w[cut].M : 0, n_off = cut_cols ? batch.w[cut].N : 0;
+        strip.w[0] = dw_window(prs[cut], 128, m_off, prs[cut].r - m_off, n_off, prs[cut].q - n_off);
+        const int tiles = strip.w[0].tiles_m * strip.w[0].tiles_n;
+        for (int i = 1; i <= dmatn::kMaxBatch; ++i) strip.first_tile[i] = tiles;
+        launch_dw_batch(strip, 128, accum, decay, dt, st);
+    }
+    return s24_launch_status();
 }
 
 extern "C" int s24_spmm_dw(const void *vals, const uint16_t *meta, const void *X, float *dW, const void *W, s24_dtype wdt,

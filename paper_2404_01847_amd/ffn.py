@@ -59,8 +59,10 @@ class SparseFFN:
 
     def __init__(self, weights: dict, p: int, act: str, lam: float, fuse_decay: bool = True, mask_interval: int = 1,
                  concat_gate_up: bool = False, mvue: bool = False, seed: int = 0, fuse_swiglu: bool = True,
-                 biases: dict | None = None):
+                 biases: dict | None = None, batch_dw: bool = True):
         self.act, self.lam, self.p = act, lam, p
+        # all dense weight gradients of the layer in one pass: the idle tail of one GEMM's tile grid takes the next one's tiles
+        self.batch_dw, self._pending_dw = batch_dw, []
         # Eq. 4 / Eq. 6: the weight gradient from an unbiasedly 2:4-pruned output gradient, as a sparse GEMM
         self.mvue, self.seed = mvue, seed
         self.fuse_swiglu = fuse_swiglu   # the activation in the epilogue of the first projection's forward GEMM
@@ -156,6 +158,10 @@ class SparseFFN:
         for name, w in self.w.items():   # the bias gradient of this weight: column sums of its output gradient
             if w is weight and self.bias[name] is not None:
                 self._k('bias_grad', s24.bias_grad, dYw, self.bias_grad[name])
+        if self.batch_dw and not self.mvue:   # collected; backward() runs them all in one pass at its end
+            self._pending_dw.append((dYw, Xw, weight.grad, weight.W if self.fuse_decay else None,
+                                     weight.mask if self.fuse_decay else None, self.lam))
+            return
         if self.mvue:
             zv, zm = weight.pruned_grad_buffers(dYw.shape[0])
             self.draws += 1   # a fresh draw for every pruned operand of every step
@@ -169,7 +175,17 @@ class SparseFFN:
         else:
             self._k('dense_dw', s24.dense_dw, dYw, Xw, weight.grad)
 
+    def _flush_dw(self):
+        if self._pending_dw:
+            self._k('dense_dw', s24.dense_dw_batch, self._pending_dw)
+            self._pending_dw = []
+
     def backward(self, X, dY):
+        out = self._backward(X, dY)
+        self._flush_dw()
+        return out
+
+    def _backward(self, X, dY):
         w = self.w
         if self.concat:
             fused = False

@@ -346,6 +346,45 @@ def test_dense_dw_round_exact_slab_plus_small_tile_strip(s24, dtype, rq, beta):
     assert_close(host_f64(fused[torch.from_numpy(rows).cuda()]), g, F32_TOL, f"dense_dw slab+strip {rq} beta={beta}")
 
 
+@pytest.mark.parametrize("case", [
+    # (dtype, p, [(r, q), ...], decay on each, beta)
+    ("bf16", 130, [(22016, 4096), (4096, 11008)], [True, True], 0.0),    # c4's pair: 2064 tiles, one tile row cut off
+    ("f16", 70, [(4096, 4352), (4096, 4096), (4112, 4096)], [True, True, True], 1.0),   # 272+256+272 = 800: 32 over, two columns cut
+    ("bf16", 90, [(4096, 4096), (4096, 8192)], [False, False], 0.0),     # whole rounds: nothing to cut
+    ("bf16", 64, [(4096, 4096), (528, 272)], [True, True], 0.0),         # a small problem: one after the other
+    ("bf16", 64, [(4096, 4096), (4096, 4096)], [True, False], 1.0),      # decay on one only: one after the other
+    ("f32", 40, [(64, 48), (32, 96)], [True, False], 0.0)])
+def test_dense_dw_batch_equals_the_single_calls_and_the_oracle(s24, case):
+    dtype, p, shapes, decays, beta = case
+    lam = 3e-4
+    probs, singles, host = [], [], []
+    for k, ((r, q), dec) in enumerate(zip(shapes, decays)):
+        dY = si.random_matrix(3000 + 10 * k, (p, r), 1e-2, dtype)
+        X = si.random_matrix(3001 + 10 * k, (p, q), 1.0, dtype)
+        W = si.random_matrix(3002 + 10 * k, (r, q), 0.02, dtype)
+        dW0 = si.random_matrix(3003 + 10 * k, (r, q), 1e-3, "f32")
+        mask = oracle.transposable_mask(W)
+        d = (dev_bf16(dY), dev_bf16(X), dev(dW0).clone(), dev_bf16(W) if dec else None, dev(mask) if dec else None, lam)
+        probs.append(d)
+        one = dev(dW0).clone()
+        if dec:
+            s24.dense_dw_decay(d[0], d[1], one, d[3], d[4], lam, beta=beta)
+        else:
+            s24.dense_dw(d[0], d[1], one, beta=beta)
+        singles.append(one)
+        host.append((dY, X, W, dW0, mask))
+    s24.dense_dw_batch(probs, beta=beta)
+    torch.cuda.synchronize()
+    for k, ((r, q), dec) in enumerate(zip(shapes, decays)):
+        assert torch.equal(probs[k][2].view(torch.int32), singles[k].view(torch.int32)), f"problem {k}"
+        dY, X, W, dW0, mask = host[k]
+        rows = np.unique(np.concatenate([[0, r - 1, r - 2, r // 2], np.random.default_rng(k).integers(0, r, 6)])).astype(np.int64)
+        g = oracle.dense_dw(dY, X, beta=beta, dW0=dW0[rows].astype(np.float64), rows=rows)
+        if dec:
+            g = g + oracle.masked_decay(np.zeros((r, q), np.float32), W, mask, lam)[rows]
+        assert_close(host_f64(probs[k][2][torch.from_numpy(rows).cuda()]), g, F32_TOL, f"dense_dw_batch {case[:2]} problem {k}")
+
+
 def test_dense_dw_no_tokens(s24):
     dW = torch.full((64, 128), 5.0, dtype=torch.float32, device="cuda")
     # with no tokens the operand pointers are never read: any aligned non-null value will do

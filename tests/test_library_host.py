@@ -194,6 +194,26 @@ def test_gated_family_argument_errors(lib):
     assert lib.s24_spmm_bwd_dx_act(P, P, P, P, P, 4, 16, 96, 1, 1, None) == SHAPE
     assert lib.s24_spmm_bwd_dx_act(P, P, P, None, P, 4, 16, 64, 1, 1, None) == NULL
     assert lib.s24_spmm_bwd_dx_act(P, P, P, P, P, 4, 16, 64, 1, 1, None) == UNSUP
+    # s24_dense_dw_batch(problems, count, beta, dt, stream): a host array of problem records
+    import ctypes
+    from paper_2404_01847_amd.binding import _DwProblem
+    good = _DwProblem(P, P, P, None, None, 4, 16, 16, 0.0)
+    arr = (_DwProblem * 2)(good, good)
+    ptr = ctypes.cast(arr, ctypes.c_void_p)
+    assert lib.s24_dense_dw_batch(ptr, 5, 0.0, 1, None) == SHAPE                     # at most four problems
+    assert lib.s24_dense_dw_batch(ptr, 2, 0.5, 1, None) == UNSUP
+    assert lib.s24_dense_dw_batch(ptr, 2, 0.0, 9, None) == DTYPE
+    assert lib.s24_dense_dw_batch(None, 2, 0.0, 1, None) == NULL
+    assert lib.s24_dense_dw_batch(None, 0, 0.0, 1, None) == OK
+    arr[1] = _DwProblem(P, P, P, None, None, 4, 24, 16, 0.0)
+    assert lib.s24_dense_dw_batch(ptr, 2, 0.0, 1, None) == SHAPE                     # the second problem's q
+    arr[1] = _DwProblem(P, None, P, None, None, 4, 16, 16, 0.0)
+    assert lib.s24_dense_dw_batch(ptr, 2, 0.0, 1, None) == NULL
+    arr[1] = _DwProblem(P, P, P, P, None, 4, 16, 16, 1e-4)
+    assert lib.s24_dense_dw_batch(ptr, 2, 0.0, 1, None) == NULL                      # decay without a mask
+    arr[0] = _DwProblem(P, P, P, None, None, 4, 16, 0, 0.0)
+    arr[1] = _DwProblem(None, None, None, None, None, 4, 0, 16, 0.0)
+    assert lib.s24_dense_dw_batch(ptr, 2, 0.0, 1, None) == OK                        # empty outputs: nothing to do
     # binary16 is a valid dtype everywhere a dtype is taken
     assert lib.s24_transposable_mask(P, 2, 6, 8, 8, P, None, None) == SHAPE
     assert lib.s24_spmm_fwd(P, P, P, P, 0, 64, 16, 2, None) == OK
