@@ -30,10 +30,11 @@ PEAK_DENSE_BF16 = 2500.0      # TFLOP/s, dense bf16 MFMA
 PEAK_SPARSE_BF16 = 5000.0     # TFLOP/s, 2:4 structured-sparse bf16 (dense-equivalent FLOPs)
 PEAK_HBM = 8000.0             # GB/s
 
-# HBM-side bytes per launch (read + written, mean over the kernel's launches in a step) measured with rocprofv3
-# PMC runs of this file (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy):
+# HBM-side bytes per call of the entry point (read + written; mean over the calls of a step; for the weight
+# gradient the one s24_dense_dw_batch pass, both of its launches) measured with rocprofv3 PMC runs of this file
+# (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy):
 # profiles/c4_step_hbm_traffic_pmc.md.  Only for the default configuration of the named workload.
-MEASURED_TRAFFIC_BYTES = {("c4", "dense_dw"): 4.214e9, ("c4", "spmm_fwd"): 3.68e9, ("c4", "spmm_bwd_dx"): 2.77e9}
+MEASURED_TRAFFIC_BYTES = {("c4", "dense_dw"): 7.609e9, ("c4", "spmm_fwd"): 3.68e9, ("c4", "spmm_bwd_dx"): 2.77e9}
 
 
 def kernel_model(wl):
