@@ -282,7 +282,12 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
             flops = 2.0 * wl.p * q * r
             t_dense = _time_ms(torch, lambda: s24.dense_gemm(A, w.W, Yd), 5)
             t_sparse = _time_ms(torch, lambda: s24.spmm_fwd(A, w.vals, w.meta, Yd), 5)
+            # context, not this library's code: the same dense GEMM through PyTorch's matmul (the vendor's GEMM library)
+            t_vendor = _time_ms(torch, lambda: torch.matmul(A, w.W.t(), out=Yd), 5)
             cmp_.append({"weight": name, "shape_p_q_r": [wl.p, q, r],
+                         "vendor_library_dense_ms": round(t_vendor, 4),
+                         "vendor_library_dense_TFLOP/s": round(flops / t_vendor / 1e9, 1),
+                         "speedup_over_vendor_library_dense": round(t_vendor / t_sparse, 3),
                          "dense_mfma_ms": round(t_dense, 4), "dense_mfma_TFLOP/s": round(flops / t_dense / 1e9, 1),
                          "sparse_smfmac_ms": round(t_sparse, 4),
                          "sparse_dense_equiv_TFLOP/s": round(flops / t_sparse / 1e9, 1),
@@ -292,6 +297,15 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
         r, q = up.W.shape
         Yd = torch.empty((wl.p, r), dtype=X.dtype, device=X.device)
         dYr = torch.empty((wl.p, r), dtype=X.dtype, device=X.device).normal_()
+        # the weight gradient next to the vendor library's dY^T X (bf16 output there, fp32 here)
+        t_dw = _time_ms(torch, lambda: s24.dense_dw(dYr, X, up.grad, 0.0), 5)
+        dWv = torch.empty((r, q), dtype=X.dtype, device=X.device)
+        t_dwv = _time_ms(torch, lambda: torch.matmul(dYr.t(), X, out=dWv), 5)
+        fl = 2.0 * wl.p * q * r
+        out["weight_gradient_vs_vendor_library"] = {
+            "shape_p_q_r": [wl.p, q, r], "s24_dense_dw_ms": round(t_dw, 4), "s24_TFLOP/s": round(fl / t_dw / 1e9, 1),
+            "vendor_library_ms": round(t_dwv, 4), "vendor_library_TFLOP/s": round(fl / t_dwv / 1e9, 1)}
+        del dWv
         clocks = {
             "spmm_fwd": _clock_mhz(torch, s24, lambda: s24.spmm_fwd(X, up.vals, up.meta, Yd)),
             "dense_dw": _clock_mhz(torch, s24, lambda: s24.dense_dw(dYr, X, up.grad, 0.0)),
