@@ -82,7 +82,7 @@ int s24_pattern_table(uint16_t out[S24_NUM_PATTERNS]);
  *   mask   [r/4][q/4] device, out
  *   index  [r/4][q/4] device, out, pattern ids; may be NULL
  * r, q multiples of 4 (S24_ERR_SHAPE otherwise); W and ldw*elemsize 8-byte
- * aligned for bf16, 16-byte for f32 (S24_ERR_ALIGN). */
+ * aligned for the 16-bit types, 16-byte for f32 (S24_ERR_ALIGN). */
 int s24_transposable_mask(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
                           uint16_t *mask, uint8_t *index, void *stream);
 
@@ -101,7 +101,7 @@ int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
 
 /* Forward sparse GEMM (Eq. 2):  Y[p][r] = X[p][q] . (M.*W)^T, contraction over
  * q against the compressed weight (vals [q/64][r][32], meta [q/64][r][4]).
- * bf16 in / fp32 accumulate / bf16 out (f32 throughout for S24_F32).
+ * 16-bit in / fp32 accumulate / 16-bit out (f32 throughout for S24_F32).
  * p >= 1; q multiple of 64; r multiple of 16. */
 int s24_spmm_fwd(const void *X, const void *vals, const uint16_t *meta, void *Y,
                  int64_t p, int64_t q, int64_t r, s24_dtype dt, void *stream);
@@ -158,7 +158,7 @@ int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, vo
  * (Eq. 3 + Sec. 5.2): dH = dY[p][r] . (M.*W_down) (valsT [r/64][f][32], metaT [r/64][f][4]) is formed tile by
  * tile, rounded to the storage type and consumed on the spot:  dGU[p][2f] = [dH .* U .* silu'(G) | dH .* silu(G)]
  * with G and U the halves of GU[p][2f].  Same bits as s24_spmm_bwd_dx followed by s24_swiglu_bwd.  Only the
- * large-tile bf16 kernel has this epilogue: other dtypes, and outputs of fewer than 192 tiles of 256 x 256, return
+ * large-tile 16-bit kernel has this epilogue: fp32, and outputs of fewer than 192 tiles of 256 x 256, return
  * S24_ERR_UNSUPPORTED and leave everything untouched (use the two calls).  r multiple of 64; f of 16. */
 int s24_spmm_bwd_dx_swiglu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
                            int64_t p, int64_t f, int64_t r, s24_dtype dt, void *stream);
@@ -282,13 +282,13 @@ int s24_mask_flips(const uint16_t *mask_new, const uint16_t *mask_old, int64_t n
 /* L1-norm gap (Sec. 4.2): gap[r/4][q/4] (device, fp64) = for every 4x4 block of W the kept L1 norm of the
  * best legal pattern minus that of the second best one (zero when two patterns tie for the best).  W as in
  * s24_transposable_mask.  The 90 sums are taken in fp64: exact, and the gap correctly rounded, whenever the
- * block's exponent spread fits fp64 (29 binades for bf16 data, 13 for fp32); beyond that the sums carry
+ * block's exponent spread fits fp64 (29 binades for bf16 data, 13 for fp32, always for binary16); beyond that the sums carry
  * fp64 rounding. */
 int s24_l1_norm_gap(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw, double *gap, void *stream);
 
 /* Instrumentation, not part of the method: registers a DEVICE buffer of two uint64 (8-byte aligned), or
  * NULL to switch the probe off (the default).  While a buffer is registered, workgroup 0 of every
- * large-tile bf16 GEMM launched by s24_spmm_fwd / s24_spmm_bwd_dx / s24_dense_dw / s24_dense_gemm
+ * large-tile 16-bit GEMM launched by s24_spmm_fwd / s24_spmm_bwd_dx / s24_dense_dw / s24_dense_gemm
  * overwrites it with {core-clock cycles, ticks of the fixed 100 MHz reference} between its first and its
  * last instruction: cycles / ticks * 100 MHz is the core clock the chip held under that kernel.  The
  * setting is process-wide and not synchronised with launches in flight; the caller keeps the buffer alive

@@ -1,10 +1,14 @@
-// GEMMs of the 2:4-sparse FFN step on gfx950 matrix cores.
+// GEMMs of the 2:4-sparse FFN step on gfx950 matrix cores, for bf16 and IEEE binary16 operands alike (fp32
+// accumulation; the element type only selects the instruction and the epilogue conversions).
 //
 //   sparse NT  out[n][m] = sum_k B[n][k] * A[m][k], A 2:4-compressed along k
-//              (Eq. 2 with A = W, Eq. 3 with A = W^T): v_smfmac_f32_32x32x32_bf16
-//   dense  NT  Y = X W^T (Eq. 1, first GEMM): v_mfma_f32_32x32x16_bf16
-//   dense  TN  dW = dY^T X (Eq. 1, third GEMM): same MFMA after an in-register
-//              8x8 transpose of both operands on their way into LDS
+//              (Eq. 2 with A = W, Eq. 3 with A = W^T): v_smfmac_f32_32x32x32_{bf16,f16},
+//              with the activation forward / backward (Sec. 5.2) and the bias as optional epilogues
+//   sparse TN  dW = S_z(dY^T) X (Eq. 4): the same instruction, the dense operand read through transposing LDS reads
+//   dense  NT  Y = X W^T (Eq. 1, first GEMM; the comparison kernel): v_mfma_f32_32x32x16_{bf16,f16}
+//   dense  TN  dW = dY^T X (Eq. 1, third GEMM): both operands copied as they lie in memory, k-contiguous
+//              fragments by ds_read_b64_tr_b16; masked decay (Eq. 10) as an optional epilogue
+//   fp32       one-thread-per-output kernels for the small checking workload (no fp32 sparse instruction exists)
 //
 // Register layout of the sparse instruction (one 32x32 tile, 32 of k):
 // lane l holds for A row l%32 the eight kept values of k in [16*(l/32),
