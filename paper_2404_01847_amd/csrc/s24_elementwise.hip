@@ -410,6 +410,7 @@ int launch_glu_fwd_t(const void *G, const void *U, void *H, int64_t rows, int64_
                      hipStream_t st)
 {
     const dim3 grid((unsigned)((cols + kTT - 1) / kTT), (unsigned)((rows + kTT - 1) / kTT)), block(kThreads);
+    S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);   // 4 M rows of the source: beyond any token count of one GPU
     auto *g = static_cast<const T *>(G), *u = static_cast<const T *>(U);
     auto *h = static_cast<T *>(H);
     if (gate == S24_GATE_SILU)
@@ -423,6 +424,7 @@ int launch_glu_bwd_t(const void *dH, const void *G, const void *U, void *dG, voi
                      int64_t ld_z, int gate, hipStream_t st)
 {
     const dim3 grid((unsigned)((cols + kTT - 1) / kTT), (unsigned)((rows + kTT - 1) / kTT)), block(kThreads);
+    S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);   // 4 M rows of the source: beyond any token count of one GPU
     auto *d = static_cast<const T *>(dH), *g = static_cast<const T *>(G), *u = static_cast<const T *>(U);
     auto *dg = static_cast<T *>(dG), *du = static_cast<T *>(dU);
     if (gate == S24_GATE_SILU)
