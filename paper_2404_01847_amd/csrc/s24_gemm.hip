@@ -867,9 +867,13 @@ struct DwWindow {
     float lambda;
 };
 constexpr int kMaxBatch = 4;
+// Workgroups are dealt round-robin to the eight XCDs.  Each XCD takes, of every problem in turn, one contiguous
+// eighth of its tile list: first_slot[i] .. first_slot[i+1]-1 are the positions in an XCD's own list that belong to
+// problem i (unused entries repeat the total), so every problem is spread over all XCDs exactly as a launch of its
+// own would spread it, and the workgroups resident on one XCD share operand rows in its L2.
 struct DwBatch {
     DwWindow w[kMaxBatch];
-    int first_tile[kMaxBatch + 1];   // first_tile[i] .. first_tile[i+1]-1 are the tiles of problem i; unused entries repeat the total
+    int first_slot[kMaxBatch + 1];
 };
 
 template <typename ET, int WT, int BT_, bool ACCUM, bool DECAY>
@@ -888,16 +892,15 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
-    // Workgroups are dealt round-robin to the eight XCDs; each XCD takes one contiguous slab of the tile list
-    const int total = batch.first_tile[kMaxBatch], per_xcd = (total + 7) / 8;
-    int t = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (t >= total) return;
-    int which = 0;   // wave-uniform: the problem this tile belongs to
+    const int slot = (int)(blockIdx.x >> 3);
+    int which = 0;   // wave-uniform: the problem this workgroup's tile belongs to
 #pragma unroll
     for (int i = 1; i < kMaxBatch; ++i)
-        if (t >= batch.first_tile[i]) which = i;
-    t -= batch.first_tile[which];
+        if (slot >= batch.first_slot[i]) which = i;
     const DwWindow &win = batch.w[which];
+    const int per_xcd = batch.first_slot[which + 1] - batch.first_slot[which];
+    const int t = (int)(blockIdx.x & 7) * per_xcd + (slot - batch.first_slot[which]);
+    if (t >= win.tiles_m * win.tiles_n) return;
     const uint16_t *__restrict__ dY = win.dY, *__restrict__ X = win.X, *__restrict__ Wt = win.Wt, *__restrict__ mask = win.mask;
     float *__restrict__ dW = win.dW;
     const int T = win.T, M = win.M, N = win.N, ldy = win.ldy, ldx = win.ldx, ldw = win.ldw;
@@ -1655,8 +1658,8 @@ dmatn::DwWindow dw_window(const DwProblem &pr, int tile, int64_t m_off, int64_t 
 // tile: 256 (large), or 128 (small; 32 tokens per stage when there are more tiles than compute units, else 64)
 void launch_dw_batch(const dmatn::DwBatch &batch, int tile, bool accum, bool decay, int dt, hipStream_t st)
 {
-    const int total = batch.first_tile[dmatn::kMaxBatch];
-    const dim3 grid(((total + 7) / 8) * 8), block(dmatn::THREADS);
+    const int slots = batch.first_slot[dmatn::kMaxBatch];   // per XCD
+    const dim3 grid(slots * 8), block(dmatn::THREADS);
 #define S24_LAUNCH_DW(WT, BT, ACC, DEC) \
     hipLaunchKernelGGL((dmatn::dense_tn_dma_kernel<T, WT, BT, ACC, DEC>), grid, block, 0, st, batch, g_clock_probe)
 #define S24_LAUNCH_DW_TILE(WT, BT)                               \
@@ -1668,7 +1671,7 @@ void launch_dw_batch(const dmatn::DwBatch &batch, int tile, bool accum, bool dec
     } while (0)
     S24_WITH_16BIT_TYPE(dt, {
         if (tile == 256) S24_LAUNCH_DW_TILE(4, 32);
-        else if (total > 256) S24_LAUNCH_DW_TILE(2, 32);
+        else if (slots * 8 > 256) S24_LAUNCH_DW_TILE(2, 32);
         else S24_LAUNCH_DW_TILE(2, 64);
     });
 #undef S24_LAUNCH_DW_TILE
@@ -1692,8 +1695,8 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
             const DwProblem pr{a, b, dW, w, fuse ? mask : nullptr, p, q, r, lambda};
             dmatn::DwBatch batch{};
             batch.w[0] = dw_window(pr, tile, m_off, mm, n_off, nn);
-            const int tiles = batch.w[0].tiles_m * batch.w[0].tiles_n;
-            for (int i = 1; i <= dmatn::kMaxBatch; ++i) batch.first_tile[i] = tiles;
+            const int slots = (batch.w[0].tiles_m * batch.w[0].tiles_n + 7) / 8;
+            for (int i = 1; i <= dmatn::kMaxBatch; ++i) batch.first_slot[i] = slots;
             launch_dw_batch(batch, tile, accum, fuse, dt, st);
         };
         // 256 x 256 tiles when they fill the chip, 128 x 128 tiles otherwise.  A grid of large tiles that is not a
@@ -1824,17 +1827,17 @@ extern "C" int s24_dense_dw_batch(const s24_dw_problem *problems, int count, flo
         const int64_t keep_m = i == cut && cut_rows ? 256ll * ((int64_t)ceil_div(prs[i].r, 256) - cut_rows) : prs[i].r;
         const int64_t keep_n = i == cut && cut_cols ? 256ll * ((int64_t)ceil_div(prs[i].q, 256) - cut_cols) : prs[i].q;
         batch.w[i] = dw_window(prs[i], 256, 0, keep_m, 0, keep_n);
-        batch.first_tile[i] = first;
-        first += batch.w[i].tiles_m * batch.w[i].tiles_n;
+        batch.first_slot[i] = first;
+        first += (batch.w[i].tiles_m * batch.w[i].tiles_n + 7) / 8;
     }
-    for (int i = count; i <= dmatn::kMaxBatch; ++i) batch.first_tile[i] = first;
+    for (int i = count; i <= dmatn::kMaxBatch; ++i) batch.first_slot[i] = first;
     launch_dw_batch(batch, 256, accum, decay, dt, st);
     if (cut >= 0) {
         dmatn::DwBatch strip{};
         const int64_t m_off = cut_rows ? batch.w[cut].M : 0, n_off = cut_cols ? batch.w[cut].N : 0;
         strip.w[0] = dw_window(prs[cut], 128, m_off, prs[cut].r - m_off, n_off, prs[cut].q - n_off);
-        const int tiles = strip.w[0].tiles_m * strip.w[0].tiles_n;
-        for (int i = 1; i <= dmatn::kMaxBatch; ++i) strip.first_tile[i] = tiles;
+        const int slots = (strip.w[0].tiles_m * strip.w[0].tiles_n + 7) / 8;
+        for (int i = 1; i <= dmatn::kMaxBatch; ++i) strip.first_slot[i] = slots;
         launch_dw_batch(strip, 128, accum, decay, dt, st);
     }
     return s24_launch_status();
