@@ -34,7 +34,7 @@ PEAK_HBM = 8000.0             # GB/s
 # gradient the one s24_dense_dw_batch pass, both of its launches) measured with rocprofv3 PMC runs of this file
 # (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy):
 # profiles/c4_step_hbm_traffic_pmc.md.  Only for the default configuration of the named workload.
-MEASURED_TRAFFIC_BYTES = {("c4", "dense_dw"): 7.609e9, ("c4", "spmm_fwd"): 3.68e9, ("c4", "spmm_bwd_dx"): 2.77e9}
+MEASURED_TRAFFIC_BYTES = {("c4", "dense_dw"): 8.625e9, ("c4", "spmm_fwd"): 3.68e9, ("c4", "spmm_bwd_dx"): 2.77e9}
 
 
 def kernel_model(wl):
