@@ -22,18 +22,20 @@ static inline int s24_launch_status() { return hipGetLastError() == hipSuccess ?
 
 __device__ __forceinline__ float s24_bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
-// fp32 -> bf16, round to nearest even (inputs are finite).
-__device__ __forceinline__ uint32_t s24_f32_to_bf16(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
+// Two fp32 values -> two bf16 in one dword (lo in bits 0..15), round to nearest even: gfx950's packed conversion,
+// one instruction where the integer form (add the rounding bias, shift, merge) takes seven.  Written as the
+// instruction itself so that every kernel rounds the same fp32 value to the same bits.
 __device__ __forceinline__ uint32_t s24_pack_bf16x2(float lo, float hi)
 {
-    return s24_f32_to_bf16(lo) | (s24_f32_to_bf16(hi) << 16);
+    uint32_t d = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(d) : "v"(lo), "v"(hi));
+#endif
+    return d;
 }
+
+// fp32 -> bf16 bits, round to nearest even.
+__device__ __forceinline__ uint32_t s24_f32_to_bf16(float f) { return s24_pack_bf16x2(f, f) & 0xFFFFu; }
 
 // Storage types of the kernels: uint16_t holds bf16 bits, s24_half is IEEE binary16, float is itself.
 // s24_num<T> converts between 16-bit storage and the fp32 the arithmetic runs in: one value from its 16 bits,
