@@ -145,6 +145,25 @@ def _time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
+INFINITY_CACHE_BYTES = 256e6   # the memory-side cache in front of HBM
+
+
+def _rotation(working_set_bytes):
+    """How many distinct sets of buffers a repeated measurement of an HBM-bound kernel cycles through so that a
+    set has left the Infinity Cache before its turn comes again (the sets together are over twice its size)."""
+    return int(2 * INFINITY_CACHE_BYTES // working_set_bytes) + 2
+
+
+def _in_turn(calls):
+    """A function that makes the next of `calls` each time it is called."""
+    state = {"i": 0}
+
+    def fn():
+        calls[state["i"] % len(calls)]()
+        state["i"] += 1
+    return fn
+
+
 def _clock_mhz(torch, s24, fn, reps=6):
     """Core clock the chip holds under `fn` (a large-tile GEMM launch): the library's clock probe makes
     workgroup 0 of the last launch report core cycles and 100 MHz reference ticks over its lifetime."""
@@ -205,7 +224,9 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     ms = _time_ms(torch, sweep, 10)
     nbytes = sum(w.W.numel() / 16 * (16 * es + 2) for w in ws)
     out["mask_search_only"] = {"ms_per_sweep": round(ms, 4), "matrices": len(ws), "GB/s": round(nbytes / ms / 1e6, 1),
-                               "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM, 4)}
+                               "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM, 4),
+                               "working_set_MB": round(nbytes / 1e6, 1),
+                               "cache_resident": bool(nbytes < 2 * INFINITY_CACHE_BYTES)}
     if wl.name == "c3":
         import numpy as np
         # the 72 matrices, stacked by shape the way a model can hold its layers' weights: [36*d_ff][d] and [36*d][d_ff]
@@ -246,7 +267,9 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     gap = torch.empty(w0.mask.shape, dtype=torch.float64, device="cuda")
     ms_g = _time_ms(torch, lambda: s24.l1_norm_gap(w0.W, gap), 5)
     nb = w0.mask.numel()
-    out["monitors"] = {"mask_flips": {"ms": round(ms_f, 4), "GB/s": round(nb * 4 / ms_f / 1e6, 1)},
+    out["monitors"] = {"buffers": "one weight, repeated: cache-resident when its bytes fit the 256 MB Infinity Cache",
+                       "mask_flips": {"ms": round(ms_f, 4), "GB/s": round(nb * 4 / ms_f / 1e6, 1),
+                                      "cache_resident": bool(nb * 4 < INFINITY_CACHE_BYTES)},
                        "l1_norm_gap": {"ms": round(ms_g, 4), "GB/s": round(nb * (16 * es + 8) / ms_g / 1e6, 1),
                                        "bound": "alu (90 x 16 fp64 select-adds per block)"}}
     # (7) the step with the weight gradient taken from the unbiasedly pruned output gradient (Eq. 4, Eq. 6)
@@ -328,33 +351,38 @@ def gated_activation_measurements(torch, s24):
     (the paper's kernel), column-major in and row-major out (the layout this library's GEMMs consume; the change of
     layout rides on the same pass through 64 x 64 LDS tiles), row-major in and out.  GB/s counts the algorithmic
     bytes: Z read once, H written once (3 f p elements).  Also the backward kernel and the bias gradient at the
-    widest input."""
-    out = {"input": "32 x 512 x d, binary16", "rows": []}
+    widest input.  The smaller inputs would fit the Infinity Cache, so each measurement goes round several distinct
+    sets of buffers."""
+    out = {"input": "32 x 512 x d, binary16", "rows": [],
+           "buffers": "every measurement cycles through distinct buffer sets of over 512 MB together, so no call finds "
+                      "its operands in the 256 MB Infinity Cache: the rates are HBM rates"}
     p = 32 * 512
+    half = lambda *shape: torch.empty(shape, dtype=torch.float16, device="cuda")
     for d in (768, 1024, 1280, 1600, 2048, 4096, 8192):
         f = d // 2
-        Zc = torch.empty((d, p), dtype=torch.float16, device="cuda").normal_()
-        Zr = torch.empty((p, d), dtype=torch.float16, device="cuda").normal_()
-        Hc = torch.empty((f, p), dtype=torch.float16, device="cuda")
-        Hr = torch.empty((p, f), dtype=torch.float16, device="cuda")
         nbytes = 3.0 * f * p * 2
-        row = {"d": d}
-        for tag, z, h, lz, lh in (("col_to_col", Zc, Hc, 1, 1), ("col_to_row", Zc, Hr, 1, 0), ("row_to_row", Zr, Hr, 0, 0)):
-            ms = _time_ms(torch, lambda: s24.glu_fwd(z, h, s24.GATE_GELU_ERF, layout_z=lz, layout_h=lh), 20)
+        n = _rotation(nbytes)
+        sets = [(half(d, p).normal_(), half(p, d).normal_(), half(f, p), half(p, f)) for _ in range(n)]
+        row = {"d": d, "buffer_sets": n}
+        for tag, zi, hi, lz, lh in (("col_to_col", 0, 2, 1, 1), ("col_to_row", 0, 3, 1, 0), ("row_to_row", 1, 3, 0, 0)):
+            calls = [lambda z=b[zi], h=b[hi]: s24.glu_fwd(z, h, s24.GATE_GELU_ERF, layout_z=lz, layout_h=lh) for b in sets]
+            ms = _time_ms(torch, _in_turn(calls), 20)
             row[tag] = {"ms": round(ms, 4), "GB/s": round(nbytes / ms / 1e6, 1)}
         out["rows"].append(row)
+        if d != 8192:
+            del sets
     # backward and bias gradient at d = 8192 (dH read, Z read, dZ written: 5 f p elements; bias gradient: 2 f p read)
-    dHc = torch.empty((f, p), dtype=torch.float16, device="cuda").normal_()
-    dHr = torch.empty((p, f), dtype=torch.float16, device="cuda").normal_()
-    dZc, dZr = torch.empty_like(Zc), torch.empty_like(Zr)
-    ms_c = _time_ms(torch, lambda: s24.glu_bwd(dHc, Zc, dZc, s24.GATE_GELU_ERF, layout_h=1, layout_z=1), 20)
-    ms_r = _time_ms(torch, lambda: s24.glu_bwd(dHr, Zr, dZr, s24.GATE_GELU_ERF), 20)
-    ms_x = _time_ms(torch, lambda: s24.glu_bwd(dHr, Zc, dZc, s24.GATE_GELU_ERF, layout_h=0, layout_z=1), 20)
+    bsets = [(half(f, p).normal_(), half(p, f).normal_(), half(d, p), half(p, d)) for _ in range(len(sets))]
+    bwd = lambda hi, zi, oi, lh, lz: _in_turn([lambda dh=b[hi], z=a[zi], dz=b[oi]: s24.glu_bwd(
+        dh, z, dz, s24.GATE_GELU_ERF, layout_h=lh, layout_z=lz) for a, b in zip(sets, bsets)])
+    ms_c = _time_ms(torch, bwd(0, 0, 2, 1, 1), 20)
+    ms_r = _time_ms(torch, bwd(1, 1, 3, 0, 0), 20)
+    ms_x = _time_ms(torch, bwd(1, 0, 2, 0, 1), 20)
     out["backward_d8192"] = {k: {"ms": round(ms, 4), "GB/s": round(5.0 * f * p * 2 / ms / 1e6, 1)}
                              for k, ms in (("col", ms_c), ("row", ms_r), ("row_dH_col_Z", ms_x))}
     db = torch.empty(d, dtype=torch.float32, device="cuda")
-    ms_br = _time_ms(torch, lambda: s24.bias_grad(dZr, db), 20)
-    ms_bc = _time_ms(torch, lambda: s24.bias_grad(dZc, db, layout=s24.COL_MAJOR), 20)
+    ms_br = _time_ms(torch, _in_turn([lambda z=a[1]: s24.bias_grad(z, db) for a in sets]), 20)
+    ms_bc = _time_ms(torch, _in_turn([lambda z=a[0]: s24.bias_grad(z, db, layout=s24.COL_MAJOR) for a in sets]), 20)
     out["bias_grad_d8192"] = {"row_major": {"ms": round(ms_br, 4), "GB/s": round(2.0 * d * p / ms_br / 1e6, 1)},
                               "col_major": {"ms": round(ms_bc, 4), "GB/s": round(2.0 * d * p / ms_bc / 1e6, 1)}}
     return out
