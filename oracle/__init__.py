@@ -125,13 +125,17 @@ def l1_norm_gap(W: np.ndarray) -> np.ndarray:
 
 
 def mvue24(dY: np.ndarray, seed: int):
-    """Unbiased 2:4 pruning of dY^T along the tokens: vals[r, p/2] (dtype of dY), meta[r, p/16]."""
-    dY = _c(dY)
+    """Unbiased 2:4 pruning of dY^T along the tokens: vals[r, p/2] (dtype of dY), meta[r, p/16].
+    dY may be a view of a wider row-major matrix (unit column stride): its row stride is passed on as it is."""
+    if not (dY.ndim == 2 and dY.strides[1] == dY.itemsize and dY.strides[0] % dY.itemsize == 0
+            and dY.strides[0] >= dY.shape[1] * dY.itemsize):
+        dY = _c(dY)
     p, r = dY.shape
+    ld = dY.strides[0] // dY.itemsize if p > 1 else r
     vals = np.zeros((r, p // 2), dtype=dY.dtype)
     meta = np.zeros((r, p // 16), dtype=np.uint16)
-    rc = _load().orc_mvue24(_p(dY), _dt(dY), C.c_int64(p), C.c_int64(r), C.c_int64(r), C.c_uint32(seed & 0xFFFFFFFF),
-                            _p(vals), _p(meta))
+    rc = _load().orc_mvue24(C.c_void_p(dY.ctypes.data), _dt(dY), C.c_int64(p), C.c_int64(r), C.c_int64(ld),
+                            C.c_uint32(seed & 0xFFFFFFFF), _p(vals), _p(meta))
     _check(rc, "mvue24")
     return vals, meta
 

@@ -85,6 +85,22 @@ def test_mask_ties_and_wide_ranges_bit_exact(s24, dtype, kind):
     assert np.array_equal(got_i, want_i), kind
 
 
+@pytest.mark.parametrize("dtype,big_exp", [("f32", 30), ("f32", 100), ("bf16", 47), ("bf16", 100)])
+def test_mask_margin_below_fp64_resolution(s24, dtype, big_exp, legal_blocks):
+    """Blocks whose best pattern wins by one unit in the last place of 1 beside six cells of 2^big_exp (sums of fp64
+    terms cannot tell it from an earlier pattern): the search alone and fused with compress."""
+    from util import absorbed_margin_blocks
+    W, want = absorbed_margin_blocks(legal_blocks, dtype, big_exp)
+    W = np.ascontiguousarray(np.tile(W[:, :320], (16, 1)))        # [64, 320]: 16 x 80 blocks
+    want_m, want_i = oracle.transposable_mask(W, want_index=True)
+    assert [int(v) for v in want_m[0]] == want[:80]
+    got_m, got_i = gpu_mask(s24, W)
+    assert np.array_equal(got_m, want_m)
+    assert np.array_equal(got_i, want_i)
+    fused = gpu_compress(s24, W, None)
+    assert np.array_equal(host_bits(fused[4]), want_m)
+
+
 def test_mask_strided_weight_and_empty(s24):
     W = si.random_matrix(5, (64, 256), 0.02, "bf16")
     Wd = dev_bf16(W)
@@ -501,6 +517,29 @@ def test_mvue24_matches_the_oracle_bit_for_bit(s24, dtype, shape):
     torch.cuda.synchronize()
     want_v2, want_m2 = oracle.pack(*oracle.mvue24(dY, 7))
     assert np.array_equal(host_bits(meta), want_m2) and not np.array_equal(want_m2, want_m)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_mvue24_degenerate_and_repeated_groups(s24, dtype):
+    """Groups with one non-zero at each position, the same four numbers in every group of every feature (only the draw
+    differs), equal magnitudes, and a dominant element (capped probability): bit for bit as the oracle."""
+    p, r = 128, 80
+    x = np.zeros((p, r), dtype=np.float32)
+    for pos in range(4):
+        x[16 * pos + pos:16 * pos + 16:4, :] = (-1.0) ** pos * (0.375 + pos)     # tokens 0..63: single non-zeros
+    x[64:96] = np.tile(np.array([1.0, -2.0, 3.0, 4.0], dtype=np.float32), 8)[:, None]
+    x[96:112] = np.tile(np.array([2.0, -2.0, 2.0, 2.0], dtype=np.float32), 4)[:, None]
+    x[112:128] = np.tile(np.array([9.0, 0.0, 2.0, -1.0], dtype=np.float32), 4)[:, None]
+    dY = x if dtype == "f32" else si.f32_to_bf16_bits(torch.from_numpy(x))
+    vals = torch.zeros((p // 64, r, 32), dtype=tdtype(dtype), device="cuda")
+    meta = torch.zeros((p // 64, r, 4), dtype=torch.int16, device="cuda")
+    for seed in (1, 2, 3):
+        s24.mvue24(dev_bf16(dY), seed, vals, meta)
+        torch.cuda.synchronize()
+        want_v, want_m = oracle.pack(*oracle.mvue24(dY, seed))
+        word = np.uint32 if dtype == "f32" else np.uint16
+        assert np.array_equal(host_bits(meta), want_m), seed
+        assert np.array_equal(host_bits(vals).view(word), want_v.view(word)), seed
 
 
 def test_mvue24_strided_input(s24):

@@ -120,6 +120,22 @@ def test_mask_fast_and_wide_paths_agree(dtype):
     assert np.array_equal(oracle.transposable_mask(W), oracle.transposable_mask(W, exact_wide=True))
 
 
+@pytest.mark.parametrize("dtype,big_exp", [("f32", 27), ("f32", 30), ("f32", 45), ("f32", 100),
+                                           ("bf16", 43), ("bf16", 47), ("bf16", 60), ("bf16", 100)])
+def test_mask_margin_below_fp64_resolution(dtype, big_exp, legal_blocks):
+    """Blocks in which the best pattern beats an earlier one by one unit in the last place of 1 while both hold six
+    cells of 2^big_exp: sums of eight fp64 terms stop seeing the margin a few binades past the width the oracle's
+    exactness check allows (53 bits), so a check that let such blocks take the fp64 route would return the earlier
+    pattern.  Expected values: by construction, and by rational arithmetic."""
+    from util import absorbed_margin_blocks
+    W, want = absorbed_margin_blocks(legal_blocks, dtype, big_exp)
+    assert len(want) >= 80
+    for kw in ({}, {"exact_wide": True}):
+        got = oracle.transposable_mask(W, **kw)
+        assert [int(v) for v in got[0]] == want, kw
+    check_against_brute_force(W[:, :64], legal_blocks)
+
+
 def test_mask_every_block_is_legal():
     W = si.random_matrix(4, (256, 512), 0.02, "bf16")
     m = expand_mask(oracle.transposable_mask(W))
@@ -492,6 +508,47 @@ def test_mvue_deterministic_groups():
     out, kept = mvue_dense(col, 3)
     assert np.array_equal(out[0][kept[0]], 2.0 * col[:, 0][kept[0]])
     assert np.all(out[0][~kept[0]] == 0)
+
+
+def test_mvue_single_nonzero_survives_at_every_position():
+    # a group with one non-zero element has nothing to draw: the element is kept as it is, wherever it stands
+    for pos in range(4):
+        for x in (7.0, -0.375):
+            col = np.zeros((16, 3), dtype=np.float32)
+            col[pos::4, :] = x
+            for seed in range(8):
+                out, kept = mvue_dense(col, seed)
+                assert np.array_equal(out, col.T.astype(np.float64)), (pos, x, seed)
+                assert kept.reshape(3, 4, 4).sum(axis=2).tolist() == [[2] * 4] * 3
+
+
+def test_mvue_draws_differ_across_features_groups_and_seeds():
+    """The same four numbers in every group of every feature: whatever differs between two outputs is the draw.
+    Kept frequencies taken over features alone (one token group), over token groups alone (one feature) and over
+    seeds alone (one group of one feature) must each approach the inclusion probabilities 2 |a_j| / S."""
+    a = np.array([1.0, -2.0, 3.0, 4.0], dtype=np.float32)
+    pi = 2 * np.abs(a) / np.abs(a).sum()
+    tol = lambda n: 5 * np.sqrt(pi * (1 - pi) / n) + 1e-9
+    r = 4096
+    _, kept = mvue_dense(np.tile(a.reshape(4, 1), (4, r)), 21)                  # 4 groups x 4096 features
+    for g in range(4):
+        freq = kept[:, 4 * g:4 * g + 4].mean(axis=0)
+        assert np.all(np.abs(freq - pi) <= tol(r)), ("over features", g, freq)
+    assert not np.array_equal(kept[:, 0:4], kept[:, 4:8])                       # and group 1 is not a copy of group 0
+    G = 4096
+    _, kept = mvue_dense(np.tile(a, G).reshape(4 * G, 1), 22)                   # 4096 groups of one feature
+    assert np.all(np.abs(kept[0].reshape(G, 4).mean(axis=0) - pi) <= tol(G))
+    n = 1024
+    seen = np.stack([mvue_dense(np.tile(a, 4).reshape(16, 1), seed)[1][0, :4] for seed in range(n)])
+    assert np.all(np.abs(seen.mean(axis=0) - pi) <= tol(n)), ("over seeds", seen.mean(axis=0))
+
+
+def test_mvue_reads_a_strided_operand():
+    wide = si.random_matrix(54, (64, 40), 1e-2, "bf16")
+    view = wide[:, 8:32]                                                         # row stride 40, 24 features
+    a = oracle.mvue24(view, 9)
+    b = oracle.mvue24(np.ascontiguousarray(view), 9)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
 
 
 @pytest.mark.parametrize("group", [(1.0, 2.0, 3.0, 4.0), (0.3, -0.2, 0.25, -0.1), (5.0, 1.0, -1.5, 0.5), (9.0, 0.0, 2.0, -1.0)])

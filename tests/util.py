@@ -72,3 +72,41 @@ def assert_close(got, ref, tol, what=""):
     assert np.isfinite(got).all(), f"{what}: non-finite output"
     assert e_max <= tol[0] and e_nrm <= tol[1], f"{what}: max rel {e_max:.3e} (<= {tol[0]}), normwise {e_nrm:.3e} (<= {tol[1]})"
     return e_max, e_nrm
+
+
+def absorbed_margin_blocks(legal, dtype: str, big_exp: int, every: int = 7):
+    """4x4 blocks whose two best patterns differ by less than fp64 sums of eight terms can see.
+
+    For a pair of legal patterns (a, b), a before b in the canonical order, that share six cells and differ by one
+    2x2 swap (no third pattern holds all six shared cells), the shared cells hold 2^big_exp, the two cells only a has
+    hold 1 and 1, the two only b has hold 1 + ulp and 1, everything else 0: b retains exactly one ulp of 1 more than
+    a, so exact scoring picks b although a comes first, while 6 * 2^big_exp + 2 + ulp rounds to 6 * 2^big_exp + 2 in
+    fp64 once big_exp is large enough - a scorer that adds in fp64 there sees a tie and takes a.
+    `legal` is the list of the 90 encodings in canonical order (bit 4i+j = m_ij).  Returns (W [4, 4n] in the storage
+    of `dtype` ("f32" or "bf16"), the n expected encodings)."""
+    ulp = {"f32": 2.0 ** -23, "bf16": 2.0 ** -7}[dtype]
+    blocks, want = [], []
+    n = 0
+    for ia, a in enumerate(legal):
+        for b in legal[ia + 1:]:
+            shared = a & b
+            if bin(shared).count("1") != 6 or any(c not in (a, b) and (c & shared) == shared for c in legal):
+                continue
+            n += 1
+            if n % every:
+                continue
+            blk = np.zeros(16, dtype=np.float64)
+            for t in range(16):
+                if (shared >> t) & 1:
+                    blk[t] = 2.0 ** big_exp
+            only_a = [t for t in range(16) if ((a & ~b) >> t) & 1]
+            only_b = [t for t in range(16) if ((b & ~a) >> t) & 1]
+            blk[only_a[0]], blk[only_a[1]] = 1.0, 1.0
+            blk[only_b[0]], blk[only_b[1]] = 1.0 + ulp, 1.0
+            sign = np.where((np.arange(16) + n) % 3 == 0, -1.0, 1.0)   # signs must not matter
+            blocks.append((blk * sign).reshape(4, 4))
+            want.append(b)
+    W = np.concatenate(blocks, axis=1).astype(np.float32)
+    if dtype == "bf16":
+        W = si.f32_to_bf16_bits(torch.from_numpy(W))
+    return W, want
