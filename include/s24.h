@@ -185,8 +185,9 @@ int s24_dense_dw_decay(const void *dY, const void *X, float *dW, const void *W, 
  * whole number of rounds by at most half a round, that excess is cut off as whole tile columns or rows of one
  * problem and run in small tiles.  `problems` is a HOST array of `count` <= 4 entries, read during the call:
  *   dY [p][r], X [p][q] (dtype dt), dW [r][q] fp32, W [r][q] (dtype dt) or NULL, mask [r/4][q/4] (with W), lambda.
- * Problems that do not fit the shared grid (fp32, no tokens, small outputs, decay on some but not all) are run one
- * after the other instead.  All problems are validated before the first launch. */
+ * Problems that are each too small for the large tile share one grid of small tiles in the same way.  Problems that
+ * fit neither shared grid (fp32, no tokens, an empty output, small and large outputs mixed, decay on some but not
+ * all) are run one after the other instead.  All problems are validated before the first launch. */
 typedef struct {
     const void *dY;
     const void *X;

@@ -1792,7 +1792,34 @@ extern "C" int s24_dense_dw_batch(const s24_dw_problem *problems, int count, flo
         shared_grid = shared_grid && pr.p > 0 && tiles >= 64 && (pr.W != nullptr) == (problems[0].W != nullptr);
         total += tiles;
     }
+    const bool accum = beta != 0.0f, decay = problems[0].W != nullptr;
+    DwProblem prs[dmatn::kMaxBatch];
+    for (int i = 0; i < count; ++i) {
+        const s24_dw_problem &pr = problems[i];
+        prs[i] = DwProblem{static_cast<const uint16_t *>(pr.dY), static_cast<const uint16_t *>(pr.X), pr.dW,
+                           static_cast<const uint16_t *>(pr.W), pr.mask, pr.p, pr.q, pr.r, pr.lambda};
+    }
     if (!shared_grid || total < 192 || count == 1) {
+        // Problems that would each run in small tiles anyway (fewer than 192 large ones) share one small-tile grid:
+        // a GPT-2-small layer's two gradients are 144 small tiles each, 0.56 of the chip one after the other.
+        bool small_grid = dt != S24_F32 && count > 1;
+        for (int i = 0; i < count; ++i) {
+            const s24_dw_problem &pr = problems[i];
+            small_grid = small_grid && pr.p > 0 && pr.q * pr.r != 0 && (pr.W != nullptr) == decay &&
+                         (int64_t)ceil_div(pr.r, 256) * ceil_div(pr.q, 256) < 192;
+        }
+        if (small_grid) {
+            dmatn::DwBatch batch{};
+            int first = 0;
+            for (int i = 0; i < count; ++i) {
+                batch.w[i] = dw_window(prs[i], 128, 0, prs[i].r, 0, prs[i].q);
+                batch.first_slot[i] = first;
+                first += (batch.w[i].tiles_m * batch.w[i].tiles_n + 7) / 8;
+            }
+            for (int i = count; i <= dmatn::kMaxBatch; ++i) batch.first_slot[i] = first;
+            launch_dw_batch(batch, 128, accum, decay, dt, st);
+            return s24_launch_status();
+        }
         for (int i = 0; i < count; ++i) {
             const s24_dw_problem &pr = problems[i];
             if (pr.q * pr.r == 0) continue;
@@ -1800,13 +1827,6 @@ extern "C" int s24_dense_dw_batch(const s24_dw_problem *problems, int count, flo
             if (rc != S24_OK) return rc;
         }
         return S24_OK;
-    }
-    const bool accum = beta != 0.0f, decay = problems[0].W != nullptr;
-    DwProblem prs[dmatn::kMaxBatch];
-    for (int i = 0; i < count; ++i) {
-        const s24_dw_problem &pr = problems[i];
-        prs[i] = DwProblem{static_cast<const uint16_t *>(pr.dY), static_cast<const uint16_t *>(pr.X), pr.dW,
-                           static_cast<const uint16_t *>(pr.W), pr.mask, pr.p, pr.q, pr.r, pr.lambda};
     }
     // The tiles of all problems make one list.  If its length is not a whole number of rounds over the 256 compute
     // units, look for a problem from which whole tile columns (or rows) amounting to exactly the excess, and to at

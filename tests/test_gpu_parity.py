@@ -368,6 +368,8 @@ def test_dense_dw_round_exact_slab_plus_small_tile_strip(s24, dtype, rq, beta):
     ("f16", 70, [(4096, 4352), (4096, 4096), (4112, 4096)], [True, True, True], 1.0),   # 272+256+272 = 800: 32 over, two columns cut
     ("bf16", 90, [(4096, 4096), (4096, 8192)], [False, False], 0.0),     # whole rounds: nothing to cut
     ("bf16", 64, [(4096, 4096), (528, 272)], [True, True], 0.0),         # a small problem: one after the other
+    ("bf16", 200, [(3072, 768), (768, 3072)], [True, True], 0.0),        # c2's pair: 144 + 144 small tiles in one grid
+    ("f16", 96, [(528, 272), (272, 528), (144, 1040)], [False, False, False], 1.0),   # 15 + 15 + 18 small tiles, ragged
     ("bf16", 64, [(4096, 4096), (4096, 4096)], [True, False], 1.0),      # decay on one only: one after the other
     ("f32", 40, [(64, 48), (32, 96)], [True, False], 0.0)])
 def test_dense_dw_batch_equals_the_single_calls_and_the_oracle(s24, case):
