@@ -263,7 +263,10 @@ static uint32_t mix32(uint32_t x)
 /* 23 random bits for (feature, token group): u = bits * 2^-23, so that u + 1 is exact in fp32 */
 static uint32_t mvue_bits(uint32_t seed, uint32_t feature, uint32_t group)
 {
-    return mix32(mix32(group ^ seed) + feature * 0x9E3779B9U) >> 9;
+    /* the seed is mixed on its own before it meets the feature, and that key before it meets the token group, so
+       that neighbouring seeds (one per step and operand) share no draws in any rearrangement */
+    const uint32_t key = mix32(mix32(seed) + feature * 0x9E3779B9U);
+    return mix32(key + group * 0x85EBCA6BU) >> 9;
 }
 
 /* one group: a[4] in, kept positions i0 < i1 and their values out */

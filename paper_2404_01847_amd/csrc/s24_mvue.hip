@@ -84,12 +84,15 @@ __global__ __launch_bounds__(kThreads) void mvue24_kernel(const T *__restrict__ 
     const uint32_t col_bytes = (uint32_t)min(lane, r - 1 - (int)blockIdx.x * 64) * (uint32_t)sizeof(T);
     float out[32];
     uint32_t words[2] = {0u, 0u};
+    // counter-based draw: the seed is hashed alone, then with the feature (the lane's key), then with the token
+    // group, so that consecutive seeds -- one per step and operand -- give unrelated streams
+    const uint32_t key = mix32(mix32(seed) + (uint32_t)f * 0x9E3779B9U);
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
         float a[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) a[i] = Elem<T>::load(reinterpret_cast<const T *>(reinterpret_cast<const char *>(src) + (col_bytes + (uint32_t)(4 * g + i) * row_bytes)));
-        const uint32_t bits = mix32(mix32((uint32_t)(16 * c + g) ^ seed) + (uint32_t)f * 0x9E3779B9U) >> 9;
+        const uint32_t bits = mix32(key + (uint32_t)(16 * c + g) * 0x85EBCA6BU) >> 9;
         const Kept k = mvue_group(a, bits);
         out[2 * g] = k.v0;
         out[2 * g + 1] = k.v1;

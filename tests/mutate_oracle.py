@@ -48,7 +48,9 @@ MUTS = [
  ("mvue top not forced", "if (capped && m[i] == mx) { pi[i] = 1.0f; mag[i] = m[i]; }", "if (capped && m[i] == mx) { mag[i] = m[i]; }"),
  ("mvue second point", "v = u + 1.0f;", "v = u + 0.5f;"),
  ("mvue sign lost", "*v0 = m[a0] == 0.0f ? 0.0f : copysignf(mag[a0], a[a0]);", "*v0 = m[a0] == 0.0f ? 0.0f : mag[a0];"),
- ("mvue hash ignores feature", "return mix32(mix32(group ^ seed) + feature * 0x9E3779B9U) >> 9;", "return mix32(mix32(group ^ seed)) >> 9;"),
+ ("mvue hash ignores feature", "const uint32_t key = mix32(mix32(seed) + feature * 0x9E3779B9U);", "const uint32_t key = mix32(mix32(seed));"),
+ ("mvue hash ignores group", "return mix32(key + group * 0x85EBCA6BU) >> 9;", "return mix32(key) >> 9;"),
+ ("mvue seed meets group unmixed", "const uint32_t key = mix32(mix32(seed) + feature * 0x9E3779B9U);\n    return mix32(key + group * 0x85EBCA6BU) >> 9;", "return mix32(mix32(group ^ seed) + feature * 0x9E3779B9U) >> 9;"),
  ("mvue token stride", "a[i] = (float)widen(dY, dt, (size_t)((4 * g + i) * ld + f));", "a[i] = (float)widen(dY, dt, (size_t)((4 * g + i) * r + f));"),
  ("flips count blocks", "for (int t = 0; t < 16; ++t) c += (x >> t) & 1u;", "c = x != 0;"),
  ("gap second best", "else if (k == 1 || wide_cmp(&s, &second) > 0) second = s;", "else if (k == 1) second = s;"),

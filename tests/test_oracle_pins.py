@@ -543,6 +543,31 @@ def test_mvue_draws_differ_across_features_groups_and_seeds():
     assert np.all(np.abs(seen.mean(axis=0) - pi) <= tol(n)), ("over seeds", seen.mean(axis=0))
 
 
+def test_mvue_neighbouring_seeds_share_no_draws_in_any_arrangement():
+    """A layer takes one seed per pruned operand and step, i.e. consecutive integers.  The streams of two
+    neighbouring seeds must be unrelated: not equal, and not the same draws dealt out to other token groups of the
+    same feature (what a seed that is merely XORed or added into the group counter would give).  The same four
+    numbers sit in every group, so the kept pair of a group is a function of its draw alone."""
+    a = np.array([1.0, -2.0, 3.0, 4.0], dtype=np.float32)
+    r, G = 256, 64
+    dY = np.tile(a.reshape(4, 1), (G, r))
+    hist = lambda kept: np.stack([np.bincount((kept.reshape(r, G, 4)[f] * (1 << np.arange(4))).sum(axis=1), minlength=16)
+                                  for f in range(r)])
+    for seed in (0, 6, 1000, 2 ** 31 - 2):
+        k0, k1 = mvue_dense(dY, seed)[1], mvue_dense(dY, seed + 1)[1]
+        same_groups = (k0.reshape(r, G, 4) == k1.reshape(r, G, 4)).all(axis=2).mean()
+        # two independent draws keep the same pair with probability sum of squared pair probabilities, about 0.3
+        assert same_groups < 0.45, (seed, same_groups)
+        # per feature, the multiset of kept pairs over the 64 groups: equal for nearly no feature if the streams are
+        # unrelated, equal for every feature if one stream is a rearrangement of the other
+        same_multiset = (hist(k0) == hist(k1)).all(axis=1).mean()
+        assert same_multiset < 0.05, (seed, same_multiset)
+        # and the neighbour is not the same stream shifted by a few groups either
+        for shift in (1, 2, 3, 4):
+            moved = np.roll(k1.reshape(r, G, 4), shift, axis=1)
+            assert (k0.reshape(r, G, 4) == moved).all(axis=2).mean() < 0.45, (seed, shift)
+
+
 def test_mvue_reads_a_strided_operand():
     wide = si.random_matrix(54, (64, 40), 1e-2, "bf16")
     view = wide[:, 8:32]                                                         # row stride 40, 24 features
