@@ -93,8 +93,11 @@ int s24_transposable_mask(const void *W, s24_dtype dt, int64_t r, int64_t q, int
  *   vals      [q/64][r][32]  meta  [q/64][r][4]    (rows of W, chunks along q)
  *   valsT     [r/64][q][32]  metaT [r/64][q][4]    (rows of W^T, chunks along r)
  *   mask_out  [r/4][q/4] device, out, may be NULL (only used when mask == NULL)
- * r, q multiples of 64.  A given mask must be legal (two kept per row and
- * column of each block); an illegal mask gives unspecified values but no fault. */
+ * r, q multiples of 64; vals and valsT 16-byte aligned, meta and metaT 8-byte aligned (S24_ERR_ALIGN).  A given
+ * mask must be legal (two kept per row and column of each block); an illegal mask gives unspecified values but no
+ * fault.  The chunk-major storage described at the top of this file is the only form the library emits or reads:
+ * it is what the sparse matrix-core instructions consume verbatim, and it is a pure permutation of the row-major
+ * form (value j of chunk c of row o <-> kept value 32c + j of that row; word j of chunk c <-> word 4c + j). */
 int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t ldw,
                  const uint16_t *mask, void *vals, uint16_t *meta, void *valsT, uint16_t *metaT,
                  uint16_t *mask_out, void *stream);
@@ -219,7 +222,7 @@ int s24_spmm_dw(const void *vals, const uint16_t *meta, const void *X, float *dW
                 void *stream);
 
 /* Dense comparison GEMM (Eq. 1, first GEMM): Y[p][r] = X[p][q] . W[r][q]^T,
- * same tiling family as the sparse kernels.  q multiple of 32; r of 16. */
+ * same tiling family as the sparse kernels.  q multiple of 64; r of 16. */
 int s24_dense_gemm(const void *X, const void *W, void *Y, int64_t p, int64_t q, int64_t r,
                    s24_dtype dt, void *stream);
 

@@ -22,14 +22,21 @@ ROW_MAJOR, COL_MAJOR = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "s24_oracle.c")
-_LIB = os.path.join(_HERE, "liborc.so")
+# S24_ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (host code only), for a checking run of the CPU tests:
+#   S24_ORACLE_SANITIZE=1 LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+#       python -m pytest tests/test_oracle_pins.py -q
+_SANITIZE = os.environ.get("S24_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "liborc_san.so" if _SANITIZE else "liborc.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                 "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
                                _SRC, "-o", _LIB, "-lm"])
     return _LIB
 

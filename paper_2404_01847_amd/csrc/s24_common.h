@@ -91,10 +91,11 @@ __device__ __forceinline__ void s24_swiglu_grad(float dh, float g, float u, floa
 
 // Normal CDF Phi(x) and e = exp(-x^2/2), for GELU(x) = x Phi(x) (the erf form: Phi(x) = (1 + erf(x / sqrt 2)) / 2) and
 // its slope Phi(x) + x e / sqrt(2 pi).  The lower tail is Phi(-s) = e * Q(t), t = 1 / (1 + 0.375 s), with Q(t) = t * (a
-// degree-8 polynomial) fitted to the exact function (csrc/fit_normal_cdf.py derives and checks the constants): one
-// hardware exp2, one hardware reciprocal and nine fused multiply-adds, no branch, shared by the value and the slope.
-// In fp32: |error| < 4e-7 for Phi, GELU and GELU' everywhere, and the tail keeps a relative accuracy of a few 1e-6
-// because the exponential is a factor, not a term.  The library routines (erff plus expf, both with range
+// degree-8 polynomial) fitted to the exact function (tests/fit_normal_cdf.py derives the constants, and
+// tests/test_gelu_constants.py checks the ones below against math.erf on the CPU): one hardware exp2, one hardware
+// reciprocal and nine fused multiply-adds, no branch, shared by the value and the slope.  In fp32: |error| < 4e-7 for
+// Phi and GELU', < 4e-7 max(1, |x|) for GELU, and the lower tail keeps a relative accuracy of a few 1e-6 because the
+// exponential is a factor, not a term.  The library routines (erff plus expf, both with range
 // reduction and two code paths that a wave walks one after the other) cost about three times as much, which
 // matters where this runs in a GEMM epilogue with nothing to hide behind.
 __device__ __forceinline__ void s24_normal(float x, float &cdf, float &e)

@@ -742,7 +742,10 @@ extern "C" int s24_compress(const void *W, s24_dtype dt, int64_t r, int64_t q, i
     const int rc = check_weight(W, dt, r, q, ldw, 64);
     if (rc != S24_OK || r == 0 || q == 0) return rc;
     S24_REQUIRE(vals && meta && valsT && metaT, S24_ERR_NULL);
-    S24_REQUIRE(s24_aligned(vals, 8) && s24_aligned(valsT, 8) && s24_aligned(meta, 2) && s24_aligned(metaT, 2),
+    // the kernel stores 16 bytes of values and 8 bytes of index words at a time (and the GEMMs that consume the
+    // operands copy them in 16-byte pieces)
+    S24_REQUIRE(s24_aligned(vals, 16) && s24_aligned(valsT, 16) && s24_aligned(meta, 8) && s24_aligned(metaT, 8) &&
+                    s24_aligned(mask, 2) && s24_aligned(mask_out, 2),
                 S24_ERR_ALIGN);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dt == S24_BF16)

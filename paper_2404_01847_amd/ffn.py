@@ -237,28 +237,53 @@ class SparseFFN:
         for w in self.w.values():
             self._k('masked_decay', s24.masked_decay_grad, w.grad, w.W, w.mask, self.lam)
 
-    def step(self, X, dY):
-        """Mask + compress, forward, backward, masked decay: the whole hot path once."""
-        self.prune(search=self.steps_done % self.mask_interval == 0)
+    def step(self, X, dY, search=None):
+        """Mask + compress, forward, backward, masked decay: the whole hot path once.  `search` forces (True) or
+        suppresses (False) the mask search of this step; by default the step count and mask_interval decide."""
+        if search is None:
+            search = self.steps_done % self.mask_interval == 0
+        self.prune(search=search)
         self.steps_done += 1
         self.forward(X)
         self.backward(X, dY)
         self.decay()
 
     def capture(self, X, dY):
-        """Record one step into a HIP graph and return it (torch.cuda.CUDAGraph; replay() reruns the step on
-        the same buffers).  Possible because the step allocates nothing, never synchronises and only
-        launches kernels on the current stream.  Worth it where launches, not kernels, bound the step."""
+        """Record the step into HIP graphs and return an object whose replay() reruns it on the same buffers.
+        Possible because the step allocates nothing, never synchronises and only launches kernels on the current
+        stream.  Worth it where launches, not kernels, bound the step.  With mask_interval == 1 that object is the one
+        torch.cuda.CUDAGraph of the step; otherwise two graphs are recorded, the step with the mask search and the
+        step that re-applies the stored mask, and replay() picks by the layer's step count exactly as step() does,
+        so the schedule of Sec. 5.1 (search every l-th step) survives the capture."""
         if self.timings is not None:
             raise RuntimeError("switch the per-kernel timing hooks off before capturing")
         if self.mvue:
             raise RuntimeError("the seed of the pruning draw is a launch argument: a replayed graph would repeat the draw")
+        done = self.steps_done
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            self.step(X, dY)   # once outside the capture: library load and lazy initialisation
+            self.step(X, dY, search=True)   # once outside the capture: library load and lazy initialisation
         torch.cuda.current_stream().wait_stream(side)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            self.step(X, dY)
-        return graph
+        graphs = {}
+        for search in ((True,) if self.mask_interval == 1 else (True, False)):
+            graphs[search] = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graphs[search]):
+                self.step(X, dY, search=search)
+        self.steps_done = done + 1          # the warm-up run was a real step (with a search); recording runs nothing
+        if self.mask_interval == 1:
+            return graphs[True]
+        return _CapturedSchedule(self, graphs[True], graphs[False])
+
+
+class _CapturedSchedule:
+    """The captured step of a layer whose mask is searched every mask_interval-th step only."""
+
+    def __init__(self, ffn, with_search, without_search):
+        self.ffn, self.with_search, self.without_search = ffn, with_search, without_search
+
+    def replay(self):
+        ffn = self.ffn
+        search = ffn.steps_done % ffn.mask_interval == 0
+        (self.with_search if search else self.without_search).replay()
+        ffn.steps_done += 1

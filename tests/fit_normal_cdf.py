@@ -1,4 +1,5 @@
-"""Derives the constants of s24_normal() in s24_common.h (the GELU kernels' normal CDF).
+"""Derives the constants of s24_normal() in paper_2404_01847_amd/csrc/s24_common.h (the GELU kernels' normal CDF);
+tests/test_gelu_constants.py refits them with fit() and checks the header against the result.
 
 For s >= 0 the lower tail is written Phi(-s) = exp(-s^2/2) * Q(t) with t = 1 / (1 + P s): Q is smooth on (0, 1],
 vanishes linearly at t = 0 (the Mills ratio) and equals 1/2 at t = 1, so Q(t) = t * poly(t) fits well, and because
@@ -7,7 +8,7 @@ weighted least-squares fit of Q(t)/t in a Chebyshev basis with Lawson reweightin
 against scipy's scaled complementary error function; the script then evaluates Phi, GELU and GELU' in emulated fp32
 with the rounded coefficients against fp64 references and prints the errors and the constants.
 
-    python paper_2404_01847_amd/csrc/fit_normal_cdf.py
+    python tests/fit_normal_cdf.py
 """
 import numpy as np
 from numpy.polynomial import Polynomial

@@ -556,6 +556,105 @@ def test_mvue24_strided_input(s24):
     assert np.array_equal(host_bits(meta), want_m) and np.array_equal(host_bits(vals), want_v)
 
 
+def gpu_mvue_dense(s24, dY, seed):
+    """The kernel's own compressed S_z(dY^T), decoded on the host (no oracle code involved) to a dense [r, p] float64
+    matrix plus the kept-position flags."""
+    p, r = dY.shape
+    vals = torch.zeros((p // 64, r, 32), dtype=torch.float32, device="cuda")
+    meta = torch.zeros((p // 64, r, 4), dtype=torch.int16, device="cuda")
+    s24.mvue24(dev(dY), seed, vals, meta)
+    torch.cuda.synchronize()
+    v = host_bits(vals).transpose(1, 0, 2).reshape(r, p // 4, 2).astype(np.float64)        # chunk-major -> per feature
+    m = host_bits(meta).transpose(1, 0, 2).reshape(r, p // 16).astype(np.int64)
+    nib = ((m[:, :, None] >> (4 * np.arange(4))) & 0xF).reshape(r, p // 4)
+    i0, i1 = nib & 3, nib >> 2
+    assert (i0 < i1).all()
+    out = np.zeros((r, p // 4, 4))
+    kept = np.zeros((r, p // 4, 4), dtype=bool)
+    rr, gg = np.meshgrid(np.arange(r), np.arange(p // 4), indexing="ij")
+    out[rr, gg, i0], out[rr, gg, i1] = v[:, :, 0], v[:, :, 1]
+    kept[rr, gg, i0] = kept[rr, gg, i1] = True
+    return out, kept
+
+
+@pytest.mark.parametrize("group", [(1.0, 2.0, 3.0, 4.0), (0.3, -0.2, 0.25, -0.1), (5.0, 1.0, -1.5, 0.5), (9.0, 0.0, 2.0, -1.0)])
+def test_mvue24_kernel_output_is_unbiased_with_the_least_second_moment(s24, group):
+    """Statistics of the KERNEL's draws, against what Eq. 6's name fixes and no code of ours: 65536 draws of one
+    group (the same four numbers in every token group of 64 features x 1024 groups).  Sample mean = the group;
+    inclusion frequencies = min(1, |a_j| / tau) with sum 2; summed second moment = the Lagrange minimum of
+    sum a_j^2 / pi_j (S^2/2 uncapped, max^2 + R^2 capped); every kept value = a_j / pi_j from the plain fp64
+    definition to a few fp32 ulp; frequencies also hold along features alone and along token groups alone."""
+    a = np.array(group, dtype=np.float32)
+    r, G = 64, 1024
+    dY = np.tile(a.reshape(4, 1), (G, r))
+    out, kept = gpu_mvue_dense(s24, dY, 7)
+    n = r * G
+    samples, flags = out.reshape(n, 4), kept.reshape(n, 4)
+    m = np.abs(a.astype(np.float64))
+    S, mx = m.sum(), m.max()
+    if 2 * mx <= S:
+        pi, second = 2 * m / S, S * S / 2
+    else:
+        R = S - mx
+        pi, second = np.where(m == mx, 1.0, m / R), mx * mx + R * R
+    assert (flags.sum(axis=1) == 2).all()
+    var = np.where(pi > 0, m * m * (1 / np.maximum(pi, 1e-300) - 1), 0.0)
+    assert np.all(np.abs(samples.mean(axis=0) - a) <= 5 * np.sqrt(var / n) + 1e-6)
+    assert np.all(np.abs(flags.mean(axis=0) - pi) <= 5 * np.sqrt(pi * (1 - pi) / n) + 1e-6)
+    assert abs((samples ** 2).sum(axis=1).mean() - second) <= 0.02 * second
+    # kept values from the definition a_j / pi_j in fp64 (zero-probability cells are kept only as exact zeros)
+    want = np.where(pi > 0, a.astype(np.float64) / np.maximum(pi, 1e-300), 0.0)
+    for j in range(4):
+        got = samples[flags[:, j], j]
+        assert np.all(np.abs(got - want[j]) <= 4 * 2.0 ** -23 * abs(want[j])), (j, want[j], got[:4])
+    assert (samples[~flags] == 0).all()
+    # the draws differ along each axis alone
+    tol = lambda k: 5 * np.sqrt(pi * (1 - pi) / k) + 1e-9
+    assert np.all(np.abs(kept[:, 0, :].mean(axis=0) - pi) <= tol(r) + 0.05)          # 64 features of one group
+    assert np.all(np.abs(kept[0].mean(axis=0) - pi) <= tol(G))                        # 1024 groups of one feature
+
+
+def test_mvue24_kernel_probabilities_follow_the_definition_on_random_groups(s24):
+    """Random groups, 512 seeds: each element's inclusion frequency over the seeds against pi_j = min(1, |a_j|/tau)
+    computed in fp64 from the plain definition (the largest element capped at one when it exceeds the others' sum),
+    each kept value against a_j / pi_j, and the mean of the estimates against the input (unbiasedness)."""
+    p, r, seeds = 64, 64, 512
+    dY = si.random_matrix(830, (p, r), 1.0, "f32")
+    dY[0:4, :8] *= np.array([8.0, 1.0, 1.0, 1.0], dtype=np.float32)[:, None]          # some capped groups
+    a = dY.T.reshape(r, p // 4, 4).astype(np.float64)
+    m = np.abs(a)
+    S, mx = m.sum(axis=2, keepdims=True), m.max(axis=2, keepdims=True)
+    capped = 2 * mx > S
+    pi = np.where(capped, np.where(m == mx, 1.0, m / (S - mx)), 2 * m / S)
+    want = a / pi
+    freq = np.zeros_like(pi)
+    mean = np.zeros_like(pi)
+    for seed in range(seeds):
+        out, kept = gpu_mvue_dense(s24, dY, 3000 + seed)
+        out, kept = out.reshape(r, p // 4, 4), kept.reshape(r, p // 4, 4)
+        assert np.all(np.abs(out[kept] - want[kept]) <= 8 * 2.0 ** -23 * np.abs(want[kept]))
+        freq += kept
+        mean += out
+    freq /= seeds
+    mean /= seeds
+    assert np.all(np.abs(freq - pi) <= 5.5 * np.sqrt(pi * (1 - pi) / seeds) + 1e-9)
+    sd = np.sqrt(m * m * (1 / pi - 1) / seeds)
+    assert np.all(np.abs(mean - a) <= 5.5 * sd + 1e-6 * m)
+
+
+def test_mvue24_kernel_neighbouring_seeds_give_unrelated_draws(s24):
+    """Consecutive seeds (what a layer passes from one operand and step to the next) on the kernel itself: the kept
+    pairs of seed s + 1 are neither those of seed s nor a rearrangement of them over the token groups of a feature."""
+    a = np.array([1.0, -2.0, 3.0, 4.0], dtype=np.float32)
+    r, G = 256, 64
+    dY = np.tile(a.reshape(4, 1), (G, r))
+    code = lambda kept: (kept.reshape(r, G, 4) * (1 << np.arange(4))).sum(axis=2)
+    k0, k1 = code(gpu_mvue_dense(s24, dY, 1000)[1]), code(gpu_mvue_dense(s24, dY, 1001)[1])
+    assert (k0 == k1).mean() < 0.45
+    hist = lambda c: np.stack([np.bincount(row, minlength=16) for row in c])
+    assert (hist(k0) == hist(k1)).all(axis=1).mean() < 0.05
+
+
 @pytest.mark.parametrize("case", [
     # (p, q, r, dtype, beta, decay)
     (64, 16, 16, "bf16", 0.0, False), (192, 272, 144, "bf16", 1.0, False), (128, 64, 48, "f32", 1.0, True),

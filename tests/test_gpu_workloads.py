@@ -281,6 +281,124 @@ def test_workload_full_size(s24, name):
                      f"{name} gelu bwd")
 
 
+def aligned_row_groups(n, k, seed):
+    """Rows of k + 2 aligned groups of four (the first, the last and k random ones): the mask is per 4x4 block."""
+    rng = np.random.default_rng(seed)
+    g = np.unique(np.concatenate([[0, n // 4 - 1], rng.integers(0, n // 4, size=k)]))
+    return (4 * g[:, None] + np.arange(4)[None, :]).reshape(-1).astype(np.int64)
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_default_step_full_size_against_the_oracle_chain(s24, name):
+    """The step exactly as bench.py times it -- gate and up projection as one stacked weight, the activation and its
+    backward inside the GEMM epilogues, all weight gradients in one batched pass with the decay in its epilogue -- at
+    the workload's full size.  Every stage but the weight gradient is local to a token, so the oracle runs the whole
+    chain (Eq. 2, Sec. 5.2, Eq. 3) on sampled token rows, rounding to the storage type where the kernels do, and each
+    stage is also checked against the oracle applied to what the GPU itself stored as that stage's input (the bar of
+    a single kernel).  Weight gradients (Eq. 1 + Eq. 10): sampled output rows from the GPU-stored operands."""
+    from paper_2404_01847_amd.ffn import SparseFFN
+    wl = si.WORKLOADS[name]
+    t = si.make(wl)
+    p, d, f = wl.p, wl.d_model, wl.d_ff
+    X, dY = t["X"], t["dY"]
+    ffn = SparseFFN({n: dev_bf16(t[n]) for n in wl.weight_names}, p, wl.act, wl.lam, concat_gate_up=True)
+    assert ffn.concat == wl.gated and ffn.fuse_swiglu and ffn.fuse_decay and ffn.batch_dw     # bench.py's defaults
+    Xd, dYd = dev_bf16(X), dev_bf16(dY)
+    ffn.step(Xd, dYd)
+    torch.cuda.synchronize()
+    if wl.gated:
+        assert ffn.fuse_gate_bwd is True, "the large layers must take the fused backward epilogue"
+        host_w = {"Wgu": np.concatenate([t["Wg"], t["Wu"]], axis=0), "Wd": t["Wd"]}
+        up, down = "Wgu", "Wd"
+    else:
+        host_w = {"W1": t["W1"], "W2": t["W2"]}
+        up, down = "W1", "W2"
+    comp, masks = {}, {}
+    for n, W in host_w.items():
+        masks[n] = oracle.transposable_mask(W)
+        assert np.array_equal(host_bits(ffn.w[n].mask), masks[n]), f"{name} {n} mask"
+        comp[n] = oracle.compress(W, masks[n])
+        packed = oracle.pack(comp[n][0], comp[n][1]) + oracle.pack(comp[n][2], comp[n][3])
+        for got, ref, what in zip((ffn.w[n].vals, ffn.w[n].meta, ffn.w[n].valsT, ffn.w[n].metaT), packed,
+                                  ("vals", "meta", "valsT", "metaT")):
+            assert np.array_equal(host_bits(got), ref), f"{name} {n} {what}"
+        del packed
+    rows = sample_rows(p, 24, 5)
+    ridx = torch.from_numpy(rows).cuda()
+    Xs, dYs = np.ascontiguousarray(X[rows]), np.ascontiguousarray(dY[rows])
+    rnd = lambda a: oracle.round_like(a, X)
+    wide = lambda a: si.to_f32(a).astype(np.float64)
+    got = lambda tens: host_f64(tens[ridx])
+    gbits = lambda tens: host_bits(tens[ridx].contiguous())
+    chain_tol = (2e-2, 5e-3)   # a chain compounds roundings: a flipped bf16 rounding upstream moves a downstream value by its own step
+    if wl.gated:
+        gate = oracle.GATE_SILU
+        Z = rnd(oracle.spmm_fwd(Xs, comp[up][0], comp[up][1]))
+        H = rnd(oracle.glu_fwd(Z, gate))
+        Y = oracle.spmm_fwd(H, comp[down][0], comp[down][1])
+        dH = rnd(oracle.spmm_bwd_dx(dYs, comp[down][2], comp[down][3]))
+        dZ = rnd(oracle.glu_bwd(dH, Z, gate))
+        dXr = oracle.spmm_bwd_dx(dZ, comp[up][2], comp[up][3])
+        assert_close(got(ffn.GU), wide(Z), BF16_TOL, f"{name} GU")            # first stage: single-kernel bar
+        assert_close(got(ffn.H), wide(H), chain_tol, f"{name} H (chain)")
+        assert_close(got(ffn.Y), Y, chain_tol, f"{name} Y (chain)")
+        assert_close(got(ffn.dGU), wide(dZ), chain_tol, f"{name} dGU (chain)")
+        assert_close(got(ffn.dX), dXr, chain_tol, f"{name} dX (chain)")
+        # each later stage on the GPU's own stored input
+        GUg, Hg, dGUg = gbits(ffn.GU), gbits(ffn.H), gbits(ffn.dGU)
+        assert_close(got(ffn.H), oracle.glu_fwd(GUg, gate), BF16_TOL, f"{name} H")
+        assert_close(got(ffn.Y), oracle.spmm_fwd(Hg, comp[down][0], comp[down][1]), BF16_TOL, f"{name} Y")
+        assert_close(got(ffn.dGU), oracle.glu_bwd(dH, GUg, gate), BF16_TOL, f"{name} dGU")
+        assert_close(got(ffn.dX), oracle.spmm_bwd_dx(dGUg, comp[up][2], comp[up][3]), BF16_TOL, f"{name} dX")
+        ops = {"Wd": (dY, host_bits(ffn.H), dYd, ffn.H), "Wgu": (host_bits(ffn.dGU), X, ffn.dGU, Xd)}
+    else:
+        act = oracle.ACT_GELU_ERF
+        Z = rnd(oracle.spmm_fwd(Xs, comp[up][0], comp[up][1]))
+        H = rnd(oracle.act_fwd(Z, act))
+        Y = oracle.spmm_fwd(H, comp[down][0], comp[down][1])
+        dH = rnd(oracle.spmm_bwd_dx(dYs, comp[down][2], comp[down][3]))
+        dZ = rnd(oracle.act_bwd(dH, Z, act))
+        dXr = oracle.spmm_bwd_dx(dZ, comp[up][2], comp[up][3])
+        assert_close(got(ffn.Z), wide(Z), BF16_TOL, f"{name} Z")
+        assert_close(got(ffn.H), wide(H), chain_tol, f"{name} H (chain)")
+        assert_close(got(ffn.Y), Y, chain_tol, f"{name} Y (chain)")
+        assert_close(got(ffn.dZ), wide(dZ), chain_tol, f"{name} dZ (chain)")
+        assert_close(got(ffn.dX), dXr, chain_tol, f"{name} dX (chain)")
+        Zg, Hg, dZg = gbits(ffn.Z), gbits(ffn.H), gbits(ffn.dZ)
+        assert_close(got(ffn.H), oracle.act_fwd(Zg, act), BF16_TOL, f"{name} H")
+        assert_close(got(ffn.Y), oracle.spmm_fwd(Hg, comp[down][0], comp[down][1]), BF16_TOL, f"{name} Y")
+        assert_close(got(ffn.dZ), oracle.act_bwd(dH, Zg, act), BF16_TOL, f"{name} dZ")
+        assert_close(got(ffn.dX), oracle.spmm_bwd_dx(dZg, comp[up][2], comp[up][3]), BF16_TOL, f"{name} dX")
+        ops = {"W2": (dY, host_bits(ffn.H), dYd, ffn.H), "W1": (host_bits(ffn.dZ), X, ffn.dZ, Xd)}
+    del comp
+    # Weight gradients with the decay term (Eq. 1 + Eq. 10) on aligned groups of output rows.  At these sizes the decay
+    # term (lambda |w| of some 4e-6) is smaller than the fp32 accumulation noise of a sum over thousands of tokens, so a
+    # tolerance comparison alone would not see it: the batched, decay-fused result is compared (a) with the oracle's
+    # dense_dw + masked_decay of the GPU-stored operands within the fp32 tolerance and (b) cell by cell with the
+    # oracle's Eq. 10 applied to the plain weight-gradient GEMM's own output for the same operands (kept cells bit
+    # for bit, pruned cells to an fp32 rounding), that GEMM in turn being held to the oracle's.
+    for n, (a, b, a_dev, b_dev) in ops.items():
+        W, r = host_w[n], host_w[n].shape[0]
+        orow = aligned_row_groups(r, 6, 11 + len(n))
+        oidx = torch.from_numpy(orow).cuda()
+        dWr = oracle.dense_dw(a, b, rows=orow)
+        Wrows, mrows = np.ascontiguousarray(W[orow]), np.ascontiguousarray(masks[n][orow[::4] // 4])
+        want = oracle.masked_decay(dWr.astype(np.float32), Wrows, mrows, wl.lam)
+        gotg = host_bits(ffn.w[n].grad[oidx])
+        assert_close(gotg.astype(np.float64), want, F32_TOL, f"{name} grad {n}")
+        plain = torch.empty_like(ffn.w[n].grad)
+        s24.dense_dw(a_dev, b_dev, plain)
+        torch.cuda.synchronize()
+        plain_rows = host_bits(plain[oidx])
+        del plain
+        assert_close(plain_rows.astype(np.float64), dWr, F32_TOL, f"{name} plain dW {n}")
+        cell = oracle.masked_decay(plain_rows, Wrows, mrows, wl.lam)
+        keep = keep_of(mrows)
+        assert np.array_equal(gotg[keep], plain_rows[keep]), f"{name} grad {n}: kept cells"
+        np.testing.assert_allclose(gotg[~keep].astype(np.float64), cell[~keep], rtol=3e-7, atol=0)
+        assert (gotg[~keep] != plain_rows[~keep]).mean() > 0.5, f"{name} grad {n}: the decay term is missing"
+
+
 def test_step_replayed_from_a_hip_graph_matches_eager_launches():
     """The captured step is replayed several times with eager work and synchronisations in between;
     every replay must reproduce the eager results bit for bit (the kernels are deterministic)."""
@@ -343,6 +461,43 @@ def test_mask_interval_keeps_the_mask_and_recompresses_the_new_weights():
     torch.cuda.synchronize()
     for n, w in ffn.w.items():
         assert np.array_equal(host_bits(w.mask), oracle.transposable_mask(new[n]))
+
+
+def test_captured_step_keeps_the_mask_schedule():
+    """A captured layer with mask_interval = 3 must search on the same steps as the eager layer does: two layers on
+    copies of the same weights, one stepped eagerly and one replayed, the weights rewritten before every step; masks,
+    compressed operands and outputs agree bit for bit after each of seven steps (replays 3 and 6 search)."""
+    from paper_2404_01847_amd.ffn import SparseFFN
+    wl = si.Workload("s", 256, 128, 256, "swiglu", "bf16", 21)
+    host = si.make(wl)
+    d = {k: dev_bf16(v) for k, v in host.items()}
+    mk = lambda: SparseFFN({n: d[n].clone() for n in wl.weight_names}, wl.p, wl.act, wl.lam, mask_interval=3,
+                           concat_gate_up=True)
+    eager, replayed = mk(), mk()
+    X, dY = d["X"], d["dY"]
+    graph = replayed.capture(X, dY)          # runs step 0 (with the search) for real
+    eager.step(X, dY)
+    searched = []
+    for step in range(1, 8):
+        new = {n: dev_bf16(si.random_matrix(2100 + 10 * step + i, tuple(w.W.shape), 0.02, "bf16"))
+               for i, (n, w) in enumerate(eager.w.items())}
+        before = {n: w.mask.clone() for n, w in replayed.w.items()}
+        for ffn in (eager, replayed):
+            for n, w in ffn.w.items():
+                w.W.copy_(new[n])
+        eager.step(X, dY)
+        graph.replay()
+        torch.cuda.synchronize()
+        searched.append(any(not torch.equal(before[n], w.mask) for n, w in replayed.w.items()))
+        for n in eager.w:
+            a, b = eager.w[n], replayed.w[n]
+            assert torch.equal(a.mask, b.mask), (step, n)
+            assert torch.equal(a.vals.view(torch.int16), b.vals.view(torch.int16)) and torch.equal(a.metaT, b.metaT), (step, n)
+            assert torch.equal(a.grad, b.grad), (step, n)
+        assert torch.equal(eager.Y.view(torch.int16), replayed.Y.view(torch.int16)), step
+        assert torch.equal(eager.dX.view(torch.int16), replayed.dX.view(torch.int16)), step
+    assert searched == [False, False, True, False, False, True, False]
+    assert eager.steps_done == replayed.steps_done == 8
 
 
 def test_gate_and_up_as_one_weight_matches_the_separate_weights():
