@@ -30,11 +30,23 @@ PEAK_DENSE_BF16 = 2500.0      # TFLOP/s, dense bf16 MFMA
 PEAK_SPARSE_BF16 = 5000.0     # TFLOP/s, 2:4 structured-sparse bf16 (dense-equivalent FLOPs)
 PEAK_HBM = 8000.0             # GB/s
 
-# HBM-side bytes per call of the entry point (read + written; mean over the calls of a step; for the weight
-# gradient the one s24_dense_dw_batch pass, both of its launches) measured with rocprofv3 PMC runs of this file
-# (FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a 1 GiB copy):
-# profiles/c4_step_hbm_traffic_pmc.md.  Only for the default configuration of the named workload.
-MEASURED_TRAFFIC_BYTES = {("c4", "dense_dw"): 8.625e9, ("c4", "spmm_fwd"): 3.68e9, ("c4", "spmm_bwd_dx"): 2.77e9}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.md")
+
+
+def measured_traffic(workload, kernel):
+    """HBM-side bytes (read + written) per call of the entry point in the default configuration of `workload`, from the
+    tracked summary of the rocprofv3 PMC runs of this file (FETCH_SIZE and WRITE_SIZE, each scaled by what the same
+    counter reads for a device copy of known size): the rows `| workload | kernel | read bytes | written bytes |` of
+    profiles/hbm_traffic_pmc.md.  None when the table has no such row (nothing is assumed)."""
+    try:
+        with open(TRAFFIC_TABLE) as fh:
+            for line in fh:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 4 and cells[0] == workload and cells[1] == kernel:
+                    return float(cells[2]) + float(cells[3])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def kernel_model(wl):
@@ -70,18 +82,16 @@ def kernel_model(wl):
 
 
 def cpu_baseline(wl, tensors_host, budget_tokens=None):
-    """The oracle, as it stands, on a bounded sample: every weight-side stage
-    (mask, compress, decay) at full size, every token-side stage (GEMMs,
-    activation) on the first `budget_tokens` tokens, extrapolated linearly in
-    the token count.  Returns dense-equivalent TFLOP/s of the whole step."""
+    """The oracle, as it stands, on a bounded sample of the same workload: every weight-side stage (mask, compress,
+    decay) at full size, every token-side stage (GEMMs, activation) on the first `budget_tokens` tokens against the
+    full weights, extrapolated linearly in the token count.  Returns dense-equivalent TFLOP/s of the whole step."""
     import numpy as np
     import oracle
-    import s24_inputs as si
     t = tensors_host
     if budget_tokens is None:
-        # about 10 s of oracle GEMM work on 16 host threads (6 d d_ff FLOPs per token and weight, some 40 GFLOP/s
-        # in fp64): the token sample shrinks with the layer's size
-        budget_tokens = max(16, min(wl.p, int(4.0e11 / (6.0 * len(wl.weight_names) * wl.d_model * wl.d_ff))))
+        # some 5 s of oracle GEMM work on 16 host threads (6 d d_ff FLOPs per token and weight, about 40 GFLOP/s in
+        # fp64): the token sample shrinks with the layer's size
+        budget_tokens = max(16, min(wl.p, int(2.0e11 / (6.0 * len(wl.weight_names) * wl.d_model * wl.d_ff))))
     n = min(budget_tokens, wl.p)
     X, dY = np.ascontiguousarray(t["X"][:n]), np.ascontiguousarray(t["dY"][:n])
     t0 = time.perf_counter()
@@ -193,6 +203,44 @@ def _capture(torch, fn):
     return graph
 
 
+def c3_mask_sweep(torch, s24, wl):
+    """The mask search over all weights of a GPT-2-large-sized model (36 layers x 2 matrices of the c3 layer's shapes,
+    944 MB: more than the 256 MB Infinity Cache holds, so the rate is an HBM rate), one launch per matrix and stacked
+    by shape into two launches."""
+    import s24_inputs as si
+    import numpy as np
+    # the 72 matrices, stacked by shape the way a model can hold its layers' weights: [36*d_ff][d] and [36*d][d_ff]
+    stacks = []
+    for which in range(2):
+        a = np.concatenate([si.sweep_weight(layer, which, wl) for layer in range(36)], axis=0)
+        t = torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if a.dtype == np.uint16 else torch.from_numpy(a).cuda()
+        stacks.append((t, torch.empty((t.shape[0] // 4, t.shape[1] // 4), dtype=torch.int16, device="cuda")))
+    rows = [wl.d_ff, wl.d_model]
+
+    def sweep_per_matrix():
+        for (t, m), r in zip(stacks, rows):
+            for layer in range(36):
+                s24.transposable_mask(t[layer * r:(layer + 1) * r], m[layer * r // 4:(layer + 1) * r // 4], None)
+
+    def sweep_stacked():
+        for t, m in stacks:
+            s24.transposable_mask(t, m, None)
+
+    ms72 = _time_ms(torch, sweep_per_matrix, 5)
+    ms2 = _time_ms(torch, sweep_stacked, 5)
+    nb72 = sum(t.numel() / 16 * 34 for t, _ in stacks)
+    result = {
+        "matrices": 72, "MB": round(sum(t.numel() * 2 for t, _ in stacks) / 1e6, 1),
+        "one_launch_per_matrix": {"ms_per_sweep": round(ms72, 4), "GB/s": round(nb72 / ms72 / 1e6, 1),
+                                  "frac_of_hbm_peak": round(nb72 / ms72 / 1e6 / PEAK_HBM, 4)},
+        "one_launch_per_shape": {"ms_per_sweep": round(ms2, 4), "GB/s": round(nb72 / ms2 / 1e6, 1),
+                                 "frac_of_hbm_peak": round(nb72 / ms2 / 1e6 / PEAK_HBM, 4)},
+        "note": "13 MB matrices are 400 workgroups each, 1.6 per compute unit: a launch per matrix is bound by "
+                "launch-to-launch latency, not by HBM; the same bytes in two launches show the kernel's rate"}
+    del stacks
+    return result
+
+
 def side_measurements(torch, s24, wl, ffn, X, dY, weights):
     """Outside the timed step:
     (1) the mask search alone, over all weights of the layer in turn (34 algorithmic bytes per 4x4 bf16
@@ -228,36 +276,7 @@ def side_measurements(torch, s24, wl, ffn, X, dY, weights):
                                "working_set_MB": round(nbytes / 1e6, 1),
                                "cache_resident": bool(nbytes < 2 * INFINITY_CACHE_BYTES)}
     if wl.name == "c3":
-        import numpy as np
-        # the 72 matrices, stacked by shape the way a model can hold its layers' weights: [36*d_ff][d] and [36*d][d_ff]
-        stacks = []
-        for which in range(2):
-            a = np.concatenate([si.sweep_weight(layer, which, wl) for layer in range(36)], axis=0)
-            t = torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if a.dtype == np.uint16 else torch.from_numpy(a).cuda()
-            stacks.append((t, torch.empty((t.shape[0] // 4, t.shape[1] // 4), dtype=torch.int16, device="cuda")))
-        rows = [wl.d_ff, wl.d_model]
-
-        def sweep_per_matrix():
-            for (t, m), r in zip(stacks, rows):
-                for layer in range(36):
-                    s24.transposable_mask(t[layer * r:(layer + 1) * r], m[layer * r // 4:(layer + 1) * r // 4], None)
-
-        def sweep_stacked():
-            for t, m in stacks:
-                s24.transposable_mask(t, m, None)
-
-        ms72 = _time_ms(torch, sweep_per_matrix, 5)
-        ms2 = _time_ms(torch, sweep_stacked, 5)
-        nb72 = sum(t.numel() / 16 * 34 for t, _ in stacks)
-        out["mask_search_only_72_matrices"] = {
-            "matrices": 72, "MB": round(sum(t.numel() * 2 for t, _ in stacks) / 1e6, 1),
-            "one_launch_per_matrix": {"ms_per_sweep": round(ms72, 4), "GB/s": round(nb72 / ms72 / 1e6, 1),
-                                      "frac_of_hbm_peak": round(nb72 / ms72 / 1e6 / PEAK_HBM, 4)},
-            "one_launch_per_shape": {"ms_per_sweep": round(ms2, 4), "GB/s": round(nb72 / ms2 / 1e6, 1),
-                                     "frac_of_hbm_peak": round(nb72 / ms2 / 1e6 / PEAK_HBM, 4)},
-            "note": "13 MB matrices are 400 workgroups each, 1.6 per compute unit: a launch per matrix is bound by "
-                    "launch-to-launch latency, not by HBM; the same bytes in two launches show the kernel's rate"}
-        del stacks
+        out["mask_search_only_72_matrices"] = c3_mask_sweep(torch, s24, wl)
     # (6) the monitors of Sec. 4.1 / 4.2 on the first weight: flip count between two masks (4 bytes read per block,
     # one uint64 written) and L1-norm gap (32 bytes read + 8 written per bf16 block, 90 fp64 sums per block)
     w0 = ws[0]
@@ -388,6 +407,102 @@ def gated_activation_measurements(torch, s24):
     return out
 
 
+def _rotating(torch, make_set, call, nbytes, min_reps=10):
+    """Time `call(set)` over enough distinct buffer sets (made by make_set) that no call finds its operands in the
+    Infinity Cache; returns (ms per call, number of sets)."""
+    n = _rotation(nbytes)
+    sets = [make_set() for _ in range(n)]
+    ms = _time_ms(torch, _in_turn([lambda b=b: call(b) for b in sets]), max(min_reps, 2 * n))
+    del sets
+    return ms, n
+
+
+def standalone_hbm_kernels(torch, s24, wl, ffn, X):
+    """The HBM-bound kernels of the path each on its own (the default step runs the activation and the decay inside
+    GEMM epilogues, so the step's own kernel list has no entry for them): gated / ungated activation forward and
+    backward at the layer's [tokens][d_ff] size, masked decay, mask search alone, compress with a given mask and
+    the fused search + compress on every weight of the layer as the step holds it.  Each measurement cycles through
+    distinct buffer sets of over 512 MB together (two sets when one call already moves that much), so the rates
+    are HBM rates.  GB/s counts the algorithmic bytes of the call."""
+    out = {"buffers": "every measurement cycles through distinct buffer sets of over 512 MB together: HBM rates, "
+                      "cache_resident false throughout"}
+    es = 4 if wl.dtype == "f32" else 2
+    p, f = wl.p, wl.d_ff
+    dt, dev = X.dtype, X.device
+    new = lambda *shape: torch.empty(shape, dtype=dt, device=dev)
+    rnd = lambda *shape: torch.empty(shape, dtype=dt, device=dev).normal_()
+
+    def entry(ms, nbytes, n):
+        return {"ms": round(ms, 4), "bytes_per_call": int(nbytes), "GB/s": round(nbytes / ms / 1e6, 1),
+                "frac_of_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM, 4), "buffer_sets": n, "cache_resident": False}
+
+    if wl.gated:
+        nb = 3.0 * p * f * es
+        ms, n = _rotating(torch, lambda: (rnd(p, f), rnd(p, f), new(p, f)), lambda b: s24.swiglu_fwd(b[0], b[1], b[2]), nb)
+        out["swiglu_fwd"] = entry(ms, nb, n)
+        nb = 5.0 * p * f * es
+        ms, n = _rotating(torch, lambda: (rnd(p, f), rnd(p, f), rnd(p, f), new(p, f), new(p, f)),
+                          lambda b: s24.swiglu_bwd(b[0], b[1], b[2], b[3], b[4]), nb)
+        out["swiglu_bwd"] = entry(ms, nb, n)
+        # the same on the halves of one [p][2 d_ff] buffer, the layout the stacked gate+up GEMM leaves
+        nb = 3.0 * p * f * es
+        ms, n = _rotating(torch, lambda: (rnd(p, 2 * f), new(p, f)), lambda b: s24.glu_fwd(b[0], b[1], s24.GATE_SILU), nb)
+        out["swiglu_fwd_on_stacked_GU"] = entry(ms, nb, n)
+    else:
+        act = s24.ACT_RELU if wl.act == "relu" else s24.ACT_GELU_ERF
+        nb = 2.0 * p * f * es
+        ms, n = _rotating(torch, lambda: (rnd(p, f), new(p, f)), lambda b: s24.act_fwd(b[0], b[1], act), nb)
+        out["act_fwd"] = entry(ms, nb, n)
+        nb = 3.0 * p * f * es
+        ms, n = _rotating(torch, lambda: (rnd(p, f), rnd(p, f), new(p, f)), lambda b: s24.act_bwd(b[0], b[1], b[2], act), nb)
+        out["act_bwd"] = entry(ms, nb, n)
+    from paper_2404_01847_amd.ffn import SparseWeight
+    for name, w in ffn.w.items():
+        r, q = w.W.shape
+        blocks = r * q / 16
+        per = {}
+
+        def make():
+            sw = SparseWeight(w.W.clone())
+            sw.mask.copy_(w.mask)
+            sw.grad.zero_()
+            return sw
+
+        nb = r * q * (8 + es + 0.125)
+        ms, n = _rotating(torch, make, lambda b: s24.masked_decay_grad(b.grad, b.W, b.mask, wl.lam), nb)
+        per["masked_decay_grad"] = entry(ms, nb, n)
+        nb = blocks * (16 * es + 2)
+        ms, n = _rotating(torch, make, lambda b: s24.transposable_mask(b.W, b.mask, None), nb)
+        per["mask_search_only"] = entry(ms, nb, n)
+        nb = blocks * (16 * es + 2 + 2 * (8 * es + 2))
+        ms, n = _rotating(torch, make, lambda b: s24.compress(b.W, b.mask, b.vals, b.meta, b.valsT, b.metaT), nb)
+        per["compress_given_mask"] = entry(ms, nb, n)
+        ms, n = _rotating(torch, make, lambda b: s24.compress(b.W, None, b.vals, b.meta, b.valsT, b.metaT, mask_out=b.mask), nb)
+        per["mask_search_and_compress"] = entry(ms, nb, n)
+        out[f"weight {name} [{r} x {q}]"] = per
+    return out
+
+
+def measured_ceilings(torch, s24):
+    """Ceilings measured on this device, next to the published ones: a register-only loop of matrix-core
+    instructions (dense MFMA and 2:4-sparse SMFMAC, bf16; no LDS, no memory traffic) and a plain device copy."""
+    out = {"label": "measured on this device in this run (the published peaks are 2500 / 5000 TFLOP/s and 8000 GB/s)"}
+    wgs, iters = 1024, 8000
+    sink = torch.empty(wgs * 512, dtype=torch.float32, device="cuda")
+    for sparse, key, flop in ((0, "dense_mfma_32x32x16_bf16", 32768.0), (1, "sparse_smfmac_32x32x32_bf16_dense_equivalent", 65536.0)):
+        ms = min(_time_ms(torch, lambda: s24.probe_matrix_rate(sparse, wgs, iters, sink), 2) for _ in range(3))
+        out[key + "_TFLOP/s"] = round(wgs * 8 * 4.0 * iters * flop / ms / 1e9, 1)
+    out["matrix_rate_probe"] = f"{wgs} workgroups x 8 waves x {4 * iters} instructions on registers only, 4 independent accumulators per wave"
+    n = 1 << 28
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    ms = min(_time_ms(torch, lambda: s24.probe_copy(src, dst), 5) for _ in range(2))
+    out["device_copy_GB/s_read_plus_written"] = round(2.0 * n * 4 / ms / 1e6, 1)
+    out["device_copy"] = "1 GiB read + 1 GiB written per call, 16-byte accesses"
+    del src, dst, sink
+    return out
+
+
 def block_level_measurements(torch, s24, wl, ffn, X, dY, weights):
     """The paper's block-level comparison (Sec. 6, speed-up of a single FFN layer and of a single transformer block,
     forward + backward): the 2:4 FFN step of this library next to the same layer run densely through the library's own
@@ -470,12 +585,69 @@ def block_level_measurements(torch, s24, wl, ffn, X, dY, weights):
     return out
 
 
+def build_layer(torch, si, SparseFFN, wl, args):
+    """Seeded inputs of the workload on the device and the layer in the configuration the flags select."""
+    import numpy as np
+    host = si.make(wl)
+
+    def to_dev(a):
+        t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+        return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
+
+    dev = {k: to_dev(v) for k, v in host.items()}
+    biases = None
+    if args.geglu_bias:
+        biases = {"Wgu": to_dev(si.random_matrix(7001, (2 * wl.d_ff,), 0.3, wl.dtype)),
+                  "Wd": to_dev(si.random_matrix(7002, (wl.d_model,), 0.3, wl.dtype))}
+    ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay,
+                    concat_gate_up=not args.separate_gate_up, mvue=args.mvue, fuse_swiglu=not args.no_fuse_swiglu,
+                    biases=biases, batch_dw=not args.no_batch_dw)
+    return host, dev, ffn
+
+
+def timed_steps(torch, wl, ffn, X, dY, steps, warmup):
+    """`warmup` untimed steps, then exactly `steps` steps between two synchronisations; per-kernel HIP-event times
+    from inside the timed region.  Returns (ms per step, per-kernel table)."""
+    for _ in range(warmup):
+        ffn.step(X, dY)
+    torch.cuda.synchronize()
+    ffn.timings = {}
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ffn.step(X, dY)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    timings, ffn.timings = ffn.timings, None
+    model = kernel_model(wl)
+    kernels = {}
+    for name, pairs in timings.items():
+        ms = [a.elapsed_time(b) for a, b in pairs]
+        per_step = sum(ms) / steps
+        kind, amount, peak, unit = model[name]
+        achieved = amount / (per_step * 1e-3) / (1e12 if kind == "mfma" else 1e9)
+        kernels[name] = {"launches_per_step": len(ms) // steps, "ms_per_step": round(per_step, 4),
+                         "avg_ms": round(sum(ms) / len(ms), 4), "median_ms": round(sorted(ms)[len(ms) // 2], 4),
+                         "min_ms": round(min(ms), 4), "share_of_step": round(per_step / ms_per_step, 4), "bound": kind,
+                         "achieved": round(achieved, 1), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
+    return ms_per_step, kernels
+
+
+def workload_label(wl):
+    return (f"{wl.name}: FFN d_model={wl.d_model} d_ff={wl.d_ff} tokens={wl.p} act={wl.act} "
+            f"{wl.dtype}, {len(wl.weight_names)} weights, mask+compress every step")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"],
+                    help="the workload of the headline line (default c5, the largest single-GPU configuration)")
+    ap.add_argument("--also", default="c2,c3,c4",
+                    help="comma-separated workloads whose step is timed as well (20 steps each) and reported under "
+                         "extras.other_workloads; empty for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the measurements outside the timed step")
     ap.add_argument("--separate-gate-up", action="store_true",
@@ -496,9 +668,9 @@ def main():
     ap.add_argument("--geglu-bias", action="store_true",
                     help="gated workloads only: the layer of Sec. 5.2 as written, GELU gate and biases on both projections "
                          "(bias add in the GEMM epilogues, bias gradients as their own kernel)")
-    ap.add_argument("--block", action="store_true",
-                    help="also time the same layer run densely and the dense rest of a transformer block (PyTorch attention): "
-                         "the FFN-level and block-level speed-ups of the paper's Sec. 6")
+    ap.add_argument("--no-block", action="store_true",
+                    help="skip the block-level comparison (the same layer run densely, and the dense rest of a transformer "
+                         "block through PyTorch attention: the FFN-level and block-level speed-ups of the paper's Sec. 6)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a 1 GiB device-to-device copy five times (reference for HBM byte counters) and exit")
     args = ap.parse_args()
@@ -524,86 +696,85 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}))
         return
     import dataclasses
-    wl = si.WORKLOADS[args.workload]
-    if args.dtype and wl.dtype != "f32":
-        wl = dataclasses.replace(wl, dtype=args.dtype)
-    if args.geglu_bias:
-        if not wl.gated or args.separate_gate_up:
-            sys.exit("bench.py: --geglu-bias needs a gated workload (c4, c5) with gate and up projection as one weight")
-        wl = dataclasses.replace(wl, act="geglu")
-    host = si.make(wl)
 
-    def to_dev(a):
-        import numpy as np
-        t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
-        return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
+    def configured(name):
+        wl = si.WORKLOADS[name]
+        if args.dtype and wl.dtype != "f32":
+            wl = dataclasses.replace(wl, dtype=args.dtype)
+        if args.geglu_bias and wl.gated:
+            wl = dataclasses.replace(wl, act="geglu")
+        return wl
 
-    dev = {k: to_dev(v) for k, v in host.items()}
-    biases = None
-    if args.geglu_bias:
-        biases = {"Wgu": to_dev(si.random_matrix(7001, (2 * wl.d_ff,), 0.3, wl.dtype)),
-                  "Wd": to_dev(si.random_matrix(7002, (wl.d_model,), 0.3, wl.dtype))}
-    ffn = SparseFFN({n: dev[n] for n in wl.weight_names}, wl.p, wl.act, wl.lam, fuse_decay=not args.no_fuse_decay,
-                    concat_gate_up=not args.separate_gate_up, mvue=args.mvue, fuse_swiglu=not args.no_fuse_swiglu,
-                    biases=biases, batch_dw=not args.no_batch_dw)
+    wl = configured(args.workload)
+    if args.geglu_bias and (not wl.gated or args.separate_gate_up):
+        sys.exit("bench.py: --geglu-bias needs a gated workload (c4, c5) with gate and up projection as one weight")
+    host, dev, ffn = build_layer(torch, si, SparseFFN, wl, args)
     X, dY = dev["X"], dev["dY"]
-
-    for _ in range(args.warmup):
-        ffn.step(X, dY)
-    torch.cuda.synchronize()
-    ffn.timings = {}
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ffn.step(X, dY)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    timings, ffn.timings = ffn.timings, None
+    ms_per_step, kernels = timed_steps(torch, wl, ffn, X, dY, args.steps, args.warmup)
     value = wl.gemm_flops / (ms_per_step * 1e-3) / 1e12
 
-    extras = None if args.no_extras else side_measurements(torch, s24, wl, ffn, X, dY, {n: dev[n] for n in wl.weight_names})
+    extras = None
+    if not args.no_extras:
+        weights = {n: dev[n] for n in wl.weight_names}
+        extras = side_measurements(torch, s24, wl, ffn, X, dY, weights)
+        extras["standalone_hbm_kernels"] = standalone_hbm_kernels(torch, s24, wl, ffn, X)
+        extras["measured_ceilings"] = measured_ceilings(torch, s24)
+        if not args.no_block and wl.dtype != "f32":
+            extras["block_level"] = block_level_measurements(torch, s24, wl, ffn, X, dY, weights)
 
-    if args.block:
-        extras = dict(extras or {})
-        extras["block_level"] = block_level_measurements(torch, s24, wl, ffn, X, dY, {n: dev[n] for n in wl.weight_names})
-
-    model = kernel_model(wl)
-    kernels = {}
-    for name, pairs in timings.items():
-        ms = [a.elapsed_time(b) for a, b in pairs]
-        per_step = sum(ms) / args.steps
-        kind, amount, peak, unit = model[name]
-        achieved = amount / (per_step * 1e-3) / (1e12 if kind == "mfma" else 1e9)
-        kernels[name] = {"launches_per_step": len(ms) // args.steps, "ms_per_step": round(per_step, 4),
-                         "avg_ms": round(sum(ms) / len(ms), 4), "median_ms": round(sorted(ms)[len(ms) // 2], 4),
-                         "min_ms": round(min(ms), 4), "share_of_step": round(per_step / ms_per_step, 4), "bound": kind,
-                         "achieved": round(achieved, 1), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
     dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])
     kd = kernels[dom]
-    default_cfg = ffn.concat == wl.gated and ffn.fuse_decay and not args.dtype and not args.geglu_bias
+    default_cfg = ffn.concat == wl.gated and ffn.fuse_decay and not args.dtype and not args.geglu_bias and not ffn.mvue
+    traffic = measured_traffic(wl.name, dom) if default_cfg else None
     roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"], "unit": kd["unit"],
-                "frac": kd["frac"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, dom)) if default_cfg else None}
+                "frac": kd["frac"], "traffic": traffic,
+                "traffic_source": "profiles/hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                  "command, bytes per call of the entry point)" if traffic is not None else None}
+    config = {"workload": workload_label(wl),
+              "gate_up_as_one_weight": ffn.concat, "decay_in_dw_epilogue": ffn.fuse_decay,
+              "swiglu_in_gemm_epilogues": bool(ffn.concat and ffn.fuse_swiglu),
+              "weight_gradients_in_one_pass": bool(ffn.batch_dw and not ffn.mvue),
+              "weight_gradient": "sparse GEMM on the MVUE-pruned output gradient" if ffn.mvue else "dense GEMM",
+              "gemm_flops_per_step": wl.gemm_flops}
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, host)
+
+    # the other workloads' steps, after the headline's buffers are gone
+    del ffn, dev, host, X, dY
+    torch.cuda.empty_cache()
+    if extras is not None and args.also.strip():
+        others = {}
+        for name in [n.strip() for n in args.also.split(",") if n.strip() and n.strip() != wl.name]:
+            if name not in si.WORKLOADS:
+                sys.exit(f"bench.py: unknown workload {name!r} in --also")
+            w2 = configured(name)
+            if args.geglu_bias and not w2.gated:
+                continue
+            _, d2, f2 = build_layer(torch, si, SparseFFN, w2, args)
+            ms2, k2 = timed_steps(torch, w2, f2, d2["X"], d2["dY"], 20, 5)
+            others[name] = {"workload": workload_label(w2), "steps": 20, "warmup": 5, "ms_per_step": round(ms2, 4),
+                            "TFLOP/s": round(w2.gemm_flops / ms2 / 1e9, 2),
+                            "pct_of_sparse_mfma_peak_whole_step": round(100 * w2.gemm_flops / ms2 / 1e9 / PEAK_SPARSE_BF16, 2),
+                            "kernels": {k: {f: v[f] for f in ("launches_per_step", "ms_per_step", "achieved", "unit", "frac")}
+                                        for k, v in k2.items()}}
+            del d2, f2
+            torch.cuda.empty_cache()
+            if name == "c3":
+                others[name]["mask_search_only_72_matrices"] = c3_mask_sweep(torch, s24, w2)
+        extras["other_workloads"] = others
 
     out = {
         "metric": "2:4 FFN fwd+bwd TFLOP/s (dense-equivalent GEMM FLOPs over the whole step)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"{wl.name}: FFN d_model={wl.d_model} d_ff={wl.d_ff} tokens={wl.p} act={wl.act} "
-                               f"{wl.dtype}, {len(wl.weight_names)} weights, mask+compress every step",
-                   "gate_up_as_one_weight": ffn.concat, "decay_in_dw_epilogue": ffn.fuse_decay,
-                   "swiglu_in_gemm_epilogues": bool(ffn.concat and ffn.fuse_swiglu),
-                   "weight_gradients_in_one_pass": bool(ffn.batch_dw and not ffn.mvue),
-                   "weight_gradient": "sparse GEMM on the MVUE-pruned output gradient" if ffn.mvue else "dense GEMM",
-                   "gemm_flops_per_step": wl.gemm_flops},
+        "config": config,
         "pct_of_sparse_mfma_peak_whole_step": round(100 * value / PEAK_SPARSE_BF16, 2),
         "roofline": roofline,
         "kernels": kernels,
         "extras": extras,
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, host)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

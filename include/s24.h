@@ -299,6 +299,15 @@ int s24_l1_norm_gap(const void *W, s24_dtype dt, int64_t r, int64_t q, int64_t l
  * until it has unregistered it and the stream has drained. */
 int s24_set_clock_probe(void *two_counters);
 
+/* Instrumentation, not part of the method: the measured ceilings a roofline of this library is read against.
+ * s24_probe_matrix_rate launches `workgroups` workgroups of 8 waves, each wave issuing 4 * iters matrix-core
+ * instructions on registers only (no LDS, no memory): v_mfma_f32_32x32x16_bf16 (sparse == 0, 32768 FLOP each) or
+ * v_smfmac_f32_32x32x32_bf16 (sparse != 0, 65536 dense-equivalent FLOP each).  sink [workgroups * 512] floats,
+ * device, receives one checksum per lane.  s24_probe_copy copies `bytes` (a multiple of 16; src and dst 16-byte
+ * aligned, not overlapping) device to device in 16-byte accesses.  The caller times the launches. */
+int s24_probe_matrix_rate(int sparse, int workgroups, int iters, float *sink, void *stream);
+int s24_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

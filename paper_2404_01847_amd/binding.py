@@ -54,6 +54,8 @@ _SIGNATURES = {
     "s24_mask_flips": (_int, [_vp, _vp, _i64, _vp, _vp, _vp]),
     "s24_l1_norm_gap": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp]),
     "s24_set_clock_probe": (_int, [_vp]),
+    "s24_probe_matrix_rate": (_int, [_int, _int, _int, _vp, _vp]),
+    "s24_probe_copy": (_int, [_vp, _vp, _i64, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -395,3 +397,20 @@ def l1_norm_gap(W, gap):
 def set_clock_probe(buf):
     """buf: int64 tensor of two elements on the GPU, or None to switch the probe off."""
     _check(lib().s24_set_clock_probe(_ptr(buf)), "s24_set_clock_probe")
+
+
+def probe_matrix_rate(sparse, workgroups, iters, sink):
+    """Register-only matrix-core loop: workgroups x 8 waves x 4*iters instructions; sink: float32 [workgroups*512]."""
+    _dense("s24_probe_matrix_rate", sink=sink)
+    if sink.numel() < workgroups * 512:
+        raise ValueError("s24_probe_matrix_rate: sink needs workgroups * 512 floats")
+    _check(lib().s24_probe_matrix_rate(int(bool(sparse)), workgroups, iters, _ptr(sink), _stream()), "s24_probe_matrix_rate")
+
+
+def probe_copy(src, dst):
+    """Plain device copy of src into dst (same byte size, a multiple of 16)."""
+    _dense("s24_probe_copy", src=src, dst=dst)
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("s24_probe_copy: sizes differ")
+    _check(lib().s24_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream()), "s24_probe_copy")

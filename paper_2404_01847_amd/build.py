@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs24.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["s24_host.hip", "s24_mask.hip", "s24_elementwise.hip", "s24_gemm.hip", "s24_mvue.hip"]
+SOURCES = ["s24_host.hip", "s24_mask.hip", "s24_elementwise.hip", "s24_gemm.hip", "s24_mvue.hip", "s24_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -43,7 +43,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     res = subprocess.run(cmd, capture_output=True, text=True)

@@ -203,7 +203,9 @@ __global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__res
 // Workgroup tile 256 (m) x 256 (n) x 64 (k), eight waves as 2 (m) x 4 (n), each
 // wave 128 x 64 = 4 x 2 accumulator tiles.  Both operands are copied from
 // global memory straight into LDS (no register staging) through a ring of
-// three 50 KB stages, two chunks ahead of the math.  LDS layouts: dense operand rows of 128 bytes with the
+// three 50 KB stages; the copies of chunk kc+3 go out while the second half of chunk kc is
+// multiplied, and the one barrier of a chunk sits between its two halves, where the matrix unit
+// still has the second half's operands in registers (see the main loop).  LDS layouts: dense operand rows of 128 bytes with the
 // 16-byte chunk c of row r at slot c ^ ((r ^ r>>3) & 7); compressed operand
 // rows of 64 bytes with chunk c at slot c ^ ((r>>2) & 3).  Both keep any 16
 // consecutive lanes of an operand read on distinct 16-byte slots modulo 256
@@ -386,35 +388,38 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         return min(m0 + i, M - 1);
     };
 
-    // per-lane source pointers of the direct-to-LDS copies (elements), advanced by one chunk per stage
-    const uint16_t *gb[4];
-    const uint16_t *ga_[2];
+    // Sources of the direct-to-LDS copies: a wave-uniform base per operand (advanced by one chunk per stage, in
+    // scalar registers) plus a 32-bit byte offset per lane, so that seven copies cost seven address registers
+    const char *baseB = reinterpret_cast<const char *>(B + (int64_t)n0 * K);
+    const char *baseV = reinterpret_cast<const char *>(Av), *baseM = reinterpret_cast<const char *>(Am);
+    uint32_t ob[4], oa[2];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = 32 * wave + 8 * i + (lane >> 3);
         const int c = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
-        gb[i] = B + (int64_t)min(n0 + row, N - 1) * K + 8 * c;
+        ob[i] = ((uint32_t)(min(n0 + row, N - 1) - n0) * (uint32_t)K + 8u * c) * 2u;   // a tile's rows span < 4 GB (host check)
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int row = 32 * wave + 16 * i + (lane >> 2);
         const int c = (lane & 3) ^ ((row >> 2) & 3);
-        ga_[i] = Av + (int64_t)a_row(row) * 32 + 8 * c;
+        oa[i] = ((uint32_t)a_row(row) * 32u + 8u * c) * 2u;
     }
     // index words: one 4-byte direct-to-LDS copy per lane and chunk (row 32*wave + lane/2, dword lane%2)
-    const uint16_t *gmeta = Am + (int64_t)a_row(32 * wave + (lane >> 1)) * 4 + 2 * (lane & 1);
+    const uint32_t om = ((uint32_t)a_row(32 * wave + (lane >> 1)) * 4u + 2u * (lane & 1)) * 2u;
     // Every call issues exactly seven copies per lane (four of the dense operand, two of the
     // values, one of the index words), so the wait counts below are constants; past the last
     // chunk it re-reads the last one into a stage nobody will read again.
     auto issue = [&](unsigned char *st, int kc) {
         kc = min(kc, nk - 1);
+        const char *pb = baseB + (int64_t)kc * 128, *pv = baseV + (int64_t)kc * M * 64, *pm = baseM + (int64_t)kc * M * 8;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(gb[i] + (int64_t)kc * 64), (lds_ptr)(st + (32 * wave + 8 * i) * 128), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_ptr)(pb + ob[i]), (lds_ptr)(st + (32 * wave + 8 * i) * 128), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(ga_[i] + (int64_t)kc * M * 32), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_ptr)(gmeta + (int64_t)kc * M * 4), (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_ptr)(pv + oa[i]), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_ptr)(pm + om), (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), 4, 0, 0);
     };
 
     f32x16 acc[4][2];
@@ -423,70 +428,96 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
 
+    // Fragments of one half (h = 0, 1: the two sparse instructions per accumulator tile and 64-chunk) of a stage
+    const int g = lane >> 5;
+    auto load_frags = [&](const unsigned char *st, int h, bf16x16 (&b)[2], bf16x8 (&a)[4]) {
+        const unsigned char *sb = st, *sa = st + B_STAGE;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int row = 64 * wn + 32 * ni + (lane & 31);
+            b[ni] = as_bf16x16(*reinterpret_cast<const uint4 *>(sb + b_slot(row, 2 * h + g)),
+                               *reinterpret_cast<const uint4 *>(sb + b_slot(row, 4 + 2 * h + g)));
+        }
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+            const int row = 128 * wm + 32 * mi + (lane & 31);
+            a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(row, 2 * g + h)));
+        }
+    };
+    auto load_index = [&](const unsigned char *st, uint32_t (&x)[4]) {
+        const unsigned char *sm = st + B_STAGE + A_STAGE;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+            x[mi] = *reinterpret_cast<const uint32_t *>(sm + (128 * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
+    };
+
     // keep the program order of these groups: the constant wait counts rely on it
     issue(s0, 0);
     __builtin_amdgcn_sched_barrier(0);
     issue(s1, 1);
     __builtin_amdgcn_sched_barrier(0);
+    issue(s2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_and_barrier<14>();   // chunk 0 has landed for everybody
+    bf16x16 fb0[2];           // first-half fragments and index words of the chunk about to be multiplied
+    bf16x8 fa0[4];
+    uint32_t ix[4];
+    load_index(s0, ix);
+    load_frags(s0, 0, fb0, fa0);
 
-    // One chunk: wait for its stage, refill the stage that was read last time, do the math.
-    auto chunk = [&](const unsigned char *cur, unsigned char *refill, int kc) {
-        // all but the seven most recent vector-memory operations (the copies of chunk kc+1) are
-        // complete, so this lane's part of chunk kc is in LDS; its own LDS reads are done too
-        wait_and_barrier<7>();   // everybody's part landed; everybody finished reading `refill`
-        issue(refill, kc + 2);
-        const unsigned char *sb = cur, *sa = cur + B_STAGE, *sm = cur + B_STAGE + A_STAGE;
-        const int g = lane >> 5;
-        uint32_t ix[4];
+    // One chunk, software-pipelined across the workgroup barrier.  On entry the first-half fragments of chunk kc
+    // are in registers.  Phase A: their eight matrix instructions, with the eight LDS reads of the second half
+    // dealt out between them.  Then the one barrier of the chunk: every wave has read all it needs of chunk
+    // kc's stage, and chunk kc+1 (copied two chunks ago) has landed for everybody.  Phase B: the second half's
+    // eight matrix instructions, whose operands are already in registers -- so the matrix unit has work while
+    // the first-half fragments of chunk kc+1 come in from LDS and the seven copies of chunk kc+3 go out into the
+    // stage chunk kc just vacated (one per matrix instruction: a wave that issues its copies in one burst sits in
+    // the memory pipeline's queue while the matrix unit idles).  A barrier at the top of the chunk instead, with
+    // nothing in registers, exposed the LDS latency of twelve reads per wave once per chunk.
+    auto chunk = [&](unsigned char *cur, const unsigned char *nxt, int kc) {
+        bf16x16 fb1[2];
+        bf16x8 fa1[4];
+        load_frags(cur, 1, fb1, fa1);
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
-            ix[mi] = *reinterpret_cast<const uint32_t *>(sm + (128 * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            bf16x16 b[2];
-            bf16x8 a[4];
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int row = 64 * wn + 32 * ni + (lane & 31);
-                b[ni] = as_bf16x16(*reinterpret_cast<const uint4 *>(sb + b_slot(row, 2 * h + g)),
-                                   *reinterpret_cast<const uint4 *>(sb + b_slot(row, 4 + 2 * h + g)));
-            }
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi) {
-                const int row = 128 * wm + 32 * mi + (lane & 31);
-                a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(row, 2 * g + h)));
-            }
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
-                    if (h == 0)
-                        acc[mi][ni] = Mma<T>::template sparse<0>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
-                    else
-                        acc[mi][ni] = Mma<T>::template sparse<1>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
-                }
-        }
-        // Issue order: the twelve LDS reads of the first half, then its eight matrix instructions with the
-        // second half's eight reads and the seven copies of chunk kc+2 dealt out between them (a wave that
-        // issues all its copies at once sits in the memory pipeline's queue while the matrix unit idles).
-        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
+            for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<T>::template sparse<0>(fa0[mi], fb0[ni], acc[mi][ni], (int)ix[mi]);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        // all but the seven most recent copies (chunk kc+2) are complete: this lane's part of chunk kc+1 is in LDS,
+        // and its own LDS reads of chunk kc are done
+        wait_and_barrier<7>();
+        issue(cur, kc + 3);
+        uint32_t ixn[4];
+        load_index(nxt, ixn);
+        load_frags(nxt, 0, fb0, fa0);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<T>::template sparse<1>(fa1[mi], fb1[ni], acc[mi][ni], (int)ix[mi]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             if (i < 7) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) ix[mi] = ixn[mi];
     };
+    // past the last chunk the prefetched fragments come from a stage that holds a re-read of the last chunk (or
+    // is being refilled with one); they are never multiplied
     int kc = 0;
     for (; kc + 3 <= nk; kc += 3) {
-        chunk(s0, s2, kc);
-        chunk(s1, s0, kc + 1);
-        chunk(s2, s1, kc + 2);
+        chunk(s0, s1, kc);
+        chunk(s1, s2, kc + 1);
+        chunk(s2, s0, kc + 2);
     }
-    if (kc < nk) chunk(s0, s2, kc);
-    if (kc + 1 < nk) chunk(s1, s0, kc + 1);
+    if (kc < nk) chunk(s0, s1, kc);
+    if (kc + 1 < nk) chunk(s1, s2, kc + 1);
     // drain the copies still in flight, then reuse the ring as a staging area for the output tile
     wait_and_barrier<0>();
     clock_report(probe, t_start);
@@ -1374,6 +1405,9 @@ int check_gemm(const void *a, const void *b, const void *c, int64_t p, int64_t q
     S24_REQUIRE(s24_valid_dtype(dt), S24_ERR_DTYPE);
     S24_REQUIRE(p >= 0 && q >= 0 && r >= 0, S24_ERR_SHAPE);
     S24_REQUIRE(p < (1ll << 31) && q < (1ll << 31) && r < (1ll << 31), S24_ERR_SHAPE);
+    // the large-tile kernels address a tile's operand rows with 32-bit byte offsets from a per-tile base:
+    // 256 rows of the contraction axis, and all rows of one 64-chunk of a compressed operand, must span < 4 GB
+    S24_REQUIRE(q < (1ll << 23) && r < (1ll << 23), S24_ERR_SHAPE);
     if (out_elems == 0) return S24_OK;
     S24_REQUIRE(a && b && c, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(a, 16) && s24_aligned(b, 16) && s24_aligned(c, 16), S24_ERR_ALIGN);

@@ -800,3 +800,19 @@ def test_act_fwd_bwd(s24, dtype, act):
     torch.cuda.synchronize()
     assert_close(host_f64(H), oracle.act_fwd(z, code[1]), tol(dtype), f"{act} fwd")
     assert_close(host_f64(dZ), oracle.act_bwd(d, z, code[1]), tol(dtype), f"{act} bwd")
+
+
+# ------------------------------------------------------------------ instrumentation
+def test_probe_copy_copies_and_matrix_rate_probe_runs(s24):
+    src = torch.arange(0, 3 * 1000 * 4 + 4, dtype=torch.int32, device="cuda")          # ragged: not a whole run
+    dst = torch.zeros_like(src)
+    s24.probe_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    sink = torch.full((4 * 512,), float("nan"), dtype=torch.float32, device="cuda")
+    for sparse in (0, 1):
+        s24.probe_matrix_rate(sparse, 4, 8, sink)
+        torch.cuda.synchronize()
+        assert torch.isfinite(sink).all()
+    # four accumulators of 32 x 32 x (16 * 8) products of values below 1/2: a loose bound that a wrong loop breaks
+    assert float(sink.abs().max()) < 4 * 16 * 8 * 32 * 0.25 * 64

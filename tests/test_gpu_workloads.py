@@ -330,7 +330,18 @@ def test_default_step_full_size_against_the_oracle_chain(s24, name):
     wide = lambda a: si.to_f32(a).astype(np.float64)
     got = lambda tens: host_f64(tens[ridx])
     gbits = lambda tens: host_bits(tens[ridx].contiguous())
-    chain_tol = (2e-2, 5e-3)   # a chain compounds roundings: a flipped bf16 rounding upstream moves a downstream value by its own step
+    def assert_chain(gotv, ref, what):
+        """The chained comparison.  A bf16 rounding that falls the other way upstream (GPU fp32 accumulation against
+        the oracle's fp64) moves that operand by 2^-8 of itself, and a contraction over thousands of such operands
+        then moves every output by some 1e-3 of the output's rms, whatever the output's own size: the element
+        bound of a chain is taken relative to max(|ref|, rms) (a single kernel's bar, relative to max(|ref|,
+        1e-2 rms), is applied below to each stage on the GPU's own stored input).  The normwise bound is the bar's."""
+        gotv, ref = np.asarray(gotv, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+        assert np.isfinite(gotv).all(), what
+        rms = np.sqrt(np.mean(ref * ref))
+        e_max = (np.abs(gotv - ref) / np.maximum(np.abs(ref), rms)).max()
+        e_nrm = np.linalg.norm(gotv - ref) / np.linalg.norm(ref)
+        assert e_max <= 2e-2 and e_nrm <= BF16_TOL[1], f"{what}: max {e_max:.3e} of max(|ref|, rms), normwise {e_nrm:.3e}"
     if wl.gated:
         gate = oracle.GATE_SILU
         Z = rnd(oracle.spmm_fwd(Xs, comp[up][0], comp[up][1]))
@@ -340,15 +351,20 @@ def test_default_step_full_size_against_the_oracle_chain(s24, name):
         dZ = rnd(oracle.glu_bwd(dH, Z, gate))
         dXr = oracle.spmm_bwd_dx(dZ, comp[up][2], comp[up][3])
         assert_close(got(ffn.GU), wide(Z), BF16_TOL, f"{name} GU")            # first stage: single-kernel bar
-        assert_close(got(ffn.H), wide(H), chain_tol, f"{name} H (chain)")
-        assert_close(got(ffn.Y), Y, chain_tol, f"{name} Y (chain)")
-        assert_close(got(ffn.dGU), wide(dZ), chain_tol, f"{name} dGU (chain)")
-        assert_close(got(ffn.dX), dXr, chain_tol, f"{name} dX (chain)")
+        assert_chain(got(ffn.H), wide(H), f"{name} H (chain)")
+        assert_chain(got(ffn.Y), Y, f"{name} Y (chain)")
+        assert_chain(got(ffn.dGU), wide(dZ), f"{name} dGU (chain)")
+        assert_chain(got(ffn.dX), dXr, f"{name} dX (chain)")
         # each later stage on the GPU's own stored input
         GUg, Hg, dGUg = gbits(ffn.GU), gbits(ffn.H), gbits(ffn.dGU)
         assert_close(got(ffn.H), oracle.glu_fwd(GUg, gate), BF16_TOL, f"{name} H")
         assert_close(got(ffn.Y), oracle.spmm_fwd(Hg, comp[down][0], comp[down][1]), BF16_TOL, f"{name} Y")
-        assert_close(got(ffn.dGU), oracle.glu_bwd(dH, GUg, gate), BF16_TOL, f"{name} dGU")
+        # the fused backward epilogue never stores dH: the plain input-gradient GEMM (whose bits the fused kernel
+        # reproduces) gives the GPU's own dH for the single-kernel bar of the activation backward
+        s24.spmm_bwd_dx(dYd, ffn.w[down].valsT, ffn.w[down].metaT, ffn.dH)
+        torch.cuda.synchronize()
+        assert_close(got(ffn.dH), wide(dH), BF16_TOL, f"{name} dH")
+        assert_close(got(ffn.dGU), oracle.glu_bwd(gbits(ffn.dH), GUg, gate), BF16_TOL, f"{name} dGU")
         assert_close(got(ffn.dX), oracle.spmm_bwd_dx(dGUg, comp[up][2], comp[up][3]), BF16_TOL, f"{name} dX")
         ops = {"Wd": (dY, host_bits(ffn.H), dYd, ffn.H), "Wgu": (host_bits(ffn.dGU), X, ffn.dGU, Xd)}
     else:
@@ -360,14 +376,17 @@ def test_default_step_full_size_against_the_oracle_chain(s24, name):
         dZ = rnd(oracle.act_bwd(dH, Z, act))
         dXr = oracle.spmm_bwd_dx(dZ, comp[up][2], comp[up][3])
         assert_close(got(ffn.Z), wide(Z), BF16_TOL, f"{name} Z")
-        assert_close(got(ffn.H), wide(H), chain_tol, f"{name} H (chain)")
-        assert_close(got(ffn.Y), Y, chain_tol, f"{name} Y (chain)")
-        assert_close(got(ffn.dZ), wide(dZ), chain_tol, f"{name} dZ (chain)")
-        assert_close(got(ffn.dX), dXr, chain_tol, f"{name} dX (chain)")
+        assert_chain(got(ffn.H), wide(H), f"{name} H (chain)")
+        assert_chain(got(ffn.Y), Y, f"{name} Y (chain)")
+        assert_chain(got(ffn.dZ), wide(dZ), f"{name} dZ (chain)")
+        assert_chain(got(ffn.dX), dXr, f"{name} dX (chain)")
         Zg, Hg, dZg = gbits(ffn.Z), gbits(ffn.H), gbits(ffn.dZ)
         assert_close(got(ffn.H), oracle.act_fwd(Zg, act), BF16_TOL, f"{name} H")
         assert_close(got(ffn.Y), oracle.spmm_fwd(Hg, comp[down][0], comp[down][1]), BF16_TOL, f"{name} Y")
-        assert_close(got(ffn.dZ), oracle.act_bwd(dH, Zg, act), BF16_TOL, f"{name} dZ")
+        s24.spmm_bwd_dx(dYd, ffn.w[down].valsT, ffn.w[down].metaT, ffn.dH)
+        torch.cuda.synchronize()
+        assert_close(got(ffn.dH), wide(dH), BF16_TOL, f"{name} dH")
+        assert_close(got(ffn.dZ), oracle.act_bwd(gbits(ffn.dH), Zg, act), BF16_TOL, f"{name} dZ")
         assert_close(got(ffn.dX), oracle.spmm_bwd_dx(dZg, comp[up][2], comp[up][3]), BF16_TOL, f"{name} dX")
         ops = {"W2": (dY, host_bits(ffn.H), dYd, ffn.H), "W1": (host_bits(ffn.dZ), X, ffn.dZ, Xd)}
     del comp
