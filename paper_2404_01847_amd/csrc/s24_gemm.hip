@@ -219,6 +219,28 @@ typedef const __attribute__((address_space(1))) void *glb_ptr;
 __device__ __forceinline__ int b_slot(int row, int c) { return row * 128 + ((c ^ ((row ^ (row >> 3)) & 7)) << 4); }
 __device__ __forceinline__ int a_slot(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
 
+// Buffer descriptor for direct-to-LDS copies: base address in scalar registers, raw (unstructured) addressing, no
+// bounds clamp that the kernels rely on (every offset they form is inside the operand; 2 GB of records declared).
+// (The host pass of the compiler does not know these builtins: it sees empty bodies.)
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t buffer_of(const void *base)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7FFFFFFF, 0x27000);
+}
+// BYTES (16 or 4) per lane from byte offset `voff` of the buffer to lds + 64 * BYTES * (lane's index in the wave)
+template <int BYTES> __device__ __forceinline__ void buffer_to_lds(rsrc_t buf, lds_ptr lds, uint32_t voff)
+{
+    static_assert(BYTES == 16 || BYTES == 4, "copy width");
+    if constexpr (BYTES == 16) __builtin_amdgcn_raw_ptr_buffer_load_lds(buf, lds, 16, voff, 0, 0, 0);
+    else __builtin_amdgcn_raw_ptr_buffer_load_lds(buf, lds, 4, voff, 0, 0, 0);
+}
+#else
+typedef const void *rsrc_t;
+__device__ __forceinline__ rsrc_t buffer_of(const void *base) { return base; }
+template <int BYTES> __device__ __forceinline__ void buffer_to_lds(rsrc_t, lds_ptr, uint32_t) {}
+#endif
+
 // s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt unconstrained
 __host__ __device__ constexpr int wait_vm_lgkm0(int n) { return (n & 15) | (7 << 4) | ((n >> 4) << 14); }
 
@@ -389,7 +411,8 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     };
 
     // Sources of the direct-to-LDS copies: a wave-uniform base per operand (advanced by one chunk per stage, in
-    // scalar registers) plus a 32-bit byte offset per lane, so that seven copies cost seven address registers
+    // scalar registers: the base of a buffer descriptor) plus a fixed 32-bit byte offset per lane, so that seven
+    // copies cost seven address registers and no vector arithmetic
     const char *baseB = reinterpret_cast<const char *>(B + (int64_t)n0 * K);
     const char *baseV = reinterpret_cast<const char *>(Av), *baseM = reinterpret_cast<const char *>(Am);
     uint32_t ob[4], oa[2];
@@ -412,14 +435,13 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     // chunk it re-reads the last one into a stage nobody will read again.
     auto issue = [&](unsigned char *st, int kc) {
         kc = min(kc, nk - 1);
-        const char *pb = baseB + (int64_t)kc * 128, *pv = baseV + (int64_t)kc * M * 64, *pm = baseM + (int64_t)kc * M * 8;
+        const rsrc_t pb = buffer_of(baseB + (int64_t)kc * 128), pv = buffer_of(baseV + (int64_t)kc * M * 64);
+        const rsrc_t pm = buffer_of(baseM + (int64_t)kc * M * 8);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(pb + ob[i]), (lds_ptr)(st + (32 * wave + 8 * i) * 128), 16, 0, 0);
+        for (int i = 0; i < 4; ++i) buffer_to_lds<16>(pb, (lds_ptr)(st + (32 * wave + 8 * i) * 128), ob[i]);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(pv + oa[i]), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_ptr)(pm + om), (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), 4, 0, 0);
+        for (int i = 0; i < 2; ++i) buffer_to_lds<16>(pv, (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), oa[i]);
+        buffer_to_lds<4>(pm, (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), om);
     };
 
     f32x16 acc[4][2];
@@ -946,32 +968,33 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
 
     // Copies: instruction g of an operand fills the 16-byte slots 64g .. 64g+63 of its stage region, slot ->
     // (row = slot / CPR, chunk = slot % CPR); the source chunk is chunk ^ (4 * (row & 3)).  Columns past the
-    // matrix edge are clamped to its last 16-byte chunk.  Offsets are elements from the chunk's first row.
-    int voffA[NIO], voffB[NIO];
+    // matrix edge are clamped to its last 16-byte chunk.  A lane's byte offsets from the first token row of a
+    // chunk are fixed for the whole kernel; only the (wave-uniform) row base moves, so a copy costs no vector
+    // arithmetic.  A chunk always starts at a row that leaves BT rows below it: the last chunk of a token count
+    // that is not a multiple of BT starts at T - BT and overlaps its predecessor (clear_tail drops the overlap);
+    // with fewer than BT tokens in all there is one chunk, rows past T - 1 re-read row T - 1.
+    uint32_t voffA[NIO], voffB[NIO];
     const int lastA = (min(M - m0, BM) >> 3) - 1, lastB = (min(N - n0, BN) >> 3) - 1;
 #pragma unroll
     for (int j = 0; j < NIO; ++j) {
-        const int slot = (wave * NIO + j) * 64 + lane, row = slot / CPR, c = (slot % CPR) ^ ((row & 3) << 2);
-        voffA[j] = row * ldy + m0 + 8 * min(c, lastA);
-        voffB[j] = row * ldx + n0 + 8 * min(c, lastB);
+        const int slot = (wave * NIO + j) * 64 + lane, row = min(slot / CPR, T - 1), c = (slot % CPR) ^ (((slot / CPR) & 3) << 2);
+        voffA[j] = (uint32_t)(row * ldy + m0 + 8 * min(c, lastA)) * 2u;
+        voffB[j] = (uint32_t)(row * ldx + n0 + 8 * min(c, lastB)) * 2u;
     }
-    // Copies first .. first+count-1 of a chunk's list (the dY tile's NIO, then the X tile's NIO).  Token rows
-    // past T (last chunk only) re-read row T-1.
+    auto first_row = [&](int kc) { return max(min(kc * BT, T - BT), 0); };
+    // Copies first .. first+count-1 of a chunk's list (the dY tile's NIO, then the X tile's NIO).
+    // The copies are buffer loads into LDS: a descriptor (scalar registers) whose base is the chunk's first token
+    // row, and the lane's fixed 32-bit offset; nothing of a copy's address is computed on the vector unit.
     auto issue = [&](unsigned char *st, int kc, int first, int count) {
-        kc = min(kc, nk - 1);
-        const char *ya = reinterpret_cast<const char *>(dY + (int64_t)kc * BT * ldy);
-        const char *xb = reinterpret_cast<const char *>(X + (int64_t)kc * BT * ldx);
-        const int lastrow = T - 1 - kc * BT;
+        const int row0 = first_row(kc);
+        const big::rsrc_t ya = big::buffer_of(dY + (int64_t)row0 * ldy), xb = big::buffer_of(X + (int64_t)row0 * ldx);
 #pragma unroll
         for (int c = first; c < first + count; ++c) {
             const int j = c < NIO ? c : c - NIO;
-            const int over = max(((wave * NIO + j) * 64 + lane) / CPR - lastrow, 0);
             if (c < NIO)
-                __builtin_amdgcn_global_load_lds((glb_ptr)(ya + (uint32_t)(voffA[j] - over * ldy) * 2u),
-                                                 (lds_ptr)(st + (wave * NIO + j) * 1024), 16, 0, 0);
+                big::buffer_to_lds<16>(ya, (lds_ptr)(st + (wave * NIO + j) * 1024), voffA[j]);
             else
-                __builtin_amdgcn_global_load_lds((glb_ptr)(xb + (uint32_t)(voffB[j] - over * ldx) * 2u),
-                                                 (lds_ptr)(st + OPERAND + (wave * NIO + j) * 1024), 16, 0, 0);
+                big::buffer_to_lds<16>(xb, (lds_ptr)(st + OPERAND + (wave * NIO + j) * 1024), voffB[j]);
         }
     };
     f32x16 acc[WT][WT];
@@ -1015,11 +1038,13 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    // token rows past T must not contribute: clear them in the dY tile of the (last, partial) chunk kc
+    // The last chunk of a token count that is not a multiple of BT holds BT - rem rows that must not contribute:
+    // the leading rows that its predecessor already covered (the chunk starts at T - BT), or, when there are
+    // fewer than BT tokens in all, the trailing rows past T.  They are cleared in the dY tile.
     auto clear_tail = [&](unsigned char *st, int kc) {
-        const int rem = T - kc * BT;
+        const int rem = T - kc * BT, skip = T >= BT ? 0 : rem;
         for (int idx = tid; idx < (BT - rem) * CPR; idx += THREADS)
-            *reinterpret_cast<uint4 *>(st + (rem + idx / CPR) * ROWB + ((idx % CPR) << 4)) = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(st + (skip + idx / CPR) * ROWB + ((idx % CPR) << 4)) = make_uint4(0, 0, 0, 0);
         __syncthreads();
     };
     const bool partial = (T % BT) != 0;
