@@ -20,6 +20,9 @@
 // (vals[K/64][M][32], meta[K/64][M][4]) makes the 64-byte value run and the
 // four index words of one row and chunk contiguous, rows back to back.
 #include "s24_common.h"
+#ifndef S24_X_EARLY
+#define S24_X_EARLY 2
+#endif
 
 namespace {
 
@@ -1027,13 +1030,15 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
     };
     // Issue order of one 16-token step: a matrix instruction, then 4/WT LDS reads of the next step's fragments
     // (4*WT reads against WT*WT matrix instructions), and after every other matrix instruction one copy.
+    // The reads go out in the first half of the step (two per matrix instruction for the large tile), so that the
+    // last fragment has arrived well before the step ends: with one wave per SIMD nobody else covers a wait.
     auto interleave = [&]() {
-        constexpr int RPM = 4 / WT;
+        constexpr int RPM = 4 / WT, EARLY = WT == 4 ? S24_X_EARLY : 1;
         static_assert(RPM * WT * WT == 4 * WT && 2 * CPS <= WT * WT, "reads and copies fit between the matrix instructions");
 #pragma unroll
         for (int i = 0; i < WT * WT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+            if (i < WT * WT / EARLY) __builtin_amdgcn_sched_group_barrier(0x100, RPM * EARLY, 0);
             if ((i & 1) && (i >> 1) < CPS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);

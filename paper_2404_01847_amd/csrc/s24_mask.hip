@@ -336,6 +336,77 @@ __device__ __forceinline__ unsigned best_pattern(const uint32_t (&mag)[16], cons
 }
 
 // ---------------------------------------------------------------------------
+// Integer fast path (bf16 data).  The same class decomposition and the same tie-break bonus as above, in
+// 32-bit integers, which the vector unit adds and compares at twice the rate of fp64: with E the exponent of the
+// block's largest magnitude, every magnitude times 2^(155-E) is an integer below 2^29 whose lowest set bit is at
+// or above bit 11 as long as it lies within ten binades of the largest (8 significand bits + 10 + 11 = 29), so a
+// sum of eight stays below 2^32 and the low 11 bits are free for the bonus.  The product with a power of two and the
+// conversion to an integer are exact.  Returns kHardBlock for a block that does not fit (an element more than ten
+// binades down, a zero or subnormal element, a block maximum below 2^-99): those take the fp64 path above.
+// ---------------------------------------------------------------------------
+constexpr unsigned kHardBlock = 0xFFFFFFFFu;
+
+__device__ __forceinline__ unsigned int_best_pattern(const uint32_t (&mag)[16], const uint16_t *lut_mask, const uint8_t *lut_id)
+{
+    uint32_t mx = mag[0], mn = mag[0];
+#pragma unroll
+    for (int t = 1; t < 16; ++t) {
+        mx = max(mx, mag[t]);
+        mn = min(mn, mag[t]);
+    }
+    const uint32_t E = mx >> 23, emin = mn >> 23;
+    if (emin == 0u || emin + 10u < E || E < 28u) return kHardBlock;
+    const float scale = __uint_as_float((282u - E) << 23);   // 2^(155-E)
+    uint32_t a[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            a[i][j] = (uint32_t)(__uint_as_float(mag[4 * i + j]) * scale) + (uint32_t)(kColBonus[j] * kRowMult[i]);
+    uint32_t dt[4], db[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        dt[j] = a[0][j] + a[1][j];
+        db[j] = a[2][j] + a[3][j];
+    }
+    // (i) both top rows keep the pair {c1,c2}, both bottom rows its complement
+    uint32_t best = 0;
+#pragma unroll
+    for (int k = 0; k < 6; ++k)
+        best = max(best, (dt[pair_c1(k)] + dt[pair_c2(k)]) + (db[pair_c1(5 - k)] + db[pair_c2(5 - k)]));
+    // (ii) complementary pairs in each half: all of one row plus the two largest gains of moving a column to the other
+    {
+        auto half = [](const uint32_t (&r0)[4], const uint32_t (&r1)[4]) {
+            const int d0 = (int)(r0[0] - r1[0]), d1 = (int)(r0[1] - r1[1]), d2 = (int)(r0[2] - r1[2]), d3 = (int)(r0[3] - r1[3]);
+            const int m1 = max(d0, d1), n1 = min(d0, d1), m2 = max(d2, d3), n2 = min(d2, d3);
+            const int hi = max(m1, m2), lo = min(m1, m2);
+            const int second = max(lo, max(n1, n2));
+            return ((r1[0] + r1[1]) + (r1[2] + r1[3])) + (uint32_t)hi + (uint32_t)second;   // modulo 2^32: a sum of four cells
+        };
+        best = max(best, half(a[0], a[1]) + half(a[2], a[3]));
+    }
+    // (iii) top rows share column x, bottom rows share column w, the two remaining columns cross in each half
+    uint32_t cross[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        const int y = pair_c1(k), z = pair_c2(k);
+        cross[k] = max(a[0][y] + a[1][z], a[0][z] + a[1][y]) + max(a[2][y] + a[3][z], a[2][z] + a[3][y]);
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w == x) continue;
+            int y = -1, z = -1;
+            for (int c = 0; c < 4; ++c)
+                if (c != x && c != w) (y < 0 ? y : z) = c;
+            best = max(best, dt[x] + db[w] + cross[pair_of(y, z)]);
+        }
+    const unsigned xi = min((best & 0x7FFu) - (unsigned)kBonusBase, 1295u);
+    return (unsigned)lut_mask[xi] | ((unsigned)lut_id[xi] << 16);
+}
+
+// ---------------------------------------------------------------------------
 // Per-dtype access to one block row (four consecutive weights).
 // ---------------------------------------------------------------------------
 template <typename T> struct RowOps;
@@ -402,7 +473,13 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     using Row = typename Ops::Row;
     using Pair = typename Ops::Pair;
     constexpr bool FAST = COMPRESS && sizeof(T) == 2;   // bf16: table-driven compressor
-    constexpr bool PREFETCH_ROWS = true;   // measured faster in every variant, even the register-heavy fused one
+    // bf16 search on its own: integer scoring with the blocks it cannot take queued for the fp64 path.  (In the fused
+    // search + compress kernel the four blocks' rows held in registers across the queue cost more than the cheaper
+    // scoring saves: measured 4-8 % slower, so it keeps the fp64 scoring inside its loop.)
+    constexpr bool DEFER = SEARCH && !COMPRESS && sizeof(T) == 2 && RowOps<T>::kWindow == 29;
+    __shared__ int s_nhard;
+    __shared__ uint16_t s_hard[DEFER ? 1024 : 1];
+    __shared__ uint32_t s_fix[DEFER ? 1024 : 1];
     __shared__ uint16_t s_lut_mask[SEARCH ? 1296 : 1];
     __shared__ uint8_t s_lut_id[(SEARCH || FAST) ? 1296 : 1];
     __shared__ uint4 s_clut[FAST ? 3 * S24_NUM_PATTERNS : 1];
@@ -410,6 +487,7 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     __shared__ uint8_t s_nibT[COMPRESS ? 4 * kTile * kPitch : 1];
 
     const int tid = threadIdx.x;
+    if (DEFER && tid == 0) s_nhard = 0;
     if constexpr (SEARCH || FAST) {
         for (int x = tid; x < 1296; x += 256) {
             if constexpr (SEARCH) s_lut_mask[x] = g_lut.mask[x];
@@ -426,8 +504,7 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
     const int bj = bj0 + lbj;
     const int64_t R = 4 * (int64_t)br, Q = 4 * (int64_t)bq;  // rows of vals / of valsT
 
-    // first weight row of this lane's first block; each step of the loop moves 8 block rows down.
-    // The rows of the next block are requested before the current one is scored.
+    // first weight row of this lane's first block; block s of the lane lies 8 s block rows further down
     const T *wrow = W + (int64_t)(4 * (bi0 + (tid >> 5))) * ldw + 4 * bj;
     auto fetch = [&](Row (&dst)[4], const T *p, bool ok) {
         if (ok) {
@@ -438,35 +515,23 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
             for (int i = 0; i < 4; ++i) dst[i] = Row{};
         }
     };
-    Row nxt[4];
-    fetch(nxt, wrow, (bi0 + (tid >> 5) < br) && (bj < bq));
-#pragma unroll 1
-    for (int s = 0; s < 4; ++s) {
+    auto magnitudes = [&](const Row (&rows)[4], uint32_t (&mag)[16]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mag[4 * i + j] = Ops::mag(rows[i], j);
+    };
+    // What follows the search for block s of this lane (rows in registers, mask m and pattern id known):
+    // the mask and id stores and, when compressing, both compressed orientations.
+    auto emit = [&](const Row (&rows)[4], unsigned m, unsigned id, int s) {
         const int lbi = (tid >> 5) + 8 * s;
         const int bi = bi0 + lbi;
         const bool valid = (bi < br) && (bj < bq);
-        Row rows[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) rows[i] = nxt[i];
-        if (!PREFETCH_ROWS && s > 0) fetch(rows, wrow, valid);
-        wrow += 32 * ldw;
-        if (PREFETCH_ROWS && s < 3) fetch(nxt, wrow, (bi + 8 < br) && (bj < bq));
-        unsigned m = 0, id = 0;
         if constexpr (SEARCH) {
-            uint32_t mag[16];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) mag[4 * i + j] = Ops::mag(rows[i], j);
-            const unsigned res = best_pattern<Ops::kWindow, Ops::kWide>(mag, s_lut_mask, s_lut_id);
-            m = res & 0xFFFFu;
-            id = res >> 16;
             if (valid) {
                 if (mask_out) mask_out[(int64_t)bi * bq + bj] = (uint16_t)m;
                 if (index_out) index_out[(int64_t)bi * bq + bj] = (uint8_t)id;
             }
-        } else {
-            m = valid ? mask_in[(int64_t)bi * bq + bj] : 0x33CCu;
         }
         if constexpr (FAST) {
             if constexpr (!SEARCH) id = s_lut_id[min(lut_index_of_mask(m), 1295u)];
@@ -547,6 +612,67 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
                 s_valsT[a] = Ops::pair(v0, v1);
                 s_nibT[a] = (uint8_t)(i0 | (i1 << 2));
             }
+        }
+    };
+
+    if constexpr (DEFER) {
+        // bf16 search: all four blocks of the lane are scored by the integer fast path first; the few blocks it
+        // cannot take (about one in forty for normally distributed weights) are queued in LDS and scored afterwards
+        // by the fp64 path, one per lane, so that a rare block costs one lane's time instead of stalling its whole
+        // wave in a divergent branch.
+        Row blk[4][4];
+        unsigned res[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) fetch(blk[s], wrow + (int64_t)(32 * s) * ldw, (bi0 + (tid >> 5) + 8 * s < br) && (bj < bq));
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bool valid = (bi0 + (tid >> 5) + 8 * s < br) && (bj < bq);
+            uint32_t mag[16];
+            magnitudes(blk[s], mag);
+            res[s] = valid ? int_best_pattern(mag, s_lut_mask, s_lut_id) : 0x33CCu;   // off the edge: pattern 0, never stored
+            if (res[s] == kHardBlock) s_hard[atomicAdd(&s_nhard, 1)] = (uint16_t)(256 * s + tid);
+        }
+        __syncthreads();
+        const int nhard = s_nhard;
+        for (int e = tid; e < nhard; e += 256) {
+            const int code = s_hard[e], hs = code >> 8, owner = code & 255;
+            const T *p = W + (int64_t)(4 * (bi0 + (owner >> 5) + 8 * hs)) * ldw + 4 * (bj0 + (owner & 31));
+            Row rows[4];
+            fetch(rows, p, true);
+            uint32_t mag[16];
+            magnitudes(rows, mag);
+            s_fix[code] = best_pattern<Ops::kWindow, Ops::kWide>(mag, s_lut_mask, s_lut_id);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const unsigned r = res[s] == kHardBlock ? s_fix[256 * s + tid] : res[s];
+            emit(blk[s], r & 0xFFFFu, r >> 16, s);
+        }
+    } else {
+        // The rows of the next block are requested before the current one is scored.
+        Row nxt[4];
+        fetch(nxt, wrow, (bi0 + (tid >> 5) < br) && (bj < bq));
+#pragma unroll 1
+        for (int s = 0; s < 4; ++s) {
+            const int bi = bi0 + (tid >> 5) + 8 * s;
+            const bool valid = (bi < br) && (bj < bq);
+            Row rows[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) rows[i] = nxt[i];
+            wrow += 32 * ldw;
+            if (s < 3) fetch(nxt, wrow, (bi + 8 < br) && (bj < bq));
+            unsigned m = 0, id = 0;
+            if constexpr (SEARCH) {
+                uint32_t mag[16];
+                magnitudes(rows, mag);
+                const unsigned res = best_pattern<Ops::kWindow, Ops::kWide>(mag, s_lut_mask, s_lut_id);
+                m = res & 0xFFFFu;
+                id = res >> 16;
+            } else {
+                m = valid ? mask_in[(int64_t)bi * bq + bj] : 0x33CCu;
+            }
+            emit(rows, m, id, s);
         }
     }
     if constexpr (COMPRESS) {

@@ -131,6 +131,8 @@ def tie_matrix(seed: int, r: int, q: int, dtype: str, kind: str) -> np.ndarray:
     kind "range":  entries 2^e with e uniform in [-120, 100] (far beyond any
                    fixed-point window), random signs and 1..3 leading digits
     kind "subnormal": bf16/fp32 subnormals mixed with normals
+    kind "window": 8-bit significands times 2^e, the exponents of a block spread over up to 11 binades above a
+                   per-block base drawn from the whole exponent range
     For "f16" the same kinds stay inside binary16: "tiny" scales by 2^-12, "range" takes
     e in [-24, 13], "subnormal" mixes multiples of 2^-24 with multiples of 2^-17.
     """
@@ -161,6 +163,16 @@ def tie_matrix(seed: int, r: int, q: int, dtype: str, kind: str) -> np.ndarray:
         m = torch.randint(0, 128, (r, q), generator=g).double()
         e = torch.where(torch.randint(0, 4, (r, q), generator=g) == 0, -17.0 if half else -126.0, -24.0 if half else -133.0)
         x = (sign.double() * m * torch.pow(torch.tensor(2.0, dtype=torch.float64), e.double())).float()
+    elif kind == "window":
+        # full 8-bit significands (few distinct ones, so sums tie or differ in the last bit) times 2^e, where the
+        # exponents of one block spread over 0 .. 11 binades above a per-block base anywhere in the type's range:
+        # blocks on both sides of a 10-binade fixed-point window, and blocks that are tiny as a whole
+        sig = torch.tensor([128.0, 129.0, 192.0, 255.0])[torch.randint(0, 4, (r, q), generator=g)]
+        lo, hi = (-20, 2) if half else (-125, 100)
+        base = torch.randint(lo, hi, (r // 4, q // 4), generator=g).repeat_interleave(4, 0).repeat_interleave(4, 1)
+        spread = torch.randint(0, 12, (r // 4, q // 4), generator=g).repeat_interleave(4, 0).repeat_interleave(4, 1)
+        e = base + (torch.rand((r, q), generator=g) * (spread + 1).float()).floor().clamp(max=11)
+        x = (sign.double() * sig.double() * torch.pow(torch.tensor(2.0, dtype=torch.float64), e.double() - 7.0)).float()
     else:
         raise ValueError(kind)
     return _store(x, dtype).copy()

@@ -76,7 +76,7 @@ def test_mask_random_bit_exact(s24, dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
-@pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal"])
+@pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal", "window"])
 def test_mask_ties_and_wide_ranges_bit_exact(s24, dtype, kind):
     W = si.tie_matrix(77, 192, 320, dtype, kind)
     want_m, want_i = oracle.transposable_mask(W, want_index=True)

@@ -102,7 +102,7 @@ def test_mask_matches_exact_brute_force_random(dtype, legal_blocks):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
-@pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal"])
+@pytest.mark.parametrize("kind", ["few", "equal", "zeros", "tiny", "range", "subnormal", "window"])
 def test_mask_matches_exact_brute_force_ties(dtype, kind, legal_blocks):
     W = si.tie_matrix(5, 16, 32, dtype, kind)
     check_against_brute_force(W, legal_blocks)
@@ -111,7 +111,7 @@ def test_mask_matches_exact_brute_force_ties(dtype, kind, legal_blocks):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_mask_fast_and_wide_paths_agree(dtype):
-    for kind in ["few", "equal", "zeros", "tiny", "range", "subnormal"]:
+    for kind in ["few", "equal", "zeros", "tiny", "range", "subnormal", "window"]:
         W = si.tie_matrix(9, 64, 128, dtype, kind)
         a = oracle.transposable_mask(W)
         b = oracle.transposable_mask(W, exact_wide=True)
