@@ -20,9 +20,6 @@
 // (vals[K/64][M][32], meta[K/64][M][4]) makes the 64-byte value run and the
 // four index words of one row and chunk contiguous, rows back to back.
 #include "s24_common.h"
-#ifndef S24_X_EARLY
-#define S24_X_EARLY 2
-#endif
 
 namespace {
 
@@ -102,108 +99,7 @@ __device__ __forceinline__ void tile_store(const TileRegs &t, unsigned char *buf
 }
 
 // ------------------------------------------------------------------ sparse NT
-struct SparseA { uint4 v[2][2]; uint32_t idx[2]; };  // per m-fragment: 32 bytes of values, one index dword
-
-__device__ __forceinline__ void sparse_a_load(SparseA &a, const uint16_t *Av, const uint16_t *Am, int K, int M, int mrow0,
-                                              int k0, int lane)
-{
-    const int ga = lane >> 5;
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
-        const int row = min(mrow0 + 32 * mi + (lane & 31), M - 1);
-        const int64_t cr = (int64_t)(k0 / 64) * M + row;  // (chunk, row) in chunk-major storage
-        const uint4 *pv = reinterpret_cast<const uint4 *>(Av + cr * 32 + 16 * ga);
-        a.v[mi][0] = pv[0];
-        a.v[mi][1] = pv[1];
-        a.idx[mi] = reinterpret_cast<const uint32_t *>(Am + cr * 4)[ga];
-    }
-}
-
-template <typename T, bool ACCUM>
-__global__ __launch_bounds__(kThreads) void spmm_nt_kernel(const uint16_t *__restrict__ B, const uint16_t *__restrict__ Av,
-                                                           const uint16_t *__restrict__ Am, uint16_t *__restrict__ Out,
-                                                           int N, int K, int M, const uint16_t *__restrict__ bias)
-{
-    __shared__ __attribute__((aligned(16))) unsigned char s_b[2][BN * 128];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const int nk = K / BK;
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
-
-    SparseA a_cur, a_nxt;
-    TileRegs breg;
-    sparse_a_load(a_cur, Av, Am, K, M, m0 + 64 * wm, 0, lane);
-    tile_load(breg, B, K, n0, N, 0, tid);
-    tile_store(breg, s_b[0], tid);
-    __syncthreads();
-
-    for (int kc = 0; kc < nk; ++kc) {
-        const bool more = kc + 1 < nk;
-        if (more) {
-            tile_load(breg, B, K, n0, N, (kc + 1) * BK, tid);
-            sparse_a_load(a_nxt, Av, Am, K, M, m0 + 64 * wm, (kc + 1) * BK, lane);
-        }
-        const unsigned char *buf = s_b[kc & 1];
-        const int gb = lane >> 5;
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const int row = 64 * wn + 32 * ni + (lane & 31);
-            const bf16x16 b0 = as_bf16x16(lds_read(buf, row, gb), lds_read(buf, row, 4 + gb));
-            const bf16x16 b1 = as_bf16x16(lds_read(buf, row, 2 + gb), lds_read(buf, row, 6 + gb));
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                acc[mi][ni] = Mma<T>::template sparse<0>(as_bf16x8(a_cur.v[mi][0]), b0, acc[mi][ni], (int)a_cur.idx[mi]);
-                acc[mi][ni] = Mma<T>::template sparse<1>(as_bf16x8(a_cur.v[mi][1]), b1, acc[mi][ni], (int)a_cur.idx[mi]);
-            }
-        }
-        if (more) tile_store(breg, s_b[(kc + 1) & 1], tid);
-        __syncthreads();
-        if (more) a_cur = a_nxt;
-    }
-
-    // epilogue: accumulator i of lane l is out[n][m] with n = l%32, m = 8*(i/4) + 4*(l/32) + i%4
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
-        if (n >= N) continue;
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int m = m0 + 64 * wm + 32 * mi + 8 * g + 4 * (lane >> 5);
-                if (m >= M) continue;  // M is a multiple of 16, so groups of four are all in or all out
-                uint2 *dst = reinterpret_cast<uint2 *>(Out + (int64_t)n * M + m);
-                float v[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][4 * g + e];
-                if (bias != nullptr) {   // Z = X W^T + d (Sec. 5.2 step 2), added before the rounding
-                    const uint2 b = *reinterpret_cast<const uint2 *>(bias + m);
-                    v[0] += s24_num<T>::lo(b.x);
-                    v[1] += s24_num<T>::hi(b.x);
-                    v[2] += s24_num<T>::lo(b.y);
-                    v[3] += s24_num<T>::hi(b.y);
-                }
-                if (ACCUM) {
-                    const uint2 old = *dst;
-                    v[0] += s24_num<T>::lo(old.x);
-                    v[1] += s24_num<T>::hi(old.x);
-                    v[2] += s24_num<T>::lo(old.y);
-                    v[3] += s24_num<T>::hi(old.y);
-                }
-                *dst = make_uint2(s24_num<T>::pack2(v[0], v[1]), s24_num<T>::pack2(v[2], v[3]));
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------ sparse NT, large tile
-// Workgroup tile 256 (m) x 256 (n) x 64 (k), eight waves as 2 (m) x 4 (n), each
+// Large tile: workgroup tile 256 (m) x 256 (n) x 64 (k), eight waves as 2 (m) x 4 (n), each
 // wave 128 x 64 = 4 x 2 accumulator tiles.  Both operands are copied from
 // global memory straight into LDS (no register staging) through a ring of
 // three 50 KB stages; the copies of chunk kc+3 go out while the second half of chunk kc is
@@ -285,18 +181,21 @@ __device__ __forceinline__ void clock_report(unsigned long long *probe, const Cl
 // accumulator writes of 32 consecutive rows (same u) fall on distinct banks; a 16-byte read gets
 // units 2c and 2c+1 from one aligned slot, in swapped order on odd rows.
 // `estage` is EWAVE bytes of LDS private to the wave and no longer used for anything else.
+// A wave tile has MI accumulator blocks along m (4: 128 features, rows of 256 bytes; 2: 64 features, rows of 128
+// bytes whose units are swizzled with row & 15).
 constexpr int EWAVE = 64 * 256;
-template <typename T>
-__device__ __forceinline__ void stage_tile(const f32x16 (&acc)[4][2], unsigned char *estage, int lane)
+template <typename T, int MI>
+__device__ __forceinline__ void stage_tile(const f32x16 (&acc)[MI][2], unsigned char *estage, int lane)
 {
+    constexpr int RB = 64 * MI, UMASK = 8 * MI - 1;
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int nl = 32 * ni + (lane & 31), u = 8 * mi + 2 * g4 + (lane >> 5);
-                *reinterpret_cast<uint2 *>(estage + nl * 256 + ((u ^ (nl & 31)) << 3)) =
+                *reinterpret_cast<uint2 *>(estage + nl * RB + ((u ^ (nl & UMASK)) << 3)) =
                     make_uint2(s24_num<T>::pack2(acc[mi][ni][4 * g4], acc[mi][ni][4 * g4 + 1]),
                                s24_num<T>::pack2(acc[mi][ni][4 * g4 + 2], acc[mi][ni][4 * g4 + 3]));
             }
@@ -304,11 +203,11 @@ __device__ __forceinline__ void stage_tile(const f32x16 (&acc)[4][2], unsigned c
 // Z = X W^T + d (Sec. 5.2 step 2): adds the bias of output feature m to the wave's 128 (m) x 64 (n) accumulator
 // tile before it is rounded.  `bias` points at the entry of the tile's first feature; features at or past `limit`
 // (edge tiles; never stored) read the last four valid entries instead.
-template <typename T>
-__device__ __forceinline__ void add_bias(f32x16 (&acc)[4][2], const uint16_t *__restrict__ bias, int limit, int lane)
+template <typename T, int MI>
+__device__ __forceinline__ void add_bias(f32x16 (&acc)[MI][2], const uint16_t *__restrict__ bias, int limit, int lane)
 {
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             const int m = min(32 * mi + 8 * g4 + 4 * (lane >> 5), limit - 4);
@@ -324,26 +223,27 @@ __device__ __forceinline__ void add_bias(f32x16 (&acc)[4][2], const uint16_t *__
     }
 }
 // 16-byte chunk c (eight bf16, columns 8c .. 8c+7) of row nl of a staged tile
-__device__ __forceinline__ uint4 staged_chunk(const unsigned char *estage, int nl, int c)
+template <int MI = 4> __device__ __forceinline__ uint4 staged_chunk(const unsigned char *estage, int nl, int c)
 {
-    const int x = nl & 31;
-    const uint4 v = *reinterpret_cast<const uint4 *>(estage + nl * 256 + ((((2 * c) ^ x) & ~1) << 3));
+    const int x = nl & (8 * MI - 1);
+    const uint4 v = *reinterpret_cast<const uint4 *>(estage + nl * (64 * MI) + ((((2 * c) ^ x) & ~1) << 3));
     return (x & 1) ? make_uint4(v.z, v.w, v.x, v.y) : v;
 }
-template <typename T>
-__device__ __forceinline__ void staged_store(const f32x16 (&acc)[4][2], unsigned char *estage, uint16_t *__restrict__ Out,
+template <typename T, int MI>
+__device__ __forceinline__ void staged_store(const f32x16 (&acc)[MI][2], unsigned char *estage, uint16_t *__restrict__ Out,
                                              int N, int M, int n_base, int m_base, int lane)
 {
-    stage_tile<T>(acc, estage, lane);
+    stage_tile<T, MI>(acc, estage, lane);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
     asm volatile("" ::: "memory");
+    constexpr int LPR = 4 * MI;   // lanes per row of the tile (16-byte pieces)
 #pragma unroll 4
-    for (int j = 0; j < 16; ++j) {
-        const int nl = 4 * j + (lane >> 4), c = lane & 15;
+    for (int j = 0; j < LPR; ++j) {
+        const int nl = (64 / LPR) * j + lane / LPR, c = lane % LPR;
         const int n = n_base + nl, m = m_base + 8 * c;
         if (n >= N || m >= M) continue;   // M is a multiple of 16 (and of 8): a chunk is all in or all out
-        *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + m) = staged_chunk(estage, nl, c);
+        *reinterpret_cast<uint4 *>(Out + (int64_t)n * M + m) = staged_chunk<MI>(estage, nl, c);
     }
 }
 
@@ -374,8 +274,8 @@ template <int ACT> __device__ __forceinline__ float act_slope(float z)
 // BIAS compiles the bias add into the plain forward kernel (the gated forward tests the pointer at run time; the
 // plain kernel without a bias keeps its register budget, which the extra loads would push into scratch).
 template <typename T, bool ACCUM, bool SWIGLU = false, bool GATE_BWD = false, int GATE = S24_GATE_SILU, bool BIAS = false,
-          int ACT_MODE = 0, int ACT = S24_ACT_RELU>
-__global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
+          int ACT_MODE = 0, int ACT = S24_ACT_RELU, int MI = 4>
+__global__ __launch_bounds__(128 * MI) void spmm_nt_big_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ Av,
                                                               const uint16_t *__restrict__ Am,
                                                               uint16_t *__restrict__ Out, int N, int K, int M,
@@ -386,6 +286,13 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
 {
     static_assert(!(ACCUM && (SWIGLU || GATE_BWD)) && !(SWIGLU && GATE_BWD), "the gated epilogues overwrite");
     static_assert(ACT_MODE == 0 || !(ACCUM || SWIGLU || GATE_BWD), "one epilogue at a time");
+    // MI = accumulator blocks per wave along m.  4: the 256 x 256 tile of eight waves (2 x 4, 128 x 64 each).
+    // 2: a 128 x 128 tile of four waves (2 x 2, 64 x 64 each) on 25 KB stages, two workgroups per compute unit,
+    // for outputs with too few large tiles to fill the chip; plain, accumulating and bias epilogues only.  A lane
+    // issues the same seven copies per chunk either way (the stage is half as tall and there are half as many lanes).
+    static_assert(MI == 4 || (MI == 2 && !SWIGLU && !GATE_BWD && ACT_MODE == 0), "the small tile has no fused activation");
+    constexpr int BM = 64 * MI, BN = 64 * MI, WM = 32 * MI;   // workgroup tile, wave tile along m
+    constexpr int B_STAGE = BN * 128, A_STAGE = BM * 64, M_STAGE = BM * 8, STAGE = B_STAGE + A_STAGE + M_STAGE;
     const ClockStamp t_start = clock_now();
     // One array per ring stage: the compiler then knows which stage a direct-to-LDS
     // copy writes and does not make reads of the other stages wait for it.
@@ -447,15 +354,15 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         buffer_to_lds<4>(pm, (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), om);
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[MI][2];
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
 
     // Fragments of one half (h = 0, 1: the two sparse instructions per accumulator tile and 64-chunk) of a stage
     const int g = lane >> 5;
-    auto load_frags = [&](const unsigned char *st, int h, bf16x16 (&b)[2], bf16x8 (&a)[4]) {
+    auto load_frags = [&](const unsigned char *st, int h, bf16x16 (&b)[2], bf16x8 (&a)[MI]) {
         const unsigned char *sb = st, *sa = st + B_STAGE;
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
@@ -464,16 +371,16 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
                                *reinterpret_cast<const uint4 *>(sb + b_slot(row, 4 + 2 * h + g)));
         }
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-            const int row = 128 * wm + 32 * mi + (lane & 31);
+        for (int mi = 0; mi < MI; ++mi) {
+            const int row = WM * wm + 32 * mi + (lane & 31);
             a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(row, 2 * g + h)));
         }
     };
-    auto load_index = [&](const unsigned char *st, uint32_t (&x)[4]) {
+    auto load_index = [&](const unsigned char *st, uint32_t (&x)[MI]) {
         const unsigned char *sm = st + B_STAGE + A_STAGE;
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-            x[mi] = *reinterpret_cast<const uint32_t *>(sm + (128 * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
+        for (int mi = 0; mi < MI; ++mi)
+            x[mi] = *reinterpret_cast<const uint32_t *>(sm + (WM * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
     };
 
     // keep the program order of these groups: the constant wait counts rely on it
@@ -485,8 +392,8 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     __builtin_amdgcn_sched_barrier(0);
     wait_and_barrier<14>();   // chunk 0 has landed for everybody
     bf16x16 fb0[2];           // first-half fragments and index words of the chunk about to be multiplied
-    bf16x8 fa0[4];
-    uint32_t ix[4];
+    bf16x8 fa0[MI];
+    uint32_t ix[MI];
     load_index(s0, ix);
     load_frags(s0, 0, fb0, fa0);
 
@@ -501,37 +408,50 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
     // nothing in registers, exposed the LDS latency of twelve reads per wave once per chunk.
     auto chunk = [&](unsigned char *cur, const unsigned char *nxt, int kc) {
         bf16x16 fb1[2];
-        bf16x8 fa1[4];
+        bf16x8 fa1[MI];
         load_frags(cur, 1, fb1, fa1);
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<T>::template sparse<0>(fa0[mi], fb0[ni], acc[mi][ni], (int)ix[mi]);
+        // second-half reads: four of the dense operand and MI of the compressed one
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 2 * MI; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i < 4 - MI) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         // all but the seven most recent copies (chunk kc+2) are complete: this lane's part of chunk kc+1 is in LDS,
         // and its own LDS reads of chunk kc are done
         wait_and_barrier<7>();
         issue(cur, kc + 3);
-        uint32_t ixn[4];
+        uint32_t ixn[MI];
         load_index(nxt, ixn);
         load_frags(nxt, 0, fb0, fa0);
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<T>::template sparse<1>(fa1[mi], fb1[ni], acc[mi][ni], (int)ix[mi]);
+        if constexpr (MI == 4) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            if (i < 7) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                if (i < 7) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+        } else {   // four matrix instructions: 4 + 2 + 2 reads and 7 copies between them
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i == 0) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                else if (i < 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                if (i < 3) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) ix[mi] = ixn[mi];
+        for (int mi = 0; mi < MI; ++mi) ix[mi] = ixn[mi];
     };
     // past the last chunk the prefetched fragments come from a stage that holds a re-read of the last chunk (or
     // is being refilled with one); they are never multiplied
@@ -553,10 +473,10 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
             const int n = n0 + 64 * wn + 32 * ni + (lane & 31);
             if (n >= N) continue;
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4) {
-                    const int m = m0 + 128 * wm + 32 * mi + 8 * g4 + 4 * (lane >> 5);
+                    const int m = m0 + WM * wm + 32 * mi + 8 * g4 + 4 * (lane >> 5);
                     if (m >= M) continue;
                     uint2 *dst = reinterpret_cast<uint2 *>(Out + (int64_t)n * M + m);
                     const uint2 old = *dst;
@@ -568,16 +488,20 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         }
         return;
     }
-    static_assert(3 * EWAVE <= STAGE, "three wave tiles must fit one ring stage");
-    auto region = [&](int w) { return (w < 3 ? s0 : (w < 6 ? s1 : s2)) + (w % 3) * EWAVE; };
+    // a wave's parking area for its output tile (64 rows of 64 MI bytes) in the drained ring
+    static_assert(MI == 4 ? 3 * EWAVE <= STAGE : 2 * (EWAVE / 2) <= STAGE, "wave tiles must fit the ring stages");
+    auto region = [&](int w) {
+        if constexpr (MI == 4) return (w < 3 ? s0 : (w < 6 ? s1 : s2)) + (w % 3) * EWAVE;
+        else return (w < 2 ? s0 : s1) + (w & 1) * (EWAVE / 2);
+    };
     if constexpr (SWIGLU) {
-        if (bias != nullptr) add_bias<T>(acc, bias + (wm ? F : 0) + m0, F - m0, lane);   // wave-uniform
+        if (bias != nullptr) add_bias<T, MI>(acc, bias + (wm ? F : 0) + m0, F - m0, lane);   // wave-uniform
     } else if constexpr (BIAS) {
-        add_bias<T>(acc, bias + m0 + 128 * wm, M - (m0 + 128 * wm), lane);   // launched only with a bias
+        add_bias<T, MI>(acc, bias + m0 + WM * wm, M - (m0 + WM * wm), lane);   // launched only with a bias
     }
     if constexpr (GATE_BWD) {
         unsigned char *est = region(wave);
-        stage_tile<T>(acc, est, lane);
+        stage_tile<T, 4>(acc, est, lane);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
         asm volatile("" ::: "memory");
@@ -614,7 +538,7 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         }
     } else if constexpr (ACT_MODE == 2) {
         unsigned char *est = region(wave);
-        stage_tile<T>(acc, est, lane);
+        stage_tile<T, 4>(acc, est, lane);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
         asm volatile("" ::: "memory");
@@ -639,7 +563,7 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
         }
     } else if constexpr (ACT_MODE == 1) {
         unsigned char *est = region(wave);
-        stage_tile<T>(acc, est, lane);
+        stage_tile<T, 4>(acc, est, lane);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));
         asm volatile("" ::: "memory");
@@ -659,11 +583,11 @@ __global__ __launch_bounds__(THREADS) void spmm_nt_big_kernel(const uint16_t *__
             *reinterpret_cast<uint4 *>(H + (int64_t)n * M + m) = make_uint4(h[0], h[1], h[2], h[3]);
         }
     } else if constexpr (!SWIGLU) {
-        staged_store<T>(acc, region(wave), Out, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
+        staged_store<T, MI>(acc, region(wave), Out, N, M, n0 + 64 * wn, m0 + WM * wm, lane);
     } else {
         // waves (0, wn) and (1, wn) hold the gate and the up tile of the same 64 tokens x 128 features: both park
         // their bf16 tiles, then each takes 32 of the 64 token rows and writes G, U and H in 16-byte pieces
-        stage_tile<T>(acc, region(wave), lane);
+        stage_tile<T, 4>(acc, region(wave), lane);
         wait_and_barrier<0>();
         const unsigned char *sg = region(2 * wn), *su = region(2 * wn + 1);
 #pragma unroll 2
@@ -857,7 +781,7 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
     if (kc < nk) chunk(s0, s1, kc);
     big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
     big::clock_report(probe, t_start);
-    big::staged_store<T>(acc, (wave < 4 ? s0 : s1) + (wave & 3) * big::EWAVE, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
+    big::staged_store<T, 4>(acc, (wave < 4 ? s0 : s1) + (wave & 3) * big::EWAVE, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
 }
 }  // namespace bignt
 
@@ -1033,7 +957,7 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
     // The reads go out in the first half of the step (two per matrix instruction for the large tile), so that the
     // last fragment has arrived well before the step ends: with one wave per SIMD nobody else covers a wait.
     auto interleave = [&]() {
-        constexpr int RPM = 4 / WT, EARLY = WT == 4 ? S24_X_EARLY : 1;
+        constexpr int RPM = 4 / WT, EARLY = WT == 4 ? 2 : 1;
         static_assert(RPM * WT * WT == 4 * WT && 2 * CPS <= WT * WT, "reads and copies fit between the matrix instructions");
 #pragma unroll
         for (int i = 0; i < WT * WT; ++i) {
@@ -1456,7 +1380,20 @@ int check_gemm(const void *a, const void *b, const void *c, int64_t p, int64_t q
         }                                 \
     } while (0)
 
-inline bool fills_chip_256(int64_t m, int64_t n) { return (int64_t)ceil_div(m, 256) * ceil_div(n, 256) >= 192; }
+// Compute units of the current device, read once (256 on MI355X; that figure also stands in where no device
+// answers, so that the host-side checks behave the same without a GPU).
+inline int s24_cu_count()
+{
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            return v;
+        return 256;
+    }();
+    return n;
+}
+inline bool fills_chip_256(int64_t m, int64_t n) { return (int64_t)ceil_div(m, 256) * ceil_div(n, 256) >= 3 * s24_cu_count() / 4; }
 
 // Out[N][M] = beta * Out + B[N][K] . A^T (+ bias[M], only with beta = 0)
 int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, int64_t N, int64_t K, int64_t M, float beta,
@@ -1475,9 +1412,18 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
     }
     auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av), *d = static_cast<const uint16_t *>(bias);
     auto *o = static_cast<uint16_t *>(Out);
-    if (fills_chip_256(M, N)) {
-        // enough 256x256 tiles to fill the chip: large-tile kernel
-        const int tiles_m = (int)ceil_div(M, big::BM), tiles_n = (int)ceil_div(N, big::BN);
+    // Large tile (256 x 256, one workgroup per compute unit) or small tile (128 x 128, two per compute unit)?  The
+    // small tile moves twice the bytes per FLOP through L2, so it only pays where the large one leaves compute units
+    // idle: few tiles, or a last round that is mostly empty.  Cost model in rounds of the large tile: a small-tile
+    // round (twice as many workgroups, half the work) takes kSmallRound of a large one (measured).
+    const int tm256 = (int)ceil_div(M, 256), tn256 = (int)ceil_div(N, 256), tm128 = (int)ceil_div(M, 128), tn128 = (int)ceil_div(N, 128);
+    const int64_t t256 = (int64_t)tm256 * tn256, t128 = (int64_t)tm128 * tn128;
+    S24_REQUIRE(t128 < (1ll << 30), S24_ERR_SHAPE);
+    constexpr double kSmallRound = 0.75;
+    const int cus = s24_cu_count();
+    const double cost_big = (double)ceil_div(t256, cus), cost_small = kSmallRound * (double)ceil_div(t128, 2 * cus);
+    if (cost_big <= cost_small) {
+        const int tiles_m = tm256, tiles_n = tn256;
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
         const dim3 grid(per_xcd * 8), block(big::THREADS);
         S24_WITH_16BIT_TYPE(dt, {
@@ -1492,11 +1438,22 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
                                    tiles_m, tiles_n, g_clock_probe, nullptr, 0, nullptr, nullptr);
         });
     } else {
-        const dim3 grid(ceil_div(M, BM), ceil_div(N, BN)), block(kThreads);
-        S24_REQUIRE(grid.y <= 65535, S24_ERR_SHAPE);
+        const int tiles_m = tm128, tiles_n = tn128;
+        const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+        const dim3 grid(per_xcd * 8), block(256);
         S24_WITH_16BIT_TYPE(dt, {
-            if (accum) hipLaunchKernelGGL((spmm_nt_kernel<T, true>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M, d);
-            else hipLaunchKernelGGL((spmm_nt_kernel<T, false>), grid, block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M, d);
+            if (accum)
+                hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, true, false, false, S24_GATE_SILU, false, 0, S24_ACT_RELU, 2>), grid,
+                                   block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M, tiles_m, tiles_n, nullptr, nullptr, 0,
+                                   nullptr, nullptr);
+            else if (d != nullptr)
+                hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, true, 0, S24_ACT_RELU, 2>), grid,
+                                   block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M, tiles_m, tiles_n, nullptr, nullptr, 0,
+                                   nullptr, d);
+            else
+                hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, false, 0, S24_ACT_RELU, 2>), grid,
+                                   block, 0, st, b, av, Am, o, (int)N, (int)K, (int)M, tiles_m, tiles_n, nullptr, nullptr, 0,
+                                   nullptr, nullptr);
         });
     }
     return s24_launch_status();
@@ -1544,7 +1501,7 @@ extern "C" int s24_spmm_fwd_glu(const void *X, const void *vals, const uint16_t 
     S24_REQUIRE(s24_aligned(meta, 4) && s24_aligned(H, 16) && s24_aligned(bias, 8), S24_ERR_ALIGN);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int tiles_m = (int)ceil_div(f, 128), tiles_n = (int)ceil_div(p, big::BN);
-    if (dt != S24_F32 && (int64_t)tiles_m * tiles_n >= 192) {
+    if (dt != S24_F32 && (int64_t)tiles_m * tiles_n >= 3 * s24_cu_count() / 4) {
         const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
         auto *x = static_cast<const uint16_t *>(X), *av = static_cast<const uint16_t *>(vals), *d = static_cast<const uint16_t *>(bias);
         auto *gu = static_cast<uint16_t *>(GU), *h = static_cast<uint16_t *>(H);
@@ -1581,7 +1538,7 @@ extern "C" int s24_spmm_bwd_dx_glu(const void *dY, const void *valsT, const uint
     S24_REQUIRE(s24_aligned(metaT, 4) && s24_aligned(GU, 16), S24_ERR_ALIGN);
     const int tiles_m = (int)ceil_div(f, big::BM), tiles_n = (int)ceil_div(p, big::BN);
     // only the large-tile 16-bit kernel carries this epilogue; other shapes take s24_spmm_bwd_dx + s24_glu_bwd
-    S24_REQUIRE(dt != S24_F32 && (int64_t)tiles_m * tiles_n >= 192, S24_ERR_UNSUPPORTED);
+    S24_REQUIRE(dt != S24_F32 && (int64_t)tiles_m * tiles_n >= 3 * s24_cu_count() / 4, S24_ERR_UNSUPPORTED);
     const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
     hipStream_t st = static_cast<hipStream_t>(stream);
     auto *dy = static_cast<const uint16_t *>(dY), *av = static_cast<const uint16_t *>(valsT), *gu = static_cast<const uint16_t *>(GU);
@@ -1735,7 +1692,7 @@ void launch_dw_batch(const dmatn::DwBatch &batch, int tile, bool accum, bool dec
     } while (0)
     S24_WITH_16BIT_TYPE(dt, {
         if (tile == 256) S24_LAUNCH_DW_TILE(4, 32);
-        else if (slots * 8 > 256) S24_LAUNCH_DW_TILE(2, 32);
+        else if (slots * 8 > s24_cu_count()) S24_LAUNCH_DW_TILE(2, 32);
         else S24_LAUNCH_DW_TILE(2, 64);
     });
 #undef S24_LAUNCH_DW_TILE
@@ -1772,15 +1729,16 @@ int run_dense_dw(const void *dY, const void *X, float *dW, int64_t p, int64_t q,
         // round) measured no better than the idle tail it replaces and stays in the single launch.  Every output
         // element belongs to exactly one launch either way, so nothing about the result changes.
         const int tm256 = (int)ceil_div(r, 256), tn256 = (int)ceil_div(q, 256), total = tm256 * tn256;
-        if (total < 192) {
+        const int cus = s24_cu_count();
+        if (total < 3 * cus / 4) {
             launch(128, 0, r, 0, q);
         } else {
             int cut_m = 0, cut_n = 0;   // tile rows / columns kept in the large-tile slab (0: no such cut)
-            if (total % 256 != 0) {
+            if (total % cus != 0) {
                 for (int k = tm256 - 1; k >= 1 && !cut_m; --k)
-                    if ((k * tn256) % 256 == 0 && (tm256 - k) * tn256 <= 128) cut_m = k;
+                    if ((k * tn256) % cus == 0 && (tm256 - k) * tn256 <= cus / 2) cut_m = k;
                 for (int k = tn256 - 1; k >= 1 && !cut_n; --k)
-                    if ((k * tm256) % 256 == 0 && (tn256 - k) * tm256 <= 128) cut_n = k;
+                    if ((k * tm256) % cus == 0 && (tn256 - k) * tm256 <= cus / 2) cut_n = k;
             }
             if (cut_m && (!cut_n || cut_m * tn256 >= cut_n * tm256)) {
                 launch(256, 0, 256ll * cut_m, 0, q);
@@ -1863,14 +1821,15 @@ extern "C" int s24_dense_dw_batch(const s24_dw_problem *problems, int count, flo
         prs[i] = DwProblem{static_cast<const uint16_t *>(pr.dY), static_cast<const uint16_t *>(pr.X), pr.dW,
                            static_cast<const uint16_t *>(pr.W), pr.mask, pr.p, pr.q, pr.r, pr.lambda};
     }
-    if (!shared_grid || total < 192 || count == 1) {
+    const int cus = s24_cu_count();
+    if (!shared_grid || total < 3 * cus / 4 || count == 1) {
         // Problems that would each run in small tiles anyway (fewer than 192 large ones) share one small-tile grid:
         // a GPT-2-small layer's two gradients are 144 small tiles each, 0.56 of the chip one after the other.
         bool small_grid = dt != S24_F32 && count > 1;
         for (int i = 0; i < count; ++i) {
             const s24_dw_problem &pr = problems[i];
             small_grid = small_grid && pr.p > 0 && pr.q * pr.r != 0 && (pr.W != nullptr) == decay &&
-                         (int64_t)ceil_div(pr.r, 256) * ceil_div(pr.q, 256) < 192;
+                         (int64_t)ceil_div(pr.r, 256) * ceil_div(pr.q, 256) < 3 * cus / 4;
         }
         if (small_grid) {
             dmatn::DwBatch batch{};
@@ -1896,8 +1855,8 @@ extern "C" int s24_dense_dw_batch(const s24_dw_problem *problems, int count, flo
     // units, look for a problem from which whole tile columns (or rows) amounting to exactly the excess, and to at
     // most half a round, can be cut: that strip runs in small tiles afterwards, the rest in whole rounds.
     int cut = -1, cut_cols = 0, cut_rows = 0;
-    const int excess = (int)(total % 256);
-    if (excess != 0 && excess <= 128) {
+    const int excess = (int)(total % cus);
+    if (excess != 0 && excess <= cus / 2) {
         for (int i = 0; i < count && cut < 0; ++i) {
             const int tm = (int)ceil_div(prs[i].r, 256), tn = (int)ceil_div(prs[i].q, 256);
             if (excess % tm == 0 && excess / tm < tn) { cut = i; cut_cols = excess / tm; }
