@@ -415,11 +415,13 @@ __global__ __launch_bounds__(128 * MI) void spmm_nt_big_kernel(const uint16_t *_
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<T>::template sparse<0>(fa0[mi], fb0[ni], acc[mi][ni], (int)ix[mi]);
         // second-half reads: four of the dense operand and MI of the compressed one
+        // (the large tile issues them two per matrix instruction in the first half of the phase, so that the last one
+        // has returned before the barrier)
 #pragma unroll
         for (int i = 0; i < 2 * MI; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < 4 - MI) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (MI == 4 ? i < 4 : i < 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            else if (MI == 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         // all but the seven most recent copies (chunk kc+2) are complete: this lane's part of chunk kc+1 is in LDS,
         // and its own LDS reads of chunk kc are done
