@@ -11,6 +11,9 @@
  * synchronises; each call only enqueues kernels on `stream` (a hipStream_t
  * passed as void*, NULL = the default stream) and returns.
  *
+ * Limits: every size is below 2^31, and the feature extents of the GEMM entry points (q, r, 2f) below 2^23: the
+ * kernels address one tile's operand rows with 32-bit byte offsets from a per-tile base (S24_ERR_SHAPE beyond).
+ *
  * Errors: every entry point returns an s24_status.  Arguments are validated on
  * the host before anything is launched, so a failing call has no effect on
  * device memory.  Nothing throws or aborts.  Inputs are assumed finite.
@@ -124,7 +127,8 @@ int s24_spmm_fwd_glu(const void *X, const void *vals, const uint16_t *meta, cons
 
 /* s24_spmm_bwd_dx_swiglu for either gate: dGU[p][2f] = [dH .* Z_2 .* act'(Z_1) | dH .* act(Z_1)] with
  * dH = dY (M.*W_down) consumed tile by tile.  Same bits as s24_spmm_bwd_dx followed by s24_glu_bwd; the same
- * S24_ERR_UNSUPPORTED rule (fp32, or fewer than 192 output tiles of 256 x 256). */
+ * S24_ERR_UNSUPPORTED rule (fp32, or fewer output tiles of 256 x 256 than three quarters of the device's compute units:
+ * 192 on MI355X). */
 int s24_spmm_bwd_dx_glu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
                         int64_t p, int64_t f, int64_t r, s24_gate gate, s24_dtype dt, void *stream);
 
@@ -136,8 +140,8 @@ int s24_spmm_fwd_act(const void *X, const void *vals, const uint16_t *meta, cons
 
 /* Input gradient of the second projection of an ungated layer with the backward of the activation in the same pass
  * (Eq. 3): dZ[p][f] = (dY[p][r] (M.*W_2)) .* act'(Z), the product rounded to the storage type before the
- * multiplication: the same bits as s24_spmm_bwd_dx followed by s24_act_bwd.  Same S24_ERR_UNSUPPORTED rule as
- * s24_spmm_bwd_dx_glu.  r multiple of 64; f of 16. */
+ * multiplication: the same bits as s24_spmm_bwd_dx followed by s24_act_bwd.  fp32 returns S24_ERR_UNSUPPORTED and
+ * leaves everything untouched (use the two calls).  r multiple of 64; f of 16. */
 int s24_spmm_bwd_dx_act(const void *dY, const void *valsT, const uint16_t *metaT, const void *Z, void *dZ,
                         int64_t p, int64_t f, int64_t r, s24_act act, s24_dtype dt, void *stream);
 
@@ -161,7 +165,8 @@ int s24_spmm_bwd_dx(const void *dY, const void *valsT, const uint16_t *metaT, vo
  * (Eq. 3 + Sec. 5.2): dH = dY[p][r] . (M.*W_down) (valsT [r/64][f][32], metaT [r/64][f][4]) is formed tile by
  * tile, rounded to the storage type and consumed on the spot:  dGU[p][2f] = [dH .* U .* silu'(G) | dH .* silu(G)]
  * with G and U the halves of GU[p][2f].  Same bits as s24_spmm_bwd_dx followed by s24_swiglu_bwd.  Only the
- * large-tile 16-bit kernel has this epilogue: fp32, and outputs of fewer than 192 tiles of 256 x 256, return
+ * large-tile 16-bit kernel has this epilogue: fp32, and outputs of fewer tiles of 256 x 256 than three quarters of the
+ * device's compute units (192 on MI355X), return
  * S24_ERR_UNSUPPORTED and leave everything untouched (use the two calls).  r multiple of 64; f of 16. */
 int s24_spmm_bwd_dx_swiglu(const void *dY, const void *valsT, const uint16_t *metaT, const void *GU, void *dGU,
                            int64_t p, int64_t f, int64_t r, s24_dtype dt, void *stream);

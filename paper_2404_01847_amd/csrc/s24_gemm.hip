@@ -119,13 +119,14 @@ __device__ __forceinline__ int b_slot(int row, int c) { return row * 128 + ((c ^
 __device__ __forceinline__ int a_slot(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
 
 // Buffer descriptor for direct-to-LDS copies: base address in scalar registers, raw (unstructured) addressing, no
-// bounds clamp that the kernels rely on (every offset they form is inside the operand; 2 GB of records declared).
+// bounds clamp that the kernels rely on (every offset they form is inside the operand and below 4 GB, which the host
+// checks; the descriptor declares the full 4 GB of records).
 // (The host pass of the compiler does not know these builtins: it sees empty bodies.)
 #if defined(__HIP_DEVICE_COMPILE__)
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t buffer_of(const void *base)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0x7FFFFFFF, 0x27000);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, 0xFFFFFFFFu, 0x27000);
 }
 // BYTES (16 or 4) per lane from byte offset `voff` of the buffer to lds + 64 * BYTES * (lane's index in the wave)
 template <int BYTES> __device__ __forceinline__ void buffer_to_lds(rsrc_t buf, lds_ptr lds, uint32_t voff)
@@ -288,9 +289,9 @@ __global__ __launch_bounds__(128 * MI) void spmm_nt_big_kernel(const uint16_t *_
     static_assert(ACT_MODE == 0 || !(ACCUM || SWIGLU || GATE_BWD), "one epilogue at a time");
     // MI = accumulator blocks per wave along m.  4: the 256 x 256 tile of eight waves (2 x 4, 128 x 64 each).
     // 2: a 128 x 128 tile of four waves (2 x 2, 64 x 64 each) on 25 KB stages, two workgroups per compute unit,
-    // for outputs with too few large tiles to fill the chip; plain, accumulating and bias epilogues only.  A lane
+    // for outputs with too few large tiles to fill the chip; every epilogue but the gated ones.  A lane
     // issues the same seven copies per chunk either way (the stage is half as tall and there are half as many lanes).
-    static_assert(MI == 4 || (MI == 2 && !SWIGLU && !GATE_BWD && ACT_MODE == 0), "the small tile has no fused activation");
+    static_assert(MI == 4 || (MI == 2 && !SWIGLU && !GATE_BWD), "the small tile has no gated epilogue");
     constexpr int BM = 64 * MI, BN = 64 * MI, WM = 32 * MI;   // workgroup tile, wave tile along m
     constexpr int B_STAGE = BN * 128, A_STAGE = BM * 64, M_STAGE = BM * 8, STAGE = B_STAGE + A_STAGE + M_STAGE;
     const ClockStamp t_start = clock_now();
@@ -540,20 +541,21 @@ __global__ __launch_bounds__(128 * MI) void spmm_nt_big_kernel(const uint16_t *_
         }
     } else if constexpr (ACT_MODE == 2) {
         unsigned char *est = region(wave);
-        stage_tile<T, 4>(acc, est, lane);
+        stage_tile<T, MI>(acc, est, lane);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
         asm volatile("" ::: "memory");
-        const int n_base = n0 + 64 * wn, m_base = m0 + 128 * wm;
-        const int c = lane & 15, m = min(m_base + 8 * c, M - 8);
-        uint4 z[16];   // the accumulators are dead: all loads of Z go out before anything is computed
+        constexpr int LPR = 4 * MI, RPP = 64 / LPR;   // lanes per tile row (16-byte pieces), rows per pass
+        const int n_base = n0 + 64 * wn, m_base = m0 + WM * wm;
+        const int c = lane % LPR, m = min(m_base + 8 * c, M - 8);
+        uint4 z[LPR];   // the accumulators are dead: all loads of Z go out before anything is computed
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
-            z[j] = *reinterpret_cast<const uint4 *>(GU + (int64_t)min(n_base + 4 * j + (lane >> 4), N - 1) * M + m);
+        for (int j = 0; j < LPR; ++j)
+            z[j] = *reinterpret_cast<const uint4 *>(GU + (int64_t)min(n_base + RPP * j + lane / LPR, N - 1) * M + m);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int nl = 4 * j + (lane >> 4), n = n_base + nl;
-            const uint4 dh = staged_chunk(est, nl, c);
+        for (int j = 0; j < LPR; ++j) {
+            const int nl = RPP * j + lane / LPR, n = n_base + nl;
+            const uint4 dh = staged_chunk<MI>(est, nl, c);
             const uint32_t dw[4] = {dh.x, dh.y, dh.z, dh.w}, zw[4] = {z[j].x, z[j].y, z[j].z, z[j].w};
             uint32_t o[4];
 #pragma unroll
@@ -565,17 +567,18 @@ __global__ __launch_bounds__(128 * MI) void spmm_nt_big_kernel(const uint16_t *_
         }
     } else if constexpr (ACT_MODE == 1) {
         unsigned char *est = region(wave);
-        stage_tile<T, 4>(acc, est, lane);
+        stage_tile<T, MI>(acc, est, lane);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wait_vm_lgkm0(0));
         asm volatile("" ::: "memory");
-        const int n_base = n0 + 64 * wn, m_base = m0 + 128 * wm;
+        constexpr int LPR = 4 * MI, RPP = 64 / LPR;
+        const int n_base = n0 + 64 * wn, m_base = m0 + WM * wm;
 #pragma unroll 4
-        for (int j = 0; j < 16; ++j) {
-            const int nl = 4 * j + (lane >> 4), c = lane & 15;
+        for (int j = 0; j < LPR; ++j) {
+            const int nl = RPP * j + lane / LPR, c = lane % LPR;
             const int n = n_base + nl, m = m_base + 8 * c;
             if (n >= N || m >= M) continue;
-            const uint4 zc = staged_chunk(est, nl, c);
+            const uint4 zc = staged_chunk<MI>(est, nl, c);
             const uint32_t zw[4] = {zc.x, zc.y, zc.z, zc.w};
             uint32_t h[4];
 #pragma unroll
@@ -1397,6 +1400,20 @@ inline int s24_cu_count()
 }
 inline bool fills_chip_256(int64_t m, int64_t n) { return (int64_t)ceil_div(m, 256) * ceil_div(n, 256) >= 3 * s24_cu_count() / 4; }
 
+// Large tile (256 x 256, one workgroup per compute unit) or small tile (128 x 128, two per compute unit)?  The small
+// tile moves twice the bytes per FLOP through L2, so it only pays where the large one leaves compute units idle (few
+// tiles, or a last round that is mostly empty) or where the contraction is so short that a tile is mostly prologue
+// and epilogue, which two co-resident workgroups overlap with each other's main loops.  Cost model in rounds of the
+// large tile: a small-tile round (twice as many workgroups, half the work) takes 0.75 of a large one, 0.6 when the
+// contraction is at most 1024 deep (measured: at K = 768 a large tile spends more time filling and draining than multiplying).
+inline bool small_tile_pays(int64_t M, int64_t N, int64_t K)
+{
+    const int cus = s24_cu_count();
+    const int64_t t256 = (int64_t)ceil_div(M, 256) * ceil_div(N, 256), t128 = (int64_t)ceil_div(M, 128) * ceil_div(N, 128);
+    const double round_small = K <= 1024 ? 0.6 : 0.75;
+    return round_small * (double)ceil_div(t128, 2 * cus) < (double)ceil_div(t256, cus);
+}
+
 // Out[N][M] = beta * Out + B[N][K] . A^T (+ bias[M], only with beta = 0)
 int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, int64_t N, int64_t K, int64_t M, float beta,
                 int dt, hipStream_t st, const void *bias = nullptr)
@@ -1414,17 +1431,9 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
     }
     auto *b = static_cast<const uint16_t *>(B), *av = static_cast<const uint16_t *>(Av), *d = static_cast<const uint16_t *>(bias);
     auto *o = static_cast<uint16_t *>(Out);
-    // Large tile (256 x 256, one workgroup per compute unit) or small tile (128 x 128, two per compute unit)?  The
-    // small tile moves twice the bytes per FLOP through L2, so it only pays where the large one leaves compute units
-    // idle: few tiles, or a last round that is mostly empty.  Cost model in rounds of the large tile: a small-tile
-    // round (twice as many workgroups, half the work) takes kSmallRound of a large one (measured).
     const int tm256 = (int)ceil_div(M, 256), tn256 = (int)ceil_div(N, 256), tm128 = (int)ceil_div(M, 128), tn128 = (int)ceil_div(N, 128);
-    const int64_t t256 = (int64_t)tm256 * tn256, t128 = (int64_t)tm128 * tn128;
-    S24_REQUIRE(t128 < (1ll << 30), S24_ERR_SHAPE);
-    constexpr double kSmallRound = 0.75;
-    const int cus = s24_cu_count();
-    const double cost_big = (double)ceil_div(t256, cus), cost_small = kSmallRound * (double)ceil_div(t128, 2 * cus);
-    if (cost_big <= cost_small) {
+    S24_REQUIRE((int64_t)tm128 * tn128 < (1ll << 30), S24_ERR_SHAPE);
+    if (!small_tile_pays(M, N, K)) {
         const int tiles_m = tm256, tiles_n = tn256;
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
         const dim3 grid(per_xcd * 8), block(big::THREADS);
@@ -1572,14 +1581,22 @@ extern "C" int s24_spmm_fwd_act(const void *X, const void *vals, const uint16_t 
     S24_REQUIRE(meta != nullptr && H != nullptr, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(meta, 4) && s24_aligned(H, 16) && s24_aligned(bias, 8), S24_ERR_ALIGN);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dt != S24_F32 && fills_chip_256(r, p)) {
-        const int tiles_m = (int)ceil_div(r, big::BM), tiles_n = (int)ceil_div(p, big::BN);
-        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
+    if (dt != S24_F32) {
+        const bool small = small_tile_pays(r, p, q);
+        const int tile = small ? 128 : 256;
+        const int tiles_m = (int)ceil_div(r, tile), tiles_n = (int)ceil_div(p, tile);
+        S24_REQUIRE((int64_t)tiles_m * tiles_n < (1ll << 30), S24_ERR_SHAPE);
+        const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(small ? 256 : big::THREADS);
         auto *x = static_cast<const uint16_t *>(X), *av = static_cast<const uint16_t *>(vals), *d = static_cast<const uint16_t *>(bias);
         auto *z = static_cast<uint16_t *>(Z), *h = static_cast<uint16_t *>(H);
-#define S24_LAUNCH_FWD_ACT(A, BIASED)                                                                                          \
-    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, BIASED, 1, A>), grid, block, 0, st, x, av, \
-                       meta, z, (int)p, (int)q, (int)r, tiles_m, tiles_n, g_clock_probe, h, 0, nullptr, d)
+#define S24_LAUNCH_FWD_ACT_MI(A, BIASED, MI_)                                                                                       \
+    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, BIASED, 1, A, MI_>), grid, block, 0, st, x, \
+                       av, meta, z, (int)p, (int)q, (int)r, tiles_m, tiles_n, small ? nullptr : g_clock_probe, h, 0, nullptr, d)
+#define S24_LAUNCH_FWD_ACT(A, BIASED)                 \
+    do {                                              \
+        if (small) S24_LAUNCH_FWD_ACT_MI(A, BIASED, 2); \
+        else S24_LAUNCH_FWD_ACT_MI(A, BIASED, 4);     \
+    } while (0)
         S24_WITH_16BIT_TYPE(dt, {
             if (act == S24_ACT_RELU && d != nullptr) S24_LAUNCH_FWD_ACT(S24_ACT_RELU, true);
             else if (act == S24_ACT_RELU) S24_LAUNCH_FWD_ACT(S24_ACT_RELU, false);
@@ -1587,9 +1604,10 @@ extern "C" int s24_spmm_fwd_act(const void *X, const void *vals, const uint16_t 
             else S24_LAUNCH_FWD_ACT(S24_ACT_GELU_ERF, false);
         });
 #undef S24_LAUNCH_FWD_ACT
+#undef S24_LAUNCH_FWD_ACT_MI
         return s24_launch_status();
     }
-    // shapes the fused epilogue does not cover: the GEMM, then the stand-alone activation
+    // fp32: the GEMM, then the stand-alone activation
     const int rc2 = launch_spmm(X, vals, meta, Z, p, q, r, 0.0f, dt, st, bias);
     if (rc2 != S24_OK) return rc2;
     return s24_act_fwd(Z, H, p * r, act, dt, st);
@@ -1604,21 +1622,30 @@ extern "C" int s24_spmm_bwd_dx_act(const void *dY, const void *valsT, const uint
     if (rc != S24_OK || p * f == 0) return rc;
     S24_REQUIRE(metaT != nullptr && Z != nullptr, S24_ERR_NULL);
     S24_REQUIRE(s24_aligned(metaT, 4) && s24_aligned(Z, 16), S24_ERR_ALIGN);
-    // only the large-tile 16-bit kernel carries this epilogue; other shapes take s24_spmm_bwd_dx + s24_act_bwd
-    S24_REQUIRE(dt != S24_F32 && fills_chip_256(f, p), S24_ERR_UNSUPPORTED);
-    const int tiles_m = (int)ceil_div(f, big::BM), tiles_n = (int)ceil_div(p, big::BN);
-    const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(big::THREADS);
+    // the 16-bit kernels carry this epilogue; fp32 takes s24_spmm_bwd_dx + s24_act_bwd
+    S24_REQUIRE(dt != S24_F32, S24_ERR_UNSUPPORTED);
+    const bool small = small_tile_pays(f, p, r);
+    const int tile = small ? 128 : 256;
+    const int tiles_m = (int)ceil_div(f, tile), tiles_n = (int)ceil_div(p, tile);
+    S24_REQUIRE((int64_t)tiles_m * tiles_n < (1ll << 30), S24_ERR_SHAPE);
+    const dim3 grid(((tiles_m * tiles_n + 7) / 8) * 8), block(small ? 256 : big::THREADS);
     hipStream_t st = static_cast<hipStream_t>(stream);
     auto *dy = static_cast<const uint16_t *>(dY), *av = static_cast<const uint16_t *>(valsT), *z = static_cast<const uint16_t *>(Z);
     auto *o = static_cast<uint16_t *>(dZ);
-#define S24_LAUNCH_BWD_ACT(A)                                                                                                 \
-    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, false, 2, A>), grid, block, 0, st, dy, av, \
-                       metaT, o, (int)p, (int)r, (int)f, tiles_m, tiles_n, g_clock_probe, nullptr, 0, z, nullptr)
+#define S24_LAUNCH_BWD_ACT_MI(A, MI_)                                                                                                 \
+    hipLaunchKernelGGL((big::spmm_nt_big_kernel<T, false, false, false, S24_GATE_SILU, false, 2, A, MI_>), grid, block, 0, st, dy, av, \
+                       metaT, o, (int)p, (int)r, (int)f, tiles_m, tiles_n, small ? nullptr : g_clock_probe, nullptr, 0, z, nullptr)
+#define S24_LAUNCH_BWD_ACT(A)                   \
+    do {                                        \
+        if (small) S24_LAUNCH_BWD_ACT_MI(A, 2); \
+        else S24_LAUNCH_BWD_ACT_MI(A, 4);       \
+    } while (0)
     S24_WITH_16BIT_TYPE(dt, {
         if (act == S24_ACT_RELU) S24_LAUNCH_BWD_ACT(S24_ACT_RELU);
         else S24_LAUNCH_BWD_ACT(S24_ACT_GELU_ERF);
     });
 #undef S24_LAUNCH_BWD_ACT
+#undef S24_LAUNCH_BWD_ACT_MI
     return s24_launch_status();
 }
 

@@ -255,7 +255,7 @@ def test_spmm_bwd_dx_glu_equals_the_separate_calls_and_the_oracle(s24, dtype, ga
 # ------------------------------------------------------------------ ungated activation in the GEMM epilogues
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("act", ["relu", "gelu"])
-@pytest.mark.parametrize("case", [(300, 128, 272), (2100, 192, 6224)])     # fallback route / fused epilogue, ragged
+@pytest.mark.parametrize("case", [(300, 128, 272), (2100, 192, 6224), (1100, 768, 528)])     # small tile / large tile / small tile with a short contraction, ragged
 @pytest.mark.parametrize("with_bias", [False, True])
 def test_spmm_fwd_act_equals_the_separate_calls_and_the_oracle(s24, dtype, act, case, with_bias):
     p, q, r = case
@@ -287,8 +287,9 @@ def test_spmm_fwd_act_equals_the_separate_calls_and_the_oracle(s24, dtype, act, 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("act", ["relu", "gelu"])
-def test_spmm_bwd_dx_act_equals_the_separate_calls_and_the_oracle(s24, dtype, act):
-    p, f, r = 1800, 6224, 192          # >= 192 tiles of 256 x 256, ragged
+@pytest.mark.parametrize("case", [(1800, 6224, 192), (300, 272, 128), (2100, 1040, 320)])   # large tile / small tile, ragged
+def test_spmm_bwd_dx_act_equals_the_separate_calls_and_the_oracle(s24, dtype, act, case):
+    p, f, r = case
     a_lib, a_orc = (s24.ACT_RELU, oracle.ACT_RELU) if act == "relu" else (s24.ACT_GELU_ERF, oracle.ACT_GELU_ERF)
     dY = si.random_matrix(1900, (p, r), 1e-2, dtype)
     W2 = si.random_matrix(1901, (r, f), 0.02, dtype)
@@ -309,13 +310,14 @@ def test_spmm_bwd_dx_act_equals_the_separate_calls_and_the_oracle(s24, dtype, ac
     dHr = oracle.round_like(oracle.spmm_bwd_dx(dY, valsT, metaT, rows=rows), dY)
     ref = oracle.act_bwd(dHr, np.ascontiguousarray(Zh[rows]), a_orc)
     assert_close(host_f64(dZ[torch.from_numpy(rows).cuda()]), ref, ACT_TOL[dtype], f"dZ {act}")
-    # small shapes decline and leave the output alone
-    small = torch.zeros((64, 64), dtype=torch_dtype(dtype), device="cuda")
-    v = torch.zeros((1, 64, 32), dtype=torch_dtype(dtype), device="cuda")
+    # fp32 declines (the caller takes the two calls) and leaves the output alone
+    small = torch.zeros((64, 64), dtype=torch.float32, device="cuda")
+    v = torch.zeros((1, 64, 32), dtype=torch.float32, device="cuda")
     m = torch.zeros((1, 64, 4), dtype=torch.int16, device="cuda")
+    out = torch.full((64, 64), 7.0, dtype=torch.float32, device="cuda")
     with pytest.raises(s24.S24Error) as e:
-        s24.spmm_bwd_dx_act(small, v, m, small, small, a_lib)
-    assert e.value.status == -6
+        s24.spmm_bwd_dx_act(small, v, m, small, out, a_lib)
+    assert e.value.status == -6 and bool((out == 7.0).all())
 
 
 # ------------------------------------------------------------------ binary16 on the large-tile matrix-core kernels

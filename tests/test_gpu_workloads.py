@@ -83,6 +83,11 @@ def run_chain(s24, wl, t, tol_act, tol_grad):
     for n in wl.weight_names:
         assert np.array_equal(host_bits(ffn.w[n].mask), ref["mask_" + n]), n
     names = ("G", "U", "H", "Y", "dH", "dG", "dU", "dX") if wl.gated else ("Z", "H", "Y", "dH", "dZ", "dX")
+    if not wl.gated and ffn.fuse_gate_bwd:
+        # the second projection's input-gradient GEMM applied act'(Z) in its epilogue: dH never reached memory.  The
+        # plain GEMM gives it here, so that the chain is still checked stage by stage.
+        s24.spmm_bwd_dx(dY, ffn.w["W2"].valsT, ffn.w["W2"].metaT, ffn.dH)
+        torch.cuda.synchronize()
     for k in names:
         want = ref[k]
         want = si.to_f32(want).astype(np.float64) if want.dtype != np.float64 else want

@@ -101,6 +101,27 @@ def test_gemm_argument_errors(lib):
     assert lib.s24_dense_dw_decay(P, P, P, P, 1, P, 1e-4, 4, 16, 0, 0.0, 1, None) == OK
     assert lib.s24_dense_gemm(P, P, P, 4, 32, 16, 1, None) == SHAPE
     assert lib.s24_dense_gemm(P, P, P, 0, 64, 16, 1, None) == OK
+    # feature extents at or beyond 2^23 (32-bit byte offsets inside a tile) and token counts at or beyond 2^31
+    big = 1 << 23
+    assert lib.s24_spmm_fwd(P, P, P, P, 4, big, 16, 1, None) == SHAPE
+    assert lib.s24_spmm_fwd(P, P, P, P, 4, 64, big, 1, None) == SHAPE
+    assert lib.s24_spmm_bwd_dx(P, P, P, P, 4, big, 64, 0.0, 1, None) == SHAPE
+    assert lib.s24_dense_dw(P, P, P, 4, big, 16, 0.0, 1, None) == SHAPE
+    assert lib.s24_dense_gemm(P, P, P, 1 << 31, 64, 16, 1, None) == SHAPE
+    # the compressed operands' alignment is what the kernels' 16- and 8-byte stores need
+    assert lib.s24_compress(P, 1, 64, 64, 64, None, P + 8, P, P, P, None, None) == ALIGN
+    assert lib.s24_compress(P, 1, 64, 64, 64, None, P, P + 2, P, P, None, None) == ALIGN
+    assert lib.s24_compress(P, 1, 64, 64, 64, None, P, P, P, P + 4, None, None) == ALIGN
+
+
+def test_probe_argument_errors(lib):
+    assert lib.s24_probe_matrix_rate(0, -1, 8, P, None) == SHAPE
+    assert lib.s24_probe_matrix_rate(1, 4, 8, None, None) == NULL
+    assert lib.s24_probe_matrix_rate(0, 0, 8, None, None) == OK
+    assert lib.s24_probe_copy(P, P, 24, None) == SHAPE
+    assert lib.s24_probe_copy(P, None, 32, None) == NULL
+    assert lib.s24_probe_copy(P + 4, P, 32, None) == ALIGN
+    assert lib.s24_probe_copy(None, None, 0, None) == OK
 
 
 def test_mvue_argument_errors(lib):
@@ -193,7 +214,7 @@ def test_gated_family_argument_errors(lib):
     # s24_spmm_bwd_dx_act(dY, valsT, metaT, Z, dZ, p, f, r, act, dt, stream)
     assert lib.s24_spmm_bwd_dx_act(P, P, P, P, P, 4, 16, 96, 1, 1, None) == SHAPE
     assert lib.s24_spmm_bwd_dx_act(P, P, P, None, P, 4, 16, 64, 1, 1, None) == NULL
-    assert lib.s24_spmm_bwd_dx_act(P, P, P, P, P, 4, 16, 64, 1, 1, None) == UNSUP
+    assert lib.s24_spmm_bwd_dx_act(P, P, P, P, P, 4, 16, 64, 1, 0, None) == UNSUP     # fp32: the two-call route
     # s24_dense_dw_batch(problems, count, beta, dt, stream): a host array of problem records
     import ctypes
     from paper_2404_01847_amd.binding import _DwProblem
