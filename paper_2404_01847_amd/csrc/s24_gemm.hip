@@ -1414,6 +1414,22 @@ inline bool small_tile_pays(int64_t M, int64_t N, int64_t K)
     return round_small * (double)ceil_div(t128, 2 * cus) < (double)ceil_div(t256, cus);
 }
 
+// A grid of large tiles whose last round is mostly empty (320 tiles on 256 compute units: two rounds for 1.25 rounds
+// of work) can give its last token-tile rows to the small tile instead: the first `slab` tokens run in whole rounds of
+// large tiles, the rest as one resident set of small tiles.  Returns the slab's token count, or 0 where the cost
+// model above does not favour the cut.  Tokens are independent rows of the product, so the result does not change.
+inline int64_t large_tile_slab_tokens(int64_t M, int64_t N, int64_t K)
+{
+    const int cus = s24_cu_count();
+    const int64_t tm = ceil_div(M, 256), tiles = tm * ceil_div(N, 256), rounds = (tiles + cus - 1) / cus;
+    if (tiles <= cus || tiles % cus == 0 || tm > cus) return 0;
+    const int64_t rows = ((rounds - 1) * cus) / tm, slab = 256 * rows;   // whole token-tile rows within rounds - 1 rounds
+    const int64_t strip_tiles = (int64_t)ceil_div(M, 128) * ceil_div(N - slab, 128);
+    const double round_small = K <= 1024 ? 0.6 : 0.75;
+    const double cost = (double)ceil_div(rows * tm, cus) + round_small * (double)ceil_div(strip_tiles, 2 * cus);
+    return cost < (double)rounds ? slab : 0;
+}
+
 // Out[N][M] = beta * Out + B[N][K] . A^T (+ bias[M], only with beta = 0)
 int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, int64_t N, int64_t K, int64_t M, float beta,
                 int dt, hipStream_t st, const void *bias = nullptr)
@@ -1434,6 +1450,11 @@ int launch_spmm(const void *B, const void *Av, const uint16_t *Am, void *Out, in
     const int tm256 = (int)ceil_div(M, 256), tn256 = (int)ceil_div(N, 256), tm128 = (int)ceil_div(M, 128), tn128 = (int)ceil_div(N, 128);
     S24_REQUIRE((int64_t)tm128 * tn128 < (1ll << 30), S24_ERR_SHAPE);
     if (!small_tile_pays(M, N, K)) {
+        if (const int64_t slab = large_tile_slab_tokens(M, N, K)) {
+            const int rc = launch_spmm(B, Av, Am, Out, slab, K, M, beta, dt, st, bias);
+            if (rc != S24_OK) return rc;
+            return launch_spmm(b + slab * K, Av, Am, o + slab * M, N - slab, K, M, beta, dt, st, bias);
+        }
         const int tiles_m = tm256, tiles_n = tn256;
         const int per_xcd = (tiles_m * tiles_n + 7) / 8;
         const dim3 grid(per_xcd * 8), block(big::THREADS);

@@ -201,6 +201,36 @@ def test_spmm_large_tile_path(s24, k):
     assert_close(host_f64(dX[ridx]), ref, BF16_TOL, f"large spmm_bwd_dx k={k}")
 
 
+def test_spmm_large_tiles_with_a_small_tile_strip(s24):
+    """296 large tiles are a whole round over 256 compute units plus a mostly empty one: the first 8192 tokens run in
+    large tiles and the last 1064 as small tiles in a second launch.  Rows on both sides of the cut, a ragged
+    tail, a bias, and beta = 1."""
+    p, r, k = 9256, 2000, 192
+    W = si.random_matrix(340, (r, k), 0.02, "bf16")
+    X = si.random_matrix(341, (p, k), 1.0, "bf16")
+    bias = si.random_matrix(342, (r,), 0.3, "bf16")
+    mask, vals, meta, valsT, metaT = compressed(W)
+    rows = np.unique(np.concatenate([[0, 8063, 8064, 8191, 8192, 8193, 8319, 8320, p - 129, p - 1],
+                                     np.random.default_rng(9).integers(0, p, 40)])).astype(np.int64)
+    ridx = torch.from_numpy(rows).cuda()
+    Y = torch.full((p, r), 3.0, dtype=torch.bfloat16, device="cuda")
+    s24.spmm_fwd(dev_bf16(X), *packed(vals, meta), Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y[ridx]), oracle.spmm_fwd(X, vals, meta, rows=rows), BF16_TOL, "strip spmm_fwd")
+    Y.fill_(3.0)
+    s24.spmm_fwd_bias(dev_bf16(X), *packed(vals, meta), dev_bf16(bias), Y)
+    torch.cuda.synchronize()
+    assert_close(host_f64(Y[ridx]), oracle.spmm_fwd_bias(X, vals, meta, bias, rows=rows), BF16_TOL, "strip spmm_fwd_bias")
+    dX0 = si.random_matrix(343, (p, r), 1e-2, "bf16")
+    dX = dev_bf16(dX0).clone()
+    s24.spmm_bwd_dx(dev_bf16(X), *packed(vals, meta), dX, beta=1.0)
+    torch.cuda.synchronize()
+    ref = oracle.spmm_bwd_dx(X, vals, meta, beta=1.0, dX0=si.to_f32(dX0[rows]).astype(np.float64), rows=rows)
+    assert_close(host_f64(dX[ridx]), ref, BF16_TOL, "strip spmm_bwd_dx")
+    # every token outside the sample: finite, and not the fill value in all of a row
+    assert torch.isfinite(dX.float()).all() and (Y.float() != 3.0).any(dim=1).all()
+
+
 def test_spmm_one_hot_reproduces_masked_weight_exactly(s24):
     q, r = 128, 144
     W = si.random_matrix(320, (r, q), 0.02, "bf16")
