@@ -6,7 +6,7 @@ resident in HBM: per weight the transposable mask search fused with
 prune/compress, the sparse forward GEMMs, the activation, the sparse
 input-gradient GEMMs, the dense weight-gradient GEMMs and the masked decay.
 
-    python bench.py [--workload c4] [--steps K] [--warmup W]
+    python bench.py [--workload c5] [--also c1,c2,c3,c4] [--steps K] [--warmup W]
 
 Prints ONE JSON line.  `value` is the dense-equivalent GEMM TFLOP/s of the whole
 step (all 6 or 9 GEMMs' 2*p*d*d_ff FLOPs divided by the wall time of the step,
@@ -645,7 +645,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"],
                     help="the workload of the headline line (default c5, the largest single-GPU configuration)")
-    ap.add_argument("--also", default="c2,c3,c4",
+    ap.add_argument("--also", default="c1,c2,c3,c4",
                     help="comma-separated workloads whose step is timed as well (20 steps each) and reported under "
                          "extras.other_workloads; empty for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -758,6 +758,9 @@ def main():
                                         for k, v in k2.items()}}
             del d2, f2
             torch.cuda.empty_cache()
+            if w2.dtype == "f32":
+                others[name]["note"] = ("fp32 correctness workload: gfx950 has no fp32 sparse matrix instruction, the GEMMs run "
+                                        "on the vector unit; fractions of the bf16 peaks are shown for form only")
             if name == "c3":
                 others[name]["mask_search_only_72_matrices"] = c3_mask_sweep(torch, s24, w2)
         extras["other_workloads"] = others
