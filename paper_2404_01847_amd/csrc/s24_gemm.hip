@@ -1020,16 +1020,37 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
     if (kc < nk) chunk(s0, s1, s3, kc);
     if (kc + 1 < nk) chunk(s1, s2, s0, kc + 1);
     if (kc + 2 < nk) chunk(s2, s3, s1, kc + 2);
-    big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
-    big::clock_report(probe, t_start);
     // Epilogue through LDS, so that global memory sees 16-byte accesses along rows: each wave parks 64 columns
     // of its tile at a time (32*WT rows of fp32, 256-byte rows) in its own ring stage, then lane l of pass j
     // owns row (64j + l) / 16, columns 4 * (l % 16) .. +3: one LDS read, one 16-byte store, and for the
     // optional terms one 16-byte load of the old gradient, one 8-byte load of W and one mask word.
+    // The W and mask loads of a whole 64-column slice are issued in one go, well before they are needed: those of
+    // the first slice ahead of the wait that drains the ring, those of the second before it is parked in LDS.
+    // Loaded pass by pass where they are used, their latency was exposed eight times per tile with only four
+    // waves on the compute unit to hide it (c5: 0.45 ms per step).
+    constexpr int NP = 8 * WT;   // passes per slice
+    uint2 wv[DECAY ? NP : 1];
+    uint32_t keep[DECAY ? NP : 1];
+    auto decay_loads = [&](int h2) {
+        if constexpr (DECAY) {
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {
+                const int idx = j * 64 + lane, row = idx >> 4, c4 = idx & 15;
+                const int m = m0 + 32 * WT * wm + row, n = n0 + 32 * WT * wn + 64 * h2 + 4 * c4;
+                const int mc = min(m, M - 1), nc = min(n, N - 4);
+                wv[j] = *reinterpret_cast<const uint2 *>(Wt + (int64_t)mc * ldw + nc);
+                keep[j] = mask[(int64_t)(mc >> 2) * (ldw >> 2) + (nc >> 2)] >> (4 * (mc & 3));
+            }
+        }
+    };
+    decay_loads(0);
+    big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
+    big::clock_report(probe, t_start);
     static_assert(32 * WT * 256 <= STAGE, "a wave's 64-column slice fits one stage");
     unsigned char *est = wave == 0 ? s0 : (wave == 1 ? s1 : (wave == 2 ? s2 : s3));
 #pragma unroll
     for (int h2 = 0; h2 < WT / 2; ++h2) {
+        if (h2 > 0) decay_loads(h2);
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
@@ -1040,14 +1061,12 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
                     *reinterpret_cast<float *>(est + row * 256 + col * 4) = acc[mi][2 * h2 + nj][e];
                 }
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // the wave reads back only what it wrote itself
+        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(63));   // LDS only: the wave reads back only what it wrote itself
         asm volatile("" ::: "memory");
         constexpr int BATCH = 8;
-#pragma unroll 1
-        for (int j0 = 0; j0 < 8 * WT; j0 += BATCH) {
+#pragma unroll
+        for (int j0 = 0; j0 < NP; j0 += BATCH) {
             float4 v[BATCH], old[BATCH];
-            uint2 wv[BATCH];
-            uint32_t keep[BATCH];
             bool live[BATCH];
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
@@ -1057,10 +1076,6 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
                 const int mc = min(m, M - 1), nc = min(n, N - 4);
                 v[b] = *reinterpret_cast<const float4 *>(est + row * 256 + c4 * 16);
                 if (ACCUM) old[b] = *reinterpret_cast<const float4 *>(dW + (int64_t)mc * ldw + nc);
-                if (DECAY) {
-                    wv[b] = *reinterpret_cast<const uint2 *>(Wt + (int64_t)mc * ldw + nc);
-                    keep[b] = mask[(int64_t)(mc >> 2) * (ldw >> 2) + (nc >> 2)] >> (4 * (mc & 3));
-                }
             }
 #pragma unroll
             for (int b = 0; b < BATCH; ++b) {
@@ -1068,17 +1083,19 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
                 const int m = m0 + 32 * WT * wm + row, n = n0 + 32 * WT * wn + 64 * h2 + 4 * c4;
                 float4 o = v[b];
                 if (ACCUM) { o.x = old[b].x + o.x; o.y = old[b].y + o.y; o.z = old[b].z + o.z; o.w = old[b].w + o.w; }
-                if (DECAY) {
-                    if (!(keep[b] & 1u)) o.x = fmaf(lambda, s24_num<ET>::lo(wv[b].x), o.x);
-                    if (!(keep[b] & 2u)) o.y = fmaf(lambda, s24_num<ET>::hi(wv[b].x), o.y);
-                    if (!(keep[b] & 4u)) o.z = fmaf(lambda, s24_num<ET>::lo(wv[b].y), o.z);
-                    if (!(keep[b] & 8u)) o.w = fmaf(lambda, s24_num<ET>::hi(wv[b].y), o.w);
+                if constexpr (DECAY) {
+                    const uint2 w2 = wv[j0 + b];
+                    const uint32_t kp = keep[j0 + b];
+                    if (!(kp & 1u)) o.x = fmaf(lambda, s24_num<ET>::lo(w2.x), o.x);
+                    if (!(kp & 2u)) o.y = fmaf(lambda, s24_num<ET>::hi(w2.x), o.y);
+                    if (!(kp & 4u)) o.z = fmaf(lambda, s24_num<ET>::lo(w2.y), o.z);
+                    if (!(kp & 8u)) o.w = fmaf(lambda, s24_num<ET>::hi(w2.y), o.w);
                 }
                 if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * ldw + n) = o;
             }
         }
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(0));   // LDS reads done before the other half overwrites
+        __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(63));   // LDS reads done before the other half overwrites
         asm volatile("" ::: "memory");
     }
 }
