@@ -1141,32 +1141,36 @@ __global__ __launch_bounds__(THREADS) void spmm_tn_big_kernel(const uint16_t *__
     const int m0 = tm * BM, n0 = tn * BN;
     const int nk = T / 64;
 
-    // copies per lane and chunk: four of the X tile (rows 8*wave .. 8*wave+7), two of the values, one index dword
-    int voffB[4];
+    // Copies per lane and chunk: four of the X tile (rows 8*wave .. 8*wave+7), two of the values, one index dword;
+    // buffer loads into LDS with a wave-uniform base per operand and chunk and a fixed 32-bit byte offset per lane
+    // (64 token rows of X and one chunk of the compressed operand span less than 4 GB: host check).
+    const char *baseX = reinterpret_cast<const char *>(X), *baseV = reinterpret_cast<const char *>(Av);
+    const char *baseM = reinterpret_cast<const char *>(Am);
+    uint32_t ob[4], oa[2];
     const int lastB = (min(N - n0, BN) >> 3) - 1;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int slot = (wave * 4 + j) * 64 + lane, row = slot / CPR, c = (slot % CPR) ^ ((row & 3) << 2);
-        voffB[j] = row * N + n0 + 8 * min(c, lastB);
+        ob[j] = ((uint32_t)row * (uint32_t)N + (uint32_t)(n0 + 8 * min(c, lastB))) * 2u;
     }
-    const uint16_t *ga_[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int row = 32 * wave + 16 * i + (lane >> 2);
         const int c = (lane & 3) ^ ((row >> 2) & 3);
-        ga_[i] = Av + (int64_t)min(m0 + row, M - 1) * 32 + 8 * c;
+        oa[i] = ((uint32_t)min(m0 + row, M - 1) * 32u + 8u * c) * 2u;
     }
-    const uint16_t *gmeta = Am + (int64_t)min(m0 + 32 * wave + (lane >> 1), M - 1) * 4 + 2 * (lane & 1);
+    const uint32_t om = ((uint32_t)min(m0 + 32 * wave + (lane >> 1), M - 1) * 4u + 2u * (lane & 1)) * 2u;
+    // exactly seven copies per lane and call; past the last chunk it re-reads the last one into a stage nobody
+    // will read again, so that the wait counts below are constants
     auto issue = [&](unsigned char *st, int kc) {
         kc = min(kc, nk - 1);
-        const char *xb = reinterpret_cast<const char *>(X + (int64_t)kc * 64 * N);
+        const big::rsrc_t px = big::buffer_of(baseX + (int64_t)kc * 128 * N), pv = big::buffer_of(baseV + (int64_t)kc * M * 64);
+        const big::rsrc_t pm = big::buffer_of(baseM + (int64_t)kc * M * 8);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(xb + (uint32_t)voffB[j] * 2u), (lds_ptr)(st + (wave * 4 + j) * 1024), 16, 0, 0);
+        for (int j = 0; j < 4; ++j) big::buffer_to_lds<16>(px, (lds_ptr)(st + (wave * 4 + j) * 1024), ob[j]);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(ga_[i] + (int64_t)kc * M * 32), (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_ptr)(gmeta + (int64_t)kc * M * 4), (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), 4, 0, 0);
+        for (int i = 0; i < 2; ++i) big::buffer_to_lds<16>(pv, (lds_ptr)(st + B_STAGE + (32 * wave + 16 * i) * 64), oa[i]);
+        big::buffer_to_lds<4>(pm, (lds_ptr)(st + B_STAGE + A_STAGE + 32 * wave * 8), om);
     };
 
     f32x16 acc[4][2];
@@ -1176,70 +1180,92 @@ __global__ __launch_bounds__(THREADS) void spmm_tn_big_kernel(const uint16_t *__
         for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
 
     // X fragment addressing: lane group G = lane/16 -> 8-token half G/2, column half G%2
-    const int gi = lane & 15, G = lane >> 4;
+    const int gi = lane & 15, G = lane >> 4, g = lane >> 5;
     const int frow = 8 * (G >> 1) + (gi >> 2), fcol = 16 * (G & 1) + 4 * (gi & 3);
     int offB[2];
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) offB[ni] = dmatn::tr_off<ROWB>(frow, 64 * wn + 32 * ni + fcol);
+    // Fragments of half h of a stage (the tokens {16h..16h+15} and {32+16h..} of the chunk): eight transposing
+    // reads of the X tile and four 128-bit reads of the values
+    auto load_frags = [&](const unsigned char *st, int h, bf16x16 (&b)[2], bf16x8 (&a)[4]) {
+        const unsigned char *sb = st, *sa = st + B_STAGE;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            struct { bf16x8 lo, hi; } pair{dmatn::tr_frag<ROWB>(sb + offB[ni] + 16 * h * ROWB),
+                                           dmatn::tr_frag<ROWB>(sb + offB[ni] + (32 + 16 * h) * ROWB)};
+            b[ni] = __builtin_bit_cast(bf16x16, pair);
+        }
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+            a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(128 * wm + 32 * mi + (lane & 31), 2 * g + h)));
+    };
+    auto load_index = [&](const unsigned char *st, uint32_t (&x)[4]) {
+        const unsigned char *sm = st + B_STAGE + A_STAGE;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+            x[mi] = *reinterpret_cast<const uint32_t *>(sm + (128 * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
+    };
 
+    // keep the program order of these groups: the constant wait counts rely on it
     issue(s0, 0);
     __builtin_amdgcn_sched_barrier(0);
     issue(s1, 1);
     __builtin_amdgcn_sched_barrier(0);
+    issue(s2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    big::wait_and_barrier<14>();   // chunk 0 has landed for everybody
+    bf16x16 fb0[2];
+    bf16x8 fa0[4];
+    uint32_t ix[4];
+    load_index(s0, ix);
+    load_frags(s0, 0, fb0, fa0);
 
-    auto chunk = [&](const unsigned char *cur, unsigned char *refill, int kc) {
-        big::wait_and_barrier<7>();   // chunk kc landed for every wave; nobody reads `refill` any more
-        issue(refill, kc + 2);
-        const unsigned char *sb = cur, *sa = cur + B_STAGE, *sm = cur + B_STAGE + A_STAGE;
-        const int g = lane >> 5;
-        uint32_t ix[4];
+    // One chunk, pipelined across the workgroup barrier exactly as in the NT kernel: the first half's matrix
+    // instructions run from registers while the second half's fragments come in; after the one barrier of the chunk
+    // the second half's matrix instructions cover the next chunk's index words and first-half fragments and the
+    // seven copies of chunk kc+3 into the stage just vacated.
+    auto chunk = [&](unsigned char *cur, const unsigned char *nxt, int kc) {
+        bf16x16 fb1[2];
+        bf16x8 fa1[4];
+        load_frags(cur, 1, fb1, fa1);
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
-            ix[mi] = *reinterpret_cast<const uint32_t *>(sm + (128 * wm + 32 * mi + (lane & 31)) * 8 + 4 * g);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            bf16x16 b[2];
-            bf16x8 a[4];
+            for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<ET>::template sparse<0>(fa0[mi], fb0[ni], acc[mi][ni], (int)ix[mi]);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                struct { bf16x8 lo, hi; } pair{dmatn::tr_frag<ROWB>(sb + offB[ni] + 16 * h * ROWB),
-                                               dmatn::tr_frag<ROWB>(sb + offB[ni] + (32 + 16 * h) * ROWB)};
-                b[ni] = __builtin_bit_cast(bf16x16, pair);
-            }
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-                a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(128 * wm + 32 * mi + (lane & 31), 2 * g + h)));
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
-                    if (h == 0)
-                        acc[mi][ni] = Mma<ET>::template sparse<0>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
-                    else
-                        acc[mi][ni] = Mma<ET>::template sparse<1>(a[mi], b[ni], acc[mi][ni], (int)ix[mi]);
-                }
-        }
-        // issue order: the sixteen LDS reads of the first half, then its eight matrix instructions with the
-        // second half's twelve reads and the seven copies of chunk kc+2 dealt out between them
-        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 8; ++i) {   // twelve reads, two per matrix instruction
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < 4) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        big::wait_and_barrier<7>();   // this lane's part of chunk kc+1 is in LDS, its own reads of chunk kc are done
+        issue(cur, kc + 3);
+        uint32_t ixn[4];
+        load_index(nxt, ixn);
+        load_frags(nxt, 0, fb0, fa0);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<ET>::template sparse<1>(fa1[mi], fb1[ni], acc[mi][ni], (int)ix[mi]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {   // sixteen reads and seven copies
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             if (i < 7) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) ix[mi] = ixn[mi];
     };
+    // past the last chunk the prefetched fragments come from a stage that holds a re-read of the last chunk (or is
+    // being refilled with one); they are never multiplied
     int kc = 0;
     for (; kc + 3 <= nk; kc += 3) {
-        chunk(s0, s2, kc);
-        chunk(s1, s0, kc + 1);
-        chunk(s2, s1, kc + 2);
+        chunk(s0, s1, kc);
+        chunk(s1, s2, kc + 1);
+        chunk(s2, s0, kc + 2);
     }
-    if (kc < nk) chunk(s0, s2, kc);
-    if (kc + 1 < nk) chunk(s1, s0, kc + 1);
+    if (kc < nk) chunk(s0, s1, kc);
+    if (kc + 1 < nk) chunk(s1, s2, kc + 1);
     big::wait_and_barrier<0>();   // copies drained, nobody reads the ring any more: reuse it
     big::clock_report(probe, t_start);
     // fp32 output through LDS in 16-byte row segments: a wave parks 64 rows x 64 columns (two of its four row
