@@ -697,8 +697,13 @@ __global__ __launch_bounds__(kThreads) void dense_nt_kernel(const uint16_t *__re
 // straight into LDS.  A dense operand tile is twice the compressed one, so the
 // ring has two 64 KB stages: the copies of chunk kc+1 fly during the math of kc.
 namespace bignt {
-constexpr int BM = 256, BN = 256, THREADS = 512, OPERAND = 256 * 128;
-using big::b_slot;
+// Dense NT GEMM, 256 x 256 tiles, eight waves of 128 x 64: the comparison kernel beside the sparse one, on the
+// same schedule.  32 of k per ring stage (two 16 KB operand tiles, 64-byte rows), four stages, three chunks in
+// flight; a chunk is two 16-wide steps of eight matrix instructions, the first running from registers while the
+// second's fragments come in, the one barrier of the chunk between them, and after it the next chunk's first-step
+// fragments and the four copies of chunk kc+4 dealt out between the second step's matrix instructions.
+constexpr int BM = 256, BN = 256, THREADS = 512, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
+using big::a_slot;
 using big::glb_ptr;
 using big::lds_ptr;
 using big::wait_vm_lgkm0;
@@ -709,8 +714,10 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
                                                                int N, int K, int M, int tiles_m, int tiles_n, unsigned long long *probe)
 {
     const big::ClockStamp t_start = big::clock_now();
-    __shared__ __attribute__((aligned(16))) unsigned char s0[2 * OPERAND];
-    __shared__ __attribute__((aligned(16))) unsigned char s1[2 * OPERAND];
+    __shared__ __attribute__((aligned(16))) unsigned char s0[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s1[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s2[STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s3[STAGE];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
@@ -722,71 +729,103 @@ __global__ __launch_bounds__(THREADS) void dense_nt_big_kernel(const uint16_t *_
     const int gw = min(GROUP, tiles_n - grp * GROUP);
     const int tm = in_grp / gw, tn = grp * GROUP + in_grp % gw;
     const int m0 = tm * BM, n0 = tn * BN;
-    const int nk = K / 64;
+    const int nk = K / 32;
 
-    const uint16_t *gx[4], *gw_[4];
+    // copies: two per operand, lane and chunk; copy i of a wave fills rows 128 i + 16 wave .. +15 (four 16-byte
+    // slots each); slot c of row r holds source chunk c ^ ((r >> 2) & 3).  Wave-uniform bases (one per operand,
+    // advanced by 64 bytes per chunk) and fixed 32-bit lane offsets: 256 rows of K elements span < 4 GB (host check).
+    const char *baseX = reinterpret_cast<const char *>(X + (int64_t)n0 * K), *baseW = reinterpret_cast<const char *>(W + (int64_t)m0 * K);
+    uint32_t ox[2], ow[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = 32 * wave + 8 * i + (lane >> 3);
-        const int c = (lane & 7) ^ ((row ^ (row >> 3)) & 7);
-        gx[i] = X + (int64_t)min(n0 + row, N - 1) * K + 8 * c;
-        gw_[i] = W + (int64_t)min(m0 + row, M - 1) * K + 8 * c;
+    for (int i = 0; i < 2; ++i) {
+        const int row = 128 * i + 16 * wave + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        ox[i] = ((uint32_t)(min(n0 + row, N - 1) - n0) * (uint32_t)K + 8u * c) * 2u;
+        ow[i] = ((uint32_t)(min(m0 + row, M - 1) - m0) * (uint32_t)K + 8u * c) * 2u;
     }
-    auto issue = [&](unsigned char *st, int kc) {   // eight copies per lane: X rows then W rows
+    // exactly four copies per lane and call; past the last chunk it re-reads the last one into a stage nobody reads
+    auto issue = [&](unsigned char *st, int kc) {
         kc = min(kc, nk - 1);
+        const big::rsrc_t px = big::buffer_of(baseX + (int64_t)kc * 64), pw = big::buffer_of(baseW + (int64_t)kc * 64);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(gx[i] + (int64_t)kc * 64), (lds_ptr)(st + (32 * wave + 8 * i) * 128), 16, 0, 0);
+        for (int i = 0; i < 2; ++i) big::buffer_to_lds<16>(px, (lds_ptr)(st + (128 * i + 16 * wave) * 64), ox[i]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr)(gw_[i] + (int64_t)kc * 64), (lds_ptr)(st + OPERAND + (32 * wave + 8 * i) * 128), 16, 0, 0);
+        for (int i = 0; i < 2; ++i) big::buffer_to_lds<16>(pw, (lds_ptr)(st + OPERAND + (128 * i + 16 * wave) * 64), ow[i]);
     };
     f32x16 acc[4][2];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = f32x16{};
+    // fragments of 16-wide step i of a stage: lane group g = lane / 32 takes source chunk 2 g + i of both operands
+    const int g = lane >> 5;
+    auto load_frags = [&](const unsigned char *st, int i, bf16x8 (&b)[2], bf16x8 (&a)[4]) {
+        const unsigned char *sb = st, *sa = st + OPERAND;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+            b[ni] = as_bf16x8(*reinterpret_cast<const uint4 *>(sb + a_slot(64 * wn + 32 * ni + (lane & 31), 2 * g + i)));
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+            a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + a_slot(128 * wm + 32 * mi + (lane & 31), 2 * g + i)));
+    };
+    // keep the program order of these groups: the constant wait counts rely on it
     issue(s0, 0);
-    auto chunk = [&](const unsigned char *cur, unsigned char *other, int kc) {
-        big::wait_and_barrier<0>();   // everyone's copies of chunk kc are in LDS, and `other` is no longer read
-        issue(other, kc + 1);
-        const unsigned char *sb = cur, *sa = cur + OPERAND;
-        const int g = lane >> 5;
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s2, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s3, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    big::wait_and_barrier<12>();   // chunk 0 has landed for everybody
+    bf16x8 fb0[2], fa0[4];
+    load_frags(s0, 0, fb0, fa0);
+    auto chunk = [&](unsigned char *cur, const unsigned char *nxt, int kc) {
+        bf16x8 fb1[2], fa1[4];
+        load_frags(cur, 1, fb1, fa1);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            bf16x8 a[4], b[2];
+        for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-                a[mi] = as_bf16x8(*reinterpret_cast<const uint4 *>(sa + b_slot(128 * wm + 32 * mi + (lane & 31), 4 * g + i)));
+            for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<T>::dense(fa0[mi], fb0[ni], acc[mi][ni]);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                b[ni] = as_bf16x8(*reinterpret_cast<const uint4 *>(sb + b_slot(64 * wn + 32 * ni + (lane & 31), 4 * g + i)));
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = Mma<T>::dense(a[mi], b[ni], acc[mi][ni]);
-        }
-        // Issue order: the six LDS reads of the first 16-wide step, then one matrix instruction at a time with
-        // the other steps' eighteen reads after the first eighteen and one copy of chunk kc+1 after every fourth.
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-#pragma unroll
-        for (int j = 0; j < 32; ++j) {
+        for (int i = 0; i < 8; ++i) {   // six reads, two per matrix instruction
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (j < 18) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if ((j & 3) == 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            if (i < 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        // all but the eight most recent copies (chunks kc+2, kc+3) are complete: this lane's part of chunk kc+1 is
+        // in LDS, and its own reads of chunk kc are done
+        big::wait_and_barrier<8>();
+        issue(cur, kc + 4);
+        load_frags(nxt, 0, fb0, fa0);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) acc[mi][ni] = Mma<T>::dense(fa1[mi], fb1[ni], acc[mi][ni]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {   // six reads and four copies
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            if (i & 1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
+    // past the last chunk the prefetched fragments come from a stage that holds a re-read of the last chunk (or is
+    // being refilled with one); they are never multiplied
     int kc = 0;
-    for (; kc + 2 <= nk; kc += 2) {
+    for (; kc + 4 <= nk; kc += 4) {
         chunk(s0, s1, kc);
-        chunk(s1, s0, kc + 1);
+        chunk(s1, s2, kc + 1);
+        chunk(s2, s3, kc + 2);
+        chunk(s3, s0, kc + 3);
     }
     if (kc < nk) chunk(s0, s1, kc);
+    if (kc + 1 < nk) chunk(s1, s2, kc + 1);
+    if (kc + 2 < nk) chunk(s2, s3, kc + 2);
     big::wait_and_barrier<0>();   // last (redundant) copies drained, nobody reads the ring any more: reuse it
     big::clock_report(probe, t_start);
-    big::staged_store<T, 4>(acc, (wave < 4 ? s0 : s1) + (wave & 3) * big::EWAVE, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
+    static_assert(2 * big::EWAVE <= STAGE, "two waves' output tiles per ring stage");
+    unsigned char *est = (wave < 2 ? s0 : (wave < 4 ? s1 : (wave < 6 ? s2 : s3))) + (wave & 1) * big::EWAVE;
+    big::staged_store<T, 4>(acc, est, Y, N, M, n0 + 64 * wn, m0 + 128 * wm, lane);
 }
 }  // namespace bignt
 
