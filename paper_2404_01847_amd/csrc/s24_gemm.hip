@@ -135,10 +135,24 @@ template <int BYTES> __device__ __forceinline__ void buffer_to_lds(rsrc_t buf, l
     if constexpr (BYTES == 16) __builtin_amdgcn_raw_ptr_buffer_load_lds(buf, lds, 16, voff, 0, 0, 0);
     else __builtin_amdgcn_raw_ptr_buffer_load_lds(buf, lds, 4, voff, 0, 0, 0);
 }
+// 8 bytes / 2 bytes into registers from byte offset voff (per lane) + soff (wave-uniform, a scalar register): a load
+// whose address costs one vector register however many of them a wave issues in a row
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 buffer_load_8(rsrc_t buf, uint32_t voff, uint32_t soff)
+{
+    const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(buf, (int)voff, (int)soff, 0);
+    return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ uint32_t buffer_load_2(rsrc_t buf, uint32_t voff, uint32_t soff)
+{
+    return __builtin_amdgcn_raw_buffer_load_b16(buf, (int)voff, (int)soff, 0);
+}
 #else
 typedef const void *rsrc_t;
 __device__ __forceinline__ rsrc_t buffer_of(const void *base) { return base; }
 template <int BYTES> __device__ __forceinline__ void buffer_to_lds(rsrc_t, lds_ptr, uint32_t) {}
+__device__ __forceinline__ uint2 buffer_load_8(rsrc_t, uint32_t, uint32_t) { return make_uint2(0, 0); }
+__device__ __forceinline__ uint32_t buffer_load_2(rsrc_t, uint32_t, uint32_t) { return 0; }
 #endif
 
 // s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt unconstrained
@@ -1067,18 +1081,27 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
     // the first slice ahead of the wait that drains the ring, those of the second before it is parked in LDS.
     // Loaded pass by pass where they are used, their latency was exposed eight times per tile with only four
     // waves on the compute unit to hide it (c5: 0.45 ms per step).
+    // They are buffer loads: pass j reads four rows further down than pass j - 1, which is a wave-uniform step (a
+    // scalar register), so the 64 loads of a slice share two address registers.  M is a multiple of 16 and a wave's
+    // rows start at a multiple of 64: the four rows of a pass are all inside the matrix or all outside, and passes
+    // past the edge re-read the last pass inside (a wave with no row inside re-reads the tile's first rows).
     constexpr int NP = 8 * WT;   // passes per slice
     uint2 wv[DECAY ? NP : 1];
     uint32_t keep[DECAY ? NP : 1];
+    const int wave_rows = min(M - m0 - 32 * WT * wm, 32 * WT);   // rows of this wave's sub-tile inside the matrix
+    const int wave_row0 = wave_rows > 0 ? 32 * WT * wm : 0, last_pass = wave_rows > 0 ? (wave_rows >> 2) - 1 : 0;
     auto decay_loads = [&](int h2) {
         if constexpr (DECAY) {
+            const int nc = min(n0 + 32 * WT * wn + 64 * h2 + 4 * (lane & 15), N - 4);
+            const big::rsrc_t wbuf = big::buffer_of(Wt + (int64_t)(m0 + wave_row0) * ldw);
+            const big::rsrc_t mbuf = big::buffer_of(mask + (int64_t)((m0 + wave_row0) >> 2) * (ldw >> 2));
+            const uint32_t voff_w = ((uint32_t)(lane >> 4) * (uint32_t)ldw + (uint32_t)nc) * 2u, voff_m = (uint32_t)(nc >> 2) * 2u;
+            const uint32_t shift = 4 * (lane >> 4);   // row of the 4 x 4 block: the tile starts at a multiple of four
 #pragma unroll
             for (int j = 0; j < NP; ++j) {
-                const int idx = j * 64 + lane, row = idx >> 4, c4 = idx & 15;
-                const int m = m0 + 32 * WT * wm + row, n = n0 + 32 * WT * wn + 64 * h2 + 4 * c4;
-                const int mc = min(m, M - 1), nc = min(n, N - 4);
-                wv[j] = *reinterpret_cast<const uint2 *>(Wt + (int64_t)mc * ldw + nc);
-                keep[j] = mask[(int64_t)(mc >> 2) * (ldw >> 2) + (nc >> 2)] >> (4 * (mc & 3));
+                const uint32_t jc = (uint32_t)min(j, last_pass);
+                wv[j] = big::buffer_load_8(wbuf, voff_w, jc * 8u * (uint32_t)ldw);
+                keep[j] = big::buffer_load_2(mbuf, voff_m, jc * 2u * (uint32_t)(ldw >> 2)) >> shift;
             }
         }
     };
@@ -1132,6 +1155,7 @@ __global__ __launch_bounds__(THREADS) void dense_tn_dma_kernel(const DwBatch bat
                 }
                 if (live[b]) *reinterpret_cast<float4 *>(dW + (int64_t)m * ldw + n) = o;
             }
+            __builtin_amdgcn_sched_barrier(0);   // one batch at a time: hoisting the next batches' reads costs registers
         }
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(big::wait_vm_lgkm0(63));   // LDS reads done before the other half overwrites
