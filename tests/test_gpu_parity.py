@@ -688,7 +688,9 @@ def test_mvue24_kernel_neighbouring_seeds_give_unrelated_draws(s24):
 @pytest.mark.parametrize("case", [
     # (p, q, r, dtype, beta, decay)
     (64, 16, 16, "bf16", 0.0, False), (192, 272, 144, "bf16", 1.0, False), (128, 64, 48, "f32", 1.0, True),
-    (448, 1040, 528, "bf16", 0.0, True), (1024, 3600, 3408, "bf16", 1.0, True)])
+    (448, 1040, 528, "bf16", 0.0, True), (1024, 3600, 3408, "bf16", 1.0, True),
+    # two and five 64-token chunks: the remaining residues of the chunk count modulo the three-stage ring
+    (128, 272, 144, "bf16", 0.0, True), (320, 528, 272, "f16", 1.0, False)])
 def test_spmm_dw_on_the_pruned_gradient(s24, case):
     """S_z(dY^T) X from the oracle's own pruned operand: the GEMM is checked on its own (its input is
     the oracle's compressed operand, not the GPU's), with and without accumulation and the decay term."""
