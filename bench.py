@@ -503,6 +503,41 @@ def measured_ceilings(torch, s24):
     return out
 
 
+def operand_value_dependence(torch, s24, wl):
+    """The GEMM kernels of the step on one weight's shape, once on the workload's kind of data (normal random) and once
+    on operands that are all zero: the same instruction stream, the same schedule and the same bytes moved, but no
+    bits toggling in the matrix cores and on the data paths.  What the zero run gains is what the chip's power
+    management, not the kernel's schedule, takes from the run on real data."""
+    if wl.dtype == "f32":
+        return None
+    p, q, r = wl.p, wl.d_model, wl.d_ff
+    dt = torch.float16 if wl.dtype == "f16" else torch.bfloat16
+    fl = 2.0 * p * q * r
+    out = {"shape_p_q_r": [p, q, r]}
+    for label, xs, ws in (("random_operands", 1.0, 0.02), ("zero_operands", 0.0, 0.0)):
+        g = torch.Generator(device="cuda").manual_seed(5)
+        X = (torch.randn(p, q, device="cuda", generator=g) * xs).to(dt)
+        W = (torch.randn(r, q, device="cuda", generator=g) * ws).to(dt)
+        dYr = (torch.randn(p, r, device="cuda", generator=g) * 1e-2 * xs).to(dt)
+        vals = torch.empty((q // 64, r, 32), dtype=dt, device="cuda")
+        meta = torch.empty((q // 64, r, 4), dtype=torch.int16, device="cuda")
+        valsT = torch.empty((r // 64, q, 32), dtype=dt, device="cuda")
+        metaT = torch.empty((r // 64, q, 4), dtype=torch.int16, device="cuda")
+        s24.compress(W, None, vals, meta, valsT, metaT)
+        Y = torch.empty(p, r, dtype=dt, device="cuda")
+        dW = torch.empty(r, q, dtype=torch.float32, device="cuda")
+        row = {}
+        for key, fn in (("spmm_fwd", lambda: s24.spmm_fwd(X, vals, meta, Y)), ("dense_dw", lambda: s24.dense_dw(dYr, X, dW)),
+                        ("dense_gemm", lambda: s24.dense_gemm(X, W, Y))):
+            ms = _time_ms(torch, fn, 5)
+            row[key] = {"ms": round(ms, 4), "TFLOP/s": round(fl / ms / 1e9, 1), "core_clock_MHz": _clock_mhz(torch, s24, fn, 3)}
+        out[label] = row
+        del X, W, dYr, vals, meta, valsT, metaT, Y, dW
+    out["zero_over_random"] = {k: round(out["zero_operands"][k]["TFLOP/s"] / out["random_operands"][k]["TFLOP/s"], 3)
+                               for k in out["zero_operands"]}
+    return out
+
+
 def block_level_measurements(torch, s24, wl, ffn, X, dY, weights):
     """The paper's block-level comparison (Sec. 6, speed-up of a single FFN layer and of a single transformer block,
     forward + backward): the 2:4 FFN step of this library next to the same layer run densely through the library's own
@@ -719,6 +754,9 @@ def main():
         extras = side_measurements(torch, s24, wl, ffn, X, dY, weights)
         extras["standalone_hbm_kernels"] = standalone_hbm_kernels(torch, s24, wl, ffn, X)
         extras["measured_ceilings"] = measured_ceilings(torch, s24)
+        ovd = operand_value_dependence(torch, s24, wl)
+        if ovd is not None:
+            extras["operand_value_dependence"] = ovd
         if not args.no_block and wl.dtype != "f32":
             extras["block_level"] = block_level_measurements(torch, s24, wl, ffn, X, dY, weights)
 
