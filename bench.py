@@ -794,6 +794,11 @@ def main():
                             "pct_of_sparse_mfma_peak_whole_step": round(100 * w2.gemm_flops / ms2 / 1e9 / PEAK_SPARSE_BF16, 2),
                             "kernels": {k: {f: v[f] for f in ("launches_per_step", "ms_per_step", "achieved", "unit", "frac")}
                                         for k, v in k2.items()}}
+            if not f2.mvue:   # the same step replayed from one HIP graph: what it costs without launch gaps
+                graph = f2.capture(d2["X"], d2["dY"])
+                ms_g = _time_ms(torch, graph.replay, 20)
+                others[name]["as_hip_graph"] = {"ms_per_step": round(ms_g, 4), "TFLOP/s": round(w2.gemm_flops / ms_g / 1e9, 2)}
+                del graph
             del d2, f2
             torch.cuda.empty_cache()
             if w2.dtype == "f32":
