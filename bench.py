@@ -794,6 +794,10 @@ def main():
                             "pct_of_sparse_mfma_peak_whole_step": round(100 * w2.gemm_flops / ms2 / 1e9 / PEAK_SPARSE_BF16, 2),
                             "kernels": {k: {f: v[f] for f in ("launches_per_step", "ms_per_step", "achieved", "unit", "frac")}
                                         for k, v in k2.items()}}
+            # the same eager step without the per-kernel timing events (two event records per launch weigh on a layer
+            # whose kernels take tens of microseconds)
+            ms_e = _time_ms(torch, lambda: f2.step(d2["X"], d2["dY"]), 20)
+            others[name]["without_kernel_events"] = {"ms_per_step": round(ms_e, 4), "TFLOP/s": round(w2.gemm_flops / ms_e / 1e9, 2)}
             if not f2.mvue:   # the same step replayed from one HIP graph: what it costs without launch gaps
                 graph = f2.capture(d2["X"], d2["dY"])
                 ms_g = _time_ms(torch, graph.replay, 20)
