@@ -537,12 +537,32 @@ __global__ __launch_bounds__(256) void mask_compress_kernel(const T *__restrict_
             if constexpr (!SEARCH) id = s_lut_id[min(lut_index_of_mask(m), 1295u)];
             const uint4 rsel = s_clut[3 * id], csel = s_clut[3 * id + 1], mt = s_clut[3 * id + 2];
             const uint32_t rs[4] = {rsel.x, rsel.y, rsel.z, rsel.w}, cs[4] = {csel.x, csel.y, csel.z, csel.w};
-            // along q: one dword (two kept bf16) per block row
+            // along q: one dword (two kept bf16) per block row.  The four lanes of a quad (four neighbouring blocks
+            // of one block row) transpose their 4 x 4 dwords among themselves, two exchanges with the lane one away and
+            // two with the lane two away, so that lane k of the quad ends up with row k of all four blocks: 16
+            // contiguous bytes of that row's run, one store instead of four 4-byte ones.  (br and bq are multiples
+            // of 16: a quad is all inside the matrix or all outside.)
+            uint32_t pr[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t pr = __builtin_amdgcn_perm(rows[i].y, rows[i].x, rs[i]);
-                if (valid) reinterpret_cast<uint32_t *>(vals)[((int64_t)(bj >> 4) * R + 4 * bi + i) * 16 + (bj & 15)] = pr;
+            for (int i = 0; i < 4; ++i) pr[i] = __builtin_amdgcn_perm(rows[i].y, rows[i].x, rs[i]);
+            {
+                const bool odd = lbj & 1, upper = lbj & 2;
+#pragma unroll
+                for (int i = 0; i < 4; i += 2) {   // with lane ^ 1: an even lane hands over row i+1, an odd one row i
+                    const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(odd ? pr[i] : pr[i + 1]), 0xB1, 0xF, 0xF, false);
+                    if (odd) pr[i] = got;
+                    else pr[i + 1] = got;
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {      // with lane ^ 2: a lower lane hands over entry j+2, an upper one entry j
+                    const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(upper ? pr[j] : pr[j + 2]), 0x4E, 0xF, 0xF, false);
+                    if (upper) pr[j] = got;
+                    else pr[j + 2] = got;
+                }
             }
+            if (valid)
+                *reinterpret_cast<uint4 *>(reinterpret_cast<uint32_t *>(vals) + ((int64_t)(bj >> 4) * R + 4 * bi + (lbj & 3)) * 16 + (bj & 12)) =
+                    make_uint4(pr[0], pr[1], pr[2], pr[3]);
             uint32_t nib_lo = mt.x, nib_hi = mt.y;
             nib_lo |= (uint32_t)__shfl_down((int)nib_lo, 1) << 4;
             nib_hi |= (uint32_t)__shfl_down((int)nib_hi, 1) << 4;
