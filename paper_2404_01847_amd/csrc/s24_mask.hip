@@ -357,40 +357,52 @@ __device__ __forceinline__ unsigned int_best_pattern(const uint32_t (&mag)[16], 
     const uint32_t E = mx >> 23, emin = mn >> 23;
     if (emin == 0u || emin + 10u < E || E < 28u) return kHardBlock;
     const float scale = __uint_as_float((282u - E) << 23);   // 2^(155-E)
-    uint32_t a[4][4];
+    // r = the scaled magnitudes; the tie-break bonus of a cell, B(i, j), never gets an instruction of its own: every
+    // sum below that takes a cell in adds the cell's bonus as part of a compile-time constant (a three-operand add),
+    // and every candidate total contains each of its eight cells exactly once.
+    uint32_t r[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            a[i][j] = (uint32_t)(__uint_as_float(mag[4 * i + j]) * scale) + (uint32_t)(kColBonus[j] * kRowMult[i]);
-    uint32_t dt[4], db[4];
+        for (int j = 0; j < 4; ++j) r[i][j] = (uint32_t)(__uint_as_float(mag[4 * i + j]) * scale);
+    auto B = [](int i, int j) { return (uint32_t)(kColBonus[j] * kRowMult[i]); };
+    uint32_t dt[4], db[4];   // both top rows / both bottom rows keep column j
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        dt[j] = a[0][j] + a[1][j];
-        db[j] = a[2][j] + a[3][j];
+        dt[j] = r[0][j] + r[1][j] + (B(0, j) + B(1, j));
+        db[j] = r[2][j] + r[3][j] + (B(2, j) + B(3, j));
     }
+    uint32_t st[4][4], sb[4][4];   // row 0 keeps column p and row 1 column q (p != q); rows 2 and 3 likewise
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (p == q) continue;
+            st[p][q] = r[0][p] + r[1][q] + (B(0, p) + B(1, q));
+            sb[p][q] = r[2][p] + r[3][q] + (B(2, p) + B(3, q));
+        }
     // (i) both top rows keep the pair {c1,c2}, both bottom rows its complement
     uint32_t best = 0;
 #pragma unroll
     for (int k = 0; k < 6; ++k)
         best = max(best, (dt[pair_c1(k)] + dt[pair_c2(k)]) + (db[pair_c1(5 - k)] + db[pair_c2(5 - k)]));
-    // (ii) complementary pairs in each half: all of one row plus the two largest gains of moving a column to the other
+    // (ii) complementary pairs in each half: row 0 (row 2) keeps {y,z}, row 1 (row 3) the other two columns {w,x}
     {
-        auto half = [](const uint32_t (&r0)[4], const uint32_t (&r1)[4]) {
-            const int d0 = (int)(r0[0] - r1[0]), d1 = (int)(r0[1] - r1[1]), d2 = (int)(r0[2] - r1[2]), d3 = (int)(r0[3] - r1[3]);
-            const int m1 = max(d0, d1), n1 = min(d0, d1), m2 = max(d2, d3), n2 = min(d2, d3);
-            const int hi = max(m1, m2), lo = min(m1, m2);
-            const int second = max(lo, max(n1, n2));
-            return ((r1[0] + r1[1]) + (r1[2] + r1[3])) + (uint32_t)hi + (uint32_t)second;   // modulo 2^32: a sum of four cells
-        };
-        best = max(best, half(a[0], a[1]) + half(a[2], a[3]));
+        uint32_t top = 0, bot = 0;
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const int y = pair_c1(k), z = pair_c2(k), w = pair_c1(5 - k), x = pair_c2(5 - k);
+            top = max(top, st[y][w] + st[z][x]);
+            bot = max(bot, sb[y][w] + sb[z][x]);
+        }
+        best = max(best, top + bot);
     }
     // (iii) top rows share column x, bottom rows share column w, the two remaining columns cross in each half
     uint32_t cross[6];
 #pragma unroll
     for (int k = 0; k < 6; ++k) {
         const int y = pair_c1(k), z = pair_c2(k);
-        cross[k] = max(a[0][y] + a[1][z], a[0][z] + a[1][y]) + max(a[2][y] + a[3][z], a[2][z] + a[3][y]);
+        cross[k] = max(st[y][z], st[z][y]) + max(sb[y][z], sb[z][y]);
     }
 #pragma unroll
     for (int x = 0; x < 4; ++x)
